@@ -1,0 +1,186 @@
+"""ctypes wrapper around the CPU reference in gfn_oracle.c.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the CPU-baseline
+leg of the benchmark.  The product package never imports this module.
+
+`Oracle("f32")` does all arithmetic in binary32 (used where a float comparison decides the
+sampled action), `Oracle("f64")` in binary64 (ground truth along a given action sequence).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gfn_oracle.c")
+
+
+def lib_path(precision: str) -> str:
+    return os.path.join(_HERE, f"liboracle_{precision}.so")
+
+
+def build(force: bool = False) -> None:
+    """Compile the reference in both precisions with gcc (plain -O2, no contraction)."""
+    for precision, ctype in (("f32", "float"), ("f64", "double")):
+        out = lib_path(precision)
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra",
+               f"-DORACLE_REAL={ctype}", _SRC, "-o", out, "-lm", "-lpthread"]
+        subprocess.run(cmd, check=True)
+
+
+class _Env(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("grid_dim", C.c_int32), ("grid_side", C.c_int32),
+                ("r0", C.c_double), ("r1", C.c_double), ("r2", C.c_double),
+                ("n_bits", C.c_int32), ("k_bits", C.c_int32), ("n_modes", C.c_int32),
+                ("modes", C.c_void_p), ("beta", C.c_double),
+                ("lattice_n", C.c_int32), ("coupling", C.c_double)]
+
+
+class _Mlp(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("h1", C.c_int32), ("h2", C.c_int32), ("n_actions", C.c_int32),
+                ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("W3", C.c_void_p), ("b3", C.c_void_p)]
+
+
+class _Grad(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dW1", "db1", "dW2", "db2", "dW3", "db3")]
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Oracle:
+    def __init__(self, precision: str = "f64"):
+        assert precision in ("f32", "f64")
+        build()
+        self.precision = precision
+        self.real = np.float32 if precision == "f32" else np.float64
+        self.creal = C.c_float if precision == "f32" else C.c_double
+        self.lib = C.CDLL(lib_path(precision))
+        assert self.lib.oracle_real_bytes() == np.dtype(self.real).itemsize
+        self.lib.oracle_uniform.restype = self.creal
+        self.lib.oracle_gumbel.restype = self.creal
+        self._keep = []
+
+    # ---- marshalling -------------------------------------------------------
+    def _env(self, env):
+        modes = None
+        if env.modes is not None:
+            modes = np.ascontiguousarray(env.modes, dtype=np.uint32)
+        e = _Env(env.kind, env.grid_dim, env.grid_side, env.r0, env.r1, env.r2, env.n_bits, env.k_bits,
+                 0 if modes is None else modes.shape[0], _ptr(modes), env.beta, env.lattice_n, env.coupling)
+        return e, modes
+
+    def _mlp(self, w: Dict[str, np.ndarray]):
+        arrs = {k: np.ascontiguousarray(w[k], dtype=self.real) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
+        m = _Mlp(arrs["W1"].shape[0], arrs["W1"].shape[1], arrs["W2"].shape[1], arrs["W3"].shape[1],
+                 *[_ptr(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")])
+        assert arrs["W2"].shape[0] == m.h1 and arrs["W3"].shape[0] == m.h2
+        return m, arrs
+
+    # ---- RNG ---------------------------------------------------------------
+    def philox(self, ctr, key) -> np.ndarray:
+        c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+        k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+        o = (C.c_uint32 * 4)()
+        self.lib.oracle_philox4x32_10(c, k, o)
+        return np.array(list(o), dtype=np.uint32)
+
+    def uniform(self, w: int) -> float:
+        return float(self.lib.oracle_uniform(C.c_uint32(int(w))))
+
+    def gumbel(self, w: int) -> float:
+        return float(self.lib.oracle_gumbel(C.c_uint32(int(w))))
+
+    # ---- environment -------------------------------------------------------
+    def env_dims(self, env):
+        e, _keep = self._env(env)
+        out = [C.c_int32() for _ in range(4)]
+        rc = self.lib.oracle_env_dims(C.byref(e), *[C.byref(o) for o in out])
+        assert rc == 0
+        return tuple(o.value for o in out)
+
+    def log_reward(self, env, state) -> float:
+        e, _keep = self._env(env)
+        s = np.ascontiguousarray(state, dtype=np.int32)
+        out = self.creal()
+        rc = self.lib.oracle_log_reward(C.byref(e), _ptr(s), C.byref(out))
+        assert rc == 0
+        return float(out.value)
+
+    def policy(self, env, w, state):
+        """(logits, log_probs, valid) of the forward policy at a non-terminal state."""
+        e, _k1 = self._env(env)
+        m, _k2 = self._mlp(w)
+        s = np.ascontiguousarray(state, dtype=np.int32)
+        logit = np.zeros(m.n_actions, dtype=self.real)
+        logp = np.zeros(m.n_actions, dtype=self.real)
+        valid = np.zeros(m.n_actions, dtype=np.int32)
+        rc = self.lib.oracle_policy_logits(C.byref(e), C.byref(m), _ptr(s), _ptr(logit), _ptr(logp), _ptr(valid))
+        assert rc == 0, rc
+        return logit, logp, valid.astype(bool)
+
+    # ---- rollout / replay ----------------------------------------------------
+    def rollout(self, env, w, seed: int, iteration: int, batch: int, b_offset: int = 0,
+                max_steps: Optional[int] = None, nthreads: int = 1) -> Dict[str, np.ndarray]:
+        e, _k1 = self._env(env)
+        m, _k2 = self._mlp(w)
+        sd, _, _, ms = env.dims()
+        T = ms if max_steps is None else max_steps
+        out = dict(actions=np.zeros((T, batch), dtype=np.uint8), length=np.zeros(batch, dtype=np.int32),
+                   terminal_state=np.zeros((sd, batch), dtype=np.int8),
+                   log_pf=np.zeros(batch, dtype=self.real), log_pb=np.zeros(batch, dtype=self.real),
+                   log_reward=np.zeros(batch, dtype=self.real), min_margin=np.zeros(batch, dtype=self.real))
+        rc = self.lib.oracle_rollout(C.byref(e), C.byref(m), C.c_uint64(seed), C.c_uint64(iteration),
+                                     C.c_int32(b_offset), C.c_int32(batch), C.c_int32(T),
+                                     _ptr(out["actions"]), _ptr(out["length"]), _ptr(out["terminal_state"]),
+                                     _ptr(out["log_pf"]), _ptr(out["log_pb"]), _ptr(out["log_reward"]),
+                                     _ptr(out["min_margin"]), C.c_int(nthreads))
+        assert rc == 0, rc
+        return out
+
+    def replay(self, env, w, seed: int, iteration: int, actions: np.ndarray, length: np.ndarray,
+               b_offset: int = 0, tie_tol: float = 1e-5, nthreads: int = 1) -> Dict[str, np.ndarray]:
+        e, _k1 = self._env(env)
+        m, _k2 = self._mlp(w)
+        sd = env.dims()[0]
+        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        length = np.ascontiguousarray(length, dtype=np.int32)
+        T, batch = actions.shape
+        out = dict(terminal_state=np.zeros((sd, batch), dtype=np.int8),
+                   log_pf=np.zeros(batch, dtype=self.real), log_pb=np.zeros(batch, dtype=self.real),
+                   log_reward=np.zeros(batch, dtype=self.real), near_ties=np.zeros(batch, dtype=np.int32),
+                   violations=np.zeros(batch, dtype=np.int32), min_margin=np.zeros(batch, dtype=self.real))
+        rc = self.lib.oracle_replay(C.byref(e), C.byref(m), C.c_uint64(seed), C.c_uint64(iteration),
+                                    C.c_int32(b_offset), C.c_int32(batch), C.c_int32(T), _ptr(actions), _ptr(length),
+                                    _ptr(out["terminal_state"]), _ptr(out["log_pf"]), _ptr(out["log_pb"]),
+                                    _ptr(out["log_reward"]), self.creal(tie_tol), _ptr(out["near_ties"]),
+                                    _ptr(out["violations"]), _ptr(out["min_margin"]), C.c_int(nthreads))
+        assert rc == 0, rc
+        return out
+
+    # ---- loss + gradient -------------------------------------------------------
+    def tb_loss_grad(self, env, w, actions: np.ndarray, length: np.ndarray, log_z: float = 0.0,
+                     nthreads: int = 1) -> Dict[str, np.ndarray]:
+        e, _k1 = self._env(env)
+        m, arrs = self._mlp(w)
+        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        length = np.ascontiguousarray(length, dtype=np.int32)
+        T, batch = actions.shape
+        g = {("d" + k): np.zeros_like(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
+        gs = _Grad(*[_ptr(g[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
+        loss, dlogz = self.creal(), self.creal()
+        delta = np.zeros(batch, dtype=self.real)
+        rc = self.lib.oracle_tb_loss_grad(C.byref(e), C.byref(m), C.c_int32(batch), C.c_int32(T), _ptr(actions),
+                                          _ptr(length), self.creal(log_z), C.byref(loss), C.byref(dlogz),
+                                          C.byref(gs), _ptr(delta), C.c_int(nthreads))
+        assert rc == 0, rc
+        g.update(loss=float(loss.value), dlogz=float(dlogz.value), delta=delta)
+        return g
