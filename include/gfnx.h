@@ -1,0 +1,155 @@
+/*
+ * gfnx.h -- C ABI of libgfnx_hip.so: batched on-device GFlowNet trajectory rollout and the
+ * Trajectory-Balance (TB) loss with its gradient, for AMD gfx950 (MI355X).
+ *
+ * Vocabulary follows the paper (arXiv 2511.16592): trajectories tau = (s_0 .. s_n), forward policy
+ * P_F, backward policy P_B, reward R, normalising constant Z (Background section).  An environment
+ * is stateless: reset gives s_0, a step maps (state, action) to the child state and emits the
+ * log-reward on the terminal transition only ("Library Details", implementation notes and usage
+ * listing).  The three environments are the hypergrid (Appendix "Hypergrid"), bit sequences in the
+ * autoregressive fixed-length scheme (Appendix "Sequential environments" / "Bit sequences") and the
+ * Ising partial-assignment environment (Appendix "Ising model").
+ *
+ * General rules for every call
+ *   - returns GFNX_OK (0) or a negative gfnx_status; never throws, aborts or synchronises;
+ *   - arguments are validated on the host before anything is launched (testable without a GPU);
+ *   - descriptors (gfnx_env_desc, gfnx_mlp, gfnx_traj, gfnx_mlp_grad) are HOST structs, read
+ *     during the call and not retained; every pointer INSIDE them is a DEVICE pointer owned by the
+ *     caller; the library allocates no device memory and owns nothing between calls;
+ *   - all work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream);
+ *     buffers must stay valid until that work has completed;
+ *   - all floating point is IEEE binary32.
+ *
+ * Conventions (the same ones the CPU reference of the test-suite follows)
+ *   policy    logits = W3^T relu(W2^T relu(W1^T onehot(s) + b1) + b2) + b3, W row-major [in][out].
+ *   one-hot   grid: H*i + x_i;  bitseq: (2^k+1)*pos + tok, tok = 2^k for "empty";
+ *             Ising: 3*site + (x+1), x = 0 for an unassigned site, site = row*N + col.
+ *   actions   grid: a < d increments coordinate a (masked when x_a = H-1), a = d stops (last
+ *             index, as in the paper's usage listing);  bitseq: step t writes token a at position t;
+ *             Ising: site = a/2, spin = 2*(a%2)-1, masked once the site is assigned.
+ *   sampling  Gumbel-max over the valid actions: argmax_a (logit_a + g_a), lowest index on ties,
+ *             g = -log(-log(u)), u = ((w >> 9) + 0.5) * 2^-23, w = word (a % 4) of
+ *             Philox4x32-10(counter = (b, t, a / 4, iteration lo32), key = (seed lo32, seed hi32)),
+ *             b = global trajectory index, t = step.  Results do not depend on how the batch is
+ *             split over workgroups.
+ *   log P_B   uniform over parents: grid increment -log #{i : child_i > 0}, grid stop 0,
+ *             bitseq 0, Ising -log(t+1).
+ */
+#ifndef GFNX_H
+#define GFNX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GFNX_OK = 0,
+  GFNX_E_NULL = -1,        /* a required pointer is NULL */
+  GFNX_E_BAD_ENV = -2,     /* environment descriptor is inconsistent */
+  GFNX_E_BAD_SHAPE = -3,   /* MLP / trajectory shapes do not match the environment */
+  GFNX_E_WORKSPACE = -4,   /* workspace missing, misaligned (256 B) or too small */
+  GFNX_E_UNSUPPORTED = -5, /* valid request outside what the kernels are built for */
+  GFNX_E_HIP = -6          /* a HIP runtime call or kernel launch failed */
+} gfnx_status;
+
+typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2 } gfnx_env_kind;
+
+/* Environment + reward descriptor (host struct, copied by value during the call).
+ *   grid   : grid_dim d in 1..16, grid_side H in 2..127; reward of the Appendix "Hypergrid" equation,
+ *            R = r0 + r1 * prod_i [0.25 < |x_i/(H-1) - 0.5|] + r2 * prod_i [0.3 < |.| < 0.4], strict.
+ *   bitseq : n_bits = k_bits * L with k_bits in 1..8 and L <= 32; modes_dev points to DEVICE memory,
+ *            n_modes x ceil(n_bits/32) uint32 words, string bit i in bit (i % 32) of word i / 32;
+ *            token bits are laid out most-significant first; R = exp(-beta * min_m Hamming / n_bits)
+ *            (Appendix "Bit sequences").
+ *   ising  : lattice_n N in 3..10 (N*N <= 100 sites, periodic), R = exp(coupling * sum over the 2*N*N
+ *            nearest-neighbour bonds of x_i x_j), each bond counted once (Appendix "Ising model",
+ *            energy equation with J = (coupling/2) * adjacency).
+ * Fields of the other kinds are ignored. */
+typedef struct {
+  int32_t kind;
+  int32_t grid_dim, grid_side;
+  float r0, r1, r2;
+  int32_t n_bits, k_bits, n_modes;
+  const uint32_t* modes_dev;
+  float beta;
+  int32_t lattice_n;
+  float coupling;
+} gfnx_env_desc;
+
+/* Policy network In -> h1 -> h2 -> n_actions with ReLU (the paper's "MLP with 2 hidden layers").
+ * Device pointers, row-major [in][out], biases [out].  h1 and h2 must be multiples of 64 and at most
+ * 512; n_actions at most 256. */
+typedef struct {
+  int32_t in_dim, h1, h2, n_actions;
+  const float *W1, *b1, *W2, *b2, *W3, *b3;
+} gfnx_mlp;
+
+/* Gradient buffers, same shapes as the weights, device pointers; OVERWRITTEN (not accumulated). */
+typedef struct {
+  float *dW1, *db1, *dW2, *db2, *dW3, *db3;
+} gfnx_mlp_grad;
+
+/* Structure-of-arrays trajectory batch, device pointers, caller-allocated.
+ *   actions        [max_steps][batch] one byte per transition, coalesced over the batch; entries with
+ *                  t >= length[b] are 0xFF padding (use length[], not the sentinel: 0xFF is also the
+ *                  valid action 255 of an environment with 256 actions);
+ *   length         [batch] number of transitions including the terminating one;
+ *   terminal_state [state_dim][batch] grid coordinate / token byte / spin of the terminal state;
+ *   log_pf, log_pb [batch] sums over the trajectory of log P_F(s_t | s_t-1) and log P_B(s_t-1 | s_t)
+ *                  (Background, eq. forward_backward_traj);
+ *   log_reward     [batch] log R of the terminal state. */
+typedef struct {
+  int32_t batch, max_steps;
+  uint8_t* actions;
+  int32_t* length;
+  int8_t* terminal_state;
+  float *log_pf, *log_pb, *log_reward;
+} gfnx_traj;
+
+/* Host-only: sizes implied by an environment descriptor.  max_steps is the longest possible
+ * trajectory: d*(H-1)+1 (grid), n_bits/k_bits (bitseq), N*N (Ising).  Any out pointer may be NULL. */
+int gfnx_env_dims(const gfnx_env_desc* env, int32_t* state_dim, int32_t* obs_dim, int32_t* n_actions,
+                  int32_t* max_steps);
+
+/* Host-only: bytes of device workspace the calls below need for this environment, network and
+ * batch (returns 0 if the arguments are invalid).  The workspace holds the re-laid-out weights, the
+ * per-transition activations the rollout keeps for the gradient pass, and reduction partials. */
+size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t batch);
+
+/* Forward rollout (the paper's forward_rollout utility, "Library Details"): samples `traj->batch`
+ * complete trajectories from P_F given by `mlp`, starting at s_0, and fills every array of `traj`.
+ * Trajectory b uses the Philox counters (b, t, ., iteration).  Also leaves in `workspace` what
+ * gfnx_tb_loss_grad needs.  traj->max_steps must be >= the environment's max_steps.
+ * Errors: NULL pointers, shape mismatches, unsupported sizes, workspace too small / misaligned. */
+int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration,
+                 gfnx_traj* traj, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Teacher-forced rollout: follows the given traj->actions / traj->length (inputs) instead of
+ * sampling, and fills log_pf, log_pb, log_reward, terminal_state and the workspace exactly as
+ * gfnx_rollout would (off-policy trajectories, the trajectory distributions of eq.
+ * forward_backward_traj for given tau).  Behaviour is undefined if an action is invalid in its state
+ * or a sequence does not end in a terminal state after length[b] steps. */
+int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, void* workspace,
+                size_t workspace_bytes, void* hip_stream);
+
+/* Trajectory-Balance loss (Background, eq. TB_loss) averaged over the batch and its gradient:
+ *   delta_b = log_z + log_pf[b] - log_reward[b] - log_pb[b],   loss = mean_b delta_b^2,
+ *   *dlogz_dev = d loss / d log Z = (2/B) sum_b delta_b,   grads = d loss / d (W1 .. b3), with P_B fixed.
+ * `traj`, `mlp`, `env`, `workspace` must be the ones of the immediately preceding gfnx_rollout or
+ * gfnx_replay on the same stream: the per-transition activations are taken from the workspace and are
+ * consumed (overwritten) by this call, so it can run once per rollout.  loss_dev and dlogz_dev are
+ * device pointers to one float each. */
+int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
+                      float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* gfnx_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GFNX_H */

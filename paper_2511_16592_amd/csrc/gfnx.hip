@@ -1,0 +1,335 @@
+// libgfnx_hip: C ABI (see include/gfnx.h), host-side validation, workspace layout and kernel launches.
+#include "../../include/gfnx.h"
+
+#include <hip/hip_runtime.h>
+
+#include "gfnx_device.h"
+#include "grad_kernels.h"
+#include "rollout_kernel.h"
+
+using namespace gfnx;
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Shapes {
+  int state_dim, obs_dim, n_actions, max_steps;
+  int H1, H2, A, A16, B;
+  size_t rows;  // max_steps * B
+  int qt3, qtot3, s3, s2, qtot2;
+};
+
+struct Layout {
+  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, part2, dbp2, part3, dbp3, total;
+};
+
+int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
+  if (!env) return GFNX_E_NULL;
+  if (env->kind == GFNX_ENV_GRID) {
+    if (env->grid_dim < 1 || env->grid_dim > 16 || env->grid_side < 2 || env->grid_side > 127) return GFNX_E_BAD_ENV;
+    *sd = env->grid_dim;
+    *od = env->grid_dim * env->grid_side;
+    *na = env->grid_dim + 1;
+    *ms = env->grid_dim * (env->grid_side - 1) + 1;
+  } else if (env->kind == GFNX_ENV_BITSEQ) {
+    if (env->k_bits < 1 || env->k_bits > 8 || env->n_bits < env->k_bits || env->n_bits % env->k_bits) return GFNX_E_BAD_ENV;
+    const int len = env->n_bits / env->k_bits;
+    if (len > 32 || env->n_modes < 1) return GFNX_E_BAD_ENV;
+    *sd = len;
+    *od = len * ((1 << env->k_bits) + 1);
+    *na = 1 << env->k_bits;
+    *ms = len;
+  } else if (env->kind == GFNX_ENV_ISING) {
+    if (env->lattice_n < 3 || env->lattice_n > 10) return GFNX_E_BAD_ENV;
+    const int d = env->lattice_n * env->lattice_n;
+    *sd = d;
+    *od = 3 * d;
+    *na = 2 * d;
+    *ms = d;
+  } else {
+    return GFNX_E_BAD_ENV;
+  }
+  return GFNX_OK;
+}
+
+int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shapes* s) {
+  if (!env || !mlp) return GFNX_E_NULL;
+  int rc = env_dims(env, &s->state_dim, &s->obs_dim, &s->n_actions, &s->max_steps);
+  if (rc) return rc;
+  if (env->kind == GFNX_ENV_BITSEQ && !env->modes_dev) return GFNX_E_NULL;
+  if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2 || !mlp->W3 || !mlp->b3) return GFNX_E_NULL;
+  if (batch <= 0) return GFNX_E_BAD_SHAPE;
+  if (mlp->in_dim != s->obs_dim || mlp->n_actions != s->n_actions) return GFNX_E_BAD_SHAPE;
+  if (mlp->h1 <= 0 || mlp->h2 <= 0) return GFNX_E_BAD_SHAPE;
+  if (mlp->h1 % 64 || mlp->h2 % 64 || mlp->h1 > 512 || mlp->h2 > 512) return GFNX_E_UNSUPPORTED;
+  if (s->n_actions > 256 || s->max_steps > 256 || s->state_dim > kMaxStateDim) return GFNX_E_UNSUPPORTED;
+  s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = s->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
+  s->rows = (size_t)s->max_steps * (size_t)batch;
+  if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+  // split factors of the weight-gradient contractions (over the transitions)
+  const int tiles2 = ((s->H1 + 127) / 128) * ((s->H2 + 127) / 128);
+  s->s2 = 1024 / tiles2; if (s->s2 > 256) s->s2 = 256; if (s->s2 < 1) s->s2 = 1;
+  s->qtot2 = ((s->H2 + 127) / 128) * 128;
+  s->qt3 = s->A16 <= 32 ? 32 : 128;
+  s->qtot3 = ((s->A16 + s->qt3 - 1) / s->qt3) * s->qt3;
+  const int tiles3 = ((s->H2 + 127) / 128) * (s->qtot3 / s->qt3);
+  s->s3 = 1024 / tiles3; if (s->s3 > 256) s->s3 = 256; if (s->s3 < 1) s->s3 = 1;
+  return GFNX_OK;
+}
+
+Layout make_layout(const Shapes& s) {
+  Layout L;
+  size_t o = 0;
+  L.hdr = o; o += align256(sizeof(int) * kHdrWords);
+  L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
+  L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
+  L.coef = o; o += align256(sizeof(float) * (size_t)s.B);
+  L.rows = o; o += align256(sizeof(int) * s.rows);
+  L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
+  L.h2 = o; o += align256(sizeof(float) * s.rows * s.H2);
+  L.e = o; o += align256(sizeof(float) * s.rows * s.A16);
+  L.part2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.H1 * s.qtot2);
+  L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
+  L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
+  L.dbp3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.qtot3);
+  L.total = o;
+  return L;
+}
+
+int check_traj(const gfnx_traj* t, const Shapes& s) {
+  if (!t) return GFNX_E_NULL;
+  if (!t->actions || !t->length || !t->terminal_state || !t->log_pf || !t->log_pb || !t->log_reward) return GFNX_E_NULL;
+  if (t->batch <= 0 || t->max_steps < s.max_steps) return GFNX_E_BAD_SHAPE;
+  return GFNX_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, const Layout& L) {
+  if (!ws) return GFNX_E_WORKSPACE;
+  if (((uintptr_t)ws) & 255) return GFNX_E_WORKSPACE;
+  if (bytes < L.total) return GFNX_E_WORKSPACE;
+  return GFNX_OK;
+}
+
+EnvParams env_params(const gfnx_env_desc* env, const Shapes& s) {
+  EnvParams e = {};
+  e.kind = env->kind;
+  e.d = env->grid_dim; e.H = env->grid_side;
+  e.r0 = env->r0; e.r1 = env->r1; e.r2 = env->r2;
+  e.n_bits = env->n_bits; e.k_bits = env->k_bits; e.n_modes = env->n_modes;
+  e.L = env->kind == GFNX_ENV_BITSEQ ? env->n_bits / env->k_bits : 0;
+  e.words = (env->n_bits + 31) / 32;
+  e.modes = env->modes_dev;
+  e.beta = env->beta;
+  e.N = env->lattice_n; e.D = env->lattice_n * env->lattice_n;
+  e.coupling = env->coupling;
+  e.state_dim = s.state_dim; e.obs_dim = s.obs_dim; e.n_actions = s.n_actions; e.max_steps = s.max_steps;
+  return e;
+}
+
+template <typename T>
+inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
+
+size_t rollout_lds_bytes(const Shapes& s) {
+  const int nchunk = s.A16 / 4, nt3 = s.A16 / 16;
+  const int ksplit = nt3 >= 4 ? 1 : 4;
+  size_t fl = (size_t)(s.H1 / 4 + s.H2 / 4 + ksplit * nchunk) * kPitch;
+  return fl * sizeof(float) + 3 * kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
+}
+
+template <int ENV, bool REPLAY>
+int launch_rollout_ntw(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
+#define GFNX_LAUNCH(N)                                                                                      \
+  {                                                                                                         \
+    auto k = rollout_kernel<ENV, REPLAY, N>;                                                                \
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
+      return GFNX_E_HIP;                                                                                    \
+    hipLaunchKernelGGL(k, grid, dim3(256), lds, st, p);                                                     \
+  }
+  switch (ntw) {
+    case 1: GFNX_LAUNCH(1) break;
+    case 2: GFNX_LAUNCH(2) break;
+    case 3: GFNX_LAUNCH(3) break;
+    case 4: GFNX_LAUNCH(4) break;
+    case 5: GFNX_LAUNCH(5) break;
+    case 6: GFNX_LAUNCH(6) break;
+    case 7: GFNX_LAUNCH(7) break;
+    case 8: GFNX_LAUNCH(8) break;
+    default: return GFNX_E_UNSUPPORTED;
+  }
+#undef GFNX_LAUNCH
+  return GFNX_OK;
+}
+
+template <bool REPLAY>
+int launch_rollout(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
+  switch (p.env.kind) {
+    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY>(p, ntw, grid, lds, st);
+    case GFNX_ENV_BITSEQ: return launch_rollout_ntw<1, REPLAY>(p, ntw, grid, lds, st);
+    default: return launch_rollout_ntw<2, REPLAY>(p, ntw, grid, lds, st);
+  }
+}
+
+int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
+                 void* ws, size_t ws_bytes, void* hip_stream, bool replay) {
+  Shapes s;
+  if (!traj) return GFNX_E_NULL;
+  int rc = check_shapes(env, mlp, traj->batch, &s);
+  if (rc) return rc;
+  rc = check_traj(traj, s);
+  if (rc) return rc;
+  const Layout L = make_layout(s);
+  rc = check_workspace(ws, ws_bytes, L);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, s.H2 / 16,
+                     at<float>(ws, L.w2p));
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(128), dim3(256), 0, st, mlp->W3, s.H2, s.A, s.A16 / 16,
+                     at<float>(ws, L.w3p));
+
+  RolloutParams p = {};
+  p.env = env_params(env, s);
+  p.In = s.obs_dim; p.H1 = s.H1; p.H2 = s.H2; p.A = s.A; p.A16 = s.A16;
+  p.W1 = mlp->W1; p.b1 = mlp->b1; p.b2 = mlp->b2; p.b3 = mlp->b3;
+  p.W2p = at<float>(ws, L.w2p); p.W3p = at<float>(ws, L.w3p);
+  p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
+  p.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFull);
+  p.B = s.B; p.T = traj->max_steps;
+  p.actions = traj->actions; p.length = traj->length; p.term = traj->terminal_state;
+  p.lpf = traj->log_pf; p.lpb = traj->log_pb; p.logr = traj->log_reward;
+  p.h1buf = at<float>(ws, L.h1); p.h2buf = at<float>(ws, L.h2); p.ebuf = at<float>(ws, L.e);
+
+  const dim3 grid((s.B + kSlots - 1) / kSlots);
+  const size_t lds = rollout_lds_bytes(s);
+  if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
+  rc = replay ? launch_rollout<true>(p, s.H2 / 64, grid, lds, st) : launch_rollout<false>(p, s.H2 / 64, grid, lds, st);
+  if (rc) return rc;
+  return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gfnx_env_dims(const gfnx_env_desc* env, int32_t* state_dim, int32_t* obs_dim, int32_t* n_actions,
+                  int32_t* max_steps) {
+  int sd, od, na, ms;
+  const int rc = env_dims(env, &sd, &od, &na, &ms);
+  if (rc) return rc;
+  if (state_dim) *state_dim = sd;
+  if (obs_dim) *obs_dim = od;
+  if (n_actions) *n_actions = na;
+  if (max_steps) *max_steps = ms;
+  return GFNX_OK;
+}
+
+size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t batch) {
+  Shapes s;
+  if (!env || !mlp) return 0;
+  // size queries need the shapes only, not the device pointers
+  gfnx_mlp m = *mlp;
+  static const float dummy = 0.f;
+  m.W1 = m.b1 = m.W2 = m.b2 = m.W3 = m.b3 = &dummy;
+  gfnx_env_desc e = *env;
+  if (e.kind == GFNX_ENV_BITSEQ && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
+  if (check_shapes(&e, &m, batch, &s)) return 0;
+  return make_layout(s).total;
+}
+
+int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rollout_impl(env, mlp, seed, iteration, traj, workspace, workspace_bytes, hip_stream, false);
+}
+
+int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+  return rollout_impl(env, mlp, 0, 0, traj, workspace, workspace_bytes, hip_stream, true);
+}
+
+int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
+                      float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes,
+                      void* hip_stream) {
+  Shapes s;
+  if (!traj || !grads || !loss_dev || !dlogz_dev) return GFNX_E_NULL;
+  int rc = check_shapes(env, mlp, traj->batch, &s);
+  if (rc) return rc;
+  rc = check_traj(traj, s);
+  if (rc) return rc;
+  if (!grads->dW1 || !grads->db1 || !grads->dW2 || !grads->db2 || !grads->dW3 || !grads->db3) return GFNX_E_NULL;
+  const Layout L = make_layout(s);
+  rc = check_workspace(ws, ws_bytes, L);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  int* hdr = at<int>(ws, L.hdr);
+  int* rows = at<int>(ws, L.rows);
+  float* coef = at<float>(ws, L.coef);
+  float* h1buf = at<float>(ws, L.h1);
+  float* h2buf = at<float>(ws, L.h2);
+  float* ebuf = at<float>(ws, L.e);
+  const int T = s.max_steps, B = s.B;
+  if ((size_t)traj->max_steps * B > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+
+  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb,
+                     traj->log_reward, log_z, B, T, coef, loss_dev, dlogz_dev, hdr);
+  hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows);
+  hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
+
+  // layer 3: dW3, db3, then G2 over h2
+  {
+    const dim3 grid((s.H2 + 127) / 128, s.qtot3 / s.qt3, s.s3);
+    float* part = at<float>(ws, L.part3);
+    float* dbp = at<float>(ws, L.dbp3);
+    if (s.qt3 == 32)
+      hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+    else
+      hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3);
+  }
+  const int row_tiles = (int)((s.rows + 63) / 64);
+  const int gx = row_tiles < 2048 ? row_tiles : 2048;
+  hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
+                     h2buf, s.H2, s.H2, rows, hdr);
+  // layer 2: dW2, db2, then G1 over h1
+  {
+    const dim3 grid((s.H1 + 127) / 128, s.qtot2 / 128, s.s2);
+    float* part = at<float>(ws, L.part2);
+    float* dbp = at<float>(ws, L.dbp2);
+    hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2);
+  }
+  hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
+                     h1buf, s.H1, s.H1, rows, hdr);
+  // layer 1: scatter along each trajectory
+  hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
+  hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
+  Dw1Params dp = {};
+  dp.env = env_params(env, s);
+  dp.H1 = s.H1; dp.B = B;
+  dp.actions = traj->actions; dp.length = traj->length; dp.term = traj->terminal_state;
+  dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
+  switch (env->kind) {
+    case GFNX_ENV_GRID: hipLaunchKernelGGL(dw1_kernel<0>, dim3(B), dim3(256), 0, st, dp); break;
+    case GFNX_ENV_BITSEQ: hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp); break;
+    default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
+  }
+  return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+const char* gfnx_status_string(int status) {
+  switch (status) {
+    case GFNX_OK: return "GFNX_OK";
+    case GFNX_E_NULL: return "GFNX_E_NULL: a required pointer is NULL";
+    case GFNX_E_BAD_ENV: return "GFNX_E_BAD_ENV: inconsistent environment descriptor";
+    case GFNX_E_BAD_SHAPE: return "GFNX_E_BAD_SHAPE: shapes do not match the environment";
+    case GFNX_E_WORKSPACE: return "GFNX_E_WORKSPACE: workspace missing, misaligned or too small";
+    case GFNX_E_UNSUPPORTED: return "GFNX_E_UNSUPPORTED: outside the supported sizes";
+    case GFNX_E_HIP: return "GFNX_E_HIP: HIP runtime error";
+    default: return "unknown gfnx status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Shared device-side definitions of libgfnx_hip: parameter blocks, MFMA wrappers, the counter-based
+// RNG and small wavefront helpers.  gfx950 only (64-wide wavefronts, fp32 MFMA).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gfnx {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kSlots = 16;         // trajectories per workgroup of the rollout kernel (one MFMA N-tile)
+constexpr int kPitch = 68;         // floats per feature-quad row of an activation tile in LDS (16 slots * 4 + 4 pad)
+constexpr int kMaxStateDim = 100;  // largest state vector (Ising 10x10)
+
+struct EnvParams {
+  int kind;
+  int d, H;  // grid
+  float r0, r1, r2;
+  int n_bits, k_bits, L, n_modes, words;  // bitseq
+  const uint32_t* modes;
+  float beta;
+  int N, D;  // ising
+  float coupling;
+  int state_dim, obs_dim, n_actions, max_steps;
+};
+
+struct RolloutParams {
+  EnvParams env;
+  int In, H1, H2, A, A16;
+  const float *W1, *b1, *b2, *b3;
+  const float *W2p, *W3p;  // weights re-laid-out as MFMA A-operands
+  uint32_t seed_lo, seed_hi, iter_lo;
+  int B, T;  // batch, traj.max_steps
+  uint8_t* actions;
+  int* length;
+  int8_t* term;
+  float *lpf, *lpb, *logr;
+  float *h1buf, *h2buf, *ebuf;  // per-transition rows, row = t*B + b
+};
+
+// D(16x16) += A(16x4) * B(4x16).  Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];
+// it receives D[i = 4*(l/16) + r][j = l%16] in register r.
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+// D(32x32) += A(32x2) * B(2x32).  Lane l supplies A[i = l%32][k = l/32] and B[k = l/32][j = l%32];
+// it receives D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32] in register r.
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies,
+// key bumped by the Weyl constants each round.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// 32 random bits -> u in (0,1) exactly representable in binary32 -> standard Gumbel variate.
+__device__ __forceinline__ float gumbel_from_bits(uint32_t w) {
+  const float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23
+  return -logf(-logf(u));
+}
+
+// reductions over the 16 lanes that serve one trajectory slot (an aligned quarter of a wavefront)
+__device__ __forceinline__ float row16_max(float v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 16));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 16);
+  return v;
+}
+__device__ __forceinline__ int row16_sum(int v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 16);
+  return v;
+}
+__device__ __forceinline__ int row16_min(int v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
+  return v;
+}
+
+}  // namespace gfnx

@@ -1,0 +1,328 @@
+// Gradient pass of the Trajectory-Balance loss over the transitions recorded by the rollout.
+//
+// The live transitions (t < length[b]) are listed in (t, b) order; every kernel below works on that
+// list, so padded steps cost nothing.  With coef_b = 2 delta_b / B the chain is
+//   G3 = coef * (onehot(a) - p)                      (scale_rows_kernel, in place)
+//   dW3 = H2^T G3, db3 = colsum G3                   (gemm_tn_kernel, split over the transitions)
+//   G2 = (G3 W3^T) . [h2 > 0]   written over h2      (gemm_nt_mask_kernel)
+//   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn_kernel)
+//   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt_mask_kernel)
+//   dW1, db1 from G1 by prefix sums along each trajectory (dw1_kernel)
+// All contractions run on the fp32 matrix cores (32x32x2 tiles) from LDS-staged operands.
+#pragma once
+#include "gfnx_device.h"
+
+namespace gfnx {
+
+constexpr int kHdrNLive = 0;    // header words (int32)
+constexpr int kHdrMaxLen = 1;
+constexpr int kHdrCnt = 16;     // cnt[t] = number of trajectories longer than t, t < 256
+constexpr int kHdrOff = 16 + 256;  // off[t] = first list position of step t
+constexpr int kHdrWords = 16 + 512;
+
+// One workgroup: TB residuals, loss, dloss/dlogZ, per-trajectory gradient scale, and the histogram of
+// lengths that positions each step's live transitions in the list.
+__global__ __launch_bounds__(1024) void prep_kernel(const int* __restrict__ length, const float* __restrict__ lpf,
+                                                    const float* __restrict__ lpb, const float* __restrict__ logr,
+                                                    float log_z, int B, int T, float* __restrict__ coef,
+                                                    float* __restrict__ loss, float* __restrict__ dlogz,
+                                                    int* __restrict__ hdr) {
+  __shared__ int hist[258];
+  __shared__ float red2[1024], red1[1024];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 258; i += 1024) hist[i] = 0;
+  __syncthreads();
+  float s2 = 0.f, s1 = 0.f;
+  for (int b = tid; b < B; b += 1024) {
+    const float delta = log_z + lpf[b] - logr[b] - lpb[b];
+    coef[b] = 2.f * delta / (float)B;
+    s2 += delta * delta;
+    s1 += delta;
+    int len = length[b];
+    len = len < 0 ? 0 : (len > T ? T : len);
+    atomicAdd(&hist[len], 1);
+  }
+  red2[tid] = s2;
+  red1[tid] = s1;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (tid < o) { red2[tid] += red2[tid + o]; red1[tid] += red1[tid + o]; }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    *loss = red2[0] / (float)B;
+    *dlogz = 2.f * red1[0] / (float)B;
+    // cnt[t] = #{b : len_b > t} = sum_{l > t} hist[l]
+    int run = 0, maxlen = 0;
+    for (int l = T; l >= 1; --l) {
+      run += hist[l];
+      hdr[kHdrCnt + l - 1] = run;
+      if (hist[l] && maxlen == 0) maxlen = l;
+    }
+    int off = 0;
+    for (int t = 0; t < T; ++t) { hdr[kHdrOff + t] = off; off += hdr[kHdrCnt + t]; }
+    hdr[kHdrNLive] = off;
+    hdr[kHdrMaxLen] = maxlen;
+  }
+}
+
+// Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b.
+__global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict__ length, int B,
+                                                          const int* __restrict__ hdr, int* __restrict__ rows) {
+  __shared__ int wsum[16];
+  __shared__ int base;
+  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (hdr[kHdrCnt + t] == 0) return;
+  if (tid == 0) base = hdr[kHdrOff + t];
+  __syncthreads();
+  for (int b0 = 0; b0 < B; b0 += 1024) {
+    const int b = b0 + tid;
+    const bool on = b < B && length[b] > t;
+    const unsigned long long bal = __ballot(on);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wv] = __popcll(bal);
+    __syncthreads();
+    int woff = 0, tot = 0;
+    for (int k = 0; k < 16; ++k) { if (k < wv) woff += wsum[k]; tot += wsum[k]; }
+    if (on) rows[base + woff + before] = t * B + b;
+    __syncthreads();
+    if (tid == 0) base += tot;
+    __syncthreads();
+  }
+}
+
+// E rows (onehot - p) -> G3 = coef_b * E, in place, live rows only.
+__global__ void scale_rows_kernel(float* __restrict__ ebuf, int A16, const float* __restrict__ coef, int B,
+                                  const int* __restrict__ rows, const int* __restrict__ hdr) {
+  const int n = hdr[kHdrNLive];
+  const int per = A16 >> 2;
+  const size_t total = (size_t)n * per;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int r = rows[i / per];
+    f32x4* p = (f32x4*)&ebuf[(size_t)r * A16 + 4 * (i % per)];
+    *p = *p * coef[r % B];
+  }
+}
+
+// part[s][p][q] = sum over this split's live rows i of X[i][p] * G[i][q]   (dW = X^T G)
+// dbpart[s][q]  = sum over the same rows of G[i][q]                         (written by the p-tile 0 groups)
+// grid = (P/128, QTOT/QT, S); tile 128 x QT, K-chunks of 32 rows gathered through the row list.
+template <int QT>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ X, int ldx, const float* __restrict__ G,
+                                                      int ldg, const int* __restrict__ rows,
+                                                      const int* __restrict__ hdr, int P, int QTOT,
+                                                      float* __restrict__ part, float* __restrict__ dbpart) {
+  constexpr int KC = 32;
+  __shared__ float XS[KC][128];
+  __shared__ float GS[KC][QT];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int ptile = blockIdx.x, qtile = blockIdx.y, s = blockIdx.z, S = gridDim.z;
+  const int n = hdr[kHdrNLive];
+  const int chunks = (n + KC - 1) / KC;
+  const int per = (chunks + S - 1) / S;
+  const int c0 = s * per, c1 = min(chunks, c0 + per);
+
+  constexpr int PB = (QT == 128) ? 2 : 1;  // 32-row blocks per wave along p
+  constexpr int QB = (QT == 128) ? 2 : 1;
+  const int pbase = (QT == 128) ? 64 * (w >> 1) : 32 * w;
+  const int qbase = (QT == 128) ? 64 * (w & 1) : 0;
+  f32x16 acc[PB][QB];
+#pragma unroll
+  for (int a = 0; a < PB; ++a)
+#pragma unroll
+    for (int b = 0; b < QB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  float dbacc = 0.f;
+
+  for (int c = c0; c < c1; ++c) {
+    for (int i = tid; i < KC * 32; i += 256) {
+      const int r = i >> 5, c4 = i & 31;
+      const int li = c * KC + r;
+      f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+      if (li < n && ptile * 128 + 4 * c4 < P) v = *(const f32x4*)&X[(size_t)rows[li] * ldx + ptile * 128 + 4 * c4];
+      *(f32x4*)&XS[r][4 * c4] = v;
+    }
+    for (int i = tid; i < KC * (QT / 4); i += 256) {
+      const int r = i / (QT / 4), c4 = i % (QT / 4);
+      const int li = c * KC + r;
+      const int col = qtile * QT + 4 * c4;
+      f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
+      if (li < n && col < ldg) v = *(const f32x4*)&G[(size_t)rows[li] * ldg + col];
+      *(f32x4*)&GS[r][4 * c4] = v;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int k = 0; k < KC; k += 2) {
+      float av[PB], bv[QB];
+#pragma unroll
+      for (int a = 0; a < PB; ++a) av[a] = XS[k + (lane >> 5)][pbase + 32 * a + (lane & 31)];
+#pragma unroll
+      for (int b = 0; b < QB; ++b) bv[b] = GS[k + (lane >> 5)][qbase + 32 * b + (lane & 31)];
+#pragma unroll
+      for (int a = 0; a < PB; ++a)
+#pragma unroll
+        for (int b = 0; b < QB; ++b) acc[a][b] = mfma32(av[a], bv[b], acc[a][b]);
+    }
+    if (ptile == 0 && tid < QT) {
+#pragma unroll 8
+      for (int k = 0; k < KC; ++k) dbacc += GS[k][tid];
+    }
+    __syncthreads();
+  }
+  float* out = part + (size_t)s * P * QTOT;
+#pragma unroll
+  for (int a = 0; a < PB; ++a)
+#pragma unroll
+    for (int b = 0; b < QB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int pi = ptile * 128 + pbase + 32 * a + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int qi = qtile * QT + qbase + 32 * b + (lane & 31);
+        if (pi < P) out[(size_t)pi * QTOT + qi] = acc[a][b][r];
+      }
+  if (ptile == 0 && tid < QT) dbpart[(size_t)s * QTOT + qtile * QT + tid] = dbacc;
+}
+
+// out[p*Q + q] = sum_s part[s][p][q] for q < Q (fixed order: reproducible); rows of `part` have QTOT columns.
+__global__ void reduce_partials_kernel(const float* __restrict__ part, int S, int P, int QTOT, int Q,
+                                       float* __restrict__ out) {
+  const size_t total = (size_t)P * Q;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int p = (int)(i / Q), q = (int)(i % Q);
+    float acc = 0.f;
+    for (int s = 0; s < S; ++s) acc += part[((size_t)s * P + p) * QTOT + q];
+    out[i] = acc;
+  }
+}
+
+// For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [Out[i][p] > 0], in place over the stored
+// activation.  Gin rows have ldgi floats (zero beyond Q), W is row-major [P][Q].
+// grid = (row tiles (grid-stride), P/128); tile 64 rows x 128 columns, K-chunks of 32.
+__global__ __launch_bounds__(256) void gemm_nt_mask_kernel(const float* __restrict__ Gin, int ldgi,
+                                                           const float* __restrict__ W, int Q,
+                                                           float* __restrict__ ActOut, int ldo, int P,
+                                                           const int* __restrict__ rows,
+                                                           const int* __restrict__ hdr) {
+  constexpr int KC = 32, KP = KC + 1;
+  __shared__ float GS[64 * KP];
+  __shared__ float WS[128 * KP];
+  __shared__ int rid[64];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n = hdr[kHdrNLive];
+  const int tiles = (n + 63) >> 6;
+  const int pt = blockIdx.y;
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    __syncthreads();
+    if (tid < 64) rid[tid] = (tile * 64 + tid < n) ? rows[tile * 64 + tid] : -1;
+    __syncthreads();
+    f32x16 acc[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
+    for (int k0 = 0; k0 < Q; k0 += KC) {
+      for (int i = tid; i < 64 * KC; i += 256) {
+        const int r = i >> 5, k = i & 31;
+        float v = 0.f;
+        if (rid[r] >= 0 && k0 + k < ldgi) v = Gin[(size_t)rid[r] * ldgi + k0 + k];
+        GS[r * KP + k] = v;
+      }
+      for (int i = tid; i < 128 * KC; i += 256) {
+        const int r = i >> 5, k = i & 31;
+        float v = 0.f;
+        if (k0 + k < Q && pt * 128 + r < P) v = W[(size_t)(pt * 128 + r) * Q + k0 + k];
+        WS[r * KP + k] = v;
+      }
+      __syncthreads();
+#pragma unroll 4
+      for (int k = 0; k < KC; k += 2) {
+        const int kk = k + (lane >> 5);
+        const float bv = WS[(32 * w + (lane & 31)) * KP + kk];
+        const float a0 = GS[(lane & 31) * KP + kk];
+        const float a1 = GS[(32 + (lane & 31)) * KP + kk];
+        acc[0] = mfma32(a0, bv, acc[0]);
+        acc[1] = mfma32(a1, bv, acc[1]);
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int i = 32 * ib + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (rid[i] >= 0 && pt * 128 + 32 * w + (lane & 31) < P) {
+          float* o = &ActOut[(size_t)rid[i] * ldo + pt * 128 + 32 * w + (lane & 31)];
+          *o = (*o > 0.f) ? acc[ib][r] : 0.f;
+        }
+      }
+  }
+}
+
+__global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+__global__ void fill_int_kernel(int* __restrict__ p, size_t n, int v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+struct Dw1Params {
+  EnvParams env;
+  int H1, B;
+  const uint8_t* actions;
+  const int* length;
+  const int8_t* term;
+  const float* g1;  // rows t*B + b, H1 floats
+  float *dW1, *db1;
+};
+
+// One workgroup per trajectory.  The set of active one-hot rows changes by one swap per transition, so
+// with the running prefix P_t = sum_{t' < t} g1_{t'} a row active on steps [t_in, t_out) receives
+// P_{t_out} - P_{t_in}: each swap adds +P to the row that leaves and -P to the row that enters, and the
+// rows still active at the last evaluated state receive the full sum, which is also the bias gradient.
+template <int ENV>
+__global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
+  __shared__ int rold[256], rnew[256], rend[kMaxStateDim];
+  __shared__ int8_t st[kMaxStateDim];
+  const EnvParams& e = p.env;
+  const int b = blockIdx.x, tid = threadIdx.x, H1 = p.H1, B = p.B;
+  const int len = p.length[b];
+  if (len <= 0) return;
+  if (tid == 0) {
+    for (int s = 0; s < e.state_dim; ++s) st[s] = 0;
+    for (int t = 0; t + 1 < len; ++t) {
+      const int a = p.actions[(size_t)t * B + b];
+      if (ENV == 0) {
+        rold[t] = e.H * a + st[a];
+        rnew[t] = e.H * a + st[a] + 1;
+        st[a] += 1;
+      } else if (ENV == 1) {
+        rold[t] = ((1 << e.k_bits) + 1) * t + (1 << e.k_bits);
+        rnew[t] = ((1 << e.k_bits) + 1) * t + a;
+      } else {
+        rold[t] = 3 * (a >> 1) + 1;
+        rnew[t] = 3 * (a >> 1) + 1 + 2 * (a & 1) - 1;
+        st[a >> 1] = (int8_t)(2 * (a & 1) - 1);
+      }
+    }
+    // rows active in the last evaluated state s_{len-1}
+    for (int s = 0; s < e.state_dim; ++s) {
+      if (ENV == 0) rend[s] = e.H * s + st[s];
+      else if (ENV == 1) rend[s] = ((1 << e.k_bits) + 1) * s + (s < len - 1 ? (int)p.actions[(size_t)s * B + b] : (1 << e.k_bits));
+      else rend[s] = 3 * s + 1 + st[s];
+    }
+  }
+  __syncthreads();
+  for (int f = tid; f < H1; f += 256) {
+    float P = 0.f;
+    for (int t = 0; t < len; ++t) {
+      P += p.g1[((size_t)t * B + b) * H1 + f];
+      if (t + 1 < len) {
+        atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], P);
+        atomicAdd(&p.dW1[(size_t)rnew[t] * H1 + f], -P);
+      }
+    }
+    for (int s = 0; s < e.state_dim; ++s) atomicAdd(&p.dW1[(size_t)rend[s] * H1 + f], P);
+    atomicAdd(&p.db1[f], P);
+  }
+}
+
+}  // namespace gfnx

@@ -1,0 +1,394 @@
+// Persistent trajectory-block rollout kernel.
+//
+// One workgroup (4 wavefronts) owns kSlots = 16 trajectories from s_0 to their terminal states.  Per step:
+//   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1),
+//       the four waves split the output features; weights stream from L2 cache in MFMA operand order,
+//       activations come from LDS;
+//   L3  logits the same way (output tiles split over the waves, or the contraction split when there
+//       are fewer than four tiles);
+//   S   per slot, 16 lanes: action mask, log-softmax, Philox + Gumbel-max argmax (wave shuffles),
+//       environment transition, log P_F / log P_B accumulation, terminal log-reward, action byte;
+//   U   layer 1 is a one-hot gather, and a transition swaps exactly one active row, so the
+//       pre-activation z1 is kept in LDS and updated as z1 += W1[new] - W1[old].
+// The post-ReLU activations h1, h2 and the logit-gradient direction (onehot(a) - p) of every transition
+// are written to HBM rows t*B + b for the gradient pass.
+#pragma once
+#include "gfnx_device.h"
+
+namespace gfnx {
+
+template <int ENV>
+__device__ __forceinline__ int initial_row(const EnvParams& e, int s) {
+  if (ENV == 0) return e.H * s;
+  if (ENV == 1) return ((1 << e.k_bits) + 1) * s + (1 << e.k_bits);
+  return 3 * s + 1;
+}
+
+// k-bit chunk `pos` of packed mode string m (string bit i sits in bit i%32 of word i/32)
+__device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words, int m, int pos, int k) {
+  const int s = k * pos;
+  const int wd = s >> 5;
+  uint64_t v = modes[(size_t)m * words + wd];
+  if (wd + 1 < words) v |= (uint64_t)modes[(size_t)m * words + wd + 1] << 32;
+  return (uint32_t)(v >> (s & 31)) & ((1u << k) - 1u);
+}
+
+template <int ENV, bool REPLAY, int NTW2>
+__global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
+  extern __shared__ float smem[];
+  const EnvParams& e = p.env;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int g = lane >> 4, j16 = lane & 15;
+  const int H1 = p.H1, H2 = p.H2, A = p.A, A16 = p.A16, B = p.B;
+  const int Q1 = H1 >> 4, Q2 = H2 >> 4;
+  const int NT3 = A16 >> 4, nchunk = A16 >> 2;
+  const int ksplit = NT3 >= 4 ? 1 : 4;
+
+  float* z1s = smem;
+  float* h2s = z1s + (H1 >> 2) * kPitch;
+  float* lgs = h2s + (H2 >> 2) * kPitch;
+  int* rowold = (int*)(lgs + ksplit * nchunk * kPitch);
+  int* rownew = rowold + kSlots;
+  int* alive = rownew + kSlots;
+  int8_t* st = (int8_t*)(alive + kSlots);
+
+  const int b0 = blockIdx.x * kSlots;
+  // roles in the sampling phase: 16 lanes (sub-lane si) per slot sj
+  const int sj = 4 * w + g, si = j16;
+  const int sb = b0 + sj;
+
+  // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows (increasing row order)
+  for (int f = tid; f < H1; f += 256) {
+    float z = p.b1[f];
+    for (int s = 0; s < e.state_dim; ++s) z += p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
+    float* dst = z1s + (f >> 2) * kPitch + (f & 3);
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) dst[j * 4] = z;
+  }
+  for (int i = tid; i < e.state_dim * kSlots; i += 256) st[i] = 0;
+  if (tid < kSlots) alive[tid] = (b0 + tid < B) ? 1 : 0;
+  float lpf = 0.f, lpb = 0.f;
+  int len_given = 0;
+  if (REPLAY && sb < B) len_given = p.length[sb];
+  __syncthreads();
+
+  for (int t = 0; t < e.max_steps; ++t) {
+    // ================= L2: h2 = relu(W2^T relu(z1) + b2)
+    for (int jj = w; jj < kSlots; jj += 4) {
+      if (!alive[jj]) continue;
+      float* dst = p.h1buf + ((size_t)t * B + b0 + jj) * H1;
+      for (int fg = lane; fg < (H1 >> 2); fg += 64) {
+        f32x4 v = *(const f32x4*)&z1s[fg * kPitch + jj * 4];
+        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+        *(f32x4*)&dst[fg * 4] = v;
+      }
+    }
+    {
+      f32x4 acc[NTW2];
+#pragma unroll
+      for (int n = 0; n < NTW2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * NTW2) * Q1 * 64 + lane;
+
+      for (int q = 0; q < Q1; ++q) {
+        f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
+        bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+#pragma unroll
+        for (int n = 0; n < NTW2; ++n) {
+          const f32x4 av = wp[((size_t)n * Q1 + q) * 64];
+          acc[n] = mfma16(av.x, bv.x, acc[n]);
+          acc[n] = mfma16(av.y, bv.y, acc[n]);
+          acc[n] = mfma16(av.z, bv.z, acc[n]);
+          acc[n] = mfma16(av.w, bv.w, acc[n]);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < NTW2; ++n) {
+        const int nt = w * NTW2 + n;
+        const f32x4 bias = *(const f32x4*)&p.b2[16 * nt + 4 * g];
+        f32x4 v = acc[n] + bias;
+        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+        *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = v;
+      }
+    }
+    __syncthreads();
+
+    // ================= L3: logits = W3^T h2 (+ b3 added in S)
+    for (int jj = w; jj < kSlots; jj += 4) {
+      if (!alive[jj]) continue;
+      float* dst = p.h2buf + ((size_t)t * B + b0 + jj) * H2;
+      for (int fg = lane; fg < (H2 >> 2); fg += 64)
+        *(f32x4*)&dst[fg * 4] = *(const f32x4*)&h2s[fg * kPitch + jj * 4];
+    }
+    if (ksplit == 1) {
+      f32x4 acc[4];
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const f32x4* wp = (const f32x4*)p.W3p + lane;
+
+      for (int q = 0; q < Q2; ++q) {
+        const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          const int nt = w + 4 * n;
+          if (nt < NT3) {
+            const f32x4 av = wp[((size_t)nt * Q2 + q) * 64];
+            acc[n] = mfma16(av.x, bv.x, acc[n]);
+            acc[n] = mfma16(av.y, bv.y, acc[n]);
+            acc[n] = mfma16(av.z, bv.z, acc[n]);
+            acc[n] = mfma16(av.w, bv.w, acc[n]);
+          }
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const int nt = w + 4 * n;
+        if (nt < NT3) *(f32x4*)&lgs[(4 * nt + g) * kPitch + j16 * 4] = acc[n];
+      }
+    } else {
+      f32x4 acc[3];
+#pragma unroll
+      for (int n = 0; n < 3; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const f32x4* wp = (const f32x4*)p.W3p + lane;
+      const int qn = Q2 >> 2;
+      for (int q = w * qn; q < (w + 1) * qn; ++q) {
+        const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+#pragma unroll
+        for (int n = 0; n < 3; ++n) {
+          if (n < NT3) {
+            const f32x4 av = wp[((size_t)n * Q2 + q) * 64];
+            acc[n] = mfma16(av.x, bv.x, acc[n]);
+            acc[n] = mfma16(av.y, bv.y, acc[n]);
+            acc[n] = mfma16(av.z, bv.z, acc[n]);
+            acc[n] = mfma16(av.w, bv.w, acc[n]);
+          }
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < 3; ++n)
+        if (n < NT3) *(f32x4*)&lgs[(w * nchunk + 4 * n + g) * kPitch + j16 * 4] = acc[n];
+    }
+    __syncthreads();
+
+    // ================= S: mask, log-softmax, sample, transition (16 lanes per slot)
+    if (alive[sj]) {
+      f32x4 lg[4];
+      uint32_t vm[4];
+      float m = -INFINITY;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const int c = si + 16 * n;
+        vm[n] = 0;
+        lg[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (c < nchunk) {
+          f32x4 v;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = (4 * c + k < A) ? p.b3[4 * c + k] : 0.f;
+          for (int ks = 0; ks < ksplit; ++ks) v += *(const f32x4*)&lgs[(ks * nchunk + c) * kPitch + sj * 4];
+          lg[n] = v;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            // branch-free: state bytes are read at a clamped index and combined with bitwise logic
+            const int a = 4 * c + k;
+            uint32_t ok;
+            if (ENV == 0) {
+              const int sv = st[min(a, e.d - 1) * kSlots + sj];
+              ok = (uint32_t)(a == e.d) | ((uint32_t)(a < e.d) & (uint32_t)(sv < e.H - 1));
+            } else if (ENV == 1) {
+              ok = (uint32_t)(a < A);
+            } else {
+              const int sv = st[min(a >> 1, e.D - 1) * kSlots + sj];
+              ok = (uint32_t)(a < A) & (uint32_t)(sv == 0);
+            }
+            vm[n] |= ok << k;
+            m = ok ? fmaxf(m, v[k]) : m;
+          }
+        }
+      }
+      m = row16_max(m);
+      float sum = 0.f;
+#pragma unroll
+      for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if ((vm[n] >> k) & 1u) sum += expf(lg[n][k] - m);
+      sum = row16_sum(sum);
+      const float lse = logf(sum);
+
+      int act;
+      float alogit;
+      if (!REPLAY) {
+        float best = -INFINITY, blog = 0.f;
+        int bidx = 0x7fffffff;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          const int c = si + 16 * n;
+          if (vm[n]) {
+            uint32_t wd[4];
+            philox4x32_10((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              if ((vm[n] >> k) & 1u) {
+                const float pert = lg[n][k] + gumbel_from_bits(wd[k]);
+                if (pert > best) { best = pert; bidx = 4 * c + k; blog = lg[n][k]; }
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+          const float ob = __shfl_xor(best, o, 16), ol = __shfl_xor(blog, o, 16);
+          const int oi = __shfl_xor(bidx, o, 16);
+          if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; blog = ol; }
+        }
+        act = bidx;
+        alogit = blog;
+      } else {
+        act = p.actions[(size_t)t * B + sb];
+        float mine = 0.f;
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (4 * (si + 16 * n) + k == act) mine = lg[n][k];
+        alogit = __shfl(mine, (act >> 2) & 15, 16);
+      }
+      lpf += (alogit - m) - lse;
+
+      {  // direction of the logit gradient: onehot(a) - p on valid actions, 0 elsewhere
+        float* erow = p.ebuf + ((size_t)t * B + sb) * A16;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          const int c = si + 16 * n;
+          if (c < nchunk) {
+            f32x4 ev;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              ev[k] = ((vm[n] >> k) & 1u) ? ((4 * c + k == act ? 1.f : 0.f) - expf((lg[n][k] - m) - lse)) : 0.f;
+            *(f32x4*)&erow[4 * c] = ev;
+          }
+        }
+      }
+
+      bool term = false;
+      float logr = 0.f;
+      int xi = 0;           // grid: this lane's coordinate after the step
+      int site = 0, spin = 0;  // ising
+      if (ENV == 0) {
+        xi = (si < e.d) ? st[si * kSlots + sj] : 0;
+        if (act != e.d) {
+          if (si == act) {
+            rowold[sj] = e.H * act + xi;
+            rownew[sj] = e.H * act + xi + 1;
+            st[si * kSlots + sj] = (int8_t)(xi + 1);
+            xi += 1;
+          }
+          const int cnt = row16_sum((si < e.d && xi > 0) ? 1 : 0);
+          lpb -= logf((float)cnt);
+        } else {
+          const float v = fabsf((float)xi / (float)(e.H - 1) - 0.5f);
+          const int bad1 = row16_sum((si < e.d && !(0.25f < v)) ? 1 : 0);
+          const int bad2 = row16_sum((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
+          const float r = e.r0 + e.r1 * (bad1 == 0 ? 1.f : 0.f) + e.r2 * (bad2 == 0 ? 1.f : 0.f);
+          logr = logf(r);
+          term = true;
+        }
+      } else if (ENV == 1) {
+        const int k = e.k_bits;
+        if (si == 0) {
+          st[t * kSlots + sj] = (int8_t)act;
+          rowold[sj] = ((1 << k) + 1) * t + (1 << k);
+          rownew[sj] = ((1 << k) + 1) * t + act;
+        }
+        if (t == e.L - 1) {
+          int dmin = 0x7fffffff;
+          for (int mm = si; mm < e.n_modes; mm += 16) {
+            int dist = 0;
+            for (int pos = 0; pos < e.L; ++pos) {
+              const uint32_t tok = (pos == t) ? (uint32_t)act : (uint32_t)(uint8_t)st[pos * kSlots + sj];
+              const uint32_t rev = __brev(tok) >> (32 - k);
+              dist += __popc(rev ^ mode_chunk(e.modes, e.words, mm, pos, k));
+            }
+            dmin = min(dmin, dist);
+          }
+          dmin = row16_min(dmin);
+          logr = -(e.beta / (float)e.n_bits) * (float)dmin;
+          term = true;
+        }
+      } else {
+        site = act >> 1;
+        spin = 2 * (act & 1) - 1;
+        if (si == 0) {
+          st[site * kSlots + sj] = (int8_t)spin;
+          rowold[sj] = 3 * site + 1;
+          rownew[sj] = 3 * site + 1 + spin;
+        }
+        lpb -= logf((float)(t + 1));
+        if (t == e.D - 1) {
+          int acc = 0;
+          for (int s = si; s < e.D; s += 16) {
+            const int r = s / e.N, c = s - r * e.N;
+            const int sr = r * e.N + (c + 1 == e.N ? 0 : c + 1);
+            const int sd = (r + 1 == e.N ? 0 : r + 1) * e.N + c;
+            const int x = (s == site) ? spin : st[s * kSlots + sj];
+            const int xr = (sr == site) ? spin : st[sr * kSlots + sj];
+            const int xd = (sd == site) ? spin : st[sd * kSlots + sj];
+            acc += x * (xr + xd);
+          }
+          acc = row16_sum(acc);
+          logr = e.coupling * (float)acc;
+          term = true;
+        }
+      }
+      if (REPLAY) term = term || (t + 1 >= len_given);
+      if (!REPLAY && si == 0) p.actions[(size_t)t * B + sb] = (uint8_t)act;
+      if (term) {
+        if (si == 0) {
+          if (!REPLAY) p.length[sb] = t + 1;
+          p.lpf[sb] = lpf;
+          p.lpb[sb] = lpb;
+          p.logr[sb] = logr;
+          alive[sj] = 0;
+        }
+        for (int s = si; s < e.state_dim; s += 16) {
+          int v;
+          if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
+          else if (ENV == 1) v = (s == t) ? act : (int)(uint8_t)st[s * kSlots + sj];
+          else v = (s == site) ? spin : st[s * kSlots + sj];
+          p.term[(size_t)s * B + sb] = (int8_t)v;
+        }
+        if (!REPLAY)
+          for (int tt = t + 1 + si; tt < p.T; tt += 16) p.actions[(size_t)tt * B + sb] = 0xFF;
+      }
+    }
+    __syncthreads();
+
+    // ================= U: z1 += W1[new row] - W1[old row] for the slots that go on
+    for (int i = tid; i < (H1 >> 2) * kSlots; i += 256) {
+      const int fg = i >> 4, jj = i & 15;
+      if (alive[jj]) {
+        f32x4* zp = (f32x4*)&z1s[fg * kPitch + jj * 4];
+        const f32x4 wo = *(const f32x4*)&p.W1[(size_t)rowold[jj] * H1 + 4 * fg];
+        const f32x4 wn = *(const f32x4*)&p.W1[(size_t)rownew[jj] * H1 + 4 * fg];
+        *zp = (*zp - wo) + wn;
+      }
+    }
+    const int any = __syncthreads_or(tid < kSlots ? alive[tid] : 0);
+    if (!any) break;
+  }
+}
+
+// W[K][N] row-major -> MFMA A-operand order: out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
+// zero beyond column N.
+__global__ void pack_weights_kernel(const float* __restrict__ W, int K, int N, int NT, float* __restrict__ out) {
+  const int Q = K >> 4;
+  const size_t total = (size_t)NT * Q * 256;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int s = (int)(i & 3), ln = (int)((i >> 2) & 63);
+    const size_t r = i >> 8;
+    const int q = (int)(r % Q), nt = (int)(r / Q);
+    const int k = 16 * q + 4 * (ln >> 4) + s, n = 16 * nt + (ln & 15);
+    out[i] = n < N ? W[(size_t)k * N + n] : 0.f;
+  }
+}
+
+}  // namespace gfnx

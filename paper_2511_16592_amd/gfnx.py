@@ -1,0 +1,180 @@
+"""Thin ctypes binding over libgfnx_hip.so (declared in include/gfnx.h).
+
+Argument marshalling only: every step of the rollout and of the Trajectory-Balance gradient runs in
+the HIP kernels of the library.  PyTorch is used for device memory and the stream, nothing else.  The
+library is loaded on first use and a missing library is an error: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
+
+GFNX_OK = 0
+EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
+           "gfnx_status_string")
+
+
+class EnvDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("grid_dim", C.c_int32), ("grid_side", C.c_int32),
+                ("r0", C.c_float), ("r1", C.c_float), ("r2", C.c_float),
+                ("n_bits", C.c_int32), ("k_bits", C.c_int32), ("n_modes", C.c_int32),
+                ("modes_dev", C.c_void_p), ("beta", C.c_float),
+                ("lattice_n", C.c_int32), ("coupling", C.c_float)]
+
+
+class Mlp(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("h1", C.c_int32), ("h2", C.c_int32), ("n_actions", C.c_int32),
+                ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("W3", C.c_void_p), ("b3", C.c_void_p)]
+
+
+class MlpGrad(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dW1", "db1", "dW2", "db2", "dW3", "db3")]
+
+
+class Traj(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("max_steps", C.c_int32), ("actions", C.c_void_p), ("length", C.c_void_p),
+                ("terminal_state", C.c_void_p), ("log_pf", C.c_void_p), ("log_pb", C.c_void_p),
+                ("log_reward", C.c_void_p)]
+
+
+class GfnxError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{message} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libgfnx_hip.so; raises if it has not been built (run __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; "
+                                    f"g.build()'`; there is no fallback path")
+        lib = C.CDLL(LIB_PATH)
+        lib.gfnx_env_dims.restype = C.c_int
+        lib.gfnx_env_dims.argtypes = [C.POINTER(EnvDesc)] + [C.POINTER(C.c_int32)] * 4
+        lib.gfnx_workspace_bytes.restype = C.c_size_t
+        lib.gfnx_workspace_bytes.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_int32]
+        lib.gfnx_rollout.restype = C.c_int
+        lib.gfnx_rollout.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_uint64, C.c_uint64, C.POINTER(Traj),
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_replay.restype = C.c_int
+        lib.gfnx_replay.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_void_p, C.c_size_t,
+                                    C.c_void_p]
+        lib.gfnx_tb_loss_grad.restype = C.c_int
+        lib.gfnx_tb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
+                                          C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_status_string.restype = C.c_char_p
+        lib.gfnx_status_string.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().gfnx_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != GFNX_OK:
+        raise GfnxError(status, status_string(status))
+
+
+def env_desc(env, modes_dev_ptr: Optional[int] = None) -> EnvDesc:
+    """C descriptor from a workloads.EnvSpec; modes_dev_ptr is the device address of the packed modes."""
+    return EnvDesc(env.kind, env.grid_dim, env.grid_side, env.r0, env.r1, env.r2, env.n_bits, env.k_bits,
+                   env.n_modes, modes_dev_ptr, env.beta, env.lattice_n, env.coupling)
+
+
+def env_dims(env):
+    out = [C.c_int32() for _ in range(4)]
+    d = env if isinstance(env, EnvDesc) else env_desc(env)
+    _check(load_library().gfnx_env_dims(C.byref(d), *[C.byref(o) for o in out]))
+    return tuple(o.value for o in out)
+
+
+def _ptr(t) -> int:
+    return int(t.data_ptr())
+
+
+class Session:
+    """Device buffers for one (environment, network, batch) and the calls of the C ABI on them."""
+
+    def __init__(self, env, weights: Dict, batch: int, device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        self.env, self.batch, self.device = env, int(batch), torch.device(device)
+        self.state_dim, self.obs_dim, self.n_actions, self.max_steps = env.dims()
+        dev = self.device
+        self.modes = None
+        if env.modes is not None:
+            import numpy as np
+            self.modes = torch.from_numpy(np.ascontiguousarray(env.modes, dtype=np.uint32).view(np.int32)).to(dev)
+        self.desc = env_desc(env, None if self.modes is None else _ptr(self.modes))
+        self.w = {k: torch.as_tensor(v, dtype=torch.float32).contiguous().to(dev) for k, v in weights.items()}
+        self.mlp = Mlp(self.w["W1"].shape[0], self.w["W1"].shape[1], self.w["W2"].shape[1], self.w["W3"].shape[1],
+                       *[_ptr(self.w[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")])
+        T, B = self.max_steps, self.batch
+        self.actions = torch.empty((T, B), dtype=torch.uint8, device=dev)
+        self.length = torch.empty(B, dtype=torch.int32, device=dev)
+        self.terminal_state = torch.empty((self.state_dim, B), dtype=torch.int8, device=dev)
+        self.log_pf = torch.empty(B, dtype=torch.float32, device=dev)
+        self.log_pb = torch.empty(B, dtype=torch.float32, device=dev)
+        self.log_reward = torch.empty(B, dtype=torch.float32, device=dev)
+        self.traj = Traj(B, T, _ptr(self.actions), _ptr(self.length), _ptr(self.terminal_state), _ptr(self.log_pf),
+                         _ptr(self.log_pb), _ptr(self.log_reward))
+        self.grads = {"d" + k: torch.empty_like(v) for k, v in self.w.items()}
+        self.cgrads = MlpGrad(*[_ptr(self.grads[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.dlogz = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.workspace_bytes = int(self.lib.gfnx_workspace_bytes(C.byref(self.desc), C.byref(self.mlp), B))
+        if self.workspace_bytes == 0:
+            raise GfnxError(-3, "gfnx_workspace_bytes rejected the configuration")
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+        assert _ptr(self.workspace) % 256 == 0
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def set_weights(self, weights: Dict) -> None:
+        for k, v in weights.items():
+            self.w[k].copy_(self.torch.as_tensor(v, dtype=self.torch.float32))
+
+    def rollout(self, seed: int, iteration: int) -> None:
+        _check(self.lib.gfnx_rollout(C.byref(self.desc), C.byref(self.mlp), seed, iteration, C.byref(self.traj),
+                                     _ptr(self.workspace), self.workspace_bytes, self._stream()))
+
+    def replay(self, actions, length) -> None:
+        """Teacher-forced pass along the given host arrays actions [T, B] (uint8) and length [B]."""
+        torch = self.torch
+        self.actions.copy_(torch.as_tensor(actions, dtype=torch.uint8))
+        self.length.copy_(torch.as_tensor(length, dtype=torch.int32))
+        _check(self.lib.gfnx_replay(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), _ptr(self.workspace),
+                                    self.workspace_bytes, self._stream()))
+
+    def tb_loss_grad(self, log_z: float = 0.0) -> None:
+        _check(self.lib.gfnx_tb_loss_grad(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), float(log_z),
+                                          _ptr(self.loss), _ptr(self.dlogz), C.byref(self.cgrads),
+                                          _ptr(self.workspace), self.workspace_bytes, self._stream()))
+
+    def trajectories(self) -> Dict:
+        """Host copies (numpy) of the trajectory arrays."""
+        self.torch.cuda.synchronize(self.device)
+        return dict(actions=self.actions.cpu().numpy(), length=self.length.cpu().numpy(),
+                    terminal_state=self.terminal_state.cpu().numpy(), log_pf=self.log_pf.cpu().numpy(),
+                    log_pb=self.log_pb.cpu().numpy(), log_reward=self.log_reward.cpu().numpy())
+
+    def gradients(self) -> Dict:
+        self.torch.cuda.synchronize(self.device)
+        out = {k: v.cpu().numpy() for k, v in self.grads.items()}
+        out["loss"] = float(self.loss.item())
+        out["dlogz"] = float(self.dlogz.item())
+        return out

@@ -1,0 +1,105 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol,
+and validates its arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_16592_amd import gfnx
+from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(gfnx.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return gfnx.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "gfnx.h")).read()
+    declared = set(re.findall(r"\b(gfnx_[a-z_]+)\s*\(", header))
+    assert declared == set(gfnx.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_env_dims_of_the_five_configurations(lib):
+    expect = {"c1": (2, 16, 3, 15), "c2": (4, 80, 5, 77), "c3": (15, 3855, 256, 15),
+              "c4": (100, 300, 200, 100), "c5": (10, 200, 11, 191)}
+    for name, dims in expect.items():
+        assert gfnx.env_dims(workloads()[name].env) == dims
+
+
+def test_status_strings(lib):
+    assert gfnx.status_string(0) == "GFNX_OK"
+    for code in range(-6, 0):
+        assert gfnx.status_string(code).startswith("GFNX_E_")
+
+
+def _mlp(in_dim, h1, h2, a, ptr=0x1000):
+    return gfnx.Mlp(in_dim, h1, h2, a, ptr, ptr, ptr, ptr, ptr, ptr)
+
+
+def _traj(batch, steps, ptr=0x1000):
+    return gfnx.Traj(batch, steps, ptr, ptr, ptr, ptr, ptr, ptr)
+
+
+def test_bad_environment_descriptors(lib):
+    bad = [grid_env(0, 8), grid_env(17, 8), grid_env(2, 1), grid_env(2, 200), ising_env(2), ising_env(11),
+           bitseq_env(120, 7, 4, 1), bitseq_env(120, 8, 4, 1)]
+    for i, env in enumerate(bad):
+        d = gfnx.env_desc(env, 0x1000)
+        if i == len(bad) - 1:
+            d.kind = 7
+        out = C.c_int32()
+        assert lib.gfnx_env_dims(C.byref(d), C.byref(out), None, None, None) == -2
+    assert lib.gfnx_env_dims(None, None, None, None, None) == -1
+
+
+def test_workspace_size_and_argument_validation(lib):
+    env = grid_env(2, 8)
+    d = gfnx.env_desc(env)
+    m = _mlp(16, 64, 64, 3)
+    need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 16)
+    assert need > 0 and need % 256 == 0
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 32) > need
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 64, 64, 4)), 16) == 0   # n_actions != env's
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(15, 64, 64, 3)), 16) == 0   # in_dim != obs_dim
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 48, 64, 3)), 16) == 0   # h1 not a multiple of 64
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 0) == 0
+    t = _traj(16, 15)
+    ws = 0x10000
+    call = lambda dd, mm, tt, w, n: lib.gfnx_rollout(dd, mm, 0, 0, tt, w, n, None)
+    assert call(None, C.byref(m), C.byref(t), ws, need) == -1
+    assert call(C.byref(d), None, C.byref(t), ws, need) == -1
+    assert call(C.byref(d), C.byref(m), None, ws, need) == -1
+    assert call(C.byref(d), C.byref(gfnx.Mlp(16, 64, 64, 3, 0, 0, 0, 0, 0, 0)), C.byref(t), ws, need) == -1
+    assert call(C.byref(d), C.byref(_mlp(16, 64, 64, 5)), C.byref(t), ws, need) == -3
+    assert call(C.byref(d), C.byref(_mlp(16, 64, 640, 3)), C.byref(t), ws, need) == -5
+    assert call(C.byref(d), C.byref(m), C.byref(_traj(16, 14)), ws, need) == -3          # max_steps too small
+    assert call(C.byref(d), C.byref(m), C.byref(_traj(0, 15)), ws, need) == -3
+    assert call(C.byref(d), C.byref(m), C.byref(gfnx.Traj(16, 15, 0, 0, 0, 0, 0, 0)), ws, need) == -1
+    assert call(C.byref(d), C.byref(m), C.byref(t), None, need) == -4
+    assert call(C.byref(d), C.byref(m), C.byref(t), ws + 4, need) == -4                  # misaligned
+    assert call(C.byref(d), C.byref(m), C.byref(t), ws, need - 1) == -4
+    bs = gfnx.env_desc(bitseq_env(120, 8, 60, 3), None)                                   # modes pointer missing
+    assert call(C.byref(bs), C.byref(_mlp(3855, 512, 512, 256)), C.byref(_traj(4, 15)), ws, 1 << 40) == -1
+    g = gfnx.MlpGrad(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0)
+    assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(m), C.byref(t), 0.0, 0x1000, 0x1000, C.byref(g), ws, need, None) == -1
+    assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(m), C.byref(t), 0.0, None, 0x1000, C.byref(g), ws, need, None) == -1
+    assert lib.gfnx_replay(C.byref(d), C.byref(m), C.byref(t), ws, need - 1, None) == -4
+
+
+def test_workspace_sizes_of_the_benchmark_configurations(lib):
+    gib = 1 << 30
+    for name, limit in (("c2", 2 * gib), ("c3", 1 * gib), ("c4", 4 * gib), ("c5", 20 * gib)):
+        wl = workloads()[name]
+        _, od, na, _ = wl.env.dims()
+        d = gfnx.env_desc(wl.env, 0x1000)
+        need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(od, wl.h1, wl.h2, na)), wl.batch)
+        assert 0 < need < limit, (name, need)

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU reference on the same seeded inputs.
+
+Bars (written out here):
+  * sampled actions, lengths and terminal states: bit-exact, except on steps where the reference's top-2
+    Gumbel-perturbed logits are closer than 1e-5 (either action is then accepted; the reference follows the
+    GPU's actions and counts such steps);
+  * log P_F, log P_B, log R: relative 1e-4 (absolute floor 1e-5) against the binary64 reference along the
+    GPU's own action sequence;
+  * loss and dloss/dlogZ: relative 1e-4 (floor 1e-6); each gradient tensor: max |diff| <= 1e-4 * max |ref| + 1e-7.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2511_16592_amd.workloads import (bitseq_env, grid_env, ising_env, random_mlp, workloads, xavier_mlp)
+from tests.helpers import (chi2_sf, enumerate_grid_trajectories, grid_reward, optimal_policy_mlp_2d,
+                           pack_trajectories)
+
+pytestmark = pytest.mark.gpu
+KEYS = ("dW1", "db1", "dW2", "db2", "dW3", "db3")
+NTHREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def gfnx():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2511_16592_amd import gfnx as g
+    g.load_library()  # raises if the HIP library is missing: no fallback
+    return g
+
+
+def padded_optimal_mlp(side):
+    """The proper policy of the 2-D grid as an MLP, its side^2 hidden units padded to the 64 the kernels need
+    (the extra units are dead: bias -1, zero weights)."""
+    w64, log_z = optimal_policy_mlp_2d(side)
+    n = side * side
+    w = dict(W1=np.zeros((2 * side, 64), np.float32), b1=-np.ones(64, np.float32),
+             W2=np.zeros((64, 64), np.float32), b2=np.zeros(64, np.float32),
+             W3=np.zeros((64, 3), np.float32), b3=np.zeros(3, np.float32))
+    w["W1"][:, :n] = w64["W1"]
+    w["W2"][:n, :n] = w64["W2"]
+    w["W3"][:n] = w64["W3"]
+    return w, log_z
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, free_run=True):
+    """Compares columns [b0, b1) of the GPU trajectories with the reference; returns number of near-tie steps."""
+    b1 = traj["length"].shape[0] if b1 is None else b1
+    acts = np.ascontiguousarray(traj["actions"][:, b0:b1])
+    length = np.ascontiguousarray(traj["length"][b0:b1])
+    sd, _, na, ms = env.dims()
+    assert (length >= 1).all() and (length <= ms).all()
+    rep = o32.replay(env, w, seed, iteration, acts, length, b_offset=b0, tie_tol=1e-5, nthreads=NTHREADS)
+    assert (rep["violations"] == 0).all(), "GPU action differs from the reference argmax beyond the 1e-5 margin"
+    clean = rep["near_ties"] == 0
+    assert clean.mean() > 0.99
+    assert (rep["terminal_state"] == traj["terminal_state"][:, b0:b1]).all()
+    for t in range(acts.shape[0]):  # padding after the end of each trajectory
+        pad = t >= length
+        if na <= 255:
+            assert (acts[t][pad] == 0xFF).all()
+    if free_run:
+        free = o32.rollout(env, w, seed, iteration, batch=b1 - b0, b_offset=b0, max_steps=acts.shape[0],
+                           nthreads=NTHREADS)
+        assert (free["length"][clean] == length[clean]).all()
+        assert (free["actions"][:, clean] == acts[:, clean]).all()
+        assert (free["terminal_state"][:, clean] == traj["terminal_state"][:, b0:b1][:, clean]).all()
+    ref = o64.replay(env, w, seed, iteration, acts, length, b_offset=b0, tie_tol=1e30, nthreads=NTHREADS)
+    for k in ("log_pf", "log_pb", "log_reward"):
+        got, want = traj[k][b0:b1].astype(np.float64), ref[k]
+        err = np.abs(got - want) - (1e-4 * np.abs(want) + 1e-5)
+        assert (err <= 0).all(), (k, float(err.max()))
+    return int(rep["near_ties"].sum())
+
+
+def check_gradients(o64, env, w, traj, grads, log_z):
+    g = o64.tb_loss_grad(env, w, traj["actions"], traj["length"], log_z, nthreads=NTHREADS)
+    assert abs(grads["loss"] - g["loss"]) <= 1e-4 * abs(g["loss"]) + 1e-6, (grads["loss"], g["loss"])
+    assert abs(grads["dlogz"] - g["dlogz"]) <= 1e-4 * abs(g["dlogz"]) + 1e-6, (grads["dlogz"], g["dlogz"])
+    for k in KEYS:
+        scale = np.abs(g[k]).max()
+        err = np.abs(grads[k].astype(np.float64) - g[k]).max()
+        assert err <= 1e-4 * scale + 1e-7, (k, float(err), float(scale))
+    return g
+
+
+def run_case(gfnx, o32, o64, env, w, batch, seed, iteration, log_z, name, free_run=True):
+    say(f"[case {name}] batch={batch} seed={seed} iteration={iteration}")
+    sess = gfnx.Session(env, w, batch)
+    sess.rollout(seed, iteration)
+    sess.tb_loss_grad(log_z)
+    traj, grads = sess.trajectories(), sess.gradients()
+    ties = check_trajectories(o32, o64, env, w, seed, iteration, traj, free_run=free_run)
+    check_gradients(o64, env, w, traj, grads, log_z)
+    say(f"[case {name}] ok: {int(traj['length'].sum())} transitions, {ties} near-tie steps, loss {grads['loss']:.6g}")
+    return sess, traj, grads
+
+
+# ------------------------------------------------------------------ small cases: several tiles, ragged tails
+def test_c1_grid_2d_side8(gfnx, oracle32, oracle64):
+    wl = workloads()["c1"]
+    run_case(gfnx, oracle32, oracle64, wl.env, wl.mlp(), wl.batch, wl.seed, 0, wl.log_z, "c1")
+
+
+@pytest.mark.parametrize("batch", [1, 37, 200])
+def test_grid_ragged_batches(gfnx, oracle32, oracle64, batch):
+    env = grid_env(3, 5)
+    w = random_mlp(15, 64, 128, 4, seed=31, scale=2.0)
+    run_case(gfnx, oracle32, oracle64, env, w, batch, seed=9, iteration=4, log_z=0.7, name=f"grid3x5_b{batch}")
+
+
+def test_grid_long_walks(gfnx, oracle32, oracle64):
+    """Stop bias -8: trajectories run to the far corner (maximum length d*(H-1)+1 occurs)."""
+    env = grid_env(2, 8)
+    w = xavier_mlp(16, 64, 64, 3, seed=1)
+    w["b3"][2] = -8.0
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, 50, seed=1, iteration=0, log_z=0.0, name="grid_long")
+    assert traj["length"].max() >= 14
+
+
+def test_bitseq_small(gfnx, oracle32, oracle64):
+    env = bitseq_env(24, 4, 7, mode_seed=2)
+    w = random_mlp(6 * 17, 64, 64, 16, seed=32, scale=2.0)
+    run_case(gfnx, oracle32, oracle64, env, w, 45, seed=5, iteration=1, log_z=-0.3, name="bitseq24")
+
+
+def test_bitseq_odd_token_width(gfnx, oracle32, oracle64):
+    """k=3: token chunks straddle the 32-bit words of the packed modes."""
+    env = bitseq_env(72, 3, 5, mode_seed=4, uniform_bits=True)
+    w = random_mlp(24 * 9, 64, 64, 8, seed=33, scale=2.0)
+    run_case(gfnx, oracle32, oracle64, env, w, 20, seed=6, iteration=0, log_z=0.0, name="bitseq72k3")
+
+
+@pytest.mark.parametrize("n", [3, 5])
+def test_ising_small(gfnx, oracle32, oracle64, n):
+    env = ising_env(n)
+    w = random_mlp(3 * n * n, 64, 64, 2 * n * n, seed=34, scale=2.0)
+    run_case(gfnx, oracle32, oracle64, env, w, 33, seed=7, iteration=2, log_z=1.5, name=f"ising{n}")
+
+
+def test_different_hidden_widths(gfnx, oracle32, oracle64):
+    env = grid_env(4, 6)
+    w = random_mlp(24, 192, 320, 5, seed=35, scale=1.5)
+    run_case(gfnx, oracle32, oracle64, env, w, 70, seed=8, iteration=3, log_z=0.2, name="grid_h192_320")
+
+
+def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
+    wl = workloads()["c1"]
+    w = wl.mlp()
+    a = gfnx.Session(wl.env, w, 64)
+    a.rollout(3, 5)
+    ta = a.trajectories()
+    a.rollout(3, 5)
+    tb = a.trajectories()
+    for k in ta:
+        assert (ta[k] == tb[k]).all()
+    small = gfnx.Session(wl.env, w, 20)  # trajectory b depends on (seed, iteration, b) only
+    small.rollout(3, 5)
+    ts = small.trajectories()
+    assert (ts["actions"] == ta["actions"][:, :20]).all()
+    assert (ts["log_pf"] == ta["log_pf"][:20]).all()
+    a.rollout(3, 6)
+    assert (a.trajectories()["actions"] != ta["actions"]).any()
+
+
+# ------------------------------------------------------------------ teacher-forced pass and the DP-optimal policy
+def test_replay_of_all_trajectories_and_optimal_policy(gfnx, oracle64):
+    """All 69 complete trajectories of the 2-D side-4 grid, teacher-forced: with the proper forward policy
+    (embedded in an MLP) every TB residual is zero, so loss and all gradients vanish; sum_tau P_F(tau) = 1."""
+    side = 4
+    env = grid_env(2, side)
+    trajs = enumerate_grid_trajectories(2, side)
+    actions, length = pack_trajectories(trajs, 7)
+    w, log_z = padded_optimal_mlp(side)
+    sess = gfnx.Session(env, w, len(trajs))
+    sess.replay(actions, length)
+    sess.tb_loss_grad(log_z)
+    traj, grads = sess.trajectories(), sess.gradients()
+    assert abs(np.exp(traj["log_pf"].astype(np.float64)).sum() - 1.0) < 1e-5
+    delta = log_z + traj["log_pf"] - traj["log_reward"] - traj["log_pb"]
+    assert np.abs(delta).max() < 5e-6
+    assert grads["loss"] < 1e-10 and abs(grads["dlogz"]) < 1e-5
+    for k in KEYS:
+        assert np.abs(grads[k]).max() < 1e-5, k
+    for b, (_a, x) in enumerate(trajs):
+        assert tuple(traj["terminal_state"][:, b]) == x
+    # a random network on the same trajectories: full parity of scalars and gradients
+    wr = random_mlp(8, 64, 64, 3, seed=36, scale=3.0)
+    sess.set_weights(wr)
+    sess.replay(actions, length)
+    sess.tb_loss_grad(0.4)
+    traj, grads = sess.trajectories(), sess.gradients()
+    ref = oracle64.replay(env, wr, 0, 0, actions, length, tie_tol=1e30)
+    for k in ("log_pf", "log_pb", "log_reward"):
+        assert np.allclose(traj[k], ref[k], rtol=1e-4, atol=1e-5)
+    check_gradients(oracle64, env, wr, dict(actions=actions, length=length), grads, 0.4)
+
+
+def test_sampler_reaches_reward_distribution_on_gpu(gfnx):
+    """Sampling on the GPU with the proper policy gives terminal states ~ R/Z (chi-square, 16 states)."""
+    side = 4
+    env = grid_env(2, side)
+    w, _ = padded_optimal_mlp(side)
+    n = 65536
+    sess = gfnx.Session(env, w, n)
+    sess.rollout(4242, 0)
+    traj = sess.trajectories()
+    idx = traj["terminal_state"][0].astype(int) * side + traj["terminal_state"][1].astype(int)
+    counts = np.bincount(idx, minlength=16)
+    probs = np.array([grid_reward((i, j), side) for i in range(side) for j in range(side)]) / 2.016
+    stat = float(((counts - probs * n) ** 2 / (probs * n)).sum())
+    assert chi2_sf(stat, 15) > 1e-4
+    assert (traj["length"] == traj["terminal_state"].sum(0) + 1).all()
+
+
+# ------------------------------------------------------------------ full-size configurations (as benchmarked)
+def _full_size(gfnx, o32, o64, name, sample, full_grad, iteration=0):
+    wl = workloads()[name]
+    w = wl.mlp()
+    say(f"[full {name}] batch={wl.batch} seed={wl.seed} iteration={iteration}")
+    sess = gfnx.Session(wl.env, w, wl.batch)
+    sess.rollout(wl.seed, iteration)
+    sess.tb_loss_grad(wl.log_z)
+    traj, grads = sess.trajectories(), sess.gradients()
+    sd, _, na, ms = wl.env.dims()
+    assert (traj["length"] >= 1).all() and (traj["length"] <= ms).all()
+    ties = 0
+    for b0 in sample:  # contiguous column blocks, checked one by one against the reference
+        ties += check_trajectories(o32, o64, wl.env, w, wl.seed, iteration, traj, b0, min(b0 + 128, wl.batch))
+    # properties that hold at any size
+    delta = wl.log_z + traj["log_pf"].astype(np.float64) - traj["log_reward"] - traj["log_pb"]
+    assert abs(grads["loss"] - np.mean(delta ** 2)) <= 1e-4 * np.mean(delta ** 2) + 1e-6
+    assert abs(grads["dlogz"] - 2 * np.mean(delta)) <= 1e-4 * abs(2 * np.mean(delta)) + 1e-6
+    assert abs(grads["db3"].sum()) <= 1e-4 * np.abs(grads["db3"]).max() * na + 1e-7
+    if wl.env.kind == 2:
+        assert np.allclose(traj["log_pb"], -math.lgamma(sd + 1), rtol=1e-5)
+    if wl.env.kind == 1:
+        assert (traj["log_pb"] == 0).all() and (traj["length"] == ms).all()
+    if wl.env.kind == 0:
+        assert (traj["length"] == traj["terminal_state"].astype(int).sum(0) + 1).all()
+    if full_grad:
+        check_gradients(o64, wl.env, w, traj, grads, wl.log_z)
+    say(f"[full {name}] ok: {int(traj['length'].sum())} transitions, {ties} near-tie steps in the sample")
+
+
+def test_full_c2(gfnx, oracle32, oracle64):
+    _full_size(gfnx, oracle32, oracle64, "c2", sample=[0, 1931, 3968], full_grad=True)
+
+
+def test_full_c2_long_walk(gfnx, oracle32, oracle64):
+    _full_size(gfnx, oracle32, oracle64, "c2_long", sample=[512], full_grad=True)
+
+
+def test_full_c3(gfnx, oracle32, oracle64):
+    _full_size(gfnx, oracle32, oracle64, "c3", sample=[0, 3968], full_grad=True)
+
+
+def test_full_c4(gfnx, oracle32, oracle64):
+    _full_size(gfnx, oracle32, oracle64, "c4", sample=[0, 2048], full_grad=True)
+
+
+def test_full_c5(gfnx, oracle32, oracle64):
+    _full_size(gfnx, oracle32, oracle64, "c5", sample=[0, 7777, 16256], full_grad=True)
+
+
+def test_full_c5_long_walk(gfnx, oracle32, oracle64):
+    """3.1 M transitions: trajectories are checked on a sample; the gradient through the identities above
+    (the full reference gradient at this size takes minutes on the host) and through the reduced batch below."""
+    _full_size(gfnx, oracle32, oracle64, "c5_long", sample=[4096], full_grad=False)
+    wl = workloads()["c5_long"]
+    run_case(gfnx, oracle32, oracle64, wl.env, wl.mlp(), 256, wl.seed, 1, wl.log_z, "c5_long_b256", free_run=False)
