@@ -168,7 +168,7 @@ class Oracle:
 
     # ---- loss + gradient -------------------------------------------------------
     def tb_loss_grad(self, env, w, actions: np.ndarray, length: np.ndarray, log_z: float = 0.0,
-                     nthreads: int = 1) -> Dict[str, np.ndarray]:
+                     nthreads: int = 1, kink_tol: float = 0.0) -> Dict[str, np.ndarray]:
         e, _k1 = self._env(env)
         m, arrs = self._mlp(w)
         actions = np.ascontiguousarray(actions, dtype=np.uint8)
@@ -178,9 +178,13 @@ class Oracle:
         gs = _Grad(*[_ptr(g[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
         loss, dlogz = self.creal(), self.creal()
         delta = np.zeros(batch, dtype=self.real)
+        slack = np.zeros(6, dtype=self.real)
+        n_kink = C.c_int64(0)
         rc = self.lib.oracle_tb_loss_grad(C.byref(e), C.byref(m), C.c_int32(batch), C.c_int32(T), _ptr(actions),
                                           _ptr(length), self.creal(log_z), C.byref(loss), C.byref(dlogz),
-                                          C.byref(gs), _ptr(delta), C.c_int(nthreads))
+                                          C.byref(gs), _ptr(delta), self.creal(kink_tol), _ptr(slack),
+                                          C.byref(n_kink), C.c_int(nthreads))
         assert rc == 0, rc
-        g.update(loss=float(loss.value), dlogz=float(dlogz.value), delta=delta)
+        g.update(loss=float(loss.value), dlogz=float(dlogz.value), delta=delta, n_kink=int(n_kink.value),
+                 slack=dict(zip(("dW1", "db1", "dW2", "db2", "dW3", "db3"), slack.astype(np.float64))))
         return g

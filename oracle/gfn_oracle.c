@@ -480,6 +480,9 @@ typedef struct {
   oracle_grad g; /* private accumulators of this worker */
   int b_begin, b_end;
   int status;
+  real kink_tol;   /* hidden units with |z| < kink_tol * (|bias| + sum |terms of z|) sit on the ReLU kink */
+  real slack[6];   /* per tensor (dW1,db1,dW2,db2,dW3,db3): bound on the change if those units' masks flipped */
+  int64_t n_kink;
 } grad_job;
 
 static size_t n_w1(const oracle_mlp* m) { return (size_t)m->in_dim * m->h1; }
@@ -546,6 +549,39 @@ static void* grad_worker(void* arg) {
         g1[i] = A.z1[i] > 0 ? acc : 0;
       }
       for (int k = 0; k < m->h2; ++k) J->g.db2[k] += g2[k];
+      if (J->kink_tol > 0) {
+        /* ReLU'(z) is decided by the sign of z; an implementation in another precision may decide a unit
+         * with |z| < kink_tol the other way.  Bound, per tensor, what such a flip changes (max-norm). */
+        for (int k = 0; k < m->h2; ++k) {
+          if (rabs(A.z2[k]) >= (real)1e-3) continue; /* cheap pre-filter */
+          real mag = rabs(m->b2[k]);
+          for (int i = 0; i < m->h1; ++i) mag += rabs(A.h1[i] * m->W2[(size_t)i * m->h2 + k]);
+          if (rabs(A.z2[k]) >= J->kink_tol * mag) continue;
+          real d = 0;
+          for (int a = 0; a < na; ++a) d += m->W3[(size_t)k * na + a] * g3[a];
+          d = rabs(d);
+          real hmax = 0, wmax = 0;
+          for (int i = 0; i < m->h1; ++i) {
+            if (A.h1[i] > hmax) hmax = A.h1[i];
+            real wv = A.z1[i] > 0 ? rabs(m->W2[(size_t)i * m->h2 + k]) : 0;
+            if (wv > wmax) wmax = wv;
+          }
+          J->slack[2] += hmax * d; J->slack[3] += d;
+          J->slack[0] += wmax * d; J->slack[1] += wmax * d;
+          J->n_kink++;
+        }
+        for (int i = 0; i < m->h1; ++i) {
+          if (rabs(A.z1[i]) >= (real)1e-3) continue;
+          real mag = rabs(m->b1[i]);
+          for (int r = 0; r < nr; ++r) mag += rabs(m->W1[(size_t)rows[r] * m->h1 + i]);
+          if (rabs(A.z1[i]) >= J->kink_tol * mag) continue;
+          real d = 0;
+          for (int k = 0; k < m->h2; ++k) d += m->W2[(size_t)i * m->h2 + k] * g2[k];
+          d = rabs(d);
+          J->slack[0] += d; J->slack[1] += d;
+          J->n_kink++;
+        }
+      }
       for (int r = 0; r < nr; ++r)
         for (int i = 0; i < m->h1; ++i) J->g.dW1[(size_t)rows[r] * m->h1 + i] += g1[i];
       for (int i = 0; i < m->h1; ++i) J->g.db1[i] += g1[i];
@@ -559,10 +595,16 @@ done:
 }
 
 /* Loss = mean_b delta_b^2, dlogz = dLoss/dlogZ = (2/B) sum_b delta_b, grads = dLoss/dtheta
- * (overwritten), delta_out[b] optional.  Everything is recomputed from the action bytes. */
+ * (overwritten), delta_out[b] optional.  Everything is recomputed from the action bytes.
+ * With kink_tol > 0 it also reports n_kink, the number of (transition, hidden unit) pairs whose
+ * pre-activation z is closer to zero than kink_tol times the sum of the magnitudes of its terms (the scale
+ * of the rounding error of a dot product), and slack[6], a per-tensor bound (max-norm, order
+ * dW1 db1 dW2 db2 dW3 db3) on what the gradient would change by if ReLU' were decided the other way on
+ * those units -- the analogue, for the derivative of the ReLU, of the near-tie margin of the sampler. */
 int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
                         const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
-                        oracle_grad* grads, real* delta_out, int nthreads) {
+                        oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out, int64_t* n_kink_out,
+                        int nthreads) {
   int32_t sd, od, na, ms;
   if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
   if (na != mlp->n_actions || od != mlp->in_dim) return -2;
@@ -585,6 +627,8 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
     jobs[k].b_begin = (int)((int64_t)batch * k / nthreads);
     jobs[k].b_end = (int)((int64_t)batch * (k + 1) / nthreads);
     jobs[k].status = 0;
+    jobs[k].kink_tol = kink_tol; jobs[k].n_kink = 0;
+    for (int q = 0; q < 6; ++q) jobs[k].slack[q] = 0;
     if (nthreads == 1) grad_worker(&jobs[k]);
     else pthread_create(&th[k], NULL, grad_worker, &jobs[k]);
   }
@@ -608,6 +652,9 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
   *loss = sum2 / (real)batch;
   *dlogz = (real)2 * sum1 / (real)batch;
   if (delta_out) memcpy(delta_out, delta, sizeof(real) * batch);
+  if (slack_out)
+    for (int q = 0; q < 6; ++q) { slack_out[q] = 0; for (int k = 0; k < nthreads; ++k) slack_out[q] += jobs[k].slack[q]; }
+  if (n_kink_out) { *n_kink_out = 0; for (int k = 0; k < nthreads; ++k) *n_kink_out += jobs[k].n_kink; }
   free(delta); free(priv); free(th); free(jobs);
   return status;
 }

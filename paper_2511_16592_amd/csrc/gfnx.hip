@@ -133,7 +133,7 @@ inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 size_t rollout_lds_bytes(const Shapes& s) {
   const int nchunk = s.A16 / 4, nt3 = s.A16 / 16;
   const int ksplit = nt3 >= 4 ? 1 : 4;
-  size_t fl = (size_t)(s.H1 / 4 + s.H2 / 4 + ksplit * nchunk) * kPitch;
+  size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ksplit * nchunk) * kPitch;
   return fl * sizeof(float) + 3 * kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
 }
 

@@ -274,13 +274,17 @@ struct Dw1Params {
   float *dW1, *db1;
 };
 
-// One workgroup per trajectory.  The set of active one-hot rows changes by one swap per transition, so
-// with the running prefix P_t = sum_{t' < t} g1_{t'} a row active on steps [t_in, t_out) receives
-// P_{t_out} - P_{t_in}: each swap adds +P to the row that leaves and -P to the row that enters, and the
-// rows still active at the last evaluated state receive the full sum, which is also the bias gradient.
+// One workgroup per trajectory; dW1[r] += sum of g1_t over the steps t at which one-hot row r is active.
+// A row is active on a contiguous run of steps, so no per-step scatter over all active rows is needed:
+//   grid    one running sum per coordinate, flushed to row (i, x_i) when coordinate i is incremented;
+//   bitseq, Ising   a position has two phases: its "empty/unassigned" row is active up to the step that
+//           fills it (a prefix sum of g1), the row of the value written is active afterwards (a suffix
+//           sum, taken in a second sweep from the end).
+// Only sums of like terms are formed (no differences of long prefix sums), the total is the bias gradient.
 template <int ENV>
 __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
   __shared__ int rold[256], rnew[256], rend[kMaxStateDim];
+  __shared__ int nend;
   __shared__ int8_t st[kMaxStateDim];
   const EnvParams& e = p.env;
   const int b = blockIdx.x, tid = threadIdx.x, H1 = p.H1, B = p.B;
@@ -291,37 +295,69 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
     for (int t = 0; t + 1 < len; ++t) {
       const int a = p.actions[(size_t)t * B + b];
       if (ENV == 0) {
-        rold[t] = e.H * a + st[a];
-        rnew[t] = e.H * a + st[a] + 1;
+        rold[t] = e.H * a + st[a];  // row left by this increment
+        rnew[t] = a;                // coordinate whose running sum is flushed
         st[a] += 1;
       } else if (ENV == 1) {
         rold[t] = ((1 << e.k_bits) + 1) * t + (1 << e.k_bits);
         rnew[t] = ((1 << e.k_bits) + 1) * t + a;
+        st[t] = 1;
       } else {
         rold[t] = 3 * (a >> 1) + 1;
         rnew[t] = 3 * (a >> 1) + 1 + 2 * (a & 1) - 1;
-        st[a >> 1] = (int8_t)(2 * (a & 1) - 1);
+        st[a >> 1] = 1;
       }
     }
-    // rows active in the last evaluated state s_{len-1}
+    // rows still in their first phase at the last evaluated state s_{len-1}
+    int n = 0;
     for (int s = 0; s < e.state_dim; ++s) {
-      if (ENV == 0) rend[s] = e.H * s + st[s];
-      else if (ENV == 1) rend[s] = ((1 << e.k_bits) + 1) * s + (s < len - 1 ? (int)p.actions[(size_t)s * B + b] : (1 << e.k_bits));
-      else rend[s] = 3 * s + 1 + st[s];
+      if (ENV == 0) rend[n++] = e.H * s + st[s];
+      else if (ENV == 1) { if (!st[s]) rend[n++] = ((1 << e.k_bits) + 1) * s + (1 << e.k_bits); }
+      else { if (!st[s]) rend[n++] = 3 * s + 1; }
     }
+    nend = n;
   }
   __syncthreads();
   for (int f = tid; f < H1; f += 256) {
-    float P = 0.f;
-    for (int t = 0; t < len; ++t) {
-      P += p.g1[((size_t)t * B + b) * H1 + f];
-      if (t + 1 < len) {
-        atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], P);
-        atomicAdd(&p.dW1[(size_t)rnew[t] * H1 + f], -P);
+    const float* g1 = p.g1 + (size_t)b * H1 + f;
+    const size_t stride = (size_t)B * H1;
+    if (ENV == 0) {
+      float acc[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+      float total = 0.f;
+      for (int t = 0; t < len; ++t) {
+        const float g = g1[t * stride];
+        total += g;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] += g;
+        if (t + 1 < len) {
+          const int a = rnew[t];
+          float v = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (i == a) { v = acc[i]; acc[i] = 0.f; }
+          atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], v);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (i < e.d) atomicAdd(&p.dW1[(size_t)rend[i] * H1 + f], acc[i]);
+      atomicAdd(&p.db1[f], total);
+    } else {
+      float P = 0.f;
+      for (int t = 0; t < len; ++t) {
+        P += g1[t * stride];
+        if (t + 1 < len) atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], P);
+      }
+      for (int i = 0; i < nend; ++i) atomicAdd(&p.dW1[(size_t)rend[i] * H1 + f], P);
+      atomicAdd(&p.db1[f], P);
+      float S = 0.f;
+      for (int t = len - 1; t >= 1; --t) {
+        S += g1[t * stride];
+        atomicAdd(&p.dW1[(size_t)rnew[t - 1] * H1 + f], S);
       }
     }
-    for (int s = 0; s < e.state_dim; ++s) atomicAdd(&p.dW1[(size_t)rend[s] * H1 + f], P);
-    atomicAdd(&p.db1[f], P);
   }
 }
 

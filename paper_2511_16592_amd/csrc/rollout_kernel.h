@@ -9,7 +9,7 @@
 //   S   per slot, 16 lanes: action mask, log-softmax, Philox + Gumbel-max argmax (wave shuffles),
 //       environment transition, log P_F / log P_B accumulation, terminal log-reward, action byte;
 //   U   layer 1 is a one-hot gather, and a transition swaps exactly one active row, so the
-//       pre-activation z1 is kept in LDS and updated as z1 += W1[new] - W1[old].
+//       pre-activation z1 is kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
 // The post-ReLU activations h1, h2 and the logit-gradient direction (onehot(a) - p) of every transition
 // are written to HBM rows t*B + b for the gradient pass.
 #pragma once
@@ -44,8 +44,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
   const int NT3 = A16 >> 4, nchunk = A16 >> 2;
   const int ksplit = NT3 >= 4 ? 1 : 4;
 
-  float* z1s = smem;
-  float* h2s = z1s + (H1 >> 2) * kPitch;
+  float* z1s = smem;                          // pre-activation of layer 1, high part
+  float* z1l = z1s + (H1 >> 2) * kPitch;      // ... low part (z1 = hi + lo carries the sum to ~48 bits)
+  float* h2s = z1l + (H1 >> 2) * kPitch;
   float* lgs = h2s + (H2 >> 2) * kPitch;
   int* rowold = (int*)(lgs + ksplit * nchunk * kPitch);
   int* rownew = rowold + kSlots;
@@ -59,11 +60,13 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 
   // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows (increasing row order)
   for (int f = tid; f < H1; f += 256) {
-    float z = p.b1[f];
-    for (int s = 0; s < e.state_dim; ++s) z += p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
-    float* dst = z1s + (f >> 2) * kPitch + (f & 3);
+    double z = (double)p.b1[f];
+    for (int s = 0; s < e.state_dim; ++s) z += (double)p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
+    const float hi = (float)z, lo = (float)(z - (double)hi);
+    float* dh = z1s + (f >> 2) * kPitch + (f & 3);
+    float* dl = z1l + (f >> 2) * kPitch + (f & 3);
 #pragma unroll
-    for (int j = 0; j < kSlots; ++j) dst[j * 4] = z;
+    for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dl[j * 4] = lo; }
   }
   for (int i = tid; i < e.state_dim * kSlots; i += 256) st[i] = 0;
   if (tid < kSlots) alive[tid] = (b0 + tid < B) ? 1 : 0;
@@ -367,9 +370,20 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       const int fg = i >> 4, jj = i & 15;
       if (alive[jj]) {
         f32x4* zp = (f32x4*)&z1s[fg * kPitch + jj * 4];
+        f32x4* lp = (f32x4*)&z1l[fg * kPitch + jj * 4];
         const f32x4 wo = *(const f32x4*)&p.W1[(size_t)rowold[jj] * H1 + 4 * fg];
         const f32x4 wn = *(const f32x4*)&p.W1[(size_t)rownew[jj] * H1 + 4 * fg];
-        *zp = (*zp - wo) + wn;
+        f32x4 hi = *zp, lo = *lp;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          // the running sum is carried as hi + lo so that, however long the walk, relu and its derivative
+          // see the correctly rounded sum of the active rows (no drift across the ReLU kink)
+          const double z = ((double)hi[k] + (double)lo[k]) - (double)wo[k] + (double)wn[k];
+          hi[k] = (float)z;
+          lo[k] = (float)(z - (double)hi[k]);
+        }
+        *zp = hi;
+        *lp = lo;
       }
     }
     const int any = __syncthreads_or(tid < kSlots ? alive[tid] : 0);

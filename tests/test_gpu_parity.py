@@ -6,7 +6,10 @@ Bars (written out here):
     GPU's actions and counts such steps);
   * log P_F, log P_B, log R: relative 1e-4 (absolute floor 1e-5) against the binary64 reference along the
     GPU's own action sequence;
-  * loss and dloss/dlogZ: relative 1e-4 (floor 1e-6); each gradient tensor: max |diff| <= 1e-4 * max |ref| + 1e-7.
+  * loss and dloss/dlogZ: relative 1e-4 (floor 1e-6); each gradient tensor: max |diff| <= 1e-4 * max |ref| + 1e-7,
+    plus, when the reference finds hidden units whose pre-activation is within 2e-6 of its terms' magnitude of the ReLU kink on some
+    transition, its bound on what deciding ReLU' the other way there would change (the sign of such a value is
+    a float-decided bit, like the near-tie argmax; the bound is 0 when there are no such units).
 """
 import math
 import os
@@ -21,6 +24,7 @@ from tests.helpers import (chi2_sf, enumerate_grid_trajectories, grid_reward, op
 pytestmark = pytest.mark.gpu
 KEYS = ("dW1", "db1", "dW2", "db2", "dW3", "db3")
 NTHREADS = min(16, os.cpu_count() or 1)
+KINK_REL = 2e-6  # |z| below this fraction of sum|terms| (32 ulp of binary32): sign is not decidable in fp32
 
 
 @pytest.fixture(scope="module")
@@ -81,13 +85,18 @@ def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, f
 
 
 def check_gradients(o64, env, w, traj, grads, log_z):
-    g = o64.tb_loss_grad(env, w, traj["actions"], traj["length"], log_z, nthreads=NTHREADS)
+    g = o64.tb_loss_grad(env, w, traj["actions"], traj["length"], log_z, nthreads=NTHREADS, kink_tol=KINK_REL)
     assert abs(grads["loss"] - g["loss"]) <= 1e-4 * abs(g["loss"]) + 1e-6, (grads["loss"], g["loss"])
     assert abs(grads["dlogz"] - g["dlogz"]) <= 1e-4 * abs(g["dlogz"]) + 1e-6, (grads["dlogz"], g["dlogz"])
+    n_units = int(traj["length"].sum()) * (w["W1"].shape[1] + w["W2"].shape[1])
+    assert g["n_kink"] <= 2e-5 * n_units + 2, g["n_kink"]  # the margin may only ever cover a sliver of the units
     for k in KEYS:
         scale = np.abs(g[k]).max()
         err = np.abs(grads[k].astype(np.float64) - g[k]).max()
-        assert err <= 1e-4 * scale + 1e-7, (k, float(err), float(scale))
+        assert err <= 1e-4 * scale + 1e-7 + g["slack"][k], (k, float(err), float(scale), g["n_kink"], g["slack"][k])
+    if g["n_kink"]:
+        say(f"    {g['n_kink']} hidden units on the ReLU kink; slack/bar " +
+            " ".join(f"{k}:{g['slack'][k] / (1e-4 * np.abs(g[k]).max() + 1e-7):.2g}" for k in KEYS))
     return g
 
 

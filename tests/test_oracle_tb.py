@@ -123,3 +123,32 @@ def test_f32_and_f64_agree_along_fixed_actions(oracle32, oracle64):
     threaded = oracle64.tb_loss_grad(env, w, out["actions"], out["length"], log_z=0.1, nthreads=4)
     for k in KEYS:
         assert np.allclose(threaded[k], g64[k], rtol=1e-12, atol=1e-14)
+
+
+def test_relu_kink_slack_bounds_a_planted_flip(oracle64):
+    """A hidden unit is placed 1e-9 above / below zero at s_0 (through its bias): the two gradients differ by
+    at most the reported bound, the unit is counted, and without near-zero units the bound is exactly zero."""
+    env = grid_env(2, 4)
+    w = random_mlp(8, 32, 32, 3, seed=41, scale=2.0, dtype=np.float64)
+    out = oracle64.rollout(env, w, seed=3, iteration=0, batch=12)
+    base = oracle64.tb_loss_grad(env, w, out["actions"], out["length"], 0.2, kink_tol=1e-6)
+    assert base["n_kink"] == 0 and all(v == 0 for v in base["slack"].values())
+    for layer, unit in ((1, 5), (2, 7)):
+        grads = []
+        for sign in (+1, -1):
+            w2 = {k: v.copy() for k, v in w.items()}
+            if layer == 1:
+                z0 = w2["b1"][unit] + w2["W1"][0, unit] + w2["W1"][4, unit]  # s_0 = (0,0): rows 0 and 4
+                w2["b1"][unit] += -z0 + sign * 1e-9
+            else:
+                z1 = np.maximum(w2["b1"] + w2["W1"][0] + w2["W1"][4], 0)
+                z0 = w2["b2"][unit] + z1 @ w2["W2"][:, unit]
+                w2["b2"][unit] += -z0 + sign * 1e-9
+            grads.append(oracle64.tb_loss_grad(env, w2, out["actions"], out["length"], 0.2, kink_tol=1e-6))
+        assert grads[0]["n_kink"] >= 12 and grads[1]["n_kink"] >= 12  # every trajectory starts at s_0
+        differs = False
+        for k in KEYS:
+            diff = np.abs(grads[0][k] - grads[1][k]).max()
+            differs = differs or diff > 1e-6
+            assert diff <= min(grads[0]["slack"][k], grads[1]["slack"][k]) + 1e-7, (layer, k, diff)
+        assert differs  # the planted flip really changes the gradient
