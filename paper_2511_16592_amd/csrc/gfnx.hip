@@ -7,9 +7,45 @@
 #include "grad_kernels.h"
 #include "rollout_kernel.h"
 
+#include <string>
+#include <vector>
+
 using namespace gfnx;
 
 namespace {
+
+// ---- optional per-kernel timing (diagnostics): HIP events recorded on the launch stream around each kernel
+struct TimingRecord { int label; hipEvent_t start, stop; };
+bool g_timing_on = false;
+std::vector<std::string> g_labels;
+std::vector<TimingRecord> g_records;
+std::vector<hipEvent_t> g_event_pool;
+
+int label_id(const char* name) {
+  for (size_t i = 0; i < g_labels.size(); ++i) if (g_labels[i] == name) return (int)i;
+  g_labels.push_back(name);
+  return (int)g_labels.size() - 1;
+}
+
+hipEvent_t take_event() {
+  if (!g_event_pool.empty()) { hipEvent_t e = g_event_pool.back(); g_event_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+struct ScopedKernelTimer {
+  hipStream_t st; int rec = -1;
+  ScopedKernelTimer(const char* name, hipStream_t s) : st(s) {
+    if (!g_timing_on) return;
+    TimingRecord r{label_id(name), take_event(), take_event()};
+    (void)hipEventRecord(r.start, st);
+    g_records.push_back(r);
+    rec = (int)g_records.size() - 1;
+  }
+  ~ScopedKernelTimer() { if (rec >= 0) (void)hipEventRecord(g_records[rec].stop, st); }
+};
+#define GFNX_TIMED(name, stream) ScopedKernelTimer gfnx_timer_##__LINE__(name, stream)
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -183,10 +219,13 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
 
-  hipLaunchKernelGGL(pack_weights_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, s.H2 / 16,
-                     at<float>(ws, L.w2p));
-  hipLaunchKernelGGL(pack_weights_kernel, dim3(128), dim3(256), 0, st, mlp->W3, s.H2, s.A, s.A16 / 16,
-                     at<float>(ws, L.w3p));
+  {
+    GFNX_TIMED("pack_weights", st);
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, s.H2 / 16,
+                       at<float>(ws, L.w2p));
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(128), dim3(256), 0, st, mlp->W3, s.H2, s.A, s.A16 / 16,
+                       at<float>(ws, L.w3p));
+  }
 
   RolloutParams p = {};
   p.env = env_params(env, s);
@@ -203,7 +242,10 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   const dim3 grid((s.B + kSlots - 1) / kSlots);
   const size_t lds = rollout_lds_bytes(s);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
-  rc = replay ? launch_rollout<true>(p, s.H2 / 64, grid, lds, st) : launch_rollout<false>(p, s.H2 / 64, grid, lds, st);
+  {
+    GFNX_TIMED("rollout", st);
+    rc = replay ? launch_rollout<true>(p, s.H2 / 64, grid, lds, st) : launch_rollout<false>(p, s.H2 / 64, grid, lds, st);
+  }
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
 }
@@ -271,41 +313,68 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   const int T = s.max_steps, B = s.B;
   if ((size_t)traj->max_steps * B > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
 
-  hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb,
-                     traj->log_reward, log_z, B, T, coef, loss_dev, dlogz_dev, hdr);
-  hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows);
-  hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
+  {
+    GFNX_TIMED("prep", st);
+    hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb,
+                       traj->log_reward, log_z, B, T, coef, loss_dev, dlogz_dev, hdr);
+  }
+  {
+    GFNX_TIMED("build_rows", st);
+    hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows);
+  }
+  {
+    GFNX_TIMED("scale_rows", st);
+    hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
+  }
 
   // layer 3: dW3, db3, then G2 over h2
   {
     const dim3 grid((s.H2 + 127) / 128, s.qtot3 / s.qt3, s.s3);
     float* part = at<float>(ws, L.part3);
     float* dbp = at<float>(ws, L.dbp3);
-    if (s.qt3 == 32)
-      hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
-    else
-      hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+    {
+      GFNX_TIMED("gemm_tn_w3", st);
+      if (s.qt3 == 32)
+        hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+      else
+        hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+    }
+    GFNX_TIMED("reduce_w3", st);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3);
   }
   const int row_tiles = (int)((s.rows + 63) / 64);
   const int gx = row_tiles < 2048 ? row_tiles : 2048;
-  hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
-                     h2buf, s.H2, s.H2, rows, hdr);
+  {
+    GFNX_TIMED("gemm_nt_g2", st);
+    hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
+                       h2buf, s.H2, s.H2, rows, hdr);
+  }
   // layer 2: dW2, db2, then G1 over h1
   {
     const dim3 grid((s.H1 + 127) / 128, s.qtot2 / 128, s.s2);
     float* part = at<float>(ws, L.part2);
     float* dbp = at<float>(ws, L.dbp2);
-    hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
+    {
+      GFNX_TIMED("gemm_tn_w2", st);
+      hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
+    }
+    GFNX_TIMED("reduce_w2", st);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2);
   }
-  hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
-                     h1buf, s.H1, s.H1, rows, hdr);
+  {
+    GFNX_TIMED("gemm_nt_g1", st);
+    hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
+                       h1buf, s.H1, s.H1, rows, hdr);
+  }
   // layer 1: scatter along each trajectory
-  hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
-  hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
+  {
+    GFNX_TIMED("fill_w1", st);
+    hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
+    hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
+  }
+  GFNX_TIMED("dw1", st);
   Dw1Params dp = {};
   dp.env = env_params(env, s);
   dp.H1 = s.H1; dp.B = B;
@@ -317,6 +386,31 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
   }
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+int gfnx_timing_enable(int on) {
+  for (auto& r : g_records) { g_event_pool.push_back(r.start); g_event_pool.push_back(r.stop); }
+  g_records.clear();
+  g_timing_on = on != 0;
+  return GFNX_OK;
+}
+
+int gfnx_timing_labels(void) { return (int)g_labels.size(); }
+
+int gfnx_timing_get(int label, const char** name, int32_t* launches, float* total_ms) {
+  if (label < 0 || label >= (int)g_labels.size() || !name || !launches || !total_ms) return GFNX_E_NULL;
+  *name = g_labels[label].c_str();
+  *launches = 0;
+  *total_ms = 0.f;
+  for (auto& r : g_records) {
+    if (r.label != label) continue;
+    if (hipEventSynchronize(r.stop) != hipSuccess) return GFNX_E_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return GFNX_E_HIP;
+    *launches += 1;
+    *total_ms += ms;
+  }
+  return GFNX_OK;
 }
 
 const char* gfnx_status_string(int status) {

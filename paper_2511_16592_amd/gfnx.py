@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
-           "gfnx_status_string")
+           "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_labels", "gfnx_timing_get")
 
 
 class EnvDesc(C.Structure):
@@ -72,6 +72,11 @@ def load_library() -> C.CDLL:
         lib.gfnx_tb_loss_grad.restype = C.c_int
         lib.gfnx_tb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
                                           C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_timing_enable.restype = C.c_int
+        lib.gfnx_timing_enable.argtypes = [C.c_int]
+        lib.gfnx_timing_labels.restype = C.c_int
+        lib.gfnx_timing_get.restype = C.c_int
+        lib.gfnx_timing_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int32), C.POINTER(C.c_float)]
         lib.gfnx_status_string.restype = C.c_char_p
         lib.gfnx_status_string.argtypes = [C.c_int]
         _lib = lib
@@ -98,6 +103,25 @@ def env_dims(env):
     d = env if isinstance(env, EnvDesc) else env_desc(env)
     _check(load_library().gfnx_env_dims(C.byref(d), *[C.byref(o) for o in out]))
     return tuple(o.value for o in out)
+
+
+class KernelTimer:
+    """Per-kernel durations from the library's own HIP events (gfnx_timing_*)."""
+
+    def __init__(self):
+        self.lib = load_library()
+
+    def enable(self, on: bool) -> None:
+        _check(self.lib.gfnx_timing_enable(1 if on else 0))
+
+    def collect(self) -> Dict[str, tuple]:
+        out = {}
+        for i in range(self.lib.gfnx_timing_labels()):
+            name, n, ms = C.c_char_p(), C.c_int32(), C.c_float()
+            _check(self.lib.gfnx_timing_get(i, C.byref(name), C.byref(n), C.byref(ms)))
+            if n.value:
+                out[name.value.decode()] = (n.value, float(ms.value))
+        return out
 
 
 def _ptr(t) -> int:
