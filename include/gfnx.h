@@ -130,8 +130,10 @@ int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
 /* Teacher-forced rollout: follows the given traj->actions / traj->length (inputs) instead of
  * sampling, and fills log_pf, log_pb, log_reward, terminal_state and the workspace exactly as
  * gfnx_rollout would (off-policy trajectories, the trajectory distributions of eq.
- * forward_backward_traj for given tau).  Behaviour is undefined if an action is invalid in its state
- * or a sequence does not end in a terminal state after length[b] steps. */
+ * forward_backward_traj for given tau).  A given action that is impossible in its state cuts that
+ * trajectory there (no transition, log_reward 0), and a sequence that does not reach a terminal state within
+ * length[b] steps ends with log_reward 0: both are memory-safe, but the loss and gradient contributions of
+ * such a trajectory are unspecified. */
 int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
 

@@ -288,12 +288,16 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
   __shared__ int8_t st[kMaxStateDim];
   const EnvParams& e = p.env;
   const int b = blockIdx.x, tid = threadIdx.x, H1 = p.H1, B = p.B;
-  const int len = p.length[b];
+  int len = p.length[b];
   if (len <= 0) return;
+  if (len > e.max_steps) len = e.max_steps;  // malformed input must not index out of bounds
+  __shared__ int bad;
   if (tid == 0) {
+    bad = 0;
     for (int s = 0; s < e.state_dim; ++s) st[s] = 0;
     for (int t = 0; t + 1 < len; ++t) {
-      const int a = p.actions[(size_t)t * B + b];
+      int a = p.actions[(size_t)t * B + b];
+      if (ENV == 0 ? (a >= e.d || st[a] >= e.H - 1) : (a >= e.n_actions)) { bad = 1; break; }
       if (ENV == 0) {
         rold[t] = e.H * a + st[a];  // row left by this increment
         rnew[t] = a;                // coordinate whose running sum is flushed
@@ -318,6 +322,7 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
     nend = n;
   }
   __syncthreads();
+  if (bad) return;  // an action that is impossible in its state: the trajectory contributes nothing
   for (int f = tid; f < H1; f += 256) {
     const float* g1 = p.g1 + (size_t)b * H1 + f;
     const size_t stride = (size_t)B * H1;

@@ -33,7 +33,10 @@ __device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words,
   return (uint32_t)(v >> (s & 31)) & ((1u << k) - 1u);
 }
 
-template <int ENV, bool REPLAY, int NTW2>
+// STAT (H1 = H2 = 256): each wave keeps its 64-feature slice of W2 (64 KiB, 256 registers per lane) in
+// registers for the whole rollout, so the layer-2 phase issues no memory traffic but the LDS operand reads;
+// with a single 16-logit tile (grids) its quarter of W3 stays in registers as well.
+template <int ENV, bool REPLAY, int NTW2, bool STAT>
 __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
   extern __shared__ float smem[];
   const EnvParams& e = p.env;
@@ -73,6 +76,18 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
   float lpf = 0.f, lpb = 0.f;
   int len_given = 0;
   if (REPLAY && sb < B) len_given = p.length[sb];
+  f32x4 w2r[STAT ? 4 : 1][STAT ? 16 : 1];
+  f32x4 w3r[STAT ? 4 : 1];
+  if constexpr (STAT) {
+    const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * 4) * 16 * 64 + lane;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) w2r[n][q] = wp[(n * 16 + q) * 64];
+    const f32x4* wp3 = (const f32x4*)p.W3p + lane;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w3r[q] = (NT3 == 1) ? wp3[(w * 4 + q) * 64] : (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
   __syncthreads();
 
   for (int t = 0; t < e.max_steps; ++t) {
@@ -90,18 +105,41 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       f32x4 acc[NTW2];
 #pragma unroll
       for (int n = 0; n < NTW2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * NTW2) * Q1 * 64 + lane;
-
-      for (int q = 0; q < Q1; ++q) {
-        f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
-        bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+      if constexpr (STAT) {
 #pragma unroll
-        for (int n = 0; n < NTW2; ++n) {
-          const f32x4 av = wp[((size_t)n * Q1 + q) * 64];
-          acc[n] = mfma16(av.x, bv.x, acc[n]);
-          acc[n] = mfma16(av.y, bv.y, acc[n]);
-          acc[n] = mfma16(av.z, bv.z, acc[n]);
-          acc[n] = mfma16(av.w, bv.w, acc[n]);
+        for (int q = 0; q < 16; ++q) {
+          f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
+          bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+#pragma unroll
+          for (int n = 0; n < 4; ++n) {
+            acc[n] = mfma16(w2r[n][q].x, bv.x, acc[n]);
+            acc[n] = mfma16(w2r[n][q].y, bv.y, acc[n]);
+            acc[n] = mfma16(w2r[n][q].z, bv.z, acc[n]);
+            acc[n] = mfma16(w2r[n][q].w, bv.w, acc[n]);
+          }
+        }
+      } else {
+        // weights stream from L2 in operand order; the loads of step q+1 are issued before the MFMAs of step q
+        const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * NTW2) * Q1 * 64 + lane;
+        f32x4 cur[NTW2];
+#pragma unroll
+        for (int n = 0; n < NTW2; ++n) cur[n] = wp[((size_t)n * Q1) * 64];
+        for (int q = 0; q < Q1; ++q) {
+          const int qn = q + 1 < Q1 ? q + 1 : q;
+          f32x4 nxt[NTW2];
+#pragma unroll
+          for (int n = 0; n < NTW2; ++n) nxt[n] = wp[((size_t)n * Q1 + qn) * 64];
+          f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
+          bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+#pragma unroll
+          for (int n = 0; n < NTW2; ++n) {
+            acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
+            acc[n] = mfma16(cur[n].y, bv.y, acc[n]);
+            acc[n] = mfma16(cur[n].z, bv.z, acc[n]);
+            acc[n] = mfma16(cur[n].w, bv.w, acc[n]);
+          }
+#pragma unroll
+          for (int n = 0; n < NTW2; ++n) cur[n] = nxt[n];
         }
       }
 #pragma unroll
@@ -127,20 +165,26 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 #pragma unroll
       for (int n = 0; n < 4; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
       const f32x4* wp = (const f32x4*)p.W3p + lane;
-
+      f32x4 cur[4];
+#pragma unroll
+      for (int n = 0; n < 4; ++n) cur[n] = wp[((size_t)min(w + 4 * n, NT3 - 1) * Q2) * 64];
       for (int q = 0; q < Q2; ++q) {
+        const int qn = q + 1 < Q2 ? q + 1 : q;
+        f32x4 nxt[4];
+#pragma unroll
+        for (int n = 0; n < 4; ++n) nxt[n] = wp[((size_t)min(w + 4 * n, NT3 - 1) * Q2 + qn) * 64];
         const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-          const int nt = w + 4 * n;
-          if (nt < NT3) {
-            const f32x4 av = wp[((size_t)nt * Q2 + q) * 64];
-            acc[n] = mfma16(av.x, bv.x, acc[n]);
-            acc[n] = mfma16(av.y, bv.y, acc[n]);
-            acc[n] = mfma16(av.z, bv.z, acc[n]);
-            acc[n] = mfma16(av.w, bv.w, acc[n]);
+          if (w + 4 * n < NT3) {
+            acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
+            acc[n] = mfma16(cur[n].y, bv.y, acc[n]);
+            acc[n] = mfma16(cur[n].z, bv.z, acc[n]);
+            acc[n] = mfma16(cur[n].w, bv.w, acc[n]);
           }
         }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) cur[n] = nxt[n];
       }
 #pragma unroll
       for (int n = 0; n < 4; ++n) {
@@ -151,18 +195,29 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       f32x4 acc[3];
 #pragma unroll
       for (int n = 0; n < 3; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const f32x4* wp = (const f32x4*)p.W3p + lane;
-      const int qn = Q2 >> 2;
-      for (int q = w * qn; q < (w + 1) * qn; ++q) {
-        const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+      if (STAT && NT3 == 1) {
 #pragma unroll
-        for (int n = 0; n < 3; ++n) {
-          if (n < NT3) {
-            const f32x4 av = wp[((size_t)n * Q2 + q) * 64];
-            acc[n] = mfma16(av.x, bv.x, acc[n]);
-            acc[n] = mfma16(av.y, bv.y, acc[n]);
-            acc[n] = mfma16(av.z, bv.z, acc[n]);
-            acc[n] = mfma16(av.w, bv.w, acc[n]);
+        for (int q = 0; q < (STAT ? 4 : 1); ++q) {
+          const f32x4 bv = *(const f32x4*)&h2s[(4 * (w * 4 + q) + g) * kPitch + j16 * 4];
+          acc[0] = mfma16(w3r[q].x, bv.x, acc[0]);
+          acc[0] = mfma16(w3r[q].y, bv.y, acc[0]);
+          acc[0] = mfma16(w3r[q].z, bv.z, acc[0]);
+          acc[0] = mfma16(w3r[q].w, bv.w, acc[0]);
+        }
+      } else {
+        const f32x4* wp = (const f32x4*)p.W3p + lane;
+        const int qn = Q2 >> 2;
+        for (int q = w * qn; q < (w + 1) * qn; ++q) {
+          const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+#pragma unroll
+          for (int n = 0; n < 3; ++n) {
+            if (n < NT3) {
+              const f32x4 av = wp[((size_t)n * Q2 + q) * 64];
+              acc[n] = mfma16(av.x, bv.x, acc[n]);
+              acc[n] = mfma16(av.y, bv.y, acc[n]);
+              acc[n] = mfma16(av.z, bv.z, acc[n]);
+              acc[n] = mfma16(av.w, bv.w, acc[n]);
+            }
           }
         }
       }
@@ -219,6 +274,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 
       int act;
       float alogit;
+      bool given_ok = true;  // teacher-forced mode: is the given action possible in this state?
       if (!REPLAY) {
         float best = -INFINITY, blog = 0.f;
         int bidx = 0x7fffffff;
@@ -248,12 +304,15 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       } else {
         act = p.actions[(size_t)t * B + sb];
         float mine = 0.f;
+        int mine_ok = 0;
 #pragma unroll
         for (int n = 0; n < 4; ++n)
 #pragma unroll
           for (int k = 0; k < 4; ++k)
-            if (4 * (si + 16 * n) + k == act) mine = lg[n][k];
+            if (4 * (si + 16 * n) + k == act) { mine = lg[n][k]; mine_ok = (int)((vm[n] >> k) & 1u); }
         alogit = __shfl(mine, (act >> 2) & 15, 16);
+        given_ok = __shfl(mine_ok, (act >> 2) & 15, 16) != 0;
+        if (!given_ok) { act = 0; alogit = m + lse; }  // log p = 0; the trajectory is cut below
       }
       lpf += (alogit - m) - lse;
 
@@ -276,7 +335,11 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       float logr = 0.f;
       int xi = 0;           // grid: this lane's coordinate after the step
       int site = 0, spin = 0;  // ising
-      if (ENV == 0) {
+      if (REPLAY && !given_ok) {
+        term = true;  // impossible action in the given sequence: cut the trajectory here, state unchanged
+        if (ENV == 0) xi = (si < e.d) ? st[si * kSlots + sj] : 0;
+        site = -1;
+      } else if (ENV == 0) {
         xi = (si < e.d) ? st[si * kSlots + sj] : 0;
         if (act != e.d) {
           if (si == act) {
@@ -355,7 +418,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         for (int s = si; s < e.state_dim; s += 16) {
           int v;
           if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
-          else if (ENV == 1) v = (s == t) ? act : (int)(uint8_t)st[s * kSlots + sj];
+          else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)st[s * kSlots + sj];
           else v = (s == site) ? spin : st[s * kSlots + sj];
           p.term[(size_t)s * B + sb] = (int8_t)v;
         }
