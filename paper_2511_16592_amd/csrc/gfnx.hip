@@ -170,36 +170,35 @@ size_t rollout_lds_bytes(const Shapes& s) {
   const int nchunk = s.A16 / 4, nt3 = s.A16 / 16;
   const int ksplit = nt3 >= 4 ? 1 : 4;
   size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ksplit * nchunk) * kPitch;
-  return fl * sizeof(float) + 3 * kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
+  return fl * sizeof(float) + kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
 }
 
-template <int ENV, bool REPLAY>
+template <int ENV, bool REPLAY, int NCH>
 int launch_rollout_ntw(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
-#define GFNX_LAUNCH(N)                                                                                      \
+#define GFNX_LAUNCH(N, STATIONARY)                                                                          \
   {                                                                                                         \
-    auto k = rollout_kernel<ENV, REPLAY, N, false>;                                                         \
+    auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH>;                                               \
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
       return GFNX_E_HIP;                                                                                    \
     hipLaunchKernelGGL(k, grid, dim3(256), lds, st, p);                                                     \
   }
   // Register-resident W2 is used for the grid environments only: the Ising instantiation of that variant
   // faulted the GPU on its first run and is switched off until the cause is shown.
-  if (ENV == 0 && p.H1 == 256 && p.H2 == 256) {
-    auto k = rollout_kernel<ENV, REPLAY, 4, true>;
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return GFNX_E_HIP;
-    hipLaunchKernelGGL(k, grid, dim3(256), lds, st, p);
-    return GFNX_OK;
+  if constexpr (ENV == 0) {
+    if (p.H1 == 256 && p.H2 == 256) {
+      GFNX_LAUNCH(4, true)
+      return GFNX_OK;
+    }
   }
   switch (ntw) {
-    case 1: GFNX_LAUNCH(1) break;
-    case 2: GFNX_LAUNCH(2) break;
-    case 3: GFNX_LAUNCH(3) break;
-    case 4: GFNX_LAUNCH(4) break;
-    case 5: GFNX_LAUNCH(5) break;
-    case 6: GFNX_LAUNCH(6) break;
-    case 7: GFNX_LAUNCH(7) break;
-    case 8: GFNX_LAUNCH(8) break;
+    case 1: GFNX_LAUNCH(1, false) break;
+    case 2: GFNX_LAUNCH(2, false) break;
+    case 3: GFNX_LAUNCH(3, false) break;
+    case 4: GFNX_LAUNCH(4, false) break;
+    case 5: GFNX_LAUNCH(5, false) break;
+    case 6: GFNX_LAUNCH(6, false) break;
+    case 7: GFNX_LAUNCH(7, false) break;
+    case 8: GFNX_LAUNCH(8, false) break;
     default: return GFNX_E_UNSUPPORTED;
   }
 #undef GFNX_LAUNCH
@@ -208,10 +207,15 @@ int launch_rollout_ntw(const RolloutParams& p, int ntw, dim3 grid, size_t lds, h
 
 template <bool REPLAY>
 int launch_rollout(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
+  const bool wide = p.A16 > 64;  // more than one chunk of four logits per sampling lane
   switch (p.env.kind) {
-    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY>(p, ntw, grid, lds, st);
-    case GFNX_ENV_BITSEQ: return launch_rollout_ntw<1, REPLAY>(p, ntw, grid, lds, st);
-    default: return launch_rollout_ntw<2, REPLAY>(p, ntw, grid, lds, st);
+    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY, 1>(p, ntw, grid, lds, st);
+    case GFNX_ENV_BITSEQ:
+      return wide ? launch_rollout_ntw<1, REPLAY, 4>(p, ntw, grid, lds, st)
+                  : launch_rollout_ntw<1, REPLAY, 1>(p, ntw, grid, lds, st);
+    default:
+      return wide ? launch_rollout_ntw<2, REPLAY, 4>(p, ntw, grid, lds, st)
+                  : launch_rollout_ntw<2, REPLAY, 1>(p, ntw, grid, lds, st);
   }
 }
 

@@ -66,32 +66,57 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// 32 random bits -> u in (0,1) exactly representable in binary32 -> standard Gumbel variate.
-__device__ __forceinline__ float gumbel_from_bits(uint32_t w) {
-  const float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23
-  return -logf(-logf(u));
+// 32 random bits -> u in (0,1), exactly representable in binary32
+__device__ __forceinline__ float uniform_from_bits(uint32_t w) {
+  return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23
 }
 
-// reductions over the 16 lanes that serve one trajectory slot (an aligned quarter of a wavefront)
+// Workgroup barrier that orders LDS traffic only: waits for this wave's LDS operations, not for its
+// outstanding global stores (the kernels using it never read back what they store to global memory).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Value of the lane `n` positions further round the aligned row of 16 lanes (DPP row rotation).
+template <int N>
+__device__ __forceinline__ int row16_rot(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, 0x120 + N, 0xF, 0xF, false);
+}
+template <int N>
+__device__ __forceinline__ float row16_rot(float v) {
+  return __builtin_bit_cast(float, row16_rot<N>(__builtin_bit_cast(int, v)));
+}
+
+// Reductions over the 16 lanes that serve one trajectory slot (an aligned quarter of a wavefront); every
+// lane of the row ends with the same result.  All 16 lanes must be active together.
 __device__ __forceinline__ float row16_max(float v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 16));
+  v = fmaxf(v, row16_rot<8>(v)); v = fmaxf(v, row16_rot<4>(v));
+  v = fmaxf(v, row16_rot<2>(v)); v = fmaxf(v, row16_rot<1>(v));
   return v;
 }
 __device__ __forceinline__ float row16_sum(float v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 16);
+  v += row16_rot<8>(v); v += row16_rot<4>(v); v += row16_rot<2>(v); v += row16_rot<1>(v);
   return v;
 }
 __device__ __forceinline__ int row16_sum(int v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 16);
+  v += row16_rot<8>(v); v += row16_rot<4>(v); v += row16_rot<2>(v); v += row16_rot<1>(v);
   return v;
 }
 __device__ __forceinline__ int row16_min(int v) {
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
+  v = min(v, row16_rot<8>(v)); v = min(v, row16_rot<4>(v));
+  v = min(v, row16_rot<2>(v)); v = min(v, row16_rot<1>(v));
   return v;
+}
+// (key, idx, payload) of the smallest key over the row; the lowest idx wins equal keys
+template <int N>
+__device__ __forceinline__ void row16_argmin_step(float& key, int& idx, float& payload) {
+  const float ok = row16_rot<N>(key), op = row16_rot<N>(payload);
+  const int oi = row16_rot<N>(idx);
+  if (ok < key || (ok == key && oi < idx)) { key = ok; idx = oi; payload = op; }
+}
+__device__ __forceinline__ void row16_argmin(float& key, int& idx, float& payload) {
+  row16_argmin_step<8>(key, idx, payload);
+  row16_argmin_step<4>(key, idx, payload);
+  row16_argmin_step<2>(key, idx, payload);
+  row16_argmin_step<1>(key, idx, payload);
 }
 
 }  // namespace gfnx

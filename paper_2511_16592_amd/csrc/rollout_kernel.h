@@ -1,17 +1,20 @@
 // Persistent trajectory-block rollout kernel.
 //
 // One workgroup (4 wavefronts) owns kSlots = 16 trajectories from s_0 to their terminal states.  Per step:
-//   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1),
-//       the four waves split the output features; weights stream from L2 cache in MFMA operand order,
-//       activations come from LDS;
-//   L3  logits the same way (output tiles split over the waves, or the contraction split when there
-//       are fewer than four tiles);
-//   S   per slot, 16 lanes: action mask, log-softmax, Philox + Gumbel-max argmax (wave shuffles),
-//       environment transition, log P_F / log P_B accumulation, terminal log-reward, action byte;
-//   U   layer 1 is a one-hot gather, and a transition swaps exactly one active row, so the
-//       pre-activation z1 is kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
+//   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1); the
+//       four waves split the output features; weights are MFMA A-operands (resident in registers, or
+//       streamed from L2 cache in operand order with the next step's loads in flight), activations come
+//       from LDS in B-operand order;
+//   L3  logits the same way (output tiles split over the waves, or the contraction split when there are
+//       fewer than four tiles);
+//   SU  per slot, 16 lanes of one wave: action mask, softmax weights, Philox draw and argmin by
+//       row-rotation DPP, log P_F / log P_B, the row of the logit gradient, environment transition,
+//       terminal log-reward, action byte; then the same lanes update the layer-1 pre-activation: layer 1
+//       is a one-hot gather and a transition swaps exactly one active row, so z1 is kept in LDS (as a
+//       high + low pair) and updated as z1 += W1[new] - W1[old].
 // The post-ReLU activations h1, h2 and the logit-gradient direction (onehot(a) - p) of every transition
-// are written to HBM rows t*B + b for the gradient pass.
+// are written to HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is
+// read back by it, so the three barriers per step order LDS traffic only (no wait for stores to land).
 #pragma once
 #include "gfnx_device.h"
 
@@ -33,10 +36,21 @@ __device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words,
   return (uint32_t)(v >> (s & 31)) & ((1u << k) - 1u);
 }
 
+__device__ __forceinline__ f32x4 relu4(f32x4 v) {
+  v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+  return v;
+}
+
+#define GFNX_MFMA4(ACC, AV, BV)            \
+  ACC = mfma16((AV).x, (BV).x, ACC);       \
+  ACC = mfma16((AV).y, (BV).y, ACC);       \
+  ACC = mfma16((AV).z, (BV).z, ACC);       \
+  ACC = mfma16((AV).w, (BV).w, ACC)
+
 // STAT (H1 = H2 = 256): each wave keeps its 64-feature slice of W2 (64 KiB, 256 registers per lane) in
-// registers for the whole rollout, so the layer-2 phase issues no memory traffic but the LDS operand reads;
-// with a single 16-logit tile (grids) its quarter of W3 stays in registers as well.
-template <int ENV, bool REPLAY, int NTW2, bool STAT>
+// registers for the whole rollout; with a single 16-logit tile (grids) its quarter of W3 stays there too.
+// NCH = logit chunks (of 4 actions) a lane may own: 1 when the action space fits 64 logits, else 4.
+template <int ENV, bool REPLAY, int NTW2, bool STAT, int NCH>
 __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
   extern __shared__ float smem[];
   const EnvParams& e = p.env;
@@ -51,17 +65,15 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
   float* z1l = z1s + (H1 >> 2) * kPitch;      // ... low part (z1 = hi + lo carries the sum to ~48 bits)
   float* h2s = z1l + (H1 >> 2) * kPitch;
   float* lgs = h2s + (H2 >> 2) * kPitch;
-  int* rowold = (int*)(lgs + ksplit * nchunk * kPitch);
-  int* rownew = rowold + kSlots;
-  int* alive = rownew + kSlots;
+  int* alive = (int*)(lgs + ksplit * nchunk * kPitch);
   int8_t* st = (int8_t*)(alive + kSlots);
 
   const int b0 = blockIdx.x * kSlots;
-  // roles in the sampling phase: 16 lanes (sub-lane si) per slot sj
+  // roles in the sampling phase: 16 lanes (sub-lane si) of one wave per slot sj
   const int sj = 4 * w + g, si = j16;
   const int sb = b0 + sj;
 
-  // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows (increasing row order)
+  // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows
   for (int f = tid; f < H1; f += 256) {
     double z = (double)p.b1[f];
     for (int s = 0; s < e.state_dim; ++s) z += (double)p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
@@ -84,22 +96,19 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
     for (int n = 0; n < 4; ++n)
 #pragma unroll
       for (int q = 0; q < 16; ++q) w2r[n][q] = wp[(n * 16 + q) * 64];
-    const f32x4* wp3 = (const f32x4*)p.W3p + lane;
+    const f32x4* wp3 = (const f32x4*)p.W3p + lane;  // tile 0, this wave's quarter of the contraction
 #pragma unroll
-    for (int q = 0; q < 4; ++q) w3r[q] = (NT3 == 1) ? wp3[(w * 4 + q) * 64] : (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < 4; ++q) w3r[q] = wp3[(w * 4 + q) * 64];
   }
-  __syncthreads();
+  lds_barrier();
 
   for (int t = 0; t < e.max_steps; ++t) {
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
     for (int jj = w; jj < kSlots; jj += 4) {
       if (!alive[jj]) continue;
       float* dst = p.h1buf + ((size_t)t * B + b0 + jj) * H1;
-      for (int fg = lane; fg < (H1 >> 2); fg += 64) {
-        f32x4 v = *(const f32x4*)&z1s[fg * kPitch + jj * 4];
-        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-        *(f32x4*)&dst[fg * 4] = v;
-      }
+      for (int fg = lane; fg < (H1 >> 2); fg += 64)
+        *(f32x4*)&dst[fg * 4] = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
     }
     {
       f32x4 acc[NTW2];
@@ -108,18 +117,11 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       if constexpr (STAT) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-          f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
-          bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+          const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
 #pragma unroll
-          for (int n = 0; n < 4; ++n) {
-            acc[n] = mfma16(w2r[n][q].x, bv.x, acc[n]);
-            acc[n] = mfma16(w2r[n][q].y, bv.y, acc[n]);
-            acc[n] = mfma16(w2r[n][q].z, bv.z, acc[n]);
-            acc[n] = mfma16(w2r[n][q].w, bv.w, acc[n]);
-          }
+          for (int n = 0; n < 4; ++n) { GFNX_MFMA4(acc[n], w2r[n][q], bv); }
         }
       } else {
-        // weights stream from L2 in operand order; the loads of step q+1 are issued before the MFMAs of step q
         const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * NTW2) * Q1 * 64 + lane;
         f32x4 cur[NTW2];
 #pragma unroll
@@ -129,15 +131,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           f32x4 nxt[NTW2];
 #pragma unroll
           for (int n = 0; n < NTW2; ++n) nxt[n] = wp[((size_t)n * Q1 + qn) * 64];
-          f32x4 bv = *(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4];
-          bv.x = fmaxf(bv.x, 0.f); bv.y = fmaxf(bv.y, 0.f); bv.z = fmaxf(bv.z, 0.f); bv.w = fmaxf(bv.w, 0.f);
+          const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
 #pragma unroll
-          for (int n = 0; n < NTW2; ++n) {
-            acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
-            acc[n] = mfma16(cur[n].y, bv.y, acc[n]);
-            acc[n] = mfma16(cur[n].z, bv.z, acc[n]);
-            acc[n] = mfma16(cur[n].w, bv.w, acc[n]);
-          }
+          for (int n = 0; n < NTW2; ++n) { GFNX_MFMA4(acc[n], cur[n], bv); }
 #pragma unroll
           for (int n = 0; n < NTW2; ++n) cur[n] = nxt[n];
         }
@@ -146,14 +142,12 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       for (int n = 0; n < NTW2; ++n) {
         const int nt = w * NTW2 + n;
         const f32x4 bias = *(const f32x4*)&p.b2[16 * nt + 4 * g];
-        f32x4 v = acc[n] + bias;
-        v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
-        *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = v;
+        *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + bias);
       }
     }
-    __syncthreads();
+    lds_barrier();
 
-    // ================= L3: logits = W3^T h2 (+ b3 added in S)
+    // ================= L3: logits = W3^T h2 (+ b3 added in SU)
     for (int jj = w; jj < kSlots; jj += 4) {
       if (!alive[jj]) continue;
       float* dst = p.h2buf + ((size_t)t * B + b0 + jj) * H2;
@@ -176,12 +170,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-          if (w + 4 * n < NT3) {
-            acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
-            acc[n] = mfma16(cur[n].y, bv.y, acc[n]);
-            acc[n] = mfma16(cur[n].z, bv.z, acc[n]);
-            acc[n] = mfma16(cur[n].w, bv.w, acc[n]);
-          }
+          if (w + 4 * n < NT3) { GFNX_MFMA4(acc[n], cur[n], bv); }
         }
 #pragma unroll
         for (int n = 0; n < 4; ++n) cur[n] = nxt[n];
@@ -199,10 +188,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 #pragma unroll
         for (int q = 0; q < (STAT ? 4 : 1); ++q) {
           const f32x4 bv = *(const f32x4*)&h2s[(4 * (w * 4 + q) + g) * kPitch + j16 * 4];
-          acc[0] = mfma16(w3r[q].x, bv.x, acc[0]);
-          acc[0] = mfma16(w3r[q].y, bv.y, acc[0]);
-          acc[0] = mfma16(w3r[q].z, bv.z, acc[0]);
-          acc[0] = mfma16(w3r[q].w, bv.w, acc[0]);
+          GFNX_MFMA4(acc[0], w3r[q], bv);
         }
       } else {
         const f32x4* wp = (const f32x4*)p.W3p + lane;
@@ -213,10 +199,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           for (int n = 0; n < 3; ++n) {
             if (n < NT3) {
               const f32x4 av = wp[((size_t)n * Q2 + q) * 64];
-              acc[n] = mfma16(av.x, bv.x, acc[n]);
-              acc[n] = mfma16(av.y, bv.y, acc[n]);
-              acc[n] = mfma16(av.z, bv.z, acc[n]);
-              acc[n] = mfma16(av.w, bv.w, acc[n]);
+              GFNX_MFMA4(acc[n], av, bv);
             }
           }
         }
@@ -225,15 +208,15 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       for (int n = 0; n < 3; ++n)
         if (n < NT3) *(f32x4*)&lgs[(w * nchunk + 4 * n + g) * kPitch + j16 * 4] = acc[n];
     }
-    __syncthreads();
+    lds_barrier();
 
-    // ================= S: mask, log-softmax, sample, transition (16 lanes per slot)
+    // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (16 lanes per slot)
     if (alive[sj]) {
-      f32x4 lg[4];
-      uint32_t vm[4];
+      f32x4 lg[NCH];
+      uint32_t vm[NCH];
       float m = -INFINITY;
 #pragma unroll
-      for (int n = 0; n < 4; ++n) {
+      for (int n = 0; n < NCH; ++n) {
         const int c = si + 16 * n;
         vm[n] = 0;
         lg[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -263,23 +246,30 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         }
       }
       m = row16_max(m);
+      // softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
+      f32x4 wv[NCH];
       float sum = 0.f;
 #pragma unroll
-      for (int n = 0; n < 4; ++n)
+      for (int n = 0; n < NCH; ++n)
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-          if ((vm[n] >> k) & 1u) sum += expf(lg[n][k] - m);
+        for (int k = 0; k < 4; ++k) {
+          wv[n][k] = ((vm[n] >> k) & 1u) ? expf(lg[n][k] - m) : 0.f;
+          sum += wv[n][k];
+        }
       sum = row16_sum(sum);
       const float lse = logf(sum);
+      const float inv_sum = 1.f / sum;
 
       int act;
       float alogit;
       bool given_ok = true;  // teacher-forced mode: is the given action possible in this state?
       if (!REPLAY) {
-        float best = -INFINITY, blog = 0.f;
+        // Gumbel-max as an exponential race: argmax_a (l_a - log(-log u_a)) = argmin_a (-log u_a) / exp(l_a - m),
+        // one logarithm per action; lowest index wins exact ties
+        float best = INFINITY, blog = 0.f;
         int bidx = 0x7fffffff;
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
+        for (int n = 0; n < NCH; ++n) {
           const int c = si + 16 * n;
           if (vm[n]) {
             uint32_t wd[4];
@@ -287,18 +277,13 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
               if ((vm[n] >> k) & 1u) {
-                const float pert = lg[n][k] + gumbel_from_bits(wd[k]);
-                if (pert > best) { best = pert; bidx = 4 * c + k; blog = lg[n][k]; }
+                const float r = -logf(uniform_from_bits(wd[k])) / wv[n][k];
+                if (r < best) { best = r; bidx = 4 * c + k; blog = lg[n][k]; }
               }
             }
           }
         }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
-          const float ob = __shfl_xor(best, o, 16), ol = __shfl_xor(blog, o, 16);
-          const int oi = __shfl_xor(bidx, o, 16);
-          if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; blog = ol; }
-        }
+        row16_argmin(best, bidx, blog);
         act = bidx;
         alogit = blog;
       } else {
@@ -306,7 +291,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         float mine = 0.f;
         int mine_ok = 0;
 #pragma unroll
-        for (int n = 0; n < 4; ++n)
+        for (int n = 0; n < NCH; ++n)
 #pragma unroll
           for (int k = 0; k < 4; ++k)
             if (4 * (si + 16 * n) + k == act) { mine = lg[n][k]; mine_ok = (int)((vm[n] >> k) & 1u); }
@@ -319,13 +304,13 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       {  // direction of the logit gradient: onehot(a) - p on valid actions, 0 elsewhere
         float* erow = p.ebuf + ((size_t)t * B + sb) * A16;
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
+        for (int n = 0; n < NCH; ++n) {
           const int c = si + 16 * n;
           if (c < nchunk) {
             f32x4 ev;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-              ev[k] = ((vm[n] >> k) & 1u) ? ((4 * c + k == act ? 1.f : 0.f) - expf((lg[n][k] - m) - lse)) : 0.f;
+              ev[k] = ((vm[n] >> k) & 1u) ? ((4 * c + k == act ? 1.f : 0.f) - wv[n][k] * inv_sum) : 0.f;
             *(f32x4*)&erow[4 * c] = ev;
           }
         }
@@ -333,8 +318,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 
       bool term = false;
       float logr = 0.f;
-      int xi = 0;           // grid: this lane's coordinate after the step
+      int xi = 0;              // grid: this lane's coordinate after the step
       int site = 0, spin = 0;  // ising
+      int rold = 0, rnew = 0;  // the one-hot row that leaves / enters (known to all 16 lanes)
       if (REPLAY && !given_ok) {
         term = true;  // impossible action in the given sequence: cut the trajectory here, state unchanged
         if (ENV == 0) xi = (si < e.d) ? st[si * kSlots + sj] : 0;
@@ -342,12 +328,10 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       } else if (ENV == 0) {
         xi = (si < e.d) ? st[si * kSlots + sj] : 0;
         if (act != e.d) {
-          if (si == act) {
-            rowold[sj] = e.H * act + xi;
-            rownew[sj] = e.H * act + xi + 1;
-            st[si * kSlots + sj] = (int8_t)(xi + 1);
-            xi += 1;
-          }
+          const int xa = st[act * kSlots + sj];
+          rold = e.H * act + xa;
+          rnew = rold + 1;
+          if (si == act) { st[si * kSlots + sj] = (int8_t)(xi + 1); xi += 1; }
           const int cnt = row16_sum((si < e.d && xi > 0) ? 1 : 0);
           lpb -= logf((float)cnt);
         } else {
@@ -360,11 +344,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         }
       } else if (ENV == 1) {
         const int k = e.k_bits;
-        if (si == 0) {
-          st[t * kSlots + sj] = (int8_t)act;
-          rowold[sj] = ((1 << k) + 1) * t + (1 << k);
-          rownew[sj] = ((1 << k) + 1) * t + act;
-        }
+        rold = ((1 << k) + 1) * t + (1 << k);
+        rnew = ((1 << k) + 1) * t + act;
+        if (si == 0) st[t * kSlots + sj] = (int8_t)act;
         if (t == e.L - 1) {
           int dmin = 0x7fffffff;
           for (int mm = si; mm < e.n_modes; mm += 16) {
@@ -383,11 +365,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       } else {
         site = act >> 1;
         spin = 2 * (act & 1) - 1;
-        if (si == 0) {
-          st[site * kSlots + sj] = (int8_t)spin;
-          rowold[sj] = 3 * site + 1;
-          rownew[sj] = 3 * site + 1 + spin;
-        }
+        rold = 3 * site + 1;
+        rnew = 3 * site + 1 + spin;
+        if (si == 0) st[site * kSlots + sj] = (int8_t)spin;
         lpb -= logf((float)(t + 1));
         if (t == e.D - 1) {
           int acc = 0;
@@ -424,33 +404,36 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         }
         if (!REPLAY)
           for (int tt = t + 1 + si; tt < p.T; tt += 16) p.actions[(size_t)tt * B + sb] = 0xFF;
-      }
-    }
-    __syncthreads();
-
-    // ================= U: z1 += W1[new row] - W1[old row] for the slots that go on
-    for (int i = tid; i < (H1 >> 2) * kSlots; i += 256) {
-      const int fg = i >> 4, jj = i & 15;
-      if (alive[jj]) {
-        f32x4* zp = (f32x4*)&z1s[fg * kPitch + jj * 4];
-        f32x4* lp = (f32x4*)&z1l[fg * kPitch + jj * 4];
-        const f32x4 wo = *(const f32x4*)&p.W1[(size_t)rowold[jj] * H1 + 4 * fg];
-        const f32x4 wn = *(const f32x4*)&p.W1[(size_t)rownew[jj] * H1 + 4 * fg];
-        f32x4 hi = *zp, lo = *lp;
+      } else {
+        // z1 += W1[new row] - W1[old row] for this slot; the running sum is carried as hi + lo so that,
+        // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
+        const float* wo_row = p.W1 + (size_t)rold * H1;
+        const float* wn_row = p.W1 + (size_t)rnew * H1;
+        for (int fg = si; fg < (H1 >> 2); fg += 16) {
+          f32x4* zp = (f32x4*)&z1s[fg * kPitch + sj * 4];
+          f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
+          const f32x4 wo = *(const f32x4*)&wo_row[4 * fg];
+          const f32x4 wn = *(const f32x4*)&wn_row[4 * fg];
+          f32x4 hi = *zp, lo = *lp;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          // the running sum is carried as hi + lo so that, however long the walk, relu and its derivative
-          // see the correctly rounded sum of the active rows (no drift across the ReLU kink)
-          const double z = ((double)hi[k] + (double)lo[k]) - (double)wo[k] + (double)wn[k];
-          hi[k] = (float)z;
-          lo[k] = (float)(z - (double)hi[k]);
+          for (int k = 0; k < 4; ++k) {
+            const double z = ((double)hi[k] + (double)lo[k]) - (double)wo[k] + (double)wn[k];
+            hi[k] = (float)z;
+            lo[k] = (float)(z - (double)hi[k]);
+          }
+          *zp = hi;
+          *lp = lo;
         }
-        *zp = hi;
-        *lp = lo;
       }
     }
-    const int any = __syncthreads_or(tid < kSlots ? alive[tid] : 0);
-    if (!any) break;
+    lds_barrier();
+    {
+      const int4* av = (const int4*)alive;
+      const int4 a0 = av[0], a1 = av[1], a2 = av[2], a3 = av[3];
+      const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
+                      a3.y | a3.z | a3.w;
+      if (!any) break;
+    }
   }
 }
 
