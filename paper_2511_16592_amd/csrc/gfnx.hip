@@ -5,6 +5,7 @@
 
 #include "gfnx_device.h"
 #include "grad_kernels.h"
+#include "grad_kernels2.h"
 #include "rollout_kernel.h"
 
 #include <string>
@@ -54,6 +55,7 @@ struct Shapes {
   int H1, H2, A, A16, B;
   size_t rows;  // max_steps * B
   int qt3, qtot3, s3, s2, qtot2;
+  bool fast;    // hidden widths <= 256: one workgroup covers a whole operand (grad_kernels2.h)
 };
 
 struct Layout {
@@ -103,6 +105,12 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = s->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
   s->rows = (size_t)s->max_steps * (size_t)batch;
   if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+  s->fast = s->H1 <= 256 && s->H2 <= 256;
+  if (s->fast) {
+    s->s2 = 256; s->qtot2 = 256;
+    s->qt3 = s->A16 <= 32 ? 32 : 256; s->qtot3 = s->qt3; s->s3 = 256;
+    return GFNX_OK;
+  }
   // split factors of the weight-gradient contractions (over the transitions)
   const int tiles2 = ((s->H1 + 127) / 128) * ((s->H2 + 127) / 128);
   s->s2 = 1024 / tiles2; if (s->s2 > 256) s->s2 = 256; if (s->s2 < 1) s->s2 = 1;
@@ -335,68 +343,142 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     GFNX_TIMED("build_rows", st);
     hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows);
   }
-  {
-    GFNX_TIMED("scale_rows", st);
-    hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
-  }
+  Dw1Params dp = {};
+  dp.env = env_params(env, s);
+  dp.H1 = s.H1; dp.B = B;
+  dp.actions = traj->actions; dp.length = traj->length; dp.term = traj->terminal_state;
+  dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
+  const int row_tiles = (int)((s.rows + 63) / 64);
 
-  // layer 3: dW3, db3, then G2 over h2
-  {
-    const dim3 grid((s.H2 + 127) / 128, s.qtot3 / s.qt3, s.s3);
-    float* part = at<float>(ws, L.part3);
-    float* dbp = at<float>(ws, L.dbp3);
+  if (s.fast) {
+    float* part3 = at<float>(ws, L.part3);
+    float* dbp3 = at<float>(ws, L.dbp3);
+    float* part2 = at<float>(ws, L.part2);
+    float* dbp2 = at<float>(ws, L.dbp2);
+    // layer 3: dW3 = H2^T G3, db3; G3 = coef * e is formed on load
     {
       GFNX_TIMED("gemm_tn_w3", st);
-      if (s.qt3 == 32)
-        hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
-      else
-        hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+      if (s.qt3 == 32) {
+        auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
+        const int lds = 32 * (256 + 32) * 4;
+        hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                           s.qtot3, part3, dbp3);
+      } else {
+        auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
+        const int lds = 32 * (256 + 256) * 4;
+        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+        hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                           s.qtot3, part3, dbp3);
+      }
     }
-    GFNX_TIMED("reduce_w3", st);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3);
-  }
-  const int row_tiles = (int)((s.rows + 63) / 64);
-  const int gx = row_tiles < 2048 ? row_tiles : 2048;
-  {
-    GFNX_TIMED("gemm_nt_g2", st);
-    hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
-                       h2buf, s.H2, s.H2, rows, hdr);
-  }
-  // layer 2: dW2, db2, then G1 over h1
-  {
-    const dim3 grid((s.H1 + 127) / 128, s.qtot2 / 128, s.s2);
-    float* part = at<float>(ws, L.part2);
-    float* dbp = at<float>(ws, L.dbp2);
+    {
+      GFNX_TIMED("reduce_w3", st);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
+    }
+    const int nt_lds = (64 * 258 + 64) * 4;
+    const int gx = row_tiles < 512 ? row_tiles : 512;
+    {
+      GFNX_TIMED("gemm_nt_g2", st);
+      auto k = gemm_nt2_kernel<true>;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2, coef, B, rows, hdr);
+    }
     {
       GFNX_TIMED("gemm_tn_w2", st);
-      hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
+      auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
+      const int lds = 32 * (256 + 256) * 4;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(1, 1, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
+                         s.qtot2, part2, dbp2);
     }
-    GFNX_TIMED("reduce_w2", st);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(256), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2);
+    {
+      GFNX_TIMED("reduce_w2", st);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2);
+    }
+    {
+      GFNX_TIMED("gemm_nt_g1", st);
+      auto k = gemm_nt2_kernel<false>;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, coef, B, rows, hdr);
+    }
+  } else {
+    {
+      GFNX_TIMED("scale_rows", st);
+      hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
+    }
+    // layer 3: dW3, db3, then G2 over h2
+    {
+      const dim3 grid((s.H2 + 127) / 128, s.qtot3 / s.qt3, s.s3);
+      float* part = at<float>(ws, L.part3);
+      float* dbp = at<float>(ws, L.dbp3);
+      {
+        GFNX_TIMED("gemm_tn_w3", st);
+        if (s.qt3 == 32)
+          hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+        else
+          hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
+      }
+      GFNX_TIMED("reduce_w3", st);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3);
+    }
+    const int gx = row_tiles < 2048 ? row_tiles : 2048;
+    {
+      GFNX_TIMED("gemm_nt_g2", st);
+      hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
+                         h2buf, s.H2, s.H2, rows, hdr);
+    }
+    // layer 2: dW2, db2, then G1 over h1
+    {
+      const dim3 grid((s.H1 + 127) / 128, s.qtot2 / 128, s.s2);
+      float* part = at<float>(ws, L.part2);
+      float* dbp = at<float>(ws, L.dbp2);
+      {
+        GFNX_TIMED("gemm_tn_w2", st);
+        hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
+      }
+      GFNX_TIMED("reduce_w2", st);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2);
+    }
+    {
+      GFNX_TIMED("gemm_nt_g1", st);
+      hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
+                         h1buf, s.H1, s.H1, rows, hdr);
+    }
   }
-  {
-    GFNX_TIMED("gemm_nt_g1", st);
-    hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
-                       h1buf, s.H1, s.H1, rows, hdr);
-  }
-  // layer 1: scatter along each trajectory
+  // layer 1: segment sums along each trajectory
   {
     GFNX_TIMED("fill_w1", st);
     hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
     hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
   }
   GFNX_TIMED("dw1", st);
-  Dw1Params dp = {};
-  dp.env = env_params(env, s);
-  dp.H1 = s.H1; dp.B = B;
-  dp.actions = traj->actions; dp.length = traj->length; dp.term = traj->terminal_state;
-  dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
-  switch (env->kind) {
-    case GFNX_ENV_GRID: hipLaunchKernelGGL(dw1_kernel<0>, dim3(B), dim3(256), 0, st, dp); break;
-    case GFNX_ENV_BITSEQ: hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp); break;
-    default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
+  const size_t dw1_lds = (size_t)s.obs_dim * 64 * 4 + (2 * 4 * 256 + 4 * kMaxStateDim + 16) * 4 + 4 * kMaxStateDim;
+  if (dw1_lds <= 150 * 1024) {
+    const int tpg = 64;
+    const dim3 grid((B + tpg - 1) / tpg, s.H1 / 64);
+#define GFNX_DW1(E)                                                                                              \
+  {                                                                                                              \
+    auto k = dw1_lds_kernel<E>;                                                                                  \
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dw1_lds) != hipSuccess) \
+      return GFNX_E_HIP;                                                                                         \
+    hipLaunchKernelGGL(k, grid, dim3(256), dw1_lds, st, dp, tpg);                                                \
+  }
+    switch (env->kind) {
+      case GFNX_ENV_GRID: GFNX_DW1(0) break;
+      case GFNX_ENV_BITSEQ: GFNX_DW1(1) break;
+      default: GFNX_DW1(2) break;
+    }
+#undef GFNX_DW1
+  } else {
+    switch (env->kind) {
+      case GFNX_ENV_GRID: hipLaunchKernelGGL(dw1_kernel<0>, dim3(B), dim3(256), 0, st, dp); break;
+      case GFNX_ENV_BITSEQ: hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp); break;
+      default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
+    }
   }
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
 }
