@@ -456,7 +456,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
   }
   GFNX_TIMED("dw1", st);
-  const size_t dw1_lds = (size_t)s.obs_dim * 64 * 4 + (2 * 4 * 256 + 4 * kMaxStateDim + 16) * 4 + 4 * kMaxStateDim;
+  const size_t dw1_lds = (size_t)s.obs_dim * 64 * 4 + (size_t)kDw1Waves * ((2 * 256 + kMaxStateDim + 4) * 4 + kMaxStateDim);
   if (dw1_lds <= 150 * 1024) {
     const int tpg = 64;
     const dim3 grid((B + tpg - 1) / tpg, s.H1 / 64);
@@ -465,7 +465,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     auto k = dw1_lds_kernel<E>;                                                                                  \
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dw1_lds) != hipSuccess) \
       return GFNX_E_HIP;                                                                                         \
-    hipLaunchKernelGGL(k, grid, dim3(256), dw1_lds, st, dp, tpg);                                                \
+    hipLaunchKernelGGL(k, grid, dim3(1024), dw1_lds, st, dp, tpg);                                                \
   }
     switch (env->kind) {
       case GFNX_ENV_GRID: GFNX_DW1(0) break;

@@ -247,38 +247,43 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
   }
 }
 
+constexpr int kDw1Waves = 16;  // trajectories a workgroup of dw1_lds_kernel works on at a time
+
 // Layer-1 weight gradient with an LDS-private copy of a 64-feature slice of dW1 (obs_dim rows).
-// grid = (trajectory groups, H1/64); 256 threads = 4 trajectories at a time x 64 features; the row bookkeeping
+// grid = (trajectory groups, H1/64); 1024 threads = 16 trajectories at a time x 64 features; the row bookkeeping
 // of a trajectory (which one-hot row leaves / enters at each step) is rebuilt from its action bytes.
 // Segment sums as in dw1_kernel: one running sum per grid coordinate, or prefix + suffix sweeps.
 template <int ENV>
-__global__ __launch_bounds__(256) void dw1_lds_kernel(const Dw1Params p, int traj_per_group) {
+__global__ __launch_bounds__(1024) void dw1_lds_kernel(const Dw1Params p, int traj_per_group) {
   extern __shared__ float smem[];
   const EnvParams& e = p.env;
   const int rows_n = e.obs_dim;
   float* tab = smem;                                   // [obs_dim][64]
-  int* rold = (int*)(smem + (size_t)rows_n * 64);      // [4][256]
-  int* rnew = rold + 4 * 256;                          // [4][256]
-  int* rend = rnew + 4 * 256;                          // [4][kMaxStateDim]
-  int* meta = rend + 4 * kMaxStateDim;                 // [4][4]: len, nend, bad
-  int8_t* st = (int8_t*)(meta + 16);                   // [4][kMaxStateDim]
+  int* rold = (int*)(smem + (size_t)rows_n * 64);      // [16][256]
+  int* rnew = rold + kDw1Waves * 256;                  // [16][256]
+  int* rend = rnew + kDw1Waves * 256;                  // [16][kMaxStateDim]
+  int* meta = rend + kDw1Waves * kMaxStateDim;         // [16][4]: len, nend
+  int8_t* st = (int8_t*)(meta + kDw1Waves * 4);        // [16][kMaxStateDim]
   const int tid = threadIdx.x, f = tid & 63, tq = tid >> 6;
   const int H1 = p.H1, B = p.B, f0 = blockIdx.y * 64;
-  for (int i = tid; i < rows_n * 64; i += 256) tab[i] = 0.f;
+  for (int i = tid; i < rows_n * 64; i += 1024) tab[i] = 0.f;
   float dbsum = 0.f;
   const int g0 = blockIdx.x * traj_per_group;
-  for (int base = 0; base < traj_per_group; base += 4) {
+  for (int base = 0; base < traj_per_group; base += kDw1Waves) {
     const int b = g0 + base + tq;
     __syncthreads();
+    // stage the action bytes of the four trajectories in LDS (rnew doubles as the staging area)
+    int len_b = (b < B) ? p.length[b] : 0;
+    len_b = len_b < 0 ? 0 : (len_b > e.max_steps ? e.max_steps : len_b);
+    for (int t = f; t + 1 < len_b; t += 64) rnew[tq * 256 + t] = p.actions[(size_t)t * B + b];
+    __syncthreads();
     if (f == 0) {
-      int len = (b < B) ? p.length[b] : 0;
-      if (len > e.max_steps) len = e.max_steps;
-      if (len < 0) len = 0;
+      const int len = len_b;
       int bad = 0;
       int8_t* s8 = st + tq * kMaxStateDim;
       for (int s = 0; s < e.state_dim; ++s) s8[s] = 0;
       for (int t = 0; t + 1 < len; ++t) {
-        const int a = p.actions[(size_t)t * B + b];
+        const int a = rnew[tq * 256 + t];
         if (ENV == 0 ? (a >= e.d || s8[a] >= e.H - 1) : (a >= e.n_actions)) { bad = 1; break; }
         if (ENV == 0) {
           rold[tq * 256 + t] = e.H * a + s8[a];
@@ -316,18 +321,27 @@ __global__ __launch_bounds__(256) void dw1_lds_kernel(const Dw1Params p, int tra
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
       float total = 0.f;
-      for (int t = 0; t < len; ++t) {
-        const float g = g1[t * stride];
-        total += g;
+      for (int t0 = 0; t0 < len; t0 += 8) {
+        float gv[8];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] += g;
-        if (t + 1 < len) {
-          const int a = rn[t];
-          float v = 0.f;
+        for (int u = 0; u < 8; ++u) gv[u] = (t0 + u < len) ? g1[(t0 + u) * stride] : 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (i == a) { v = acc[i]; acc[i] = 0.f; }
-          atomicAdd(&tab[ro[t] * 64 + f], v);
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u;
+          if (t < len) {
+            const float g = gv[u];
+            total += g;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] += g;
+            if (t + 1 < len) {
+              const int a = rn[t];
+              float v = 0.f;
+#pragma unroll
+              for (int i = 0; i < 16; ++i)
+                if (i == a) { v = acc[i]; acc[i] = 0.f; }
+              atomicAdd(&tab[ro[t] * 64 + f], v);
+            }
+          }
         }
       }
 #pragma unroll
@@ -336,21 +350,39 @@ __global__ __launch_bounds__(256) void dw1_lds_kernel(const Dw1Params p, int tra
       dbsum += total;
     } else {
       float P = 0.f;
-      for (int t = 0; t < len; ++t) {
-        P += g1[t * stride];
-        if (t + 1 < len) atomicAdd(&tab[ro[t] * 64 + f], P);
+      for (int t0 = 0; t0 < len; t0 += 8) {
+        float gv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gv[u] = (t0 + u < len) ? g1[(t0 + u) * stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 + u;
+          if (t < len) {
+            P += gv[u];
+            if (t + 1 < len) atomicAdd(&tab[ro[t] * 64 + f], P);
+          }
+        }
       }
       for (int i = 0; i < nend; ++i) atomicAdd(&tab[re[i] * 64 + f], P);
       dbsum += P;
       float S = 0.f;
-      for (int t = len - 1; t >= 1; --t) {
-        S += g1[t * stride];
-        atomicAdd(&tab[rn[t - 1] * 64 + f], S);
+      for (int t0 = len - 1; t0 >= 1; t0 -= 8) {
+        float gv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gv[u] = (t0 - u >= 1) ? g1[(t0 - u) * stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int t = t0 - u;
+          if (t >= 1) {
+            S += gv[u];
+            atomicAdd(&tab[rn[t - 1] * 64 + f], S);
+          }
+        }
       }
     }
   }
   __syncthreads();
-  for (int i = tid; i < rows_n * 64; i += 256) {
+  for (int i = tid; i < rows_n * 64; i += 1024) {
     const float v = tab[i];
     if (v != 0.f) atomicAdd(&p.dW1[(size_t)(i >> 6) * H1 + f0 + (i & 63)], v);
   }
