@@ -55,11 +55,12 @@ struct Shapes {
   int H1, H2, A, A16, B;
   size_t rows;  // max_steps * B
   int qt3, qtot3, s3, s2, qtot2;
+  int mw1, mw2; // 64-bit sign-mask words per transition row for h1 / h2
   bool fast;    // hidden widths <= 256: one workgroup covers a whole operand (grad_kernels2.h)
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, part2, dbp2, part3, dbp3, total;
+  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, m1, m2, part2, dbp2, part3, dbp3, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -105,6 +106,8 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = s->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
   s->rows = (size_t)s->max_steps * (size_t)batch;
   if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+  s->mw1 = 4 * ((s->H1 + 255) / 256);
+  s->mw2 = 4 * ((s->H2 + 255) / 256);
   s->fast = s->H1 <= 256 && s->H2 <= 256;
   if (s->fast) {
     s->s2 = 256; s->qtot2 = 256;
@@ -133,6 +136,8 @@ Layout make_layout(const Shapes& s) {
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
   L.h2 = o; o += align256(sizeof(float) * s.rows * s.H2);
   L.e = o; o += align256(sizeof(float) * s.rows * s.A16);
+  L.m1 = o; o += align256(8 * s.rows * (size_t)s.mw1);
+  L.m2 = o; o += align256(8 * s.rows * (size_t)s.mw2);
   L.part2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.H1 * s.qtot2);
   L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
   L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
@@ -259,6 +264,8 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.actions = traj->actions; p.length = traj->length; p.term = traj->terminal_state;
   p.lpf = traj->log_pf; p.lpb = traj->log_pb; p.logr = traj->log_reward;
   p.h1buf = at<float>(ws, L.h1); p.h2buf = at<float>(ws, L.h2); p.ebuf = at<float>(ws, L.e);
+  p.m1buf = at<unsigned long long>(ws, L.m1); p.m2buf = at<unsigned long long>(ws, L.m2);
+  p.MW1 = s.mw1; p.MW2 = s.mw2;
 
   const dim3 grid((s.B + kSlots - 1) / kSlots);
   const size_t lds = rollout_lds_bytes(s);
@@ -376,13 +383,14 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
       hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
     }
-    const int nt_lds = (64 * 258 + 64) * 4;
+    const int nt_lds = (64 * 258 + 192 + 512) * 4;
     const int gx = row_tiles < 512 ? row_tiles : 512;
     {
       GFNX_TIMED("gemm_nt_g2", st);
       auto k = gemm_nt2_kernel<true>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2, coef, B, rows, hdr);
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2,
+                         at<unsigned long long>(ws, L.m2), s.mw2, coef, B, rows, hdr);
     }
     {
       GFNX_TIMED("gemm_tn_w2", st);
@@ -401,7 +409,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       GFNX_TIMED("gemm_nt_g1", st);
       auto k = gemm_nt2_kernel<false>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, coef, B, rows, hdr);
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1,
+                         at<unsigned long long>(ws, L.m1), s.mw1, coef, B, rows, hdr);
     }
   } else {
     {

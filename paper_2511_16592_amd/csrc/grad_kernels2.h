@@ -47,27 +47,36 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
   float dbacc = 0.f;
 
+  // software pipeline: row ids of chunk c+2 and rows of chunk c+1 are in flight while chunk c is multiplied
   f32x4 xr[XV], gr[GV];
-  auto load_chunk = [&](int c) {
+  int xid[XV], gid[GV];
+  auto load_ids = [&](int c) {
 #pragma unroll
     for (int m = 0; m < XV; ++m) {
-      const int i = tid + 512 * m;
-      const int r = i / (PT / 4), c4 = i % (PT / 4);
-      const int li = c * KC + r;
-      xr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (li < n && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)rows[li] * ldx + ptile * PT + 4 * c4];
+      const int li = c * KC + (tid + 512 * m) / (PT / 4);
+      xid[m] = (c < c1 && li < n) ? rows[li] : -1;
     }
 #pragma unroll
     for (int m = 0; m < GV; ++m) {
       const int i = tid + 512 * m;
-      const int r = i / (QT / 4), c4 = i % (QT / 4);
-      const int li = c * KC + r;
-      const int col = qtile * QT + 4 * c4;
+      const int li = c * KC + i / (QT / 4);
+      gid[m] = (c < c1 && i < KC * QT / 4 && li < n) ? rows[li] : -1;
+    }
+  };
+  auto load_rows = [&]() {
+#pragma unroll
+    for (int m = 0; m < XV; ++m) {
+      const int c4 = (tid + 512 * m) % (PT / 4);
+      xr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      if (xid[m] >= 0 && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)xid[m] * ldx + ptile * PT + 4 * c4];
+    }
+#pragma unroll
+    for (int m = 0; m < GV; ++m) {
+      const int col = qtile * QT + 4 * ((tid + 512 * m) % (QT / 4));
       gr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (i < KC * QT / 4 && li < n && col < ldg) {
-        const int rid = rows[li];
-        f32x4 v = *(const f32x4*)&G[(size_t)rid * ldg + col];
-        if (SCALE) v = v * coef[rid % B];
+      if (gid[m] >= 0 && col < ldg) {
+        f32x4 v = *(const f32x4*)&G[(size_t)gid[m] * ldg + col];
+        if (SCALE) v = v * coef[gid[m] % B];
         gr[m] = v;
       }
     }
@@ -85,11 +94,14 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
     }
   };
 
-  if (c0 < c1) load_chunk(c0);
+  load_ids(c0);
+  load_rows();
+  load_ids(c0 + 1);
   for (int c = c0; c < c1; ++c) {
     store_chunk();
     lds_barrier();
-    if (c + 1 < c1) load_chunk(c + 1);
+    load_rows();        // chunk c+1, ids already here
+    load_ids(c + 2);
 #pragma unroll 4
     for (int k = 0; k < KC; k += 2) {
       const int kk = k + (lane >> 5);
@@ -148,23 +160,28 @@ __global__ void reduce2_kernel(const float* __restrict__ part, int S, int P, int
   }
 }
 
-// For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [Out[i][p] > 0], in place over the stored
-// activation; contraction length K <= 256 (rows of Gin hold K floats, W rows hold Kvalid <= K).
+// For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [act[i][p] > 0], written over the stored
+// activation; the ReLU derivative comes from the 1-bit sign masks the rollout recorded (word k of a row holds
+// bit l for unit 4l+k), so the epilogue only stores.  Contraction length K <= 256 (rows of Gin hold K floats,
+// W rows hold Kvalid <= K).
 // grid = (row-tile workers (grid-stride), ceil(P/256)); 8 waves, wave w owns output columns 32w .. 32w+31.
 template <bool SCALE>
 __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__ Gin, int ldgi, int K,
                                                        const float* __restrict__ W, int Kvalid,
                                                        float* __restrict__ ActOut, int ldo, int P,
+                                                       const unsigned long long* __restrict__ mask, int MW,
                                                        const float* __restrict__ coef, int B,
                                                        const int* __restrict__ rows, const int* __restrict__ hdr) {
   constexpr int KP = 258;  // LDS row pitch in floats: even (8-byte reads) and 2 mod 32 (conflict-free rows)
   extern __shared__ float smem[];
   float* GS = smem;                    // [64][KP]
-  int* rid = (int*)(smem + 64 * KP);   // [64]
+  int* ridb = (int*)(smem + 64 * KP);  // [3][64] physical row ids of three consecutive tiles
+  uint32_t* MS = (uint32_t*)(ridb + 192);  // [64 rows][8]: the four 64-bit mask words of this column tile
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = hdr[kHdrNLive];
   const int tiles = (n + 63) >> 6;
   const int pcol = blockIdx.y * 256 + 32 * w + (lane & 31);
+  const uint32_t* mask32 = (const uint32_t*)mask + (size_t)blockIdx.y * 8;
   const int kk = lane >> 5;
 
   // B operand: step s consumes contraction index q = 4*(s/2) + 2*kk + (s%2)
@@ -176,70 +193,86 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
   }
 
   const int kv = K >> 2;               // f32x4 per row
+  // Software pipeline over the row tiles of this workgroup (it = 0, 1, ...): the row ids of tile it+2 (one
+  // register on 64 threads) and the rows + mask words of tile it+1 are in flight during the MFMAs of tile it.
+  // Row ids live in LDS, three tiles deep: ridb[it % 3].
   f32x4 pre[8];
-  int my_rid[8];
-  auto load_tile = [&](int tile) {
+  uint32_t mpre = 0;
+  int idreg = -1;
+  auto fetch_ids = [&](int tile) {  // threads 0..63
+    if (tid < 64) idreg = (tile < tiles && tile * 64 + tid < n) ? rows[tile * 64 + tid] : -1;
+  };
+  auto load_rows = [&](const int* ids) {
+    {
+      const int rr = ids[tid >> 3];    // mask tile: 64 rows x 8 words of 32 bits, one per thread
+      mpre = rr >= 0 ? mask32[(size_t)rr * MW * 2 + (tid & 7)] : 0u;
+    }
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       const int i = tid + 512 * m;     // 64 rows x 64 quads
-      const int r = i >> 6, c4 = i & 63;
-      const int li = tile * 64 + r;
+      const int rr = ids[i >> 6], c4 = i & 63;
       pre[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      my_rid[m] = -1;
-      if (li < n) {
-        const int rr = rows[li];
-        my_rid[m] = rr;
-        if (c4 < kv) {
-          f32x4 v = *(const f32x4*)&Gin[(size_t)rr * ldgi + 4 * c4];
-          if (SCALE) v = v * coef[rr % B];
-          pre[m] = v;
-        }
+      if (rr >= 0 && c4 < kv) {
+        f32x4 v = *(const f32x4*)&Gin[(size_t)rr * ldgi + 4 * c4];
+        if (SCALE) v = v * coef[rr % B];
+        pre[m] = v;
       }
     }
   };
 
   int tile = blockIdx.x;
-  if (tile < tiles) load_tile(tile);
-  for (; tile < tiles; tile += gridDim.x) {
+  fetch_ids(tile);
+  if (tid < 64) ridb[tid] = idreg;
+  lds_barrier();
+  load_rows(ridb);
+  fetch_ids(tile + gridDim.x);
+  for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+    const int* rid = ridb + 64 * (it % 3);
+    int* rid_next = ridb + 64 * ((it + 1) % 3);
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       const int i = tid + 512 * m;
-      const int r = i >> 6, c4 = i & 63;
-      float* d = &GS[r * KP + 4 * c4];
+      float* d = &GS[(i >> 6) * KP + 4 * (i & 63)];
       *(float2*)d = make_float2(pre[m].x, pre[m].y);
       *(float2*)(d + 2) = make_float2(pre[m].z, pre[m].w);
-      if (c4 == 0) rid[r] = my_rid[m];
     }
+    MS[tid] = mpre;
+    if (tid < 64) rid_next[tid] = idreg;
     lds_barrier();
-    if (tile + (int)gridDim.x < tiles) load_tile(tile + gridDim.x);
-    f32x16 acc0, acc1;
+    load_rows(rid_next);
+    fetch_ids(tile + 2 * (int)gridDim.x);
+    // the 64 rows of the tile as two passes of 32, one accumulator block live at a time
+    const int pl = 32 * w + (lane & 31);
+    const int mk = pl & 3, ml = pl >> 2;  // unit p = 4l + k of this column tile: bit l of mask word k
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      f32x16 acc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
-    const float* g0 = &GS[(lane & 31) * KP + 2 * kk];
-    const float* g1 = g0 + 32 * KP;
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const float* g0 = &GS[(32 * half + (lane & 31)) * KP + 2 * kk];
+      // K is a multiple of 16: one uniform branch per 16 contraction indices, so that inside a group the LDS
+      // reads of the later steps are issued under the MFMAs of the earlier ones
 #pragma unroll
-    for (int s2 = 0; s2 < 64; ++s2) {
-      if (4 * s2 < K) {
-        const float2 a0 = *(const float2*)&g0[4 * s2];
-        const float2 a1 = *(const float2*)&g1[4 * s2];
-        acc0 = mfma32(a0.x, wreg[2 * s2], acc0);
-        acc1 = mfma32(a1.x, wreg[2 * s2], acc1);
-        acc0 = mfma32(a0.y, wreg[2 * s2 + 1], acc0);
-        acc1 = mfma32(a1.y, wreg[2 * s2 + 1], acc1);
-      }
-    }
-    if (pcol < P) {
+      for (int grp = 0; grp < 16; ++grp) {
+        if (16 * grp < K) {
+          float2 a0[4];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = 8 * (r >> 2) + 4 * kk + (r & 3);
-        const int r0 = rid[i], r1 = rid[32 + i];
-        if (r0 >= 0) {
-          float* o = &ActOut[(size_t)r0 * ldo + pcol];
-          *o = (*o > 0.f) ? acc0[r] : 0.f;
+          for (int u = 0; u < 4; ++u) a0[u] = *(const float2*)&g0[16 * grp + 4 * u];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int s2 = 4 * grp + u;
+            acc = mfma32(a0[u].x, wreg[2 * s2], acc);
+            acc = mfma32(a0[u].y, wreg[2 * s2 + 1], acc);
+          }
         }
-        if (r1 >= 0) {
-          float* o = &ActOut[(size_t)r1 * ldo + pcol];
-          *o = (*o > 0.f) ? acc1[r] : 0.f;
+      }
+      if (pcol < P) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = 32 * half + 8 * (r >> 2) + 4 * kk + (r & 3);
+          const int r0 = rid[i];
+          const uint32_t b0 = (MS[i * 8 + 2 * mk + (ml >> 5)] >> (ml & 31)) & 1u;
+          if (r0 >= 0) ActOut[(size_t)r0 * ldo + pcol] = b0 ? acc[r] : 0.f;
         }
       }
     }

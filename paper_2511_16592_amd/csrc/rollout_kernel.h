@@ -12,8 +12,8 @@
 //       terminal log-reward, action byte; then the same lanes update the layer-1 pre-activation: layer 1
 //       is a one-hot gather and a transition swaps exactly one active row, so z1 is kept in LDS (as a
 //       high + low pair) and updated as z1 += W1[new] - W1[old].
-// The post-ReLU activations h1, h2 and the logit-gradient direction (onehot(a) - p) of every transition
-// are written to HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is
+// The post-ReLU activations h1, h2, their sign masks (1 bit per unit) and the logit-gradient direction
+// (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is
 // read back by it, so the three barriers per step order LDS traffic only (no wait for stores to land).
 #pragma once
 #include "gfnx_device.h"
@@ -39,6 +39,14 @@ __device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words,
 __device__ __forceinline__ f32x4 relu4(f32x4 v) {
   v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
   return v;
+}
+
+// Sign mask of 256 activations held four per lane (lane l: features 4l .. 4l+3): word k (k < 4) gets bit l
+// set iff feature 4l+k is positive.  This is the ReLU derivative the gradient pass needs, at 1 bit per unit.
+__device__ __forceinline__ void store_sign_mask(unsigned long long* dst, f32x4 v, int lane) {
+  const unsigned long long m0 = __ballot(v.x > 0.f), m1 = __ballot(v.y > 0.f);
+  const unsigned long long m2 = __ballot(v.z > 0.f), m3 = __ballot(v.w > 0.f);
+  if (lane < 4) dst[lane] = lane == 0 ? m0 : (lane == 1 ? m1 : (lane == 2 ? m2 : m3));
 }
 
 #define GFNX_MFMA4(ACC, AV, BV)            \
@@ -106,9 +114,17 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
     for (int jj = w; jj < kSlots; jj += 4) {
       if (!alive[jj]) continue;
-      float* dst = p.h1buf + ((size_t)t * B + b0 + jj) * H1;
-      for (int fg = lane; fg < (H1 >> 2); fg += 64)
-        *(f32x4*)&dst[fg * 4] = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
+      const size_t row = (size_t)t * B + b0 + jj;
+      float* dst = p.h1buf + row * H1;
+      for (int it = 0; it * 64 < (H1 >> 2); ++it) {
+        const int fg = lane + 64 * it;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (fg < (H1 >> 2)) {
+          v = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
+          *(f32x4*)&dst[fg * 4] = v;
+        }
+        store_sign_mask(p.m1buf + (row * p.MW1 + 4 * it), v, lane);
+      }
     }
     {
       f32x4 acc[NTW2];
@@ -150,9 +166,17 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
     // ================= L3: logits = W3^T h2 (+ b3 added in SU)
     for (int jj = w; jj < kSlots; jj += 4) {
       if (!alive[jj]) continue;
-      float* dst = p.h2buf + ((size_t)t * B + b0 + jj) * H2;
-      for (int fg = lane; fg < (H2 >> 2); fg += 64)
-        *(f32x4*)&dst[fg * 4] = *(const f32x4*)&h2s[fg * kPitch + jj * 4];
+      const size_t row = (size_t)t * B + b0 + jj;
+      float* dst = p.h2buf + row * H2;
+      for (int it = 0; it * 64 < (H2 >> 2); ++it) {
+        const int fg = lane + 64 * it;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (fg < (H2 >> 2)) {
+          v = *(const f32x4*)&h2s[fg * kPitch + jj * 4];
+          *(f32x4*)&dst[fg * 4] = v;
+        }
+        store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
+      }
     }
     if (ksplit == 1) {
       f32x4 acc[4];
