@@ -180,38 +180,30 @@ template <typename T>
 inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
 size_t rollout_lds_bytes(const Shapes& s) {
-  const int nchunk = s.A16 / 4, nt3 = s.A16 / 16;
-  const int ksplit = nt3 >= 4 ? 1 : 4;
-  size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ksplit * nchunk) * kPitch;
+  const int nchunk = s.A16 / 4;
+  const int ks = logits_ksplit(s.A16 / 16, s.H2 / 16);
+  size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ks * nchunk) * kPitch;
   return fl * sizeof(float) + kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
 }
 
 template <int ENV, bool REPLAY, int NCH>
-int launch_rollout_ntw(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
+int launch_rollout_ntw(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st) {
 #define GFNX_LAUNCH(N, STATIONARY)                                                                          \
   {                                                                                                         \
     auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH>;                                               \
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
       return GFNX_E_HIP;                                                                                    \
-    hipLaunchKernelGGL(k, grid, dim3(256), lds, st, p);                                                     \
+    hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, p);                                         \
   }
-  // Register-resident W2 is used for the grid environments only: the Ising instantiation of that variant
-  // faulted the GPU on its first run and is switched off until the cause is shown.
-  if constexpr (ENV == 0) {
-    if (p.H1 == 256 && p.H2 == 256) {
-      GFNX_LAUNCH(4, true)
-      return GFNX_OK;
-    }
+  if (p.H1 == 256 && p.H2 == 256) {  // layer 2 resident in registers
+    GFNX_LAUNCH(2, true)
+    return GFNX_OK;
   }
-  switch (ntw) {
+  switch ((p.H2 / 16 + 7) / 8) {  // 16-feature tiles of layer 2 per wave
     case 1: GFNX_LAUNCH(1, false) break;
     case 2: GFNX_LAUNCH(2, false) break;
     case 3: GFNX_LAUNCH(3, false) break;
     case 4: GFNX_LAUNCH(4, false) break;
-    case 5: GFNX_LAUNCH(5, false) break;
-    case 6: GFNX_LAUNCH(6, false) break;
-    case 7: GFNX_LAUNCH(7, false) break;
-    case 8: GFNX_LAUNCH(8, false) break;
     default: return GFNX_E_UNSUPPORTED;
   }
 #undef GFNX_LAUNCH
@@ -219,16 +211,14 @@ int launch_rollout_ntw(const RolloutParams& p, int ntw, dim3 grid, size_t lds, h
 }
 
 template <bool REPLAY>
-int launch_rollout(const RolloutParams& p, int ntw, dim3 grid, size_t lds, hipStream_t st) {
-  const bool wide = p.A16 > 64;  // more than one chunk of four logits per sampling lane
+int launch_rollout(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st) {
+  const bool wide = p.A16 > 128;  // more than one chunk of four logits per sampling lane
   switch (p.env.kind) {
-    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY, 1>(p, ntw, grid, lds, st);
+    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY, 1>(p, grid, lds, st);
     case GFNX_ENV_BITSEQ:
-      return wide ? launch_rollout_ntw<1, REPLAY, 4>(p, ntw, grid, lds, st)
-                  : launch_rollout_ntw<1, REPLAY, 1>(p, ntw, grid, lds, st);
+      return wide ? launch_rollout_ntw<1, REPLAY, 2>(p, grid, lds, st) : launch_rollout_ntw<1, REPLAY, 1>(p, grid, lds, st);
     default:
-      return wide ? launch_rollout_ntw<2, REPLAY, 4>(p, ntw, grid, lds, st)
-                  : launch_rollout_ntw<2, REPLAY, 1>(p, ntw, grid, lds, st);
+      return wide ? launch_rollout_ntw<2, REPLAY, 2>(p, grid, lds, st) : launch_rollout_ntw<2, REPLAY, 1>(p, grid, lds, st);
   }
 }
 
@@ -272,7 +262,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
   {
     GFNX_TIMED("rollout", st);
-    rc = replay ? launch_rollout<true>(p, s.H2 / 64, grid, lds, st) : launch_rollout<false>(p, s.H2 / 64, grid, lds, st);
+    rc = replay ? launch_rollout<true>(p, grid, lds, st) : launch_rollout<false>(p, grid, lds, st);
   }
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;

@@ -121,4 +121,21 @@ __device__ __forceinline__ void row16_argmin(float& key, int& idx, float& payloa
   row16_argmin_step<1>(key, idx, payload);
 }
 
+// ---- the same over 32 lanes (an aligned half of a wavefront): row reduction, then one exchange with the
+// other row of the half through the swizzle network (lane i <-> lane i ^ 16)
+__device__ __forceinline__ int swz_xor16(int v) { return __builtin_amdgcn_ds_swizzle(v, 0x401F); }
+__device__ __forceinline__ float swz_xor16(float v) {
+  return __builtin_bit_cast(float, swz_xor16(__builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ float grp32_max(float v) { v = row16_max(v); return fmaxf(v, swz_xor16(v)); }
+__device__ __forceinline__ float grp32_sum(float v) { v = row16_sum(v); return v + swz_xor16(v); }
+__device__ __forceinline__ int grp32_sum(int v) { v = row16_sum(v); return v + swz_xor16(v); }
+__device__ __forceinline__ int grp32_min(int v) { v = row16_min(v); return min(v, swz_xor16(v)); }
+__device__ __forceinline__ void grp32_argmin(float& key, int& idx, float& payload) {
+  row16_argmin(key, idx, payload);
+  const float ok = swz_xor16(key), op = swz_xor16(payload);
+  const int oi = swz_xor16(idx);
+  if (ok < key || (ok == key && oi < idx)) { key = ok; idx = oi; payload = op; }
+}
+
 }  // namespace gfnx

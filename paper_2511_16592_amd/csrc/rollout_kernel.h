@@ -1,24 +1,29 @@
 // Persistent trajectory-block rollout kernel.
 //
-// One workgroup (4 wavefronts) owns kSlots = 16 trajectories from s_0 to their terminal states.  Per step:
+// One workgroup (8 wavefronts, two per SIMD) owns kSlots = 16 trajectories from s_0 to their terminal
+// states.  Per step:
 //   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1); the
-//       four waves split the output features; weights are MFMA A-operands (resident in registers, or
-//       streamed from L2 cache in operand order with the next step's loads in flight), activations come
-//       from LDS in B-operand order;
-//   L3  logits the same way (output tiles split over the waves, or the contraction split when there are
-//       fewer than four tiles);
-//   SU  per slot, 16 lanes of one wave: action mask, softmax weights, Philox draw and argmin by
-//       row-rotation DPP, log P_F / log P_B, the row of the logit gradient, environment transition,
-//       terminal log-reward, action byte; then the same lanes update the layer-1 pre-activation: layer 1
-//       is a one-hot gather and a transition swaps exactly one active row, so z1 is kept in LDS (as a
-//       high + low pair) and updated as z1 += W1[new] - W1[old].
+//       eight waves split the output features; weights are MFMA A-operands (resident in registers when the
+//       layer is 256 x 256: 128 registers per lane, or streamed from L2 cache in operand order with the next
+//       step's loads in flight), activations come from LDS in B-operand order;
+//   L3  logits the same way: output tiles split over the waves, and the contraction split as well when there
+//       are fewer than eight tiles;
+//   SU  per slot, 32 lanes of one wave: action mask, softmax weights, Philox draw and argmin by DPP row
+//       rotations plus one swizzle, log P_F / log P_B, the row of the logit gradient, environment
+//       transition, terminal log-reward, action byte; then the same lanes update the layer-1
+//       pre-activation: layer 1 is a one-hot gather and a transition swaps exactly one active row, so z1 is
+//       kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
 // The post-ReLU activations h1, h2, their sign masks (1 bit per unit) and the logit-gradient direction
-// (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is
-// read back by it, so the three barriers per step order LDS traffic only (no wait for stores to land).
+// (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the
+// kernel writes to global memory is read back by it, so the three barriers per step order LDS traffic only
+// (no wait for stores to land).
 #pragma once
 #include "gfnx_device.h"
 
 namespace gfnx {
+
+constexpr int kRolloutWaves = 8;
+constexpr int kRolloutThreads = 64 * kRolloutWaves;
 
 template <int ENV>
 __device__ __forceinline__ int initial_row(const EnvParams& e, int s) {
@@ -49,40 +54,50 @@ __device__ __forceinline__ void store_sign_mask(unsigned long long* dst, f32x4 v
   if (lane < 4) dst[lane] = lane == 0 ? m0 : (lane == 1 ? m1 : (lane == 2 ? m2 : m3));
 }
 
+// How the logits GEMM is split over the eight waves: with at least eight 16-logit tiles each wave takes
+// whole tiles; otherwise the contraction is cut into KS parts so that (tiles x KS) fills the waves.
+__host__ __device__ inline int logits_ksplit(int nt3, int q2) {
+  if (nt3 >= 8) return 1;
+  int ks = 1;
+  while (ks * 2 * nt3 <= 8 && q2 % (ks * 2) == 0) ks *= 2;
+  return ks;
+}
+
 #define GFNX_MFMA4(ACC, AV, BV)            \
   ACC = mfma16((AV).x, (BV).x, ACC);       \
   ACC = mfma16((AV).y, (BV).y, ACC);       \
   ACC = mfma16((AV).z, (BV).z, ACC);       \
   ACC = mfma16((AV).w, (BV).w, ACC)
 
-// STAT (H1 = H2 = 256): each wave keeps its 64-feature slice of W2 (64 KiB, 256 registers per lane) in
-// registers for the whole rollout; with a single 16-logit tile (grids) its quarter of W3 stays there too.
-// NCH = logit chunks (of 4 actions) a lane may own: 1 when the action space fits 64 logits, else 4.
-template <int ENV, bool REPLAY, int NTW2, bool STAT, int NCH>
-__global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
+// NTW  = 16-feature tiles of layer 2 per wave, ceil(H2 / 128).
+// STAT = layer 2 is 256 x 256: each wave keeps its two tiles of W2 (32 KiB, 128 registers per lane) in
+//        registers for the whole rollout; with a single logit tile (grids) its eighth of W3 as well.
+// NCH  = chunks of four logits a lane may own in SU: 1 up to 128 actions, else 2.
+template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH>
+__global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutParams p) {
   extern __shared__ float smem[];
   const EnvParams& e = p.env;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int g = lane >> 4, j16 = lane & 15;
   const int H1 = p.H1, H2 = p.H2, A = p.A, A16 = p.A16, B = p.B;
   const int Q1 = H1 >> 4, Q2 = H2 >> 4;
-  const int NT3 = A16 >> 4, nchunk = A16 >> 2;
-  const int ksplit = NT3 >= 4 ? 1 : 4;
+  const int NT2 = H2 >> 4, NT3 = A16 >> 4, nchunk = A16 >> 2;
+  const int KS = logits_ksplit(NT3, Q2);
 
   float* z1s = smem;                          // pre-activation of layer 1, high part
   float* z1l = z1s + (H1 >> 2) * kPitch;      // ... low part (z1 = hi + lo carries the sum to ~48 bits)
   float* h2s = z1l + (H1 >> 2) * kPitch;
-  float* lgs = h2s + (H2 >> 2) * kPitch;
-  int* alive = (int*)(lgs + ksplit * nchunk * kPitch);
+  float* lgs = h2s + (H2 >> 2) * kPitch;      // [KS][nchunk] partial logits
+  int* alive = (int*)(lgs + KS * nchunk * kPitch);
   int8_t* st = (int8_t*)(alive + kSlots);
 
   const int b0 = blockIdx.x * kSlots;
-  // roles in the sampling phase: 16 lanes (sub-lane si) of one wave per slot sj
-  const int sj = 4 * w + g, si = j16;
+  // roles in the SU phase: 32 lanes (sub-lane si) of one wave per slot sj
+  const int sj = 2 * w + (lane >> 5), si = lane & 31;
   const int sb = b0 + sj;
 
   // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows
-  for (int f = tid; f < H1; f += 256) {
+  for (int f = tid; f < H1; f += kRolloutThreads) {
     double z = (double)p.b1[f];
     for (int s = 0; s < e.state_dim; ++s) z += (double)p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
     const float hi = (float)z, lo = (float)(z - (double)hi);
@@ -91,28 +106,28 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dl[j * 4] = lo; }
   }
-  for (int i = tid; i < e.state_dim * kSlots; i += 256) st[i] = 0;
+  for (int i = tid; i < e.state_dim * kSlots; i += kRolloutThreads) st[i] = 0;
   if (tid < kSlots) alive[tid] = (b0 + tid < B) ? 1 : 0;
   float lpf = 0.f, lpb = 0.f;
   int len_given = 0;
   if (REPLAY && sb < B) len_given = p.length[sb];
-  f32x4 w2r[STAT ? 4 : 1][STAT ? 16 : 1];
-  f32x4 w3r[STAT ? 4 : 1];
+  f32x4 w2r[STAT ? 2 : 1][STAT ? 16 : 1];
+  f32x4 w3r[STAT ? 2 : 1];
   if constexpr (STAT) {
-    const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * 4) * 16 * 64 + lane;
+    const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * 2) * 16 * 64 + lane;
 #pragma unroll
-    for (int n = 0; n < 4; ++n)
+    for (int n = 0; n < 2; ++n)
 #pragma unroll
       for (int q = 0; q < 16; ++q) w2r[n][q] = wp[(n * 16 + q) * 64];
-    const f32x4* wp3 = (const f32x4*)p.W3p + lane;  // tile 0, this wave's quarter of the contraction
+    const f32x4* wp3 = (const f32x4*)p.W3p + lane;  // tile 0, this wave's eighth of the contraction
 #pragma unroll
-    for (int q = 0; q < 4; ++q) w3r[q] = wp3[(w * 4 + q) * 64];
+    for (int q = 0; q < 2; ++q) w3r[q] = wp3[(w * 2 + q) * 64];
   }
   lds_barrier();
 
   for (int t = 0; t < e.max_steps; ++t) {
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
-    for (int jj = w; jj < kSlots; jj += 4) {
+    for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
       if (!alive[jj]) continue;
       const size_t row = (size_t)t * B + b0 + jj;
       float* dst = p.h1buf + row * H1;
@@ -127,44 +142,50 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       }
     }
     {
-      f32x4 acc[NTW2];
+      f32x4 acc[NTW];
 #pragma unroll
-      for (int n = 0; n < NTW2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int n = 0; n < NTW; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if constexpr (STAT) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
           const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
 #pragma unroll
-          for (int n = 0; n < 4; ++n) { GFNX_MFMA4(acc[n], w2r[n][q], bv); }
+          for (int n = 0; n < 2; ++n) { GFNX_MFMA4(acc[n], w2r[n][q], bv); }
         }
-      } else {
-        const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * NTW2) * Q1 * 64 + lane;
-        f32x4 cur[NTW2];
+      } else if (w * NTW < NT2) {
+        // tiles w*NTW .. w*NTW+NTW-1 (clamped: a clamped tile is computed twice and stored once)
+        const f32x4* wp = (const f32x4*)p.W2p + lane;
+        int tn[NTW];
 #pragma unroll
-        for (int n = 0; n < NTW2; ++n) cur[n] = wp[((size_t)n * Q1) * 64];
+        for (int n = 0; n < NTW; ++n) tn[n] = min(w * NTW + n, NT2 - 1);
+        f32x4 cur[NTW];
+#pragma unroll
+        for (int n = 0; n < NTW; ++n) cur[n] = wp[((size_t)tn[n] * Q1) * 64];
         for (int q = 0; q < Q1; ++q) {
           const int qn = q + 1 < Q1 ? q + 1 : q;
-          f32x4 nxt[NTW2];
+          f32x4 nxt[NTW];
 #pragma unroll
-          for (int n = 0; n < NTW2; ++n) nxt[n] = wp[((size_t)n * Q1 + qn) * 64];
+          for (int n = 0; n < NTW; ++n) nxt[n] = wp[((size_t)tn[n] * Q1 + qn) * 64];
           const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
 #pragma unroll
-          for (int n = 0; n < NTW2; ++n) { GFNX_MFMA4(acc[n], cur[n], bv); }
+          for (int n = 0; n < NTW; ++n) { GFNX_MFMA4(acc[n], cur[n], bv); }
 #pragma unroll
-          for (int n = 0; n < NTW2; ++n) cur[n] = nxt[n];
+          for (int n = 0; n < NTW; ++n) cur[n] = nxt[n];
         }
       }
 #pragma unroll
-      for (int n = 0; n < NTW2; ++n) {
-        const int nt = w * NTW2 + n;
-        const f32x4 bias = *(const f32x4*)&p.b2[16 * nt + 4 * g];
-        *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + bias);
+      for (int n = 0; n < NTW; ++n) {
+        const int nt = w * NTW + n;
+        if (nt < NT2) {
+          const f32x4 bias = *(const f32x4*)&p.b2[16 * nt + 4 * g];
+          *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + bias);
+        }
       }
     }
     lds_barrier();
 
     // ================= L3: logits = W3^T h2 (+ b3 added in SU)
-    for (int jj = w; jj < kSlots; jj += 4) {
+    for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
       if (!alive[jj]) continue;
       const size_t row = (size_t)t * B + b0 + jj;
       float* dst = p.h2buf + row * H2;
@@ -178,77 +199,66 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
       }
     }
-    if (ksplit == 1) {
-      f32x4 acc[4];
+    if (KS == 1) {
+      // whole tiles: w and w + 8
+      f32x4 acc[2];
 #pragma unroll
-      for (int n = 0; n < 4; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const f32x4* wp = (const f32x4*)p.W3p + lane;
-      f32x4 cur[4];
-#pragma unroll
-      for (int n = 0; n < 4; ++n) cur[n] = wp[((size_t)min(w + 4 * n, NT3 - 1) * Q2) * 64];
-      for (int q = 0; q < Q2; ++q) {
-        const int qn = q + 1 < Q2 ? q + 1 : q;
-        f32x4 nxt[4];
-#pragma unroll
-        for (int n = 0; n < 4; ++n) nxt[n] = wp[((size_t)min(w + 4 * n, NT3 - 1) * Q2 + qn) * 64];
-        const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-          if (w + 4 * n < NT3) { GFNX_MFMA4(acc[n], cur[n], bv); }
+      for (int n = 0; n < 2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      if (w < NT3) {
+        const f32x4* wp = (const f32x4*)p.W3p + lane;
+        const int t0 = w, t1 = min(w + 8, NT3 - 1);
+        f32x4 c0 = wp[((size_t)t0 * Q2) * 64], c1 = wp[((size_t)t1 * Q2) * 64];
+        for (int q = 0; q < Q2; ++q) {
+          const int qn = q + 1 < Q2 ? q + 1 : q;
+          const f32x4 n0 = wp[((size_t)t0 * Q2 + qn) * 64], n1 = wp[((size_t)t1 * Q2 + qn) * 64];
+          const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+          GFNX_MFMA4(acc[0], c0, bv);
+          if (w + 8 < NT3) { GFNX_MFMA4(acc[1], c1, bv); }
+          c0 = n0; c1 = n1;
         }
-#pragma unroll
-        for (int n = 0; n < 4; ++n) cur[n] = nxt[n];
-      }
-#pragma unroll
-      for (int n = 0; n < 4; ++n) {
-        const int nt = w + 4 * n;
-        if (nt < NT3) *(f32x4*)&lgs[(4 * nt + g) * kPitch + j16 * 4] = acc[n];
+        *(f32x4*)&lgs[(4 * w + g) * kPitch + j16 * 4] = acc[0];
+        if (w + 8 < NT3) *(f32x4*)&lgs[(4 * (w + 8) + g) * kPitch + j16 * 4] = acc[1];
       }
     } else {
-      f32x4 acc[3];
+      // wave w: tile w / KS, contraction part w % KS
+      const int nt = w / KS, ks = w - nt * KS;
+      if (nt < NT3) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        const int qn = Q2 / KS;
+        if (STAT && NT3 == 1 && KS == 8) {
 #pragma unroll
-      for (int n = 0; n < 3; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (STAT && NT3 == 1) {
-#pragma unroll
-        for (int q = 0; q < (STAT ? 4 : 1); ++q) {
-          const f32x4 bv = *(const f32x4*)&h2s[(4 * (w * 4 + q) + g) * kPitch + j16 * 4];
-          GFNX_MFMA4(acc[0], w3r[q], bv);
-        }
-      } else {
-        const f32x4* wp = (const f32x4*)p.W3p + lane;
-        const int qn = Q2 >> 2;
-        for (int q = w * qn; q < (w + 1) * qn; ++q) {
-          const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
-#pragma unroll
-          for (int n = 0; n < 3; ++n) {
-            if (n < NT3) {
-              const f32x4 av = wp[((size_t)n * Q2 + q) * 64];
-              GFNX_MFMA4(acc[n], av, bv);
-            }
+          for (int q = 0; q < (STAT ? 2 : 1); ++q) {
+            const f32x4 bv = *(const f32x4*)&h2s[(4 * (w * 2 + q) + g) * kPitch + j16 * 4];
+            GFNX_MFMA4(acc, w3r[q], bv);
+          }
+        } else {
+          const f32x4* wp = (const f32x4*)p.W3p + lane;
+          for (int q = ks * qn; q < (ks + 1) * qn; ++q) {
+            const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+            const f32x4 av = wp[((size_t)nt * Q2 + q) * 64];
+            GFNX_MFMA4(acc, av, bv);
           }
         }
+        *(f32x4*)&lgs[(ks * nchunk + 4 * nt + g) * kPitch + j16 * 4] = acc;
       }
-#pragma unroll
-      for (int n = 0; n < 3; ++n)
-        if (n < NT3) *(f32x4*)&lgs[(w * nchunk + 4 * n + g) * kPitch + j16 * 4] = acc[n];
     }
     lds_barrier();
 
-    // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (16 lanes per slot)
+    // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (32 lanes per slot)
     if (alive[sj]) {
       f32x4 lg[NCH];
       uint32_t vm[NCH];
       float m = -INFINITY;
 #pragma unroll
       for (int n = 0; n < NCH; ++n) {
-        const int c = si + 16 * n;
+        const int c = si + 32 * n;
         vm[n] = 0;
         lg[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
         if (c < nchunk) {
           f32x4 v;
 #pragma unroll
           for (int k = 0; k < 4; ++k) v[k] = (4 * c + k < A) ? p.b3[4 * c + k] : 0.f;
-          for (int ks = 0; ks < ksplit; ++ks) v += *(const f32x4*)&lgs[(ks * nchunk + c) * kPitch + sj * 4];
+          for (int ks = 0; ks < KS; ++ks) v += *(const f32x4*)&lgs[(ks * nchunk + c) * kPitch + sj * 4];
           lg[n] = v;
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
@@ -269,7 +279,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           }
         }
       }
-      m = row16_max(m);
+      m = grp32_max(m);
       // softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
       f32x4 wv[NCH];
       float sum = 0.f;
@@ -280,7 +290,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           wv[n][k] = ((vm[n] >> k) & 1u) ? expf(lg[n][k] - m) : 0.f;
           sum += wv[n][k];
         }
-      sum = row16_sum(sum);
+      sum = grp32_sum(sum);
       const float lse = logf(sum);
       const float inv_sum = 1.f / sum;
 
@@ -294,7 +304,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         int bidx = 0x7fffffff;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-          const int c = si + 16 * n;
+          const int c = si + 32 * n;
           if (vm[n]) {
             uint32_t wd[4];
             philox4x32_10((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
@@ -307,7 +317,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
             }
           }
         }
-        row16_argmin(best, bidx, blog);
+        grp32_argmin(best, bidx, blog);
         act = bidx;
         alogit = blog;
       } else {
@@ -318,9 +328,9 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         for (int n = 0; n < NCH; ++n)
 #pragma unroll
           for (int k = 0; k < 4; ++k)
-            if (4 * (si + 16 * n) + k == act) { mine = lg[n][k]; mine_ok = (int)((vm[n] >> k) & 1u); }
-        alogit = __shfl(mine, (act >> 2) & 15, 16);
-        given_ok = __shfl(mine_ok, (act >> 2) & 15, 16) != 0;
+            if (4 * (si + 32 * n) + k == act) { mine = lg[n][k]; mine_ok = (int)((vm[n] >> k) & 1u); }
+        alogit = __shfl(mine, (act >> 2) & 31, 32);
+        given_ok = __shfl(mine_ok, (act >> 2) & 31, 32) != 0;
         if (!given_ok) { act = 0; alogit = m + lse; }  // log p = 0; the trajectory is cut below
       }
       lpf += (alogit - m) - lse;
@@ -329,7 +339,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         float* erow = p.ebuf + ((size_t)t * B + sb) * A16;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-          const int c = si + 16 * n;
+          const int c = si + 32 * n;
           if (c < nchunk) {
             f32x4 ev;
 #pragma unroll
@@ -344,7 +354,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
       float logr = 0.f;
       int xi = 0;              // grid: this lane's coordinate after the step
       int site = 0, spin = 0;  // ising
-      int rold = 0, rnew = 0;  // the one-hot row that leaves / enters (known to all 16 lanes)
+      int rold = 0, rnew = 0;  // the one-hot row that leaves / enters (known to all lanes of the slot)
       if (REPLAY && !given_ok) {
         term = true;  // impossible action in the given sequence: cut the trajectory here, state unchanged
         if (ENV == 0) xi = (si < e.d) ? st[si * kSlots + sj] : 0;
@@ -356,12 +366,12 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           rold = e.H * act + xa;
           rnew = rold + 1;
           if (si == act) { st[si * kSlots + sj] = (int8_t)(xi + 1); xi += 1; }
-          const int cnt = row16_sum((si < e.d && xi > 0) ? 1 : 0);
+          const int cnt = grp32_sum((si < e.d && xi > 0) ? 1 : 0);
           lpb -= logf((float)cnt);
         } else {
           const float v = fabsf((float)xi / (float)(e.H - 1) - 0.5f);
-          const int bad1 = row16_sum((si < e.d && !(0.25f < v)) ? 1 : 0);
-          const int bad2 = row16_sum((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
+          const int bad1 = grp32_sum((si < e.d && !(0.25f < v)) ? 1 : 0);
+          const int bad2 = grp32_sum((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
           const float r = e.r0 + e.r1 * (bad1 == 0 ? 1.f : 0.f) + e.r2 * (bad2 == 0 ? 1.f : 0.f);
           logr = logf(r);
           term = true;
@@ -373,7 +383,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         if (si == 0) st[t * kSlots + sj] = (int8_t)act;
         if (t == e.L - 1) {
           int dmin = 0x7fffffff;
-          for (int mm = si; mm < e.n_modes; mm += 16) {
+          for (int mm = si; mm < e.n_modes; mm += 32) {
             int dist = 0;
             for (int pos = 0; pos < e.L; ++pos) {
               const uint32_t tok = (pos == t) ? (uint32_t)act : (uint32_t)(uint8_t)st[pos * kSlots + sj];
@@ -382,7 +392,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
             }
             dmin = min(dmin, dist);
           }
-          dmin = row16_min(dmin);
+          dmin = grp32_min(dmin);
           logr = -(e.beta / (float)e.n_bits) * (float)dmin;
           term = true;
         }
@@ -395,7 +405,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
         lpb -= logf((float)(t + 1));
         if (t == e.D - 1) {
           int acc = 0;
-          for (int s = si; s < e.D; s += 16) {
+          for (int s = si; s < e.D; s += 32) {
             const int r = s / e.N, c = s - r * e.N;
             const int sr = r * e.N + (c + 1 == e.N ? 0 : c + 1);
             const int sd = (r + 1 == e.N ? 0 : r + 1) * e.N + c;
@@ -404,7 +414,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
             const int xd = (sd == site) ? spin : st[sd * kSlots + sj];
             acc += x * (xr + xd);
           }
-          acc = row16_sum(acc);
+          acc = grp32_sum(acc);
           logr = e.coupling * (float)acc;
           term = true;
         }
@@ -419,7 +429,7 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           p.logr[sb] = logr;
           alive[sj] = 0;
         }
-        for (int s = si; s < e.state_dim; s += 16) {
+        for (int s = si; s < e.state_dim; s += 32) {
           int v;
           if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
           else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)st[s * kSlots + sj];
@@ -427,13 +437,13 @@ __global__ __launch_bounds__(256) void rollout_kernel(const RolloutParams p) {
           p.term[(size_t)s * B + sb] = (int8_t)v;
         }
         if (!REPLAY)
-          for (int tt = t + 1 + si; tt < p.T; tt += 16) p.actions[(size_t)tt * B + sb] = 0xFF;
+          for (int tt = t + 1 + si; tt < p.T; tt += 32) p.actions[(size_t)tt * B + sb] = 0xFF;
       } else {
         // z1 += W1[new row] - W1[old row] for this slot; the running sum is carried as hi + lo so that,
         // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
         const float* wo_row = p.W1 + (size_t)rold * H1;
         const float* wn_row = p.W1 + (size_t)rnew * H1;
-        for (int fg = si; fg < (H1 >> 2); fg += 16) {
+        for (int fg = si; fg < (H1 >> 2); fg += 32) {
           f32x4* zp = (f32x4*)&z1s[fg * kPitch + sj * 4];
           f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
           const f32x4 wo = *(const f32x4*)&wo_row[4 * fg];
