@@ -183,7 +183,8 @@ size_t rollout_lds_bytes(const Shapes& s) {
   const int nchunk = s.A16 / 4;
   const int ks = logits_ksplit(s.A16 / 16, s.H2 / 16);
   size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ks * nchunk) * kPitch;
-  return fl * sizeof(float) + kSlots * sizeof(int) + (size_t)s.state_dim * kSlots;
+  fl += 2 * (size_t)s.H1;  // z1(s_0) for restarting slots
+  return fl * sizeof(float) + (2 * kSlots + 4) * sizeof(int) + (size_t)s.state_dim * kSlots;
 }
 
 template <int ENV, bool REPLAY, int NCH>
@@ -257,7 +258,12 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.m1buf = at<unsigned long long>(ws, L.m1); p.m2buf = at<unsigned long long>(ws, L.m2);
   p.MW1 = s.mw1; p.MW2 = s.mw2;
 
-  const dim3 grid((s.B + kSlots - 1) / kSlots);
+  // Each workgroup owns a contiguous range of trajectories and runs them 16 at a time; ranges longer than 16
+  // (large batches) let a slot start the next trajectory as soon as its current one ends.
+  int tpw = kSlots * ((s.B + 256 * kSlots - 1) / (256 * kSlots));
+  if (tpw > 128) tpw = 128;
+  p.tpw = tpw;
+  const dim3 grid((s.B + tpw - 1) / tpw);
   const size_t lds = rollout_lds_bytes(s);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
   {
@@ -370,11 +376,11 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     }
     {
       GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
     }
     const int nt_lds = (64 * 258 + 192 + 512) * 4;
-    const int gx = row_tiles < 512 ? row_tiles : 512;
+    const int gx = row_tiles < 256 ? row_tiles : 256;  // persistent: one workgroup per CU
     {
       GFNX_TIMED("gemm_nt_g2", st);
       auto k = gemm_nt2_kernel<true>;
@@ -392,8 +398,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     }
     {
       GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
     }
     {
       GFNX_TIMED("gemm_nt_g1", st);
@@ -420,8 +426,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
           hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
       }
       GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3, (const int*)nullptr);
     }
     const int gx = row_tiles < 2048 ? row_tiles : 2048;
     {
@@ -439,8 +445,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
       }
       GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2, (const int*)nullptr);
     }
     {
       GFNX_TIMED("gemm_nt_g1", st);

@@ -32,6 +32,7 @@ struct RolloutParams {
   const float *W2p, *W3p;  // weights re-laid-out as MFMA A-operands
   uint32_t seed_lo, seed_hi, iter_lo;
   int B, T;  // batch, traj.max_steps
+  int tpw;   // trajectories owned by one workgroup (multiple of kSlots)
   uint8_t* actions;
   int* length;
   int8_t* term;

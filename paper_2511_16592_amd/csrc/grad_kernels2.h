@@ -17,6 +17,13 @@
 
 namespace gfnx {
 
+// The live transitions are cut into chunks of 32 rows and the chunks into at most S parts of at least 4
+// chunks each, so that short batches do not pay for S partial tiles.
+__device__ __forceinline__ int split_chunks_per_part(int chunks, int S) {
+  const int per = (chunks + S - 1) / S;
+  return per < 4 ? 4 : per;
+}
+
 template <int WP, int WQ, int PBW, int QBW, bool SCALE>
 __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__ X, int ldx, int P,
                                                        const float* __restrict__ G, int ldg,
@@ -34,8 +41,9 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
   const int ptile = blockIdx.x, qtile = blockIdx.y, s = blockIdx.z, S = gridDim.z;
   const int n = hdr[kHdrNLive];
   const int chunks = (n + KC - 1) / KC;
-  const int per = (chunks + S - 1) / S;
+  const int per = split_chunks_per_part(chunks, S);
   const int c0 = s * per, c1 = min(chunks, c0 + per);
+  if (c0 >= c1) return;  // parts beyond the live transitions write nothing; the reduction skips them too
   const int pbase = (w / WQ) * PBW * 32, qbase = (w % WQ) * QBW * 32;
 
   f32x16 acc[PBW][QBW];
@@ -136,7 +144,13 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
 }
 
 // out[p*Q + q] = sum_s part[s][p][q], q < Q; four outputs per thread, eight partials in flight.
-__global__ void reduce2_kernel(const float* __restrict__ part, int S, int P, int QTOT, int Q, float* __restrict__ out) {
+__global__ void reduce2_kernel(const float* __restrict__ part, int S, int P, int QTOT, int Q, float* __restrict__ out,
+                               const int* __restrict__ hdr) {
+  if (hdr) {  // partials come from gemm_tn2_kernel: only the parts that hold live transitions were written
+    const int chunks = (hdr[kHdrNLive] + 31) / 32;
+    const int per = split_chunks_per_part(chunks, S);
+    S = (chunks + per - 1) / per;
+  }
   const int qv = QTOT >> 2;
   const size_t total = (size_t)P * qv;
   const size_t stride = (size_t)P * QTOT;

@@ -1,7 +1,9 @@
 // Persistent trajectory-block rollout kernel.
 //
-// One workgroup (8 wavefronts, two per SIMD) owns kSlots = 16 trajectories from s_0 to their terminal
-// states.  Per step:
+// One workgroup (8 wavefronts, two per SIMD) runs kSlots = 16 trajectories at a time from s_0 to their
+// terminal states; it owns a contiguous range of p.tpw trajectories and a slot whose trajectory has ended
+// starts the next one of the range (trajectory b is a pure function of (seed, iteration, b), so which slot
+// runs it changes nothing).  Per step:
 //   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1); the
 //       eight waves split the output features; weights are MFMA A-operands (resident in registers when the
 //       layer is 256 x 256: 128 registers per lane, or streamed from L2 cache in operand order with the next
@@ -88,13 +90,18 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   float* z1l = z1s + (H1 >> 2) * kPitch;      // ... low part (z1 = hi + lo carries the sum to ~48 bits)
   float* h2s = z1l + (H1 >> 2) * kPitch;
   float* lgs = h2s + (H2 >> 2) * kPitch;      // [KS][nchunk] partial logits
-  int* alive = (int*)(lgs + KS * nchunk * kPitch);
-  int8_t* st = (int8_t*)(alive + kSlots);
+  float* z1i = lgs + KS * nchunk * kPitch;    // z1(s_0): [2][H1] high and low parts, for slots that restart
+  int* alive = (int*)(z1i + 2 * H1);          // [kSlots] slot is running a trajectory
+  int* srow = alive + kSlots;                 // [kSlots] row t*B + b of the slot's current transition
+  int* qnext = srow + kSlots;                 // next trajectory of this workgroup's range to start
+  int8_t* st = (int8_t*)(qnext + 4);
 
-  const int b0 = blockIdx.x * kSlots;
+  const int b0 = blockIdx.x * p.tpw;                    // this workgroup's trajectories: [b0, bend)
+  const int bend = min(B, b0 + p.tpw);
   // roles in the SU phase: 32 lanes (sub-lane si) of one wave per slot sj
   const int sj = 2 * w + (lane >> 5), si = lane & 31;
-  const int sb = b0 + sj;
+  int sb = b0 + sj;                                     // trajectory in this slot
+  int ts = 0;                                           // its step counter
 
   // ---- reset: s_0, z1(s_0) = b1 + sum of the initially active rows
   for (int f = tid; f < H1; f += kRolloutThreads) {
@@ -105,12 +112,18 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     float* dl = z1l + (f >> 2) * kPitch + (f & 3);
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dl[j * 4] = lo; }
+    z1i[f] = hi;
+    z1i[H1 + f] = lo;
   }
   for (int i = tid; i < e.state_dim * kSlots; i += kRolloutThreads) st[i] = 0;
-  if (tid < kSlots) alive[tid] = (b0 + tid < B) ? 1 : 0;
+  if (tid < kSlots) {
+    alive[tid] = (b0 + tid < bend) ? 1 : 0;
+    srow[tid] = b0 + tid;
+  }
+  if (tid == 0) *qnext = b0 + kSlots;
   float lpf = 0.f, lpb = 0.f;
   int len_given = 0;
-  if (REPLAY && sb < B) len_given = p.length[sb];
+  if (REPLAY && sb < bend) len_given = p.length[sb];
   f32x4 w2r[STAT ? 2 : 1][STAT ? 16 : 1];
   f32x4 w3r[STAT ? 2 : 1];
   if constexpr (STAT) {
@@ -125,11 +138,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   }
   lds_barrier();
 
-  for (int t = 0; t < e.max_steps; ++t) {
+  // list-scheduling bound on the number of steps: (sum of lengths) / kSlots + longest trajectory
+  const int max_iters = e.max_steps * ((p.tpw + kSlots - 1) / kSlots + 1);
+  for (int iter = 0; iter < max_iters; ++iter) {
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
     for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
       if (!alive[jj]) continue;
-      const size_t row = (size_t)t * B + b0 + jj;
+      const size_t row = (size_t)srow[jj];
       float* dst = p.h1buf + row * H1;
       for (int it = 0; it * 64 < (H1 >> 2); ++it) {
         const int fg = lane + 64 * it;
@@ -187,7 +202,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     // ================= L3: logits = W3^T h2 (+ b3 added in SU)
     for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
       if (!alive[jj]) continue;
-      const size_t row = (size_t)t * B + b0 + jj;
+      const size_t row = (size_t)srow[jj];
       float* dst = p.h2buf + row * H2;
       for (int it = 0; it * 64 < (H2 >> 2); ++it) {
         const int fg = lane + 64 * it;
@@ -246,6 +261,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 
     // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (32 lanes per slot)
     if (alive[sj]) {
+      const int t = ts;
       f32x4 lg[NCH];
       uint32_t vm[NCH];
       float m = -INFINITY;
@@ -427,7 +443,6 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           p.lpf[sb] = lpf;
           p.lpb[sb] = lpb;
           p.logr[sb] = logr;
-          alive[sj] = 0;
         }
         for (int s = si; s < e.state_dim; s += 32) {
           int v;
@@ -438,7 +453,28 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
         if (!REPLAY)
           for (int tt = t + 1 + si; tt < p.T; tt += 32) p.actions[(size_t)tt * B + sb] = 0xFF;
+        // the slot starts the next trajectory of the workgroup's range, if any is left
+        int nb = 0;
+        if (si == 0) nb = atomicAdd(qnext, 1);
+        nb = __shfl(nb, 0, 32);
+        if (nb < bend) {
+          sb = nb;
+          ts = 0;
+          lpf = 0.f;
+          lpb = 0.f;
+          if (REPLAY) len_given = p.length[sb];
+          for (int s2 = si; s2 < e.state_dim; s2 += 32) st[s2 * kSlots + sj] = 0;
+          for (int fg = si; fg < (H1 >> 2); fg += 32) {
+            *(f32x4*)&z1s[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
+            *(f32x4*)&z1l[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[H1 + 4 * fg];
+          }
+          if (si == 0) srow[sj] = sb;
+        } else if (si == 0) {
+          alive[sj] = 0;
+        }
       } else {
+        ts = t + 1;
+        if (si == 0) srow[sj] = ts * B + sb;
         // z1 += W1[new row] - W1[old row] for this slot; the running sum is carried as hi + lo so that,
         // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
         const float* wo_row = p.W1 + (size_t)rold * H1;
