@@ -56,11 +56,14 @@ struct Shapes {
   size_t rows;  // max_steps * B
   int qt3, qtot3, s3, s2, qtot2;
   int mw1, mw2; // 64-bit sign-mask words per transition row for h1 / h2
+  int onehot;   // layer-1 weight gradient as a one-hot contraction: 0 no, 1 grid, 2 Ising
+  int sbytes;   // state bytes recorded per transition row for it
+  int p1;       // rows of that contraction's output tile
   bool fast;    // hidden widths <= 256: one workgroup covers a whole operand (grad_kernels2.h)
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, m1, m2, part2, dbp2, part3, dbp3, total;
+  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -109,6 +112,9 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   s->mw1 = 4 * ((s->H1 + 255) / 256);
   s->mw2 = 4 * ((s->H2 + 255) / 256);
   s->fast = s->H1 <= 256 && s->H2 <= 256;
+  s->onehot = 0; s->sbytes = 0; s->p1 = 0;
+  if (s->fast && env->kind == GFNX_ENV_GRID && s->obs_dim <= 256) { s->onehot = 1; s->sbytes = 16; s->p1 = s->obs_dim; }
+  if (s->fast && env->kind == GFNX_ENV_ISING) { s->onehot = 2; s->sbytes = 112; s->p1 = 2 * s->state_dim; }
   if (s->fast) {
     s->s2 = 256; s->qtot2 = 256;
     s->qt3 = s->A16 <= 32 ? 32 : 256; s->qtot3 = s->qt3; s->s3 = 256;
@@ -138,6 +144,9 @@ Layout make_layout(const Shapes& s) {
   L.e = o; o += align256(sizeof(float) * s.rows * s.A16);
   L.m1 = o; o += align256(8 * s.rows * (size_t)s.mw1);
   L.m2 = o; o += align256(8 * s.rows * (size_t)s.mw2);
+  L.sb = o; o += align256(s.rows * (size_t)s.sbytes);
+  L.part1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)256 * s.p1 * 256 : 0);
+  L.dbp1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)256 * 256 : 0);
   L.part2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.H1 * s.qtot2);
   L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
   L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
@@ -257,6 +266,8 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.h1buf = at<float>(ws, L.h1); p.h2buf = at<float>(ws, L.h2); p.ebuf = at<float>(ws, L.e);
   p.m1buf = at<unsigned long long>(ws, L.m1); p.m2buf = at<unsigned long long>(ws, L.m2);
   p.MW1 = s.mw1; p.MW2 = s.mw2;
+  p.sbuf = s.onehot ? at<uint8_t>(ws, L.sb) : nullptr;
+  p.SB = s.sbytes;
 
   // Each workgroup owns a contiguous range of trajectories and runs them 16 at a time; ranges longer than 16
   // (large batches) let a slot start the next trajectory as soon as its current one ends.
@@ -365,13 +376,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
         const int lds = 32 * (256 + 32) * 4;
         hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                           s.qtot3, part3, dbp3);
+                           s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
       } else {
         auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
         const int lds = 32 * (256 + 256) * 4;
         if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
         hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                           s.qtot3, part3, dbp3);
+                           s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
       }
     }
     {
@@ -394,7 +405,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       const int lds = 32 * (256 + 256) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(1, 1, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
-                         s.qtot2, part2, dbp2);
+                         s.qtot2, part2, dbp2, (const uint8_t*)nullptr, 0, 1);
     }
     {
       GFNX_TIMED("reduce_w2", st);
@@ -454,31 +465,42 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                          h1buf, s.H1, s.H1, rows, hdr);
     }
   }
-  // layer 1: segment sums along each trajectory
-  {
-    GFNX_TIMED("fill_w1", st);
-    hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
-    hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
-  }
-  GFNX_TIMED("dw1", st);
-  const size_t dw1_lds = (size_t)s.obs_dim * 64 * 4 + (size_t)kDw1Waves * ((2 * 256 + kMaxStateDim + 4) * 4 + kMaxStateDim);
-  if (dw1_lds <= 150 * 1024) {
-    const int tpg = 64;
-    const dim3 grid((B + tpg - 1) / tpg, s.H1 / 64);
-#define GFNX_DW1(E)                                                                                              \
-  {                                                                                                              \
-    auto k = dw1_lds_kernel<E>;                                                                                  \
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dw1_lds) != hipSuccess) \
-      return GFNX_E_HIP;                                                                                         \
-    hipLaunchKernelGGL(k, grid, dim3(1024), dw1_lds, st, dp, tpg);                                                \
-  }
-    switch (env->kind) {
-      case GFNX_ENV_GRID: GFNX_DW1(0) break;
-      case GFNX_ENV_BITSEQ: GFNX_DW1(1) break;
-      default: GFNX_DW1(2) break;
+  // layer 1
+  if (s.onehot) {
+    // dW1 = onehot^T G1 on the matrix cores, the one-hot operand rebuilt from the recorded state bytes
+    float* part1 = at<float>(ws, L.part1);
+    float* dbp1 = at<float>(ws, L.dbp1);
+    const uint8_t* sbuf = at<uint8_t>(ws, L.sb);
+    const int lds = 32 * (256 + 256) * 4;
+    {
+      GFNX_TIMED("dw1", st);
+      if (s.onehot == 1) {
+        auto k = gemm_tn2_kernel<2, 4, 4, 2, false, 1>;
+        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+        hipLaunchKernelGGL(k, dim3(1, 1, 256), dim3(512), lds, st, (const float*)nullptr, 0, s.p1, h1buf, s.H1, coef, B, rows, hdr,
+                           256, part1, dbp1, sbuf, s.sbytes, env->grid_side);
+      } else {
+        auto k = gemm_tn2_kernel<2, 4, 4, 2, false, 2>;
+        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+        hipLaunchKernelGGL(k, dim3(1, 1, 256), dim3(512), lds, st, (const float*)nullptr, 0, s.p1, h1buf, s.H1, coef, B, rows, hdr,
+                           256, part1, dbp1, sbuf, s.sbytes, 1);
+      }
     }
-#undef GFNX_DW1
+    GFNX_TIMED("reduce_w1", st);
+    hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp1, 256, 1, 256, s.H1, grads->db1, hdr);
+    if (s.onehot == 1)
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.p1 * 64 + 255) / 256), dim3(256), 0, st, part1, 256, s.p1, 256, s.H1, grads->dW1, hdr);
+    else
+      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 255) / 256), dim3(256), 0, st, part1, 256, s.p1,
+                         256, s.H1, hdr, grads->db1, grads->dW1);
   } else {
+    // segment sums along each trajectory with atomics (large observation spaces: bit sequences)
+    {
+      GFNX_TIMED("fill_w1", st);
+      hipLaunchKernelGGL(fill_kernel, dim3(512), dim3(256), 0, st, grads->dW1, (size_t)s.obs_dim * s.H1, 0.f);
+      hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(256), 0, st, grads->db1, (size_t)s.H1, 0.f);
+    }
+    GFNX_TIMED("dw1", st);
     switch (env->kind) {
       case GFNX_ENV_GRID: hipLaunchKernelGGL(dw1_kernel<0>, dim3(B), dim3(256), 0, st, dp); break;
       case GFNX_ENV_BITSEQ: hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp); break;

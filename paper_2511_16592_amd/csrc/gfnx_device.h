@@ -40,6 +40,8 @@ struct RolloutParams {
   float *h1buf, *h2buf, *ebuf;  // per-transition rows, row = t*B + b
   unsigned long long *m1buf, *m2buf;  // sign masks of h1 / h2: MW1 / MW2 words of 64 bits per row
   int MW1, MW2;
+  uint8_t* sbuf;  // state bytes of every transition (SB per row), or null when the gradient pass needs none
+  int SB;
 };
 
 // D(16x16) += A(16x4) * B(4x16).  Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];

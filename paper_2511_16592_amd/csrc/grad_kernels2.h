@@ -6,8 +6,7 @@
 //                     column sums of G (the bias gradient) ride along.
 //   gemm_nt2_kernel   Out = (G W^T) . [act > 0]: each wave keeps a 32-column slice of W in registers as the
 //                     MFMA B operand for the whole kernel; tiles of 64 transition rows stream through LDS.
-//   dw1_lds_kernel    layer-1 weight gradient: per-trajectory segment sums accumulated in an LDS copy of a
-//                     feature slice of dW1 (LDS float atomics), flushed once per workgroup.
+//   reduce_dw1_ising_kernel  Ising layer-1 weight gradient from the partial tiles of the one-hot contraction.
 //   reduce2_kernel    fixed-order sum of the split partials.
 // With SCALE the G operand is (2 delta_b / B) * e, formed while the rows are loaded, so the logit-gradient rows
 // are never rewritten in HBM.
@@ -24,13 +23,20 @@ __device__ __forceinline__ int split_chunks_per_part(int chunks, int S) {
   return per < 4 ? 4 : per;
 }
 
-template <int WP, int WQ, int PBW, int QBW, bool SCALE>
+// XSRC selects the left operand: 0 = rows of the matrix X; 1, 2 = the one-hot observation of the transition,
+// rebuilt from the state bytes the rollout recorded (sbuf, SB bytes per row), never stored as floats:
+//   1 (grid)  column p = H*i + x is 1 iff coordinate i equals x;
+//   2 (Ising) column p = 2*site + s is 1 iff the site holds spin 2s-1 (the "unassigned" rows follow from the
+//             column sums: every site has exactly one active row per transition).
+// This turns the layer-1 weight gradient dW1 = onehot^T G1 into the same matrix-core contraction as dW2.
+template <int WP, int WQ, int PBW, int QBW, bool SCALE, int XSRC = 0>
 __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__ X, int ldx, int P,
                                                        const float* __restrict__ G, int ldg,
                                                        const float* __restrict__ coef, int B,
                                                        const int* __restrict__ rows, const int* __restrict__ hdr,
                                                        int QTOT, float* __restrict__ part,
-                                                       float* __restrict__ dbpart) {
+                                                       float* __restrict__ dbpart,
+                                                       const uint8_t* __restrict__ sbuf, int SB, int envH) {
   constexpr int PT = WP * PBW * 32, QT = WQ * QBW * 32, KC = 32;
   constexpr int XV = KC * PT / 4 / 512, GV = (KC * QT / 4 + 511) / 512;  // f32x4 per thread per chunk
   static_assert(WP * WQ == 8, "eight waves");
@@ -71,12 +77,42 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
       gid[m] = (c < c1 && i < KC * QT / 4 && li < n) ? rows[li] : -1;
     }
   };
+  // one-hot sources: this thread's four columns are the same for every row it loads
+  int oh_word[4] = {0, 0, 0, 0}, oh_shift[4] = {0, 0, 0, 0}, oh_val[4] = {-1, -1, -1, -1};
+  if (XSRC == 1) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int col = ptile * PT + 4 * (tid % (PT / 4)) + k;
+      if (col < P) {
+        const int i = col / envH;
+        oh_word[k] = i >> 2; oh_shift[k] = 8 * (i & 3); oh_val[k] = col - i * envH;
+      }
+    }
+  }
   auto load_rows = [&]() {
 #pragma unroll
     for (int m = 0; m < XV; ++m) {
       const int c4 = (tid + 512 * m) % (PT / 4);
       xr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (xid[m] >= 0 && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)xid[m] * ldx + ptile * PT + 4 * c4];
+      if (XSRC == 0) {
+        if (xid[m] >= 0 && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)xid[m] * ldx + ptile * PT + 4 * c4];
+      } else if (XSRC == 1) {
+        if (xid[m] >= 0) {
+          const uint4 sv = *(const uint4*)&sbuf[(size_t)xid[m] * SB];  // the (up to 16) coordinates of the state
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const uint32_t wd = oh_word[k] == 0 ? sv.x : (oh_word[k] == 1 ? sv.y : (oh_word[k] == 2 ? sv.z : sv.w));
+            xr[m][k] = ((int)((wd >> oh_shift[k]) & 255u) == oh_val[k]) ? 1.f : 0.f;
+          }
+        }
+      } else {
+        const int p0 = ptile * PT + 4 * c4;  // sites p0/2 and p0/2 + 1
+        if (xid[m] >= 0 && p0 < P) {
+          const uint32_t sv = *(const uint16_t*)&sbuf[(size_t)xid[m] * SB + (p0 >> 1)];
+          const uint32_t s0 = sv & 255u, s1 = sv >> 8;
+          xr[m] = (f32x4){s0 == 255u ? 1.f : 0.f, s0 == 1u ? 1.f : 0.f, s1 == 255u ? 1.f : 0.f, s1 == 1u ? 1.f : 0.f};
+        }
+      }
     }
 #pragma unroll
     for (int m = 0; m < GV; ++m) {
@@ -294,146 +330,38 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
   }
 }
 
-constexpr int kDw1Waves = 16;  // trajectories a workgroup of dw1_lds_kernel works on at a time
-
-// Layer-1 weight gradient with an LDS-private copy of a 64-feature slice of dW1 (obs_dim rows).
-// grid = (trajectory groups, H1/64); 1024 threads = 16 trajectories at a time x 64 features; the row bookkeeping
-// of a trajectory (which one-hot row leaves / enters at each step) is rebuilt from its action bytes.
-// Segment sums as in dw1_kernel: one running sum per grid coordinate, or prefix + suffix sweeps.
-template <int ENV>
-__global__ __launch_bounds__(1024) void dw1_lds_kernel(const Dw1Params p, int traj_per_group) {
-  extern __shared__ float smem[];
-  const EnvParams& e = p.env;
-  const int rows_n = e.obs_dim;
-  float* tab = smem;                                   // [obs_dim][64]
-  int* rold = (int*)(smem + (size_t)rows_n * 64);      // [16][256]
-  int* rnew = rold + kDw1Waves * 256;                  // [16][256]
-  int* rend = rnew + kDw1Waves * 256;                  // [16][kMaxStateDim]
-  int* meta = rend + kDw1Waves * kMaxStateDim;         // [16][4]: len, nend
-  int8_t* st = (int8_t*)(meta + kDw1Waves * 4);        // [16][kMaxStateDim]
-  const int tid = threadIdx.x, f = tid & 63, tq = tid >> 6;
-  const int H1 = p.H1, B = p.B, f0 = blockIdx.y * 64;
-  for (int i = tid; i < rows_n * 64; i += 1024) tab[i] = 0.f;
-  float dbsum = 0.f;
-  const int g0 = blockIdx.x * traj_per_group;
-  for (int base = 0; base < traj_per_group; base += kDw1Waves) {
-    const int b = g0 + base + tq;
-    __syncthreads();
-    // stage the action bytes of the four trajectories in LDS (rnew doubles as the staging area)
-    int len_b = (b < B) ? p.length[b] : 0;
-    len_b = len_b < 0 ? 0 : (len_b > e.max_steps ? e.max_steps : len_b);
-    for (int t = f; t + 1 < len_b; t += 64) rnew[tq * 256 + t] = p.actions[(size_t)t * B + b];
-    __syncthreads();
-    if (f == 0) {
-      const int len = len_b;
-      int bad = 0;
-      int8_t* s8 = st + tq * kMaxStateDim;
-      for (int s = 0; s < e.state_dim; ++s) s8[s] = 0;
-      for (int t = 0; t + 1 < len; ++t) {
-        const int a = rnew[tq * 256 + t];
-        if (ENV == 0 ? (a >= e.d || s8[a] >= e.H - 1) : (a >= e.n_actions)) { bad = 1; break; }
-        if (ENV == 0) {
-          rold[tq * 256 + t] = e.H * a + s8[a];
-          rnew[tq * 256 + t] = a;
-          s8[a] += 1;
-        } else if (ENV == 1) {
-          rold[tq * 256 + t] = ((1 << e.k_bits) + 1) * t + (1 << e.k_bits);
-          rnew[tq * 256 + t] = ((1 << e.k_bits) + 1) * t + a;
-          s8[t] = 1;
-        } else {
-          rold[tq * 256 + t] = 3 * (a >> 1) + 1;
-          rnew[tq * 256 + t] = 3 * (a >> 1) + 1 + 2 * (a & 1) - 1;
-          s8[a >> 1] = 1;
-        }
-      }
-      int nend = 0;
-      for (int s = 0; s < e.state_dim; ++s) {
-        if (ENV == 0) rend[tq * kMaxStateDim + nend++] = e.H * s + s8[s];
-        else if (ENV == 1) { if (!s8[s]) rend[tq * kMaxStateDim + nend++] = ((1 << e.k_bits) + 1) * s + (1 << e.k_bits); }
-        else { if (!s8[s]) rend[tq * kMaxStateDim + nend++] = 3 * s + 1; }
-      }
-      meta[tq * 4 + 0] = bad ? 0 : len;
-      meta[tq * 4 + 1] = nend;
+// Ising dW1 from the partial tiles of the one-hot contraction (fixed order over the parts that were written):
+// tile rows 2*site, 2*site+1 are the spin rows 3*site, 3*site+2 of dW1; the unassigned row 3*site+1 is db1 minus
+// the two (db1 = column sums of G1, reduced before this kernel runs).  Four columns per thread.
+__global__ void reduce_dw1_ising_kernel(const float* __restrict__ part, int S, int P, int QTOT, int H1,
+                                        const int* __restrict__ hdr, const float* __restrict__ db1,
+                                        float* __restrict__ dW1) {
+  const int chunks = (hdr[kHdrNLive] + 31) / 32;
+  const int per = split_chunks_per_part(chunks, S);
+  S = (chunks + per - 1) / per;
+  const size_t stride = (size_t)P * QTOT;
+  const int qv = H1 >> 2;
+  const size_t total = (size_t)(P / 2) * qv;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int u = (int)(i / qv), q = (int)(i % qv) * 4;
+    const float* src = part + (size_t)(2 * u) * QTOT + q;
+    f32x4 m0 = {0.f, 0.f, 0.f, 0.f}, m1 = m0, p0 = m0, p1 = m0;
+    int s = 0;
+    for (; s + 2 <= S; s += 2) {
+      m0 += *(const f32x4*)&src[(size_t)s * stride];
+      p0 += *(const f32x4*)&src[(size_t)s * stride + QTOT];
+      m1 += *(const f32x4*)&src[(size_t)(s + 1) * stride];
+      p1 += *(const f32x4*)&src[(size_t)(s + 1) * stride + QTOT];
     }
-    __syncthreads();
-    const int len = meta[tq * 4 + 0], nend = meta[tq * 4 + 1];
-    if (len <= 0) continue;
-    const float* g1 = p.g1 + (size_t)b * H1 + f0 + f;
-    const size_t stride = (size_t)B * H1;
-    const int* ro = rold + tq * 256;
-    const int* rn = rnew + tq * 256;
-    const int* re = rend + tq * kMaxStateDim;
-    if (ENV == 0) {
-      float acc[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-      float total = 0.f;
-      for (int t0 = 0; t0 < len; t0 += 8) {
-        float gv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) gv[u] = (t0 + u < len) ? g1[(t0 + u) * stride] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int t = t0 + u;
-          if (t < len) {
-            const float g = gv[u];
-            total += g;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] += g;
-            if (t + 1 < len) {
-              const int a = rn[t];
-              float v = 0.f;
-#pragma unroll
-              for (int i = 0; i < 16; ++i)
-                if (i == a) { v = acc[i]; acc[i] = 0.f; }
-              atomicAdd(&tab[ro[t] * 64 + f], v);
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (i < e.d) atomicAdd(&tab[re[i] * 64 + f], acc[i]);
-      dbsum += total;
-    } else {
-      float P = 0.f;
-      for (int t0 = 0; t0 < len; t0 += 8) {
-        float gv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) gv[u] = (t0 + u < len) ? g1[(t0 + u) * stride] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int t = t0 + u;
-          if (t < len) {
-            P += gv[u];
-            if (t + 1 < len) atomicAdd(&tab[ro[t] * 64 + f], P);
-          }
-        }
-      }
-      for (int i = 0; i < nend; ++i) atomicAdd(&tab[re[i] * 64 + f], P);
-      dbsum += P;
-      float S = 0.f;
-      for (int t0 = len - 1; t0 >= 1; t0 -= 8) {
-        float gv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) gv[u] = (t0 - u >= 1) ? g1[(t0 - u) * stride] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int t = t0 - u;
-          if (t >= 1) {
-            S += gv[u];
-            atomicAdd(&tab[rn[t - 1] * 64 + f], S);
-          }
-        }
-      }
+    for (; s < S; ++s) {
+      m0 += *(const f32x4*)&src[(size_t)s * stride];
+      p0 += *(const f32x4*)&src[(size_t)s * stride + QTOT];
     }
+    const f32x4 mi = m0 + m1, pl = p0 + p1;
+    *(f32x4*)&dW1[(size_t)(3 * u) * H1 + q] = mi;
+    *(f32x4*)&dW1[(size_t)(3 * u + 2) * H1 + q] = pl;
+    *(f32x4*)&dW1[(size_t)(3 * u + 1) * H1 + q] = *(const f32x4*)&db1[q] - mi - pl;
   }
-  __syncthreads();
-  for (int i = tid; i < rows_n * 64; i += 1024) {
-    const float v = tab[i];
-    if (v != 0.f) atomicAdd(&p.dW1[(size_t)(i >> 6) * H1 + f0 + (i & 63)], v);
-  }
-  atomicAdd(&p.db1[f0 + f], dbsum);
 }
 
 }  // namespace gfnx

@@ -15,8 +15,8 @@
 //       transition, terminal log-reward, action byte; then the same lanes update the layer-1
 //       pre-activation: layer 1 is a one-hot gather and a transition swaps exactly one active row, so z1 is
 //       kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
-// The post-ReLU activations h1, h2, their sign masks (1 bit per unit) and the logit-gradient direction
-// (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the
+// The post-ReLU activations h1, h2, their sign masks (1 bit per unit), the state bytes and the logit-gradient
+// direction (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the
 // kernel writes to global memory is read back by it, so the three barriers per step order LDS traffic only
 // (no wait for stores to land).
 #pragma once
@@ -262,6 +262,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (32 lanes per slot)
     if (alive[sj]) {
       const int t = ts;
+      if (p.sbuf) {  // the state the policy is evaluated at, for the one-hot contraction of the gradient pass
+        uint8_t* srowp = p.sbuf + ((size_t)t * B + sb) * p.SB;
+        for (int s = si; s < p.SB; s += 32) srowp[s] = s < e.state_dim ? (uint8_t)st[s * kSlots + sj] : (uint8_t)0;
+      }
       f32x4 lg[NCH];
       uint32_t vm[NCH];
       float m = -INFINITY;
