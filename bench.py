@@ -1,16 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the rollout + Trajectory-Balance gradient step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-extra] [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over one batch of synthetic input: gfnx_rollout (fresh
 Philox iteration counter each step) followed by gfnx_tb_loss_grad, inputs and outputs resident in
 HBM.  Prints one JSON line: environment transitions per second (valid transitions only), the roofline
-of the dominant kernel measured with HIP events in the same run, and the CPU reference timed on a
-bounded sample of the same workload.
+of the dominant kernel measured with HIP events on its launch stream inside the timed region, and the
+CPU reference timed on a bounded sample of the same workload.  The warm-up steps run with events
+around every kernel to find the dominant one; in the timed region only that kernel carries events.
 """
 import argparse
-import ctypes as C
+import hashlib
 import json
 import os
 import sys
@@ -31,32 +32,110 @@ DESCRIPTIONS = {
     "c5": "10-D grid H=20, MLP 200-256-256-11 (seeded Xavier), batch 16384, max 191 steps",
     "c5_long": "10-D grid H=20, MLP 200-256-256-11 with stop bias -8 (long walks), batch 16384",
 }
+KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "gfnx_device.h", "gfnx.hip")
 
 
-def cpu_baseline(wl, w, seconds_target=15.0):
+def kernel_source_hash():
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2511_16592_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there is
+    none for this workload / kernel or the kernel sources changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        rec = json.load(open(path))
+    except ValueError:
+        return None
+    entry = rec.get(workload, {}).get(kernel)
+    if not entry or rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return entry["bytes_per_launch"]
+
+
+def flop_shares(h1, h2, a):
+    """Algorithmic matrix-core flops per transition of each kernel (layer 1 is a gather / scatter)."""
+    return {"rollout": 2.0 * (h1 * h2 + h2 * a), "gemm_tn_w2": 2.0 * h1 * h2, "gemm_nt_g1": 2.0 * h1 * h2,
+            "gemm_tn_w3": 2.0 * h2 * a, "gemm_nt_g2": 2.0 * h2 * a}
+
+
+def cpu_baseline(wl, w, seconds_target=12.0):
     """The CPU reference as it stands (untuned), on a bounded sample of the same workload."""
     from oracle import Oracle
     o32 = Oracle("f32")
     cores = min(os.cpu_count() or 1, 16)
     batch = min(wl.batch, 64)
-    used = 0.0
-    done_tr = 0
-    sample_batches = []
+    used, done_tr, batches = 0.0, 0, []
     while True:
         t0 = time.perf_counter()
-        out = o32.rollout(wl.env, w, wl.seed, len(sample_batches), batch=batch, nthreads=cores)
+        out = o32.rollout(wl.env, w, wl.seed, len(batches), batch=batch, nthreads=cores)
         o32.tb_loss_grad(wl.env, w, out["actions"], out["length"], wl.log_z, nthreads=cores)
         dt = time.perf_counter() - t0
         used += dt
         done_tr += int(out["length"].sum())
-        sample_batches.append(batch)
-        if used >= seconds_target or len(sample_batches) >= 64:
+        batches.append(batch)
+        if used >= seconds_target or len(batches) >= 64:
             break
         if dt < seconds_target / 8 and batch < wl.batch:
             batch = min(wl.batch, batch * 4)
     return {"value": done_tr / used, "unit": "transitions/s", "cores": cores, "kind": "oracle",
-            "sample": "%d passes (rollout + TB gradient, fp32 build) over batches %s of the same workload, "
-                      "%d transitions in %.1f s" % (len(sample_batches), sample_batches, done_tr, used)}
+            "sample": "%d passes (rollout + TB gradient, binary32 build, %d threads) over batches %s of the same "
+                      "workload: %d transitions in %.1f s" % (len(batches), cores, batches, done_tr, used)}
+
+
+def run_workload(name, steps, warmup, events=True):
+    import torch
+    from paper_2511_16592_amd import gfnx
+    from paper_2511_16592_amd.workloads import workloads
+
+    wl = workloads()[name]
+    w = wl.mlp()
+    sess = gfnx.Session(wl.env, w, wl.batch)
+    timer = gfnx.KernelTimer()
+
+    timer.enable(events)
+    for i in range(warmup):
+        sess.rollout(wl.seed, i)
+        sess.tb_loss_grad(wl.log_z)
+    torch.cuda.synchronize()
+    breakdown = timer.collect() if events else {}
+    dominant = max(breakdown, key=lambda k: breakdown[k][1]) if breakdown else None
+
+    timer.enable(events and dominant is not None, only=dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        sess.rollout(wl.seed, warmup + i)
+        sess.tb_loss_grad(wl.log_z)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dom = timer.collect().get(dominant) if dominant else None
+    timer.enable(False)
+
+    # valid transitions of the timed steps (the rollout is a pure function of seed and iteration)
+    transitions = 0
+    for i in range(steps):
+        sess.rollout(wl.seed, warmup + i)
+        transitions += int(sess.length.sum().item())
+    torch.cuda.synchronize()
+    return dict(wl=wl, weights=w, elapsed=elapsed, transitions=transitions, dominant=dominant, dom=dom,
+                breakdown={k: v[1] / max(1, warmup) for k, v in breakdown.items()})
+
+
+def summary(name, r, steps):
+    wl = r["wl"]
+    a = wl.env.dims()[2]
+    per_step = r["transitions"] / steps
+    flops_all = 6.0 * (wl.h1 * wl.h2 + wl.h2 * a)
+    return {"workload": "%s: %s" % (name, DESCRIPTIONS[name]), "value": r["transitions"] / r["elapsed"],
+            "unit": "transitions/s", "ms_per_step": r["elapsed"] / steps * 1e3, "transitions_per_step": per_step,
+            "whole_step_mfma_frac": flops_all * per_step / (r["elapsed"] / steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
 
 
 def main():
@@ -66,72 +145,55 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
     import torch
-    from paper_2511_16592_amd import gfnx
-    from paper_2511_16592_amd.workloads import workloads
-
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
-    wl = workloads()[args.workload]
-    w = wl.mlp()
-    sess = gfnx.Session(wl.env, w, wl.batch)
-    timing = gfnx.KernelTimer()
 
-    for i in range(args.warmup):
-        sess.rollout(wl.seed, i)
-        sess.tb_loss_grad(wl.log_z)
-    torch.cuda.synchronize()
+    r = run_workload(args.workload, args.steps, max(1, args.warmup))
+    wl = r["wl"]
+    a = wl.env.dims()[2]
+    head = summary(args.workload, r, args.steps)
+    per_step = head["transitions_per_step"]
 
-    timing.enable(True)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        sess.rollout(wl.seed, args.warmup + i)
-        sess.tb_loss_grad(wl.log_z)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernels = timing.collect()  # {name: (launches, total ms)} from HIP events recorded on the launch stream
-    timing.enable(False)
+    roofline = None
+    if r["dom"]:
+        launches, total_ms = r["dom"]
+        avg_ms = total_ms / launches
+        share = flop_shares(wl.h1, wl.h2, a).get(r["dominant"], 0.0)
+        achieved = share * per_step * (args.steps / launches) / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": r["dominant"], "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                    "traffic": measured_traffic(args.workload, r["dominant"]),
+                    "avg_kernel_ms": avg_ms, "launches": launches,
+                    "algorithmic_flops_per_launch": share * per_step * (args.steps / launches),
+                    "whole_step_frac": head["whole_step_mfma_frac"]}
 
-    # count the valid transitions of the timed steps (the rollout is a pure function of seed and iteration)
-    transitions = 0
-    for i in range(args.steps):
-        sess.rollout(wl.seed, args.warmup + i)
-        transitions += int(sess.length.sum().item())
-    per_step = transitions / args.steps
-
-    h1, h2, a = wl.h1, wl.h2, wl.env.dims()[2]
-    flops_fwd = 2.0 * (h1 * h2 + h2 * a)  # per transition, layers 2 and 3 (layer 1 is a gather)
-    flops_all = 6.0 * (h1 * h2 + h2 * a)  # forward + backward
-    dom = max(kernels, key=lambda k: kernels[k][1])
-    launches, total_ms = kernels[dom]
-    avg_ms = total_ms / launches
-    launches_per_step = launches / args.steps
-    # algorithmic flops of the dominant kernel per launch
-    share = {"rollout": flops_fwd, "gemm_tn_w2": 2.0 * h1 * h2, "gemm_nt_g1": 2.0 * h1 * h2,
-             "gemm_tn_w3": 2.0 * h2 * a, "gemm_nt_g2": 2.0 * h2 * a}.get(dom, 0.0)
-    achieved = share * per_step / launches_per_step / (avg_ms * 1e-3) / 1e12
     out = {
         "metric": "env transitions/s for rollout+TB-grad step",
-        "value": transitions / elapsed,
-        "unit": "transitions/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %s" % (args.workload, DESCRIPTIONS[args.workload]),
-                   "transitions_per_step": per_step},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
-                     "avg_kernel_ms": avg_ms,
-                     "whole_step_frac": flops_all * per_step / (elapsed / args.steps) / 1e12 / PEAK_FP32_MFMA_TFLOPS},
-        "kernels_ms_per_step": {k: v[1] / args.steps for k, v in sorted(kernels.items(), key=lambda kv: -kv[1][1])},
+        "value": head["value"], "unit": "transitions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": head["workload"], "transitions_per_step": per_step},
+        "roofline": roofline,
+        "kernels_ms_per_step": {k: round(v, 5) for k, v in sorted(r["breakdown"].items(), key=lambda kv: -kv[1])},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, w)
+        out["cpu_baseline"] = cpu_baseline(wl, r["weights"])
+    if not args.no_extra:
+        # other workloads of the same path, short runs without per-kernel events (context for the headline line:
+        # the 4-D grid at Xavier initialisation has ~5-step trajectories, i.e. little work per launch)
+        extra = {}
+        for name in ("c2_long", "c4", "c5", "c5_long", "c3"):
+            if name == args.workload:
+                continue
+            steps = 5 if name == "c5_long" else 20
+            extra[name] = summary(name, run_workload(name, steps, 3, events=False), steps)
+        out["extra"] = extra
     print(json.dumps(out))
 
 

@@ -150,11 +150,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
 
 /* Measurement aid (not part of the method; not thread-safe).  While enabled, every kernel (or small group
  * of kernels) the library launches is bracketed by HIP events recorded on the launch stream, labelled
- * "rollout", "gemm_tn_w2", ...  gfnx_timing_enable(on) also discards the records taken so far.
+ * "rollout", "gemm_tn_w2", ...  gfnx_timing_enable(on) also discards the records taken so far;
+ * gfnx_timing_only(label) restricts recording to one label (two events per step instead of dozens).
  * gfnx_timing_labels() returns the number of labels seen; gfnx_timing_get(label, ...) WAITS for the recorded
  * events of that label (the one call of the library that synchronises) and returns how many launches were
  * recorded and their summed duration in milliseconds; *name points to static storage. */
 int gfnx_timing_enable(int on);
+int gfnx_timing_only(const char* label); /* record this label only (NULL or "" = every label) */
 int gfnx_timing_labels(void);
 int gfnx_timing_get(int label, const char** name, int32_t* launches, float* total_ms);
 

@@ -18,6 +18,7 @@ namespace {
 // ---- optional per-kernel timing (diagnostics): HIP events recorded on the launch stream around each kernel
 struct TimingRecord { int label; hipEvent_t start, stop; };
 bool g_timing_on = false;
+std::string g_timing_only;  // when not empty, only this label is recorded
 std::vector<std::string> g_labels;
 std::vector<TimingRecord> g_records;
 std::vector<hipEvent_t> g_event_pool;
@@ -39,6 +40,7 @@ struct ScopedKernelTimer {
   hipStream_t st; int rec = -1;
   ScopedKernelTimer(const char* name, hipStream_t s) : st(s) {
     if (!g_timing_on) return;
+    if (!g_timing_only.empty() && g_timing_only != name) return;
     TimingRecord r{label_id(name), take_event(), take_event()};
     (void)hipEventRecord(r.start, st);
     g_records.push_back(r);
@@ -514,6 +516,11 @@ int gfnx_timing_enable(int on) {
   for (auto& r : g_records) { g_event_pool.push_back(r.start); g_event_pool.push_back(r.stop); }
   g_records.clear();
   g_timing_on = on != 0;
+  return GFNX_OK;
+}
+
+int gfnx_timing_only(const char* label) {
+  g_timing_only = label ? label : "";
   return GFNX_OK;
 }
 

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
-           "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_labels", "gfnx_timing_get")
+           "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
 
 class EnvDesc(C.Structure):
@@ -74,6 +74,8 @@ def load_library() -> C.CDLL:
                                           C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
         lib.gfnx_timing_enable.restype = C.c_int
         lib.gfnx_timing_enable.argtypes = [C.c_int]
+        lib.gfnx_timing_only.restype = C.c_int
+        lib.gfnx_timing_only.argtypes = [C.c_char_p]
         lib.gfnx_timing_labels.restype = C.c_int
         lib.gfnx_timing_get.restype = C.c_int
         lib.gfnx_timing_get.argtypes = [C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int32), C.POINTER(C.c_float)]
@@ -111,7 +113,8 @@ class KernelTimer:
     def __init__(self):
         self.lib = load_library()
 
-    def enable(self, on: bool) -> None:
+    def enable(self, on: bool, only: Optional[str] = None) -> None:
+        _check(self.lib.gfnx_timing_only(only.encode() if only else None))
         _check(self.lib.gfnx_timing_enable(1 if on else 0))
 
     def collect(self) -> Dict[str, tuple]:
