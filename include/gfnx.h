@@ -93,7 +93,8 @@ typedef struct {
 } gfnx_mlp_grad;
 
 /* Structure-of-arrays trajectory batch, device pointers, caller-allocated.
- *   actions        [max_steps][batch] one byte per transition, coalesced over the batch; entries with
+ *   actions        [max_steps][batch] one byte per transition, coalesced over the batch, the buffer 4-byte
+ *                  aligned; entries with
  *                  t >= length[b] are 0xFF padding (use length[], not the sentinel: 0xFF is also the
  *                  valid action 255 of an environment with 256 actions);
  *   length         [batch] number of transitions including the terminating one;

@@ -279,6 +279,11 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   const dim3 grid((s.B + tpw - 1) / tpw);
   const size_t lds = rollout_lds_bytes(s);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
+  if (!replay) {
+    // every action byte starts as the 0xFF padding; the rollout overwrites the transitions it takes
+    GFNX_TIMED("pad_actions", st);
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(256), dim3(256), 0, st, traj->actions, (size_t)traj->max_steps * s.B, (uint8_t)0xFF);
+  }
   {
     GFNX_TIMED("rollout", st);
     rc = replay ? launch_rollout<true>(p, grid, lds, st) : launch_rollout<false>(p, grid, lds, st);

@@ -260,6 +260,14 @@ __global__ __launch_bounds__(256) void gemm_nt_mask_kernel(const float* __restri
 __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
+// bytes [0, n) <- v, as 32-bit words where aligned (p is 4-byte aligned)
+__global__ void fill_bytes_kernel(uint8_t* __restrict__ p, size_t n, uint8_t v) {
+  const size_t words = n >> 2;
+  const uint32_t vv = 0x01010101u * v;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+    ((uint32_t*)p)[i] = vv;
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) p[(words << 2) + threadIdx.x] = v;
+}
 __global__ void fill_int_kernel(int* __restrict__ p, size_t n, int v) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }

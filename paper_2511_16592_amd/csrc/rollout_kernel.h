@@ -263,8 +263,17 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     if (alive[sj]) {
       const int t = ts;
       if (p.sbuf) {  // the state the policy is evaluated at, for the one-hot contraction of the gradient pass
-        uint8_t* srowp = p.sbuf + ((size_t)t * B + sb) * p.SB;
-        for (int s = si; s < p.SB; s += 32) srowp[s] = s < e.state_dim ? (uint8_t)st[s * kSlots + sj] : (uint8_t)0;
+        uint32_t* srowp = (uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB);  // SB is a multiple of 16
+        for (int s4 = si; 4 * s4 < p.SB; s4 += 32) {
+          uint32_t packed = 0;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int s = 4 * s4 + k;
+            const uint32_t byte = s < e.state_dim ? (uint32_t)(uint8_t)st[s * kSlots + sj] : 0u;
+            packed |= byte << (8 * k);
+          }
+          srowp[s4] = packed;
+        }
       }
       f32x4 lg[NCH];
       uint32_t vm[NCH];
@@ -455,8 +464,6 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           else v = (s == site) ? spin : st[s * kSlots + sj];
           p.term[(size_t)s * B + sb] = (int8_t)v;
         }
-        if (!REPLAY)
-          for (int tt = t + 1 + si; tt < p.T; tt += 32) p.actions[(size_t)tt * B + sb] = 0xFF;
         // the slot starts the next trajectory of the workgroup's range, if any is left
         int nb = 0;
         if (si == 0) nb = atomicAdd(qnext, 1);
