@@ -190,12 +190,14 @@ EnvParams env_params(const gfnx_env_desc* env, const Shapes& s) {
 template <typename T>
 inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
+// bytes per slot of the state kept in LDS by the rollout kernel
+int rollout_state_pitch(const Shapes& s) {
+  const int r = (s.state_dim + 15) / 16 * 16;
+  return r > s.sbytes ? r : s.sbytes;
+}
+
 size_t rollout_lds_bytes(const Shapes& s) {
-  const int nchunk = s.A16 / 4;
-  const int ks = logits_ksplit(s.A16 / 16, s.H2 / 16);
-  size_t fl = (size_t)(2 * (s.H1 / 4) + s.H2 / 4 + ks * nchunk) * kPitch;
-  fl += 2 * (size_t)s.H1;  // z1(s_0) for restarting slots
-  return fl * sizeof(float) + (2 * kSlots + 4) * sizeof(int) + (size_t)s.state_dim * kSlots;
+  return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), s.H1 == 256 && s.H2 == 256).total;
 }
 
 template <int ENV, bool REPLAY, int NCH>
@@ -270,6 +272,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.MW1 = s.mw1; p.MW2 = s.mw2;
   p.sbuf = s.onehot ? at<uint8_t>(ws, L.sb) : nullptr;
   p.SB = s.sbytes;
+  p.SBL = rollout_state_pitch(s);
 
   // Each workgroup owns a contiguous range of trajectories and runs them 16 at a time; ranges longer than 16
   // (large batches) let a slot start the next trajectory as soon as its current one ends.

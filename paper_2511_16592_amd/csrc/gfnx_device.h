@@ -42,6 +42,7 @@ struct RolloutParams {
   int MW1, MW2;
   uint8_t* sbuf;  // state bytes of every transition (SB per row), or null when the gradient pass needs none
   int SB;
+  int SBL;        // bytes per slot of the state kept in LDS: a multiple of 16, >= max(state_dim, SB)
 };
 
 // D(16x16) += A(16x4) * B(4x16).  Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];
@@ -67,6 +68,24 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The same with a wavefront-uniform key.  The round keys are bumped on the scalar unit as the rounds go; the empty
+// asm keeps the compiler from precomputing all ten pairs outside the caller's loop, where they would occupy
+// twenty scalar registers for the whole kernel.
+__device__ __forceinline__ void philox4x32_10_ukey(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                   uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+    asm volatile("" : "+s"(k0), "+s"(k1));
   }
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
@@ -134,6 +153,20 @@ __device__ __forceinline__ float grp32_max(float v) { v = row16_max(v); return f
 __device__ __forceinline__ float grp32_sum(float v) { v = row16_sum(v); return v + swz_xor16(v); }
 __device__ __forceinline__ int grp32_sum(int v) { v = row16_sum(v); return v + swz_xor16(v); }
 __device__ __forceinline__ int grp32_min(int v) { v = row16_min(v); return min(v, swz_xor16(v)); }
+// unsigned 64-bit minimum over the 32 lanes
+template <int N>
+__device__ __forceinline__ unsigned long long row16_min_u64_step(unsigned long long v) {
+  const uint32_t oh = (uint32_t)row16_rot<N>((int)(uint32_t)(v >> 32)), ol = (uint32_t)row16_rot<N>((int)(uint32_t)v);
+  const unsigned long long o = ((unsigned long long)oh << 32) | ol;
+  return o < v ? o : v;
+}
+__device__ __forceinline__ unsigned long long grp32_min_u64(unsigned long long v) {
+  v = row16_min_u64_step<8>(v); v = row16_min_u64_step<4>(v);
+  v = row16_min_u64_step<2>(v); v = row16_min_u64_step<1>(v);
+  const uint32_t oh = (uint32_t)swz_xor16((int)(uint32_t)(v >> 32)), ol = (uint32_t)swz_xor16((int)(uint32_t)v);
+  const unsigned long long o = ((unsigned long long)oh << 32) | ol;
+  return o < v ? o : v;
+}
 __device__ __forceinline__ void grp32_argmin(float& key, int& idx, float& payload) {
   row16_argmin(key, idx, payload);
   const float ok = swz_xor16(key), op = swz_xor16(payload);

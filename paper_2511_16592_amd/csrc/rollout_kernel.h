@@ -43,8 +43,10 @@ __device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words,
   return (uint32_t)(v >> (s & 31)) & ((1u << k) - 1u);
 }
 
+// max(v, 0) as a three-operand median: one instruction per element
+__device__ __forceinline__ float relu1(float v) { return __builtin_amdgcn_fmed3f(v, 0.f, INFINITY); }
 __device__ __forceinline__ f32x4 relu4(f32x4 v) {
-  v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+  v.x = relu1(v.x); v.y = relu1(v.y); v.z = relu1(v.z); v.w = relu1(v.w);
   return v;
 }
 
@@ -53,7 +55,20 @@ __device__ __forceinline__ f32x4 relu4(f32x4 v) {
 __device__ __forceinline__ void store_sign_mask(unsigned long long* dst, f32x4 v, int lane) {
   const unsigned long long m0 = __ballot(v.x > 0.f), m1 = __ballot(v.y > 0.f);
   const unsigned long long m2 = __ballot(v.z > 0.f), m3 = __ballot(v.w > 0.f);
-  if (lane < 4) dst[lane] = lane == 0 ? m0 : (lane == 1 ? m1 : (lane == 2 ? m2 : m3));
+  if (lane == 0) {  // dst is 32-byte aligned: rows hold a multiple of four words
+    ((ulonglong2*)dst)[0] = make_ulonglong2(m0, m1);
+    ((ulonglong2*)dst)[1] = make_ulonglong2(m2, m3);
+  }
+}
+
+// exp(x) for x <= 0 on the transcendental unit: 2^(x log2 e) with the rounding error of the product fed back as a
+// first-order correction; relative error below 2e-7 down to x = -40 (measured over 2^23 arguments), results under
+// 2^-126 flush to zero.
+__device__ __forceinline__ float exp_nonpos(float x) {
+  const float t = x * 1.44269504088896341f;
+  const float lo = __builtin_fmaf(x, 1.44269504088896341f, -t) + x * 1.92596299e-8f;
+  const float e = __builtin_amdgcn_exp2f(t);
+  return __builtin_fmaf(e, lo * 0.693147180559945f, e);
 }
 
 // How the logits GEMM is split over the eight waves: with at least eight 16-logit tiles each wave takes
@@ -71,35 +86,62 @@ __host__ __device__ inline int logits_ksplit(int nt3, int q2) {
   ACC = mfma16((AV).z, (BV).z, ACC);       \
   ACC = mfma16((AV).w, (BV).w, ACC)
 
+constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile held in registers; the rest sit in LDS
+
+// Byte offsets of the kernel's LDS regions (shared by the launch code, which sizes the allocation).
+struct RolloutLds {
+  int z1s, z1l, h2s, lgs, z1i, flags, st, w2l, total;
+};
+__host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16, int SBL, bool stat) {
+  const int ks = logits_ksplit(A16 >> 4, H2 >> 4);
+  RolloutLds L;
+  int o = 0;
+  L.z1s = o; o += (H1 >> 2) * kPitch * 4;            // pre-activation of layer 1, high part
+  L.z1l = o; o += (H1 >> 2) * kPitch * 4;            // ... low part (z1 = hi + lo carries the sum to ~48 bits)
+  L.h2s = o; o += (H2 >> 2) * kPitch * 4;
+  L.lgs = o; o += ks * (A16 >> 2) * kPitch * 4;      // [KS][A16 / 4] partial logits
+  L.z1i = o; o += 2 * H1 * 4;                        // z1(s_0): high and low parts, for slots that restart
+  L.flags = o; o += (2 * kSlots + 4) * 4;            // alive[kSlots], srow[kSlots], qnext
+  L.st = o; o += kSlots * SBL;                       // state bytes, SBL per slot (a multiple of 16)
+  L.w2l = o; if (stat) o += (16 - kW2RegQ) * 16 * 64 * 16;  // 16 tiles x (16 - kW2RegQ) steps x 64 lanes x 16 bytes
+  L.total = o;
+  return L;
+}
+
 // NTW  = 16-feature tiles of layer 2 per wave, ceil(H2 / 128).
-// STAT = layer 2 is 256 x 256: each wave keeps its two tiles of W2 (32 KiB, 128 registers per lane) in
-//        registers for the whole rollout; with a single logit tile (grids) its eighth of W3 as well.
+// STAT = layer 2 is 256 x 256: each wave keeps its two tiles of W2 (32 KiB) on chip for the whole rollout,
+//        kW2RegQ/16 of them in registers and the rest in LDS; with a single logit tile (grids) its eighth of
+//        W3 as well.
 // NCH  = chunks of four logits a lane may own in SU: 1 up to 128 actions, else 2.
 template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH>
 __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutParams p) {
-  extern __shared__ float smem[];
+  extern __shared__ __align__(16) unsigned char smem_raw[];
   const EnvParams& e = p.env;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int g = lane >> 4, j16 = lane & 15;
-  const int H1 = p.H1, H2 = p.H2, A = p.A, A16 = p.A16, B = p.B;
+  const int H1 = STAT ? 256 : p.H1, H2 = STAT ? 256 : p.H2;
+  const int A = p.A, A16 = p.A16, B = p.B, SBL = p.SBL;
   const int Q1 = H1 >> 4, Q2 = H2 >> 4;
   const int NT2 = H2 >> 4, NT3 = A16 >> 4, nchunk = A16 >> 2;
   const int KS = logits_ksplit(NT3, Q2);
 
-  float* z1s = smem;                          // pre-activation of layer 1, high part
-  float* z1l = z1s + (H1 >> 2) * kPitch;      // ... low part (z1 = hi + lo carries the sum to ~48 bits)
-  float* h2s = z1l + (H1 >> 2) * kPitch;
-  float* lgs = h2s + (H2 >> 2) * kPitch;      // [KS][nchunk] partial logits
-  float* z1i = lgs + KS * nchunk * kPitch;    // z1(s_0): [2][H1] high and low parts, for slots that restart
-  int* alive = (int*)(z1i + 2 * H1);          // [kSlots] slot is running a trajectory
+  const RolloutLds L = rollout_lds_layout(H1, H2, A16, SBL, STAT);
+  float* z1s = (float*)(smem_raw + L.z1s);
+  float* z1l = (float*)(smem_raw + L.z1l);
+  float* h2s = (float*)(smem_raw + L.h2s);
+  float* lgs = (float*)(smem_raw + L.lgs);
+  float* z1i = (float*)(smem_raw + L.z1i);
+  int* alive = (int*)(smem_raw + L.flags);    // [kSlots] slot is running a trajectory
   int* srow = alive + kSlots;                 // [kSlots] row t*B + b of the slot's current transition
   int* qnext = srow + kSlots;                 // next trajectory of this workgroup's range to start
-  int8_t* st = (int8_t*)(qnext + 4);
+  int8_t* st = (int8_t*)(smem_raw + L.st);
+  const f32x4* w2l = (const f32x4*)(smem_raw + L.w2l);
 
   const int b0 = blockIdx.x * p.tpw;                    // this workgroup's trajectories: [b0, bend)
   const int bend = min(B, b0 + p.tpw);
   // roles in the SU phase: 32 lanes (sub-lane si) of one wave per slot sj
   const int sj = 2 * w + (lane >> 5), si = lane & 31;
+  int8_t* stj = st + sj * SBL;                          // this slot's state bytes
   int sb = b0 + sj;                                     // trajectory in this slot
   int ts = 0;                                           // its step counter
 
@@ -115,7 +157,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     z1i[f] = hi;
     z1i[H1 + f] = lo;
   }
-  for (int i = tid; i < e.state_dim * kSlots; i += kRolloutThreads) st[i] = 0;
+  for (int i = tid; 4 * i < SBL * kSlots; i += kRolloutThreads) ((uint32_t*)st)[i] = 0u;
   if (tid < kSlots) {
     alive[tid] = (b0 + tid < bend) ? 1 : 0;
     srow[tid] = b0 + tid;
@@ -124,18 +166,33 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   float lpf = 0.f, lpb = 0.f;
   int len_given = 0;
   if (REPLAY && sb < bend) len_given = p.length[sb];
-  f32x4 w2r[STAT ? 2 : 1][STAT ? 16 : 1];
+  f32x4 w2r[STAT ? 2 : 1][STAT ? kW2RegQ : 1];
   f32x4 w3r[STAT ? 2 : 1];
   if constexpr (STAT) {
     const f32x4* wp = (const f32x4*)p.W2p + (size_t)(w * 2) * 16 * 64 + lane;
 #pragma unroll
-    for (int n = 0; n < 2; ++n)
+    for (int n = 0; n < 2; ++n) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) w2r[n][q] = wp[(n * 16 + q) * 64];
+      for (int q = 0; q < kW2RegQ; ++q) w2r[n][q] = wp[(n * 16 + q) * 64];
+#pragma unroll
+      for (int q = kW2RegQ; q < 16; ++q)
+        ((f32x4*)w2l)[((w * 2 + n) * (16 - kW2RegQ) + (q - kW2RegQ)) * 64 + lane] = wp[(n * 16 + q) * 64];
+    }
     const f32x4* wp3 = (const f32x4*)p.W3p + lane;  // tile 0, this wave's eighth of the contraction
 #pragma unroll
     for (int q = 0; q < 2; ++q) w3r[q] = wp3[(w * 2 + q) * 64];
   }
+  // bias of the logits this lane owns in the SU phase
+  f32x4 b3r[NCH];
+#pragma unroll
+  for (int n = 0; n < NCH; ++n) {
+    const int c = si + 32 * n;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) b3r[n][k] = (c < nchunk && 4 * c + k < A) ? p.b3[4 * c + k] : 0.f;
+  }
+  // partial logits of a split contraction are summed across lanes when (parts x chunks) is exactly the 32
+  // lanes of a slot (1, 2 or 4 logit tiles); otherwise by the owning lane
+  const bool lane_sum = KS > 1 && KS * nchunk == 32;
   lds_barrier();
 
   // list-scheduling bound on the number of steps: (sum of lengths) / kSlots + longest trajectory
@@ -161,11 +218,22 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 #pragma unroll
       for (int n = 0; n < NTW; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if constexpr (STAT) {
+        const f32x4* wl = w2l + (size_t)(w * 2) * (16 - kW2RegQ) * 64 + lane;
+        f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-          const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
-#pragma unroll
-          for (int n = 0; n < 2; ++n) { GFNX_MFMA4(acc[n], w2r[n][q], bv); }
+          const f32x4 bv = relu4(bvn);
+          if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + j16 * 4];
+          f32x4 a0, a1;
+          if (q < kW2RegQ) {
+            a0 = w2r[0][q];
+            a1 = w2r[1][q];
+          } else {
+            a0 = wl[(q - kW2RegQ) * 64];
+            a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];
+          }
+          GFNX_MFMA4(acc[0], a0, bv);
+          GFNX_MFMA4(acc[1], a1, bv);
         }
       } else if (w * NTW < NT2) {
         // tiles w*NTW .. w*NTW+NTW-1 (clamped: a clamped tile is computed twice and stored once)
@@ -215,24 +283,36 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       }
     }
     if (KS == 1) {
-      // whole tiles: w and w + 8
+      // whole tiles: w and w + 8; the weights stream from L2 cache four contraction steps ahead of their use
       f32x4 acc[2];
 #pragma unroll
       for (int n = 0; n < 2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if (w < NT3) {
-        const f32x4* wp = (const f32x4*)p.W3p + lane;
-        const int t0 = w, t1 = min(w + 8, NT3 - 1);
-        f32x4 c0 = wp[((size_t)t0 * Q2) * 64], c1 = wp[((size_t)t1 * Q2) * 64];
-        for (int q = 0; q < Q2; ++q) {
-          const int qn = q + 1 < Q2 ? q + 1 : q;
-          const f32x4 n0 = wp[((size_t)t0 * Q2 + qn) * 64], n1 = wp[((size_t)t1 * Q2 + qn) * 64];
-          const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
-          GFNX_MFMA4(acc[0], c0, bv);
-          if (w + 8 < NT3) { GFNX_MFMA4(acc[1], c1, bv); }
-          c0 = n0; c1 = n1;
+        const bool two = w + 8 < NT3;
+        const f32x4* wp0 = (const f32x4*)p.W3p + (size_t)w * Q2 * 64 + lane;
+        const f32x4* wp1 = (const f32x4*)p.W3p + (size_t)(two ? w + 8 : w) * Q2 * 64 + lane;
+        f32x4 r0[4], r1[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          r0[d] = wp0[min(d, Q2 - 1) * 64];
+          r1[d] = wp1[min(d, Q2 - 1) * 64];
+        }
+#pragma nounroll
+        for (int q0 = 0; q0 < Q2; q0 += 4) {  // Q2 is a multiple of 4 (hidden widths are multiples of 64)
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const int q = q0 + d;
+            const f32x4 c0 = r0[d], c1 = r1[d];
+            const int qn = min(q + 4, Q2 - 1);
+            r0[d] = wp0[qn * 64];
+            r1[d] = wp1[qn * 64];
+            const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+            GFNX_MFMA4(acc[0], c0, bv);
+            if (two) { GFNX_MFMA4(acc[1], c1, bv); }
+          }
         }
         *(f32x4*)&lgs[(4 * w + g) * kPitch + j16 * 4] = acc[0];
-        if (w + 8 < NT3) *(f32x4*)&lgs[(4 * (w + 8) + g) * kPitch + j16 * 4] = acc[1];
+        if (two) *(f32x4*)&lgs[(4 * (w + 8) + g) * kPitch + j16 * 4] = acc[1];
       }
     } else {
       // wave w: tile w / KS, contraction part w % KS
@@ -263,60 +343,66 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     if (alive[sj]) {
       const int t = ts;
       if (p.sbuf) {  // the state the policy is evaluated at, for the one-hot contraction of the gradient pass
-        uint32_t* srowp = (uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB);  // SB is a multiple of 16
-        for (int s4 = si; 4 * s4 < p.SB; s4 += 32) {
-          uint32_t packed = 0;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int s = 4 * s4 + k;
-            const uint32_t byte = s < e.state_dim ? (uint32_t)(uint8_t)st[s * kSlots + sj] : 0u;
-            packed |= byte << (8 * k);
-          }
-          srowp[s4] = packed;
-        }
+        uint32_t* srowp = (uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB);  // SB is a multiple of 16, <= SBL
+        for (int s4 = si; 4 * s4 < p.SB; s4 += 32) srowp[s4] = ((const uint32_t*)stj)[s4];
       }
+      // ---- logits of this lane's chunks, validity bits, running maximum
       f32x4 lg[NCH];
       uint32_t vm[NCH];
       float m = -INFINITY;
 #pragma unroll
       for (int n = 0; n < NCH; ++n) {
         const int c = si + 32 * n;
-        vm[n] = 0;
-        lg[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (c < nchunk) {
-          f32x4 v;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = (4 * c + k < A) ? p.b3[4 * c + k] : 0.f;
-          for (int ks = 0; ks < KS; ++ks) v += *(const f32x4*)&lgs[(ks * nchunk + c) * kPitch + sj * 4];
-          lg[n] = v;
+        f32x4 v = b3r[n];
+        if (lane_sum) {
+          // lane si holds part si / nchunk of chunk si % nchunk; the parts of a chunk are nchunk lanes apart
+          f32x4 pv = *(const f32x4*)&lgs[si * kPitch + sj * 4];
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
-            // branch-free: state bytes are read at a clamped index and combined with bitwise logic
-            const int a = 4 * c + k;
-            uint32_t ok;
-            if (ENV == 0) {
-              const int sv = st[min(a, e.d - 1) * kSlots + sj];
-              ok = (uint32_t)(a == e.d) | ((uint32_t)(a < e.d) & (uint32_t)(sv < e.H - 1));
-            } else if (ENV == 1) {
-              ok = (uint32_t)(a < A);
-            } else {
-              const int sv = st[min(a >> 1, e.D - 1) * kSlots + sj];
-              ok = (uint32_t)(a < A) & (uint32_t)(sv == 0);
-            }
-            vm[n] |= ok << k;
-            m = ok ? fmaxf(m, v[k]) : m;
+            float x = pv[k];
+            x += swz_xor16(x);
+            if (nchunk <= 8) x += row16_rot<8>(x);
+            if (nchunk <= 4) x += row16_rot<4>(x);
+            pv[k] = x;
           }
+          v += pv;
+        } else if (c < nchunk) {
+          for (int ks = 0; ks < KS; ++ks) v += *(const f32x4*)&lgs[(ks * nchunk + c) * kPitch + sj * 4];
         }
+        lg[n] = v;
+        // state bytes that decide the validity of actions 4c .. 4c+3, fetched as one word at a clamped index
+        uint32_t sw = 0;
+        if (ENV == 0) sw = ((const uint32_t*)stj)[min(c, (SBL >> 2) - 1)];
+        if (ENV == 2) sw = ((const uint16_t*)stj)[min(c, (SBL >> 1) - 1)];
+        uint32_t bits = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int a = 4 * c + k;
+          uint32_t ok;
+          if (ENV == 0) {
+            const int sv = (int)((sw >> (8 * k)) & 0xFFu);
+            ok = (uint32_t)(a == e.d) | ((uint32_t)(a < e.d) & (uint32_t)(sv < e.H - 1));
+          } else if (ENV == 1) {
+            ok = (uint32_t)(a < A);
+          } else {
+            const uint32_t sv = (sw >> (8 * (k >> 1))) & 0xFFu;
+            ok = (uint32_t)(a < A) & (uint32_t)(sv == 0u);
+          }
+          bits |= ok << k;
+          m = fmaxf(m, ok ? v[k] : -INFINITY);
+        }
+        vm[n] = bits;
       }
       m = grp32_max(m);
-      // softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
+      // ---- softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
       f32x4 wv[NCH];
       float sum = 0.f;
 #pragma unroll
       for (int n = 0; n < NCH; ++n)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          wv[n][k] = ((vm[n] >> k) & 1u) ? expf(lg[n][k] - m) : 0.f;
+          const float ex = exp_nonpos(fminf(lg[n][k] - m, 0.f));
+          wv[n][k] = ((vm[n] >> k) & 1u) ? ex : 0.f;
           sum += wv[n][k];
         }
       sum = grp32_sum(sum);
@@ -324,47 +410,80 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       const float inv_sum = 1.f / sum;
 
       int act;
-      float alogit;
       bool given_ok = true;  // teacher-forced mode: is the given action possible in this state?
       if (!REPLAY) {
         // Gumbel-max as an exponential race: argmax_a (l_a - log(-log u_a)) = argmin_a (-log u_a) / exp(l_a - m),
-        // one logarithm per action; lowest index wins exact ties
-        float best = INFINITY, blog = 0.f;
-        int bidx = 0x7fffffff;
+        // one logarithm per action (base 2: the common factor ln 2 does not move the argmin); logarithm and
+        // reciprocal on the transcendental unit, relative error of the key below 4e-7.  An action of weight 0
+        // (invalid, or underflowed) gets the key +inf and cannot win: the largest valid logit has weight 1.  Key
+        // (a non-negative float, ordered like its bit pattern) and action index are packed into 64 bits, so one
+        // unsigned minimum finds the winner and lets the lowest index win exact ties.
+        unsigned long long best = ~0ull;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
           const int c = si + 32 * n;
-          if (vm[n]) {
-            uint32_t wd[4];
-            philox4x32_10((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
+          uint32_t wd[4];
+          philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              if ((vm[n] >> k) & 1u) {
-                const float r = -logf(uniform_from_bits(wd[k])) / wv[n][k];
-                if (r < best) { best = r; bidx = 4 * c + k; blog = lg[n][k]; }
-              }
-            }
+          for (int k = 0; k < 4; ++k) {
+            const float r = -__builtin_amdgcn_logf(uniform_from_bits(wd[k])) * __builtin_amdgcn_rcpf(wv[n][k]);
+            const unsigned long long key =
+                ((unsigned long long)__builtin_bit_cast(uint32_t, r) << 32) | (uint32_t)(4 * c + k);
+            best = key < best ? key : best;
           }
         }
-        grp32_argmin(best, bidx, blog);
-        act = bidx;
-        alogit = blog;
+        best = grp32_min_u64(best);
+        act = (int)(uint32_t)best;
       } else {
         act = p.actions[(size_t)t * B + sb];
+      }
+      // logit of the action taken, from the lane that owns it
+      float alogit;
+      {
         float mine = 0.f;
         int mine_ok = 0;
 #pragma unroll
-        for (int n = 0; n < NCH; ++n)
-#pragma unroll
-          for (int k = 0; k < 4; ++k)
-            if (4 * (si + 32 * n) + k == act) { mine = lg[n][k]; mine_ok = (int)((vm[n] >> k) & 1u); }
+        for (int n = 0; n < NCH; ++n) {
+          const bool own = (act >> 7) == n;  // chunk act / 4 = si + 32 n
+          const int k = act & 3;
+          const float x = k == 0 ? lg[n].x : (k == 1 ? lg[n].y : (k == 2 ? lg[n].z : lg[n].w));
+          mine = own ? x : mine;
+          mine_ok = own ? (int)((vm[n] >> k) & 1u) : mine_ok;
+        }
         alogit = __shfl(mine, (act >> 2) & 31, 32);
-        given_ok = __shfl(mine_ok, (act >> 2) & 31, 32) != 0;
-        if (!given_ok) { act = 0; alogit = m + lse; }  // log p = 0; the trajectory is cut below
+        if (REPLAY) {
+          given_ok = (act < A) && __shfl(mine_ok, (act >> 2) & 31, 32) != 0;
+          if (!given_ok) { act = 0; alogit = m + lse; }  // log p = 0; the trajectory is cut below
+        }
       }
       lpf += (alogit - m) - lse;
 
-      {  // direction of the logit gradient: onehot(a) - p on valid actions, 0 elsewhere
+      // the one-hot row that leaves / enters the input with this action (known to all lanes of the slot); the
+      // two rows of W1 are requested now so that their latency overlaps the bookkeeping below
+      int rold = 0, rnew = 0;
+      if (!REPLAY || given_ok) {
+        if (ENV == 0) {
+          if (act != e.d) {
+            rold = e.H * act + stj[act];
+            rnew = rold + 1;
+          }
+        } else if (ENV == 1) {
+          rold = ((1 << e.k_bits) + 1) * ts + (1 << e.k_bits);
+          rnew = ((1 << e.k_bits) + 1) * ts + act;
+        } else {
+          rold = 3 * (act >> 1) + 1;
+          rnew = 3 * (act >> 1) + 2 * (act & 1);
+        }
+      }
+      f32x4 wo[2], wn[2];
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int fg = min(si + 32 * it, (H1 >> 2) - 1);
+        wo[it] = *(const f32x4*)&p.W1[(size_t)rold * H1 + 4 * fg];
+        wn[it] = *(const f32x4*)&p.W1[(size_t)rnew * H1 + 4 * fg];
+      }
+
+      {  // direction of the logit gradient: onehot(a) - p on valid actions, 0 elsewhere (weight 0 there)
         float* erow = p.ebuf + ((size_t)t * B + sb) * A16;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
@@ -372,8 +491,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           if (c < nchunk) {
             f32x4 ev;
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-              ev[k] = ((vm[n] >> k) & 1u) ? ((4 * c + k == act ? 1.f : 0.f) - wv[n][k] * inv_sum) : 0.f;
+            for (int k = 0; k < 4; ++k) ev[k] = (4 * c + k == act ? 1.f : 0.f) - wv[n][k] * inv_sum;
+            if (REPLAY && !given_ok) ev = (f32x4){0.f, 0.f, 0.f, 0.f};
             *(f32x4*)&erow[4 * c] = ev;
           }
         }
@@ -383,18 +502,14 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       float logr = 0.f;
       int xi = 0;              // grid: this lane's coordinate after the step
       int site = 0, spin = 0;  // ising
-      int rold = 0, rnew = 0;  // the one-hot row that leaves / enters (known to all lanes of the slot)
       if (REPLAY && !given_ok) {
         term = true;  // impossible action in the given sequence: cut the trajectory here, state unchanged
-        if (ENV == 0) xi = (si < e.d) ? st[si * kSlots + sj] : 0;
+        if (ENV == 0) xi = (si < e.d) ? stj[si] : 0;
         site = -1;
       } else if (ENV == 0) {
-        xi = (si < e.d) ? st[si * kSlots + sj] : 0;
+        xi = (si < e.d) ? stj[si] : 0;
         if (act != e.d) {
-          const int xa = st[act * kSlots + sj];
-          rold = e.H * act + xa;
-          rnew = rold + 1;
-          if (si == act) { st[si * kSlots + sj] = (int8_t)(xi + 1); xi += 1; }
+          if (si == act) { stj[si] = (int8_t)(xi + 1); xi += 1; }
           const int cnt = grp32_sum((si < e.d && xi > 0) ? 1 : 0);
           lpb -= logf((float)cnt);
         } else {
@@ -407,15 +522,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
       } else if (ENV == 1) {
         const int k = e.k_bits;
-        rold = ((1 << k) + 1) * t + (1 << k);
-        rnew = ((1 << k) + 1) * t + act;
-        if (si == 0) st[t * kSlots + sj] = (int8_t)act;
+        if (si == 0) stj[t] = (int8_t)act;
         if (t == e.L - 1) {
           int dmin = 0x7fffffff;
           for (int mm = si; mm < e.n_modes; mm += 32) {
             int dist = 0;
             for (int pos = 0; pos < e.L; ++pos) {
-              const uint32_t tok = (pos == t) ? (uint32_t)act : (uint32_t)(uint8_t)st[pos * kSlots + sj];
+              const uint32_t tok = (pos == t) ? (uint32_t)act : (uint32_t)(uint8_t)stj[pos];
               const uint32_t rev = __brev(tok) >> (32 - k);
               dist += __popc(rev ^ mode_chunk(e.modes, e.words, mm, pos, k));
             }
@@ -428,9 +541,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       } else {
         site = act >> 1;
         spin = 2 * (act & 1) - 1;
-        rold = 3 * site + 1;
-        rnew = 3 * site + 1 + spin;
-        if (si == 0) st[site * kSlots + sj] = (int8_t)spin;
+        if (si == 0) stj[site] = (int8_t)spin;
         lpb -= logf((float)(t + 1));
         if (t == e.D - 1) {
           int acc = 0;
@@ -438,9 +549,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             const int r = s / e.N, c = s - r * e.N;
             const int sr = r * e.N + (c + 1 == e.N ? 0 : c + 1);
             const int sd = (r + 1 == e.N ? 0 : r + 1) * e.N + c;
-            const int x = (s == site) ? spin : st[s * kSlots + sj];
-            const int xr = (sr == site) ? spin : st[sr * kSlots + sj];
-            const int xd = (sd == site) ? spin : st[sd * kSlots + sj];
+            const int x = (s == site) ? spin : stj[s];
+            const int xr = (sr == site) ? spin : stj[sr];
+            const int xd = (sd == site) ? spin : stj[sd];
             acc += x * (xr + xd);
           }
           acc = grp32_sum(acc);
@@ -460,8 +571,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         for (int s = si; s < e.state_dim; s += 32) {
           int v;
           if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
-          else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)st[s * kSlots + sj];
-          else v = (s == site) ? spin : st[s * kSlots + sj];
+          else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)stj[s];
+          else v = (s == site) ? spin : stj[s];
           p.term[(size_t)s * B + sb] = (int8_t)v;
         }
         // the slot starts the next trajectory of the workgroup's range, if any is left
@@ -474,7 +585,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           lpf = 0.f;
           lpb = 0.f;
           if (REPLAY) len_given = p.length[sb];
-          for (int s2 = si; s2 < e.state_dim; s2 += 32) st[s2 * kSlots + sj] = 0;
+          for (int s4 = si; 4 * s4 < SBL; s4 += 32) ((uint32_t*)stj)[s4] = 0u;
           for (int fg = si; fg < (H1 >> 2); fg += 32) {
             *(f32x4*)&z1s[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
             *(f32x4*)&z1l[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[H1 + 4 * fg];
@@ -490,15 +601,18 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
         const float* wo_row = p.W1 + (size_t)rold * H1;
         const float* wn_row = p.W1 + (size_t)rnew * H1;
-        for (int fg = si; fg < (H1 >> 2); fg += 32) {
+        for (int it = 0; si + 32 * it < (H1 >> 2); ++it) {
+          const int fg = si + 32 * it;
           f32x4* zp = (f32x4*)&z1s[fg * kPitch + sj * 4];
           f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
-          const f32x4 wo = *(const f32x4*)&wo_row[4 * fg];
-          const f32x4 wn = *(const f32x4*)&wn_row[4 * fg];
+          f32x4 o, n;
+          if (it == 0) { o = wo[0]; n = wn[0]; }
+          else if (it == 1) { o = wo[1]; n = wn[1]; }
+          else { o = *(const f32x4*)&wo_row[4 * fg]; n = *(const f32x4*)&wn_row[4 * fg]; }
           f32x4 hi = *zp, lo = *lp;
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
-            const double z = ((double)hi[k] + (double)lo[k]) - (double)wo[k] + (double)wn[k];
+            const double z = ((double)hi[k] + (double)lo[k]) - (double)o[k] + (double)n[k];
             hi[k] = (float)z;
             lo[k] = (float)(z - (double)hi[k]);
           }
