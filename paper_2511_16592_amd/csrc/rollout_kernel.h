@@ -43,8 +43,11 @@ __device__ __forceinline__ uint32_t mode_chunk(const uint32_t* modes, int words,
   return (uint32_t)(v >> (s & 31)) & ((1u << k) - 1u);
 }
 
-// max(v, 0) as a three-operand median: one instruction per element
-__device__ __forceinline__ float relu1(float v) { return __builtin_amdgcn_fmed3f(v, 0.f, INFINITY); }
+// max(v, 0) on the bit pattern: a negative float is a negative integer, a positive one keeps its order (one
+// integer instruction, no canonicalisation of the operand)
+__device__ __forceinline__ float relu1(float v) {
+  return __builtin_bit_cast(float, max(__builtin_bit_cast(int, v), 0));
+}
 __device__ __forceinline__ f32x4 relu4(f32x4 v) {
   v.x = relu1(v.x); v.y = relu1(v.y); v.z = relu1(v.z); v.w = relu1(v.w);
   return v;
@@ -182,6 +185,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 #pragma unroll
     for (int q = 0; q < 2; ++q) w3r[q] = wp3[(w * 2 + q) * 64];
   }
+  // bias of the layer-2 features this lane finishes in L2
+  f32x4 b2r[NTW];
+#pragma unroll
+  for (int n = 0; n < NTW; ++n) b2r[n] = *(const f32x4*)&p.b2[16 * min(w * NTW + n, NT2 - 1) + 4 * g];
   // bias of the logits this lane owns in the SU phase
   f32x4 b3r[NCH];
 #pragma unroll
@@ -220,21 +227,38 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       if constexpr (STAT) {
         const f32x4* wl = w2l + (size_t)(w * 2) * (16 - kW2RegQ) * 64 + lane;
         f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const f32x4 bv = relu4(bvn);
-          if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + j16 * 4];
-          f32x4 a0, a1;
-          if (q < kW2RegQ) {
-            a0 = w2r[0][q];
-            a1 = w2r[1][q];
-          } else {
-            a0 = wl[(q - kW2RegQ) * 64];
-            a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];
-          }
-          GFNX_MFMA4(acc[0], a0, bv);
-          GFNX_MFMA4(acc[1], a1, bv);
+        // One contraction step; NEXT_READS = LDS reads of the following step (activations, plus the two weight
+        // operands once past the register-resident part), which are issued before this step's eight matrix
+        // instructions so that their latency is covered.
+#define GFNX_L2_STEP(NEXT_READS)                                                                     \
+        {                                                                                            \
+          const f32x4 bv = relu4(bvn);                                                               \
+          if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + j16 * 4];           \
+          f32x4 a0, a1;                                                                              \
+          if (q < kW2RegQ) {                                                                         \
+            a0 = w2r[0][q];                                                                          \
+            a1 = w2r[1][q];                                                                          \
+          } else {                                                                                   \
+            a0 = wl[(q - kW2RegQ) * 64];                                                             \
+            a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];                                          \
+          }                                                                                          \
+          GFNX_MFMA4(acc[0], a0, bv);                                                                \
+          GFNX_MFMA4(acc[1], a1, bv);                                                                \
+          __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                                \
+          __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                         \
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0); /* relu of the next step's activations */ \
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the read of step 0 above
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // and its relu
+#pragma unroll
+        for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1)
+#pragma unroll
+        for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3)
+        {
+          constexpr int q = 15;
+          GFNX_L2_STEP(0)
+        }
+#undef GFNX_L2_STEP
       } else if (w * NTW < NT2) {
         // tiles w*NTW .. w*NTW+NTW-1 (clamped: a clamped tile is computed twice and stored once)
         const f32x4* wp = (const f32x4*)p.W2p + lane;
@@ -259,10 +283,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 #pragma unroll
       for (int n = 0; n < NTW; ++n) {
         const int nt = w * NTW + n;
-        if (nt < NT2) {
-          const f32x4 bias = *(const f32x4*)&p.b2[16 * nt + 4 * g];
-          *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + bias);
-        }
+        if (nt < NT2) *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + b2r[n]);
       }
     }
     lds_barrier();
@@ -282,8 +303,11 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
       }
     }
-    if (KS == 1) {
-      // whole tiles: w and w + 8; the weights stream from L2 cache four contraction steps ahead of their use
+    if (ENV != 0 && KS == 1) {
+      // whole tiles: w and w + 8 (a wave without a second tile repeats its first: two independent accumulator
+      // chains either way); the weights stream from L2 cache kL3Ahead contraction steps ahead of their use.
+      // Grids have at most two logit tiles and never take this path.
+      constexpr int kL3Ahead = 2;
       f32x4 acc[2];
 #pragma unroll
       for (int n = 0; n < 2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -291,24 +315,33 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         const bool two = w + 8 < NT3;
         const f32x4* wp0 = (const f32x4*)p.W3p + (size_t)w * Q2 * 64 + lane;
         const f32x4* wp1 = (const f32x4*)p.W3p + (size_t)(two ? w + 8 : w) * Q2 * 64 + lane;
-        f32x4 r0[4], r1[4];
+        f32x4 r0[kL3Ahead], r1[kL3Ahead];
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
+        for (int d = 0; d < kL3Ahead; ++d) {
           r0[d] = wp0[min(d, Q2 - 1) * 64];
           r1[d] = wp1[min(d, Q2 - 1) * 64];
         }
+        f32x4 bvn = *(const f32x4*)&h2s[g * kPitch + j16 * 4];
 #pragma nounroll
-        for (int q0 = 0; q0 < Q2; q0 += 4) {  // Q2 is a multiple of 4 (hidden widths are multiples of 64)
+        for (int q0 = 0; q0 < Q2; q0 += kL3Ahead) {  // Q2 is a multiple of 4 (hidden widths are multiples of 64)
 #pragma unroll
-          for (int d = 0; d < 4; ++d) {
+          for (int d = 0; d < kL3Ahead; ++d) {
             const int q = q0 + d;
             const f32x4 c0 = r0[d], c1 = r1[d];
-            const int qn = min(q + 4, Q2 - 1);
+            const int qn = min(q + kL3Ahead, Q2 - 1);
             r0[d] = wp0[qn * 64];
             r1[d] = wp1[qn * 64];
-            const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
-            GFNX_MFMA4(acc[0], c0, bv);
-            if (two) { GFNX_MFMA4(acc[1], c1, bv); }
+            const f32x4 bv = bvn;
+            bvn = *(const f32x4*)&h2s[(4 * min(q + 1, Q2 - 1) + g) * kPitch + j16 * 4];
+            acc[0] = mfma16(c0.x, bv.x, acc[0]); acc[1] = mfma16(c1.x, bv.x, acc[1]);
+            acc[0] = mfma16(c0.y, bv.y, acc[0]); acc[1] = mfma16(c1.y, bv.y, acc[1]);
+            acc[0] = mfma16(c0.z, bv.z, acc[0]); acc[1] = mfma16(c1.z, bv.z, acc[1]);
+            acc[0] = mfma16(c0.w, bv.w, acc[0]); acc[1] = mfma16(c1.w, bv.w, acc[1]);
+            // issue order: the two weight loads kL3Ahead steps ahead, the next step's activations, then this
+            // step's eight matrix instructions
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
           }
         }
         *(f32x4*)&lgs[(4 * w + g) * kPitch + j16 * 4] = acc[0];
