@@ -167,6 +167,17 @@ __device__ __forceinline__ unsigned long long grp32_min_u64(unsigned long long v
   const unsigned long long o = ((unsigned long long)oh << 32) | ol;
   return o < v ? o : v;
 }
+// Reductions over the LPS = 16 or 32 lanes that serve one slot
+template <int LPS> __device__ __forceinline__ float grp_max(float v) { return LPS == 32 ? grp32_max(v) : row16_max(v); }
+template <int LPS> __device__ __forceinline__ float grp_sum(float v) { return LPS == 32 ? grp32_sum(v) : row16_sum(v); }
+template <int LPS> __device__ __forceinline__ int grp_sum(int v) { return LPS == 32 ? grp32_sum(v) : row16_sum(v); }
+template <int LPS> __device__ __forceinline__ int grp_min(int v) { return LPS == 32 ? grp32_min(v) : row16_min(v); }
+template <int LPS> __device__ __forceinline__ unsigned long long grp_min_u64(unsigned long long v) {
+  if (LPS == 32) return grp32_min_u64(v);
+  v = row16_min_u64_step<8>(v); v = row16_min_u64_step<4>(v);
+  v = row16_min_u64_step<2>(v); v = row16_min_u64_step<1>(v);
+  return v;
+}
 __device__ __forceinline__ void grp32_argmin(float& key, int& idx, float& payload) {
   row16_argmin(key, idx, payload);
   const float ok = swz_xor16(key), op = swz_xor16(payload);

@@ -10,7 +10,7 @@
 //       step's loads in flight), activations come from LDS in B-operand order;
 //   L3  logits the same way: output tiles split over the waves, and the contraction split as well when there
 //       are fewer than eight tiles;
-//   SU  per slot, 32 lanes of one wave: action mask, softmax weights, Philox draw and argmin by DPP row
+//   SU  per slot, 16 (grids) or 32 lanes of one wave: action mask, softmax weights, Philox draw and argmin by DPP row
 //       rotations plus one swizzle, log P_F / log P_B, the row of the logit gradient, environment
 //       transition, terminal log-reward, action byte; then the same lanes update the layer-1
 //       pre-activation: layer 1 is a one-hot gather and a transition swaps exactly one active row, so z1 is
@@ -142,8 +142,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 
   const int b0 = blockIdx.x * p.tpw;                    // this workgroup's trajectories: [b0, bend)
   const int bend = min(B, b0 + p.tpw);
-  // roles in the SU phase: 32 lanes (sub-lane si) of one wave per slot sj
-  const int sj = 2 * w + (lane >> 5), si = lane & 31;
+  // roles in the SU phase: LPS lanes (sub-lane si) of one wave per slot sj.  Grids have at most 32 logits, so 16
+  // lanes per slot are enough and four waves (one per SIMD, with the vector unit to itself) serve all slots.
+  constexpr int LPS = ENV == 0 ? 16 : 32;
+  constexpr int kSuWaves = kSlots / (64 / LPS);
+  const int sj = (64 / LPS) * (w % kSuWaves) + lane / LPS, si = lane % LPS;
+  const bool su_wave = w < kSuWaves;
   int8_t* stj = st + sj * SBL;                          // this slot's state bytes
   int sb = b0 + sj;                                     // trajectory in this slot
   int ts = 0;                                           // its step counter
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   f32x4 b3r[NCH];
 #pragma unroll
   for (int n = 0; n < NCH; ++n) {
-    const int c = si + 32 * n;
+    const int c = si + LPS * n;
 #pragma unroll
     for (int k = 0; k < 4; ++k) b3r[n][k] = (c < nchunk && 4 * c + k < A) ? p.b3[4 * c + k] : 0.f;
   }
@@ -372,12 +376,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     }
     lds_barrier();
 
-    // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (32 lanes per slot)
-    if (alive[sj]) {
+    // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (LPS lanes per slot)
+    if (su_wave && alive[sj]) {
       const int t = ts;
       if (p.sbuf) {  // the state the policy is evaluated at, for the one-hot contraction of the gradient pass
         uint32_t* srowp = (uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB);  // SB is a multiple of 16, <= SBL
-        for (int s4 = si; 4 * s4 < p.SB; s4 += 32) srowp[s4] = ((const uint32_t*)stj)[s4];
+        for (int s4 = si; 4 * s4 < p.SB; s4 += LPS) srowp[s4] = ((const uint32_t*)stj)[s4];
       }
       // ---- logits of this lane's chunks, validity bits, running maximum
       f32x4 lg[NCH];
@@ -385,15 +389,16 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       float m = -INFINITY;
 #pragma unroll
       for (int n = 0; n < NCH; ++n) {
-        const int c = si + 32 * n;
+        const int c = si + LPS * n;
         f32x4 v = b3r[n];
         if (lane_sum) {
           // lane si holds part si / nchunk of chunk si % nchunk; the parts of a chunk are nchunk lanes apart
           f32x4 pv = *(const f32x4*)&lgs[si * kPitch + sj * 4];
+          if (LPS == 16) pv += *(const f32x4*)&lgs[(si + 16) * kPitch + sj * 4];
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             float x = pv[k];
-            x += swz_xor16(x);
+            if (LPS == 32) x += swz_xor16(x);
             if (nchunk <= 8) x += row16_rot<8>(x);
             if (nchunk <= 4) x += row16_rot<4>(x);
             pv[k] = x;
@@ -426,7 +431,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
         vm[n] = bits;
       }
-      m = grp32_max(m);
+      m = grp_max<LPS>(m);
       // ---- softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
       f32x4 wv[NCH];
       float sum = 0.f;
@@ -438,9 +443,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           wv[n][k] = ((vm[n] >> k) & 1u) ? ex : 0.f;
           sum += wv[n][k];
         }
-      sum = grp32_sum(sum);
-      const float lse = logf(sum);
-      const float inv_sum = 1.f / sum;
+      sum = grp_sum<LPS>(sum);
+      // logarithm and reciprocal on the transcendental unit (1 ulp): log P_F accumulates errors of ~1e-7 per step
+      const float lse = __builtin_amdgcn_logf(sum) * 0.693147180559945f;
+      const float inv_sum = __builtin_amdgcn_rcpf(sum);
 
       int act;
       bool given_ok = true;  // teacher-forced mode: is the given action possible in this state?
@@ -454,7 +460,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         unsigned long long best = ~0ull;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-          const int c = si + 32 * n;
+          const int c = si + LPS * n;
           uint32_t wd[4];
           philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
 #pragma unroll
@@ -465,7 +471,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             best = key < best ? key : best;
           }
         }
-        best = grp32_min_u64(best);
+        best = grp_min_u64<LPS>(best);
         act = (int)(uint32_t)best;
       } else {
         act = p.actions[(size_t)t * B + sb];
@@ -477,15 +483,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         int mine_ok = 0;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-          const bool own = (act >> 7) == n;  // chunk act / 4 = si + 32 n
+          const bool own = (act >> 2) / LPS == n;  // chunk act / 4 = si + LPS n
           const int k = act & 3;
           const float x = k == 0 ? lg[n].x : (k == 1 ? lg[n].y : (k == 2 ? lg[n].z : lg[n].w));
           mine = own ? x : mine;
           mine_ok = own ? (int)((vm[n] >> k) & 1u) : mine_ok;
         }
-        alogit = __shfl(mine, (act >> 2) & 31, 32);
+        alogit = __shfl(mine, (act >> 2) % LPS, LPS);
         if (REPLAY) {
-          given_ok = (act < A) && __shfl(mine_ok, (act >> 2) & 31, 32) != 0;
+          given_ok = (act < A) && __shfl(mine_ok, (act >> 2) % LPS, LPS) != 0;
           if (!given_ok) { act = 0; alogit = m + lse; }  // log p = 0; the trajectory is cut below
         }
       }
@@ -508,10 +514,11 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           rnew = 3 * (act >> 1) + 2 * (act & 1);
         }
       }
-      f32x4 wo[2], wn[2];
+      constexpr int kPre = 64 / LPS;  // W1 row pieces requested early: all of a 256-wide layer
+      f32x4 wo[kPre], wn[kPre];
 #pragma unroll
-      for (int it = 0; it < 2; ++it) {
-        const int fg = min(si + 32 * it, (H1 >> 2) - 1);
+      for (int it = 0; it < kPre; ++it) {
+        const int fg = min(si + LPS * it, (H1 >> 2) - 1);
         wo[it] = *(const f32x4*)&p.W1[(size_t)rold * H1 + 4 * fg];
         wn[it] = *(const f32x4*)&p.W1[(size_t)rnew * H1 + 4 * fg];
       }
@@ -520,7 +527,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         float* erow = p.ebuf + ((size_t)t * B + sb) * A16;
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
-          const int c = si + 32 * n;
+          const int c = si + LPS * n;
           if (c < nchunk) {
             f32x4 ev;
 #pragma unroll
@@ -543,12 +550,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         xi = (si < e.d) ? stj[si] : 0;
         if (act != e.d) {
           if (si == act) { stj[si] = (int8_t)(xi + 1); xi += 1; }
-          const int cnt = grp32_sum((si < e.d && xi > 0) ? 1 : 0);
-          lpb -= logf((float)cnt);
+          const int cnt = grp_sum<LPS>((si < e.d && xi > 0) ? 1 : 0);
+          lpb -= __builtin_amdgcn_logf((float)cnt) * 0.693147180559945f;
         } else {
           const float v = fabsf((float)xi / (float)(e.H - 1) - 0.5f);
-          const int bad1 = grp32_sum((si < e.d && !(0.25f < v)) ? 1 : 0);
-          const int bad2 = grp32_sum((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
+          const int bad1 = grp_sum<LPS>((si < e.d && !(0.25f < v)) ? 1 : 0);
+          const int bad2 = grp_sum<LPS>((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
           const float r = e.r0 + e.r1 * (bad1 == 0 ? 1.f : 0.f) + e.r2 * (bad2 == 0 ? 1.f : 0.f);
           logr = logf(r);
           term = true;
@@ -558,7 +565,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         if (si == 0) stj[t] = (int8_t)act;
         if (t == e.L - 1) {
           int dmin = 0x7fffffff;
-          for (int mm = si; mm < e.n_modes; mm += 32) {
+          for (int mm = si; mm < e.n_modes; mm += LPS) {
             int dist = 0;
             for (int pos = 0; pos < e.L; ++pos) {
               const uint32_t tok = (pos == t) ? (uint32_t)act : (uint32_t)(uint8_t)stj[pos];
@@ -567,7 +574,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             }
             dmin = min(dmin, dist);
           }
-          dmin = grp32_min(dmin);
+          dmin = grp_min<LPS>(dmin);
           logr = -(e.beta / (float)e.n_bits) * (float)dmin;
           term = true;
         }
@@ -575,10 +582,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         site = act >> 1;
         spin = 2 * (act & 1) - 1;
         if (si == 0) stj[site] = (int8_t)spin;
-        lpb -= logf((float)(t + 1));
+        lpb -= __builtin_amdgcn_logf((float)(t + 1)) * 0.693147180559945f;
         if (t == e.D - 1) {
           int acc = 0;
-          for (int s = si; s < e.D; s += 32) {
+          for (int s = si; s < e.D; s += LPS) {
             const int r = s / e.N, c = s - r * e.N;
             const int sr = r * e.N + (c + 1 == e.N ? 0 : c + 1);
             const int sd = (r + 1 == e.N ? 0 : r + 1) * e.N + c;
@@ -587,7 +594,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             const int xd = (sd == site) ? spin : stj[sd];
             acc += x * (xr + xd);
           }
-          acc = grp32_sum(acc);
+          acc = grp_sum<LPS>(acc);
           logr = e.coupling * (float)acc;
           term = true;
         }
@@ -601,7 +608,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           p.lpb[sb] = lpb;
           p.logr[sb] = logr;
         }
-        for (int s = si; s < e.state_dim; s += 32) {
+        for (int s = si; s < e.state_dim; s += LPS) {
           int v;
           if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
           else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)stj[s];
@@ -611,15 +618,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         // the slot starts the next trajectory of the workgroup's range, if any is left
         int nb = 0;
         if (si == 0) nb = atomicAdd(qnext, 1);
-        nb = __shfl(nb, 0, 32);
+        nb = __shfl(nb, 0, LPS);
         if (nb < bend) {
           sb = nb;
           ts = 0;
           lpf = 0.f;
           lpb = 0.f;
           if (REPLAY) len_given = p.length[sb];
-          for (int s4 = si; 4 * s4 < SBL; s4 += 32) ((uint32_t*)stj)[s4] = 0u;
-          for (int fg = si; fg < (H1 >> 2); fg += 32) {
+          for (int s4 = si; 4 * s4 < SBL; s4 += LPS) ((uint32_t*)stj)[s4] = 0u;
+          for (int fg = si; fg < (H1 >> 2); fg += LPS) {
             *(f32x4*)&z1s[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
             *(f32x4*)&z1l[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[H1 + 4 * fg];
           }
@@ -634,14 +641,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
         const float* wo_row = p.W1 + (size_t)rold * H1;
         const float* wn_row = p.W1 + (size_t)rnew * H1;
-        for (int it = 0; si + 32 * it < (H1 >> 2); ++it) {
-          const int fg = si + 32 * it;
+        auto update = [&](int fg, f32x4 o, f32x4 n) {
           f32x4* zp = (f32x4*)&z1s[fg * kPitch + sj * 4];
           f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
-          f32x4 o, n;
-          if (it == 0) { o = wo[0]; n = wn[0]; }
-          else if (it == 1) { o = wo[1]; n = wn[1]; }
-          else { o = *(const f32x4*)&wo_row[4 * fg]; n = *(const f32x4*)&wn_row[4 * fg]; }
           f32x4 hi = *zp, lo = *lp;
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
@@ -651,7 +653,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           }
           *zp = hi;
           *lp = lo;
-        }
+        };
+#pragma unroll
+        for (int it = 0; it < kPre; ++it)
+          if (si + LPS * it < (H1 >> 2)) update(si + LPS * it, wo[it], wn[it]);
+        for (int fg = si + LPS * kPre; fg < (H1 >> 2); fg += LPS)
+          update(fg, *(const f32x4*)&wo_row[4 * fg], *(const f32x4*)&wn_row[4 * fg]);
       }
     }
     lds_barrier();
