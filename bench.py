@@ -32,7 +32,7 @@ DESCRIPTIONS = {
     "c5": "10-D grid H=20, MLP 200-256-256-11 (seeded Xavier), batch 16384, max 191 steps",
     "c5_long": "10-D grid H=20, MLP 200-256-256-11 with stop bias -8 (long walks), batch 16384",
 }
-KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "gfnx_device.h", "gfnx.hip")
+KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "gfnx_device.h", "gfnx.hip")
 
 
 def kernel_source_hash():

@@ -6,6 +6,7 @@
 #include "gfnx_device.h"
 #include "grad_kernels.h"
 #include "grad_kernels2.h"
+#include "grad_kernels3.h"
 #include "rollout_kernel.h"
 
 #include <string>
@@ -481,19 +482,19 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     float* part1 = at<float>(ws, L.part1);
     float* dbp1 = at<float>(ws, L.dbp1);
     const uint8_t* sbuf = at<uint8_t>(ws, L.sb);
-    const int lds = 32 * (256 + 256) * 4;
+    const int lds = (int)dw1_onehot_lds_bytes();
     {
       GFNX_TIMED("dw1", st);
       if (s.onehot == 1) {
-        auto k = gemm_tn2_kernel<2, 4, 4, 2, false, 1>;
+        auto k = dw1_onehot_kernel<1>;
         if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-        hipLaunchKernelGGL(k, dim3(1, 1, 256), dim3(512), lds, st, (const float*)nullptr, 0, s.p1, h1buf, s.H1, coef, B, rows, hdr,
-                           256, part1, dbp1, sbuf, s.sbytes, env->grid_side);
+        hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes,
+                           (int)env->grid_side, s.p1, part1, dbp1);
       } else {
-        auto k = gemm_tn2_kernel<2, 4, 4, 2, false, 2>;
+        auto k = dw1_onehot_kernel<2>;
         if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-        hipLaunchKernelGGL(k, dim3(1, 1, 256), dim3(512), lds, st, (const float*)nullptr, 0, s.p1, h1buf, s.H1, coef, B, rows, hdr,
-                           256, part1, dbp1, sbuf, s.sbytes, 1);
+        hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes, 1, s.p1,
+                           part1, dbp1);
       }
     }
     GFNX_TIMED("reduce_w1", st);
