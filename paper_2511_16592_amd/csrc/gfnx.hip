@@ -398,8 +398,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     }
     {
       GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
     }
     const int nt_lds = (64 * 258 + 192 + 512) * 4;
     const int gx = row_tiles < 256 ? row_tiles : 256;  // persistent: one workgroup per CU
@@ -420,8 +420,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     }
     {
       GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
     }
     {
       GFNX_TIMED("gemm_nt_g1", st);
@@ -448,8 +448,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
           hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
       }
       GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 255) / 256), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3, (const int*)nullptr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3, (const int*)nullptr);
     }
     const int gx = row_tiles < 2048 ? row_tiles : 2048;
     {
@@ -467,8 +467,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
       }
       GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 255) / 256), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, (const int*)nullptr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, (const int*)nullptr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2, (const int*)nullptr);
     }
     {
       GFNX_TIMED("gemm_nt_g1", st);
@@ -498,11 +498,11 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       }
     }
     GFNX_TIMED("reduce_w1", st);
-    hipLaunchKernelGGL(reduce2_kernel, dim3(1), dim3(64), 0, st, dbp1, 256, 1, 256, s.H1, grads->db1, hdr);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((256 / 4 + 63) / 64), dim3(256), 0, st, dbp1, 256, 1, 256, s.H1, grads->db1, hdr);
     if (s.onehot == 1)
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.p1 * 64 + 255) / 256), dim3(256), 0, st, part1, 256, s.p1, 256, s.H1, grads->dW1, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3(s.p1), dim3(256), 0, st, part1, 256, s.p1, 256, s.H1, grads->dW1, hdr);
     else
-      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 255) / 256), dim3(256), 0, st, part1, 256, s.p1,
+      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 63) / 64), dim3(256), 0, st, part1, 256, s.p1,
                          256, s.H1, hdr, grads->db1, grads->dW1);
   } else {
     // segment sums along each trajectory with atomics (large observation spaces: bit sequences)
