@@ -66,7 +66,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, coef, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
+  size_t hdr, w2p, w3p, w2t, w3t, coef, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -140,6 +140,8 @@ Layout make_layout(const Shapes& s) {
   L.hdr = o; o += align256(sizeof(int) * kHdrWords);
   L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
+  L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T, W3^T for the gradient pass
+  L.w3t = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
   L.coef = o; o += align256(sizeof(float) * (size_t)s.B);
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
@@ -402,12 +404,19 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
     }
     const int nt_lds = (64 * 258 + 192 + 512) * 4;
+    float* w2t = at<float>(ws, L.w2t);
+    float* w3t = at<float>(ws, L.w3t);
+    {
+      GFNX_TIMED("transpose_w", st);
+      hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, st, mlp->W3, s.H2, s.A, w3t);
+      hipLaunchKernelGGL(transpose_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, w2t);
+    }
     const int gx = row_tiles < 256 ? row_tiles : 256;  // persistent: one workgroup per CU
     {
       GFNX_TIMED("gemm_nt_g2", st);
       auto k = gemm_nt2_kernel<true>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2,
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
                          at<unsigned long long>(ws, L.m2), s.mw2, coef, B, rows, hdr);
     }
     {
@@ -427,7 +436,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       GFNX_TIMED("gemm_nt_g1", st);
       auto k = gemm_nt2_kernel<false>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1,
+      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
                          at<unsigned long long>(ws, L.m1), s.mw1, coef, B, rows, hdr);
     }
   } else {

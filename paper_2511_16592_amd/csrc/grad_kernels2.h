@@ -220,14 +220,24 @@ __global__ __launch_bounds__(256) void reduce2_kernel(const float* __restrict__ 
   }
 }
 
+// Wt[q][p] = W[p][q] for a row-major W of P rows and Q columns: the weight slices gemm_nt2_kernel keeps in
+// registers are then read with consecutive lanes on consecutive addresses.
+__global__ void transpose_kernel(const float* __restrict__ W, int P, int Q, float* __restrict__ Wt) {
+  const int total = P * Q;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int q = i / P, p = i - q * P;
+    Wt[i] = W[(size_t)p * Q + q];
+  }
+}
+
 // For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [act[i][p] > 0], written over the stored
-// activation; the ReLU derivative comes from the 1-bit sign masks the rollout recorded (word k of a row holds
+// activation; W is given transposed (Wt[q][p], P columns per row); the ReLU derivative comes from the 1-bit sign masks the rollout recorded (word k of a row holds
 // bit l for unit 4l+k), so the epilogue only stores.  Contraction length K <= 256 (rows of Gin hold K floats,
 // W rows hold Kvalid <= K).
 // grid = (row-tile workers (grid-stride), ceil(P/256)); 8 waves, wave w owns output columns 32w .. 32w+31.
 template <bool SCALE>
 __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__ Gin, int ldgi, int K,
-                                                       const float* __restrict__ W, int Kvalid,
+                                                       const float* __restrict__ Wt, int Kvalid,
                                                        float* __restrict__ ActOut, int ldo, int P,
                                                        const unsigned long long* __restrict__ mask, int MW,
                                                        const float* __restrict__ coef, int B,
@@ -249,7 +259,7 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
 #pragma unroll
   for (int s = 0; s < 128; ++s) {
     const int q = 4 * (s >> 1) + 2 * kk + (s & 1);
-    wreg[s] = (q < Kvalid && pcol < P) ? W[(size_t)pcol * Kvalid + q] : 0.f;
+    wreg[s] = (q < Kvalid && pcol < P) ? Wt[(size_t)q * P + pcol] : 0.f;
   }
 
   const int kv = K >> 2;               // f32x4 per row
