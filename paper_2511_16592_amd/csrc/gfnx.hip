@@ -66,7 +66,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, coef, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
+  size_t hdr, w2p, w3p, w2t, w3t, coef, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -144,6 +144,7 @@ Layout make_layout(const Shapes& s) {
   L.w3t = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
   L.coef = o; o += align256(sizeof(float) * (size_t)s.B);
   L.rows = o; o += align256(sizeof(int) * s.rows);
+  L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
   L.h2 = o; o += align256(sizeof(float) * s.rows * s.H2);
   L.e = o; o += align256(sizeof(float) * s.rows * s.A16);
@@ -355,6 +356,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   int* hdr = at<int>(ws, L.hdr);
   int* rows = at<int>(ws, L.rows);
   float* coef = at<float>(ws, L.coef);
+  float* crow = at<float>(ws, L.crow);
   float* h1buf = at<float>(ws, L.h1);
   float* h2buf = at<float>(ws, L.h2);
   float* ebuf = at<float>(ws, L.e);
@@ -368,7 +370,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   }
   {
     GFNX_TIMED("build_rows", st);
-    hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows);
+    hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows, (const float*)coef, crow);
   }
   Dw1Params dp = {};
   dp.env = env_params(env, s);
@@ -382,20 +384,31 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     float* dbp3 = at<float>(ws, L.dbp3);
     float* part2 = at<float>(ws, L.part2);
     float* dbp2 = at<float>(ws, L.dbp2);
-    // layer 3: dW3 = H2^T G3, db3; G3 = coef * e is formed on load
-    {
-      GFNX_TIMED("gemm_tn_w3", st);
-      if (s.qt3 == 32) {
-        auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
-        const int lds = 32 * (256 + 32) * 4;
-        hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                           s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
-      } else {
-        auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
-        const int lds = 32 * (256 + 256) * 4;
-        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-        hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                           s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
+    // narrow action spaces (grids): dW3, db3 and G2 in one HBM-bound sweep instead of two 16-wide GEMMs
+    const bool narrow = s.A16 == 16 && s.H2 == 256 && s.qtot3 == 32;
+    if (narrow) {
+      GFNX_TIMED("logit_bwd", st);
+      auto k = logit_bwd_narrow_kernel;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(s.s3), dim3(512), kNarrowLdsBytes, st, h2buf, (const float*)ebuf, (const float*)crow,
+                         mlp->W3, s.A, (const int*)rows,
+                         (const int*)hdr, part3, s.qtot3, dbp3);
+    } else {
+      // layer 3: dW3 = H2^T G3, db3; G3 = coef * e is formed on load
+      {
+        GFNX_TIMED("gemm_tn_w3", st);
+        if (s.qt3 == 32) {
+          auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
+          const int lds = 32 * (256 + 32) * 4;
+          hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                             s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
+        } else {
+          auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
+          const int lds = 32 * (256 + 256) * 4;
+          if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+          hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                             s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
+        }
       }
     }
     {
@@ -412,7 +425,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       hipLaunchKernelGGL(transpose_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, w2t);
     }
     const int gx = row_tiles < 256 ? row_tiles : 256;  // persistent: one workgroup per CU
-    {
+    if (!narrow) {
       GFNX_TIMED("gemm_nt_g2", st);
       auto k = gemm_nt2_kernel<true>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;

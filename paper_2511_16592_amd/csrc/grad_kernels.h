@@ -66,9 +66,11 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int* __restrict__ leng
   }
 }
 
-// Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b.
+// Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b, and next to
+// each its trajectory's coefficient crow[off[t] + rank] = coef[b].
 __global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict__ length, int B,
-                                                          const int* __restrict__ hdr, int* __restrict__ rows) {
+                                                          const int* __restrict__ hdr, int* __restrict__ rows,
+                                                          const float* __restrict__ coef, float* __restrict__ crow) {
   __shared__ int wsum[16];
   __shared__ int base;
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -84,7 +86,10 @@ __global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict_
     __syncthreads();
     int woff = 0, tot = 0;
     for (int k = 0; k < 16; ++k) { if (k < wv) woff += wsum[k]; tot += wsum[k]; }
-    if (on) rows[base + woff + before] = t * B + b;
+    if (on) {
+      rows[base + woff + before] = t * B + b;
+      crow[base + woff + before] = coef[b];
+    }
     __syncthreads();
     if (tid == 0) base += tot;
     __syncthreads();

@@ -181,4 +181,112 @@ __global__ __launch_bounds__(512) void dw1_onehot_kernel(const float* __restrict
 
 inline size_t dw1_onehot_lds_bytes() { return 3 * kDw1Round * 4 + kDw1Round * 112 + 2 * 4 * 2 * 256 * 16; }
 
+// Backward pass of the logit layer for narrow action spaces (at most 16 logits, 256 hidden units), one sweep
+// over the live transitions instead of two GEMM kernels whose contraction / output width would be 16:
+//   g3 = c_b * e (16 values), dW3 += h2^T g3, db3 += g3, G2 = (W3 g3) . [h2 > 0] written over h2.
+// A wave takes one transition at a time (four in flight): lane l owns hidden units 4l .. 4l+3, i.e. 16 bytes of
+// the 1 KiB row it reads and writes, its 4 x 16 slice of W3 and a 4 x 16 accumulator of dW3 in registers.  The
+// work is HBM-bound (read h2, write G2: 2 KiB per transition); the 128 multiply-adds per lane hide under it.
+// Transitions are split over the workgroups as in gemm_tn2_kernel and the partial tiles / column sums have its
+// layout (part[s][unit][QTOT], dbpart[s][QTOT]), so the same reduction finishes dW3 and db3.
+// crow[i] is the coefficient 2 delta_b / B of live transition i.
+constexpr int kNarrowInFlight = 4;
+constexpr int kNarrowLdsBytes = 8 * 16 * 64 * 16;
+__global__ __launch_bounds__(512) void logit_bwd_narrow_kernel(float* __restrict__ h2buf, const float* __restrict__ ebuf,
+                                                               const float* __restrict__ crow,
+                                                               const float* __restrict__ W3, int A,
+                                                               const int* __restrict__ rows, const int* __restrict__ hdr,
+                                                               float* __restrict__ part, int QTOT,
+                                                               float* __restrict__ dbpart) {
+  constexpr int U = kNarrowInFlight;  // transitions in flight per wave
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  f32x4 (*red)[16][64] = (f32x4 (*)[16][64])smem_raw;  // [wave][logit][lane]: 4 units each; 128 KiB
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int s = blockIdx.x, S = gridDim.x;
+  const int n = hdr[kHdrNLive];
+  const int chunks = (n + 31) / 32;
+  const int per = split_chunks_per_part(chunks, S);
+  const int c0 = s * per, c1 = min(chunks, c0 + per);
+  if (c0 >= c1) return;
+  const int row0 = 32 * c0, row1 = min(n, 32 * c1);
+
+  float w3r[4][16], acc[4][16];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      w3r[j][k] = k < A ? W3[(size_t)(4 * lane + j) * A + k] : 0.f;
+      acc[j][k] = 0.f;
+    }
+  float dbl = 0.f;  // lanes 0..15: column sum of g3 for logit `lane`
+
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  for (int base = row0 + wu * U; base < row1; base += 8 * U) {
+    // row id, coefficient and the 16 values of e are the same for every lane: they are fetched through the
+    // scalar cache and stay in scalar registers; per lane only the 16 bytes of h2 and one value of e (for db3)
+    int id[U];
+    float c[U], el[U];
+    f32x4 h[U];
+    const float* er[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int li = base + u;
+      id[u] = li < row1 ? rows[li] : -1;
+      c[u] = li < row1 ? crow[li] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t r = (size_t)(id[u] < 0 ? 0 : id[u]);
+      h[u] = *(const f32x4*)&h2buf[r * 256 + 4 * lane];
+      er[u] = ebuf + r * 16;
+      el[u] = er[u][lane & 15];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (id[u] < 0) continue;  // uniform: the row index does not depend on the lane
+      float g3[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) g3[k] = c[u] * er[u][k];
+      if (lane < 16) dbl += c[u] * el[u];
+      f32x4 t = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          acc[j][k] = __builtin_fmaf(h[u][j], g3[k], acc[j][k]);
+          t[j] = __builtin_fmaf(w3r[j][k], g3[k], t[j]);
+        }
+      // ReLU derivative from the activation itself: it is still in hand before G2 goes over it
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t[j] = h[u][j] > 0.f ? t[j] : 0.f;
+      *(f32x4*)&h2buf[(size_t)id[u] * 256 + 4 * lane] = t;
+    }
+  }
+
+  // fixed-order sum over the eight waves, then the partial tile of this workgroup
+#pragma unroll
+  for (int k = 0; k < 16; ++k) red[w][k][lane] = (f32x4){acc[0][k], acc[1][k], acc[2][k], acc[3][k]};
+  __syncthreads();
+  float* out = part + (size_t)s * 256 * QTOT;
+  for (int i = tid; i < 16 * 64; i += 512) {
+    const int k = i >> 6, l = i & 63;
+    f32x4 v = red[0][k][l];
+#pragma unroll
+    for (int ww = 1; ww < 8; ++ww) v += red[ww][k][l];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[(size_t)(4 * l + j) * QTOT + k] = v[j];
+  }
+  __syncthreads();
+  float* dbs = (float*)&red[0][0][0];
+  if (lane < 16) dbs[w * 16 + lane] = dbl;
+  __syncthreads();
+  if (tid < QTOT) {
+    float v = 0.f;
+    if (tid < 16)
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) v += dbs[ww * 16 + tid];
+    dbpart[(size_t)s * QTOT + tid] = v;
+  }
+}
+
 }  // namespace gfnx
