@@ -399,12 +399,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         GFNX_TIMED("gemm_tn_w3", st);
         if (s.qt3 == 32) {
           auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
-          const int lds = 32 * (256 + 32) * 4;
+          const int lds = 2 * 32 * (256 + 32) * 4;
+          if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
           hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
                              s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
         } else {
           auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
-          const int lds = 32 * (256 + 256) * 4;
+          const int lds = 2 * 32 * (256 + 256) * 4;
           if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
           hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
                              s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
@@ -435,7 +436,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     {
       GFNX_TIMED("gemm_tn_w2", st);
       auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
-      const int lds = 32 * (256 + 256) * 4;
+      const int lds = 2 * 32 * (256 + 256) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(1, 1, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
                          s.qtot2, part2, dbp2, (const uint8_t*)nullptr, 0, 1);

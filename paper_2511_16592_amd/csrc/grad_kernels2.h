@@ -40,9 +40,8 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
   constexpr int PT = WP * PBW * 32, QT = WQ * QBW * 32, KC = 32;
   constexpr int XV = KC * PT / 4 / 512, GV = (KC * QT / 4 + 511) / 512;  // f32x4 per thread per chunk
   static_assert(WP * WQ == 8, "eight waves");
-  extern __shared__ float smem[];
-  float* XS = smem;             // [KC][PT]
-  float* GS = smem + KC * PT;   // [KC][QT]
+  extern __shared__ float smem[];  // two buffers of [KC][PT] + [KC][QT]
+  constexpr int kBuf = KC * (PT + QT);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int ptile = blockIdx.x, qtile = blockIdx.y, s = blockIdx.z, S = gridDim.z;
   const int n = hdr[kHdrNLive];
@@ -125,7 +124,7 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
       }
     }
   };
-  auto store_chunk = [&]() {
+  auto store_chunk = [&](float* XS, float* GS) {
 #pragma unroll
     for (int m = 0; m < XV; ++m) {
       const int i = tid + 512 * m;
@@ -138,14 +137,22 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
     }
   };
 
+  // Chunk c is multiplied out of LDS buffer c % 2 while chunk c+1 (already in registers) is written to the other
+  // buffer and the rows of chunk c+2 are requested: one barrier per chunk.
   load_ids(c0);
   load_rows();
   load_ids(c0 + 1);
+  store_chunk(smem, smem + KC * PT);
+  load_rows();          // chunk c0+1
+  load_ids(c0 + 2);
+  lds_barrier();
   for (int c = c0; c < c1; ++c) {
-    store_chunk();
-    lds_barrier();
-    load_rows();        // chunk c+1, ids already here
-    load_ids(c + 2);
+    const float* XS = smem + ((c - c0) & 1) * kBuf;
+    const float* GS = XS + KC * PT;
+    float* XSn = smem + ((c - c0 + 1) & 1) * kBuf;
+    store_chunk(XSn, XSn + KC * PT);  // chunk c+1 (zeros past the end); its buffer was last read for chunk c-1
+    load_rows();                      // chunk c+2, ids already here
+    load_ids(c + 3);
 #pragma unroll 4
     for (int k = 0; k < KC; k += 2) {
       const int kk = k + (lane >> 5);
