@@ -160,6 +160,28 @@ def test_different_hidden_widths(gfnx, oracle32, oracle64):
     run_case(gfnx, oracle32, oracle64, env, w, 70, seed=8, iteration=3, log_z=0.2, name="grid_h192_320")
 
 
+def _wide_cases():
+    """256-wide networks on small environments: the on-chip-W2 rollout, the bf16 one-hot contraction with a ragged
+    number of one-hot columns, the one-sweep logit backward (<= 16 logits) and the GEMM pair (17..32 logits),
+    slot refill (batch > 4096), and unequal hidden widths on the fast gradient kernels."""
+    return [
+        ("grid3x7_256", grid_env(3, 7), (21, 256, 256, 4), 100),
+        ("grid3x7_256_refill", grid_env(3, 7), (21, 256, 256, 4), 5000),
+        ("grid16x3_256", grid_env(16, 3), (48, 256, 256, 17), 90),
+        ("ising3_256", ising_env(3), (27, 256, 256, 18), 40),
+        ("bitseq24k4_256", bitseq_env(24, 4, 7, mode_seed=2), (6 * 17, 256, 256, 16), 45),
+        ("grid4x6_128_256", grid_env(4, 6), (24, 128, 256, 5), 70),
+        ("grid4x6_256_64", grid_env(4, 6), (24, 256, 64, 5), 70),
+    ]
+
+
+@pytest.mark.parametrize("case", _wide_cases(), ids=lambda c: c[0])
+def test_wide_networks_small_envs(gfnx, oracle32, oracle64, case):
+    name, env, (n_in, h1, h2, n_act), batch = case
+    w = random_mlp(n_in, h1, h2, n_act, seed=36, scale=1.5)
+    run_case(gfnx, oracle32, oracle64, env, w, batch, seed=11, iteration=5, log_z=0.4, name=name)
+
+
 def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
     wl = workloads()["c1"]
     w = wl.mlp()
