@@ -57,12 +57,12 @@ struct Shapes {
   int state_dim, obs_dim, n_actions, max_steps;
   int H1, H2, A, A16, B;
   size_t rows;  // max_steps * B
-  int qt3, qtot3, s3, s2, qtot2;
+  int qt3, qtot3, s3, s2, qtot2;  // output tiling / split factors of dW3 and dW2
+  int s1, qtot1;                  // ... of the one-hot dW1 contraction
   int mw1, mw2; // 64-bit sign-mask words per transition row for h1 / h2
   int onehot;   // layer-1 weight gradient as a one-hot contraction: 0 no, 1 grid, 2 Ising
   int sbytes;   // state bytes recorded per transition row for it
   int p1;       // rows of that contraction's output tile
-  bool fast;    // hidden widths <= 256: one workgroup covers a whole operand (grad_kernels2.h)
 };
 
 struct Layout {
@@ -114,23 +114,19 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
   s->mw1 = 4 * ((s->H1 + 255) / 256);
   s->mw2 = 4 * ((s->H2 + 255) / 256);
-  s->fast = s->H1 <= 256 && s->H2 <= 256;
   s->onehot = 0; s->sbytes = 0; s->p1 = 0;
-  if (s->fast && env->kind == GFNX_ENV_GRID && s->obs_dim <= 256) { s->onehot = 1; s->sbytes = 16; s->p1 = s->obs_dim; }
-  if (s->fast && env->kind == GFNX_ENV_ISING) { s->onehot = 2; s->sbytes = 112; s->p1 = 2 * s->state_dim; }
-  if (s->fast) {
-    s->s2 = 256; s->qtot2 = 256;
-    s->qt3 = s->A16 <= 32 ? 32 : 256; s->qtot3 = s->qt3; s->s3 = 256;
-    return GFNX_OK;
-  }
-  // split factors of the weight-gradient contractions (over the transitions)
-  const int tiles2 = ((s->H1 + 127) / 128) * ((s->H2 + 127) / 128);
-  s->s2 = 1024 / tiles2; if (s->s2 > 256) s->s2 = 256; if (s->s2 < 1) s->s2 = 1;
-  s->qtot2 = ((s->H2 + 127) / 128) * 128;
-  s->qt3 = s->A16 <= 32 ? 32 : 128;
-  s->qtot3 = ((s->A16 + s->qt3 - 1) / s->qt3) * s->qt3;
-  const int tiles3 = ((s->H2 + 127) / 128) * (s->qtot3 / s->qt3);
-  s->s3 = 1024 / tiles3; if (s->s3 > 256) s->s3 = 256; if (s->s3 < 1) s->s3 = 1;
+  if (env->kind == GFNX_ENV_GRID && s->obs_dim <= 256) { s->onehot = 1; s->sbytes = 16; s->p1 = s->obs_dim; }
+  if (env->kind == GFNX_ENV_ISING) { s->onehot = 2; s->sbytes = 112; s->p1 = 2 * s->state_dim; }
+  // Weight-gradient contractions: 256 x 256 output tiles (256 x 32 for at most 32 logits), the transitions split
+  // over the workgroups so that about 256 of them run
+  const int pt2 = (s->H1 + 255) / 256, qn2 = (s->H2 + 255) / 256, pt3 = (s->H2 + 255) / 256;
+  s->qtot2 = 256 * qn2;
+  s->s2 = 256 / (pt2 * qn2);
+  s->qt3 = s->A16 <= 32 ? 32 : 256;
+  s->qtot3 = s->qt3;
+  s->s3 = 256 / pt3;
+  s->qtot1 = 256 * pt2;
+  s->s1 = 256 / pt2;
   return GFNX_OK;
 }
 
@@ -151,8 +147,8 @@ Layout make_layout(const Shapes& s) {
   L.m1 = o; o += align256(8 * s.rows * (size_t)s.mw1);
   L.m2 = o; o += align256(8 * s.rows * (size_t)s.mw2);
   L.sb = o; o += align256(s.rows * (size_t)s.sbytes);
-  L.part1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)256 * s.p1 * 256 : 0);
-  L.dbp1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)256 * 256 : 0);
+  L.part1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)s.s1 * s.p1 * s.qtot1 : 0);
+  L.dbp1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)s.s1 * s.qtot1 : 0);
   L.part2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.H1 * s.qtot2);
   L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
   L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
@@ -379,124 +375,91 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
   const int row_tiles = (int)((s.rows + 63) / 64);
 
-  if (s.fast) {
-    float* part3 = at<float>(ws, L.part3);
-    float* dbp3 = at<float>(ws, L.dbp3);
-    float* part2 = at<float>(ws, L.part2);
-    float* dbp2 = at<float>(ws, L.dbp2);
-    // narrow action spaces (grids): dW3, db3 and G2 in one HBM-bound sweep instead of two 16-wide GEMMs
-    const bool narrow = s.A16 == 16 && s.H2 == 256 && s.qtot3 == 32;
-    if (narrow) {
-      GFNX_TIMED("logit_bwd", st);
-      auto k = logit_bwd_narrow_kernel;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(s.s3), dim3(512), kNarrowLdsBytes, st, h2buf, (const float*)ebuf, (const float*)crow,
-                         mlp->W3, s.A, (const int*)rows,
-                         (const int*)hdr, part3, s.qtot3, dbp3);
+  float* part3 = at<float>(ws, L.part3);
+  float* dbp3 = at<float>(ws, L.dbp3);
+  float* part2 = at<float>(ws, L.part2);
+  float* dbp2 = at<float>(ws, L.dbp2);
+  const int pt2 = (s.H1 + 255) / 256, pt3 = (s.H2 + 255) / 256;
+  // layer 3.  Narrow action spaces (at most 16 logits, 256 hidden units): dW3, db3 and G2 in one HBM-bound sweep
+  // instead of two GEMMs that would be 16 wide
+  const bool narrow = s.A16 == 16 && s.H2 == 256;
+  if (narrow) {
+    GFNX_TIMED("logit_bwd", st);
+    auto k = logit_bwd_narrow_kernel;
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess) return GFNX_E_HIP;
+    hipLaunchKernelGGL(k, dim3(s.s3), dim3(512), kNarrowLdsBytes, st, h2buf, (const float*)ebuf, (const float*)crow,
+                       mlp->W3, s.A, (const int*)rows, (const int*)hdr, part3, s.qtot3, dbp3);
+  } else {
+    // dW3 = H2^T G3, db3; G3 = coef * e is formed on load
+    GFNX_TIMED("gemm_tn_w3", st);
+    if (s.qt3 == 32) {
+      auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
+      const int lds = 2 * 32 * (256 + 32) * 4;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                         s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
     } else {
-      // layer 3: dW3 = H2^T G3, db3; G3 = coef * e is formed on load
-      {
-        GFNX_TIMED("gemm_tn_w3", st);
-        if (s.qt3 == 32) {
-          auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
-          const int lds = 2 * 32 * (256 + 32) * 4;
-          if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-          hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                             s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
-        } else {
-          auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
-          const int lds = 2 * 32 * (256 + 256) * 4;
-          if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-          hipLaunchKernelGGL(k, dim3(1, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                             s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
-        }
-      }
-    }
-    {
-      GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
-    }
-    const int nt_lds = (64 * 258 + 192 + 512) * 4;
-    float* w2t = at<float>(ws, L.w2t);
-    float* w3t = at<float>(ws, L.w3t);
-    {
-      GFNX_TIMED("transpose_w", st);
-      hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, st, mlp->W3, s.H2, s.A, w3t);
-      hipLaunchKernelGGL(transpose_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, w2t);
-    }
-    const int gx = row_tiles < 256 ? row_tiles : 256;  // persistent: one workgroup per CU
-    if (!narrow) {
-      GFNX_TIMED("gemm_nt_g2", st);
-      auto k = gemm_nt2_kernel<true>;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
-                         at<unsigned long long>(ws, L.m2), s.mw2, coef, B, rows, hdr);
-    }
-    {
-      GFNX_TIMED("gemm_tn_w2", st);
-      auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
+      auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
       const int lds = 2 * 32 * (256 + 256) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(1, 1, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
-                         s.qtot2, part2, dbp2, (const uint8_t*)nullptr, 0, 1);
+      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+                         s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
     }
-    {
-      GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
-    }
-    {
-      GFNX_TIMED("gemm_nt_g1", st);
+  }
+  {
+    GFNX_TIMED("reduce_w3", st);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
+  }
+  const int nt_lds = (64 * 258 + 192 + 512) * 4;
+  float* w2t = at<float>(ws, L.w2t);
+  float* w3t = at<float>(ws, L.w3t);
+  {
+    GFNX_TIMED("transpose_w", st);
+    hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, st, mlp->W3, s.H2, s.A, w3t);
+    hipLaunchKernelGGL(transpose_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, w2t);
+  }
+  if (!narrow) {
+    // G2 = ((coef * e) W3^T) . [h2 > 0] over h2; persistent: about one workgroup per CU
+    GFNX_TIMED("gemm_nt_g2", st);
+    const int gx = row_tiles < 256 / pt3 ? row_tiles : 256 / pt3;
+    auto k = gemm_nt2_kernel<true>;
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
+    hipLaunchKernelGGL(k, dim3(gx, pt3), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
+                       at<unsigned long long>(ws, L.m2), s.mw2, coef, B, rows, hdr);
+  }
+  {
+    // layer 2: dW2 = H1^T G2, db2
+    GFNX_TIMED("gemm_tn_w2", st);
+    auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
+    const int lds = 2 * 32 * (256 + 256) * 4;
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+    hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
+                       s.qtot2, part2, dbp2, (const uint8_t*)nullptr, 0, 1);
+  }
+  {
+    GFNX_TIMED("reduce_w2", st);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
+  }
+  {
+    // G1 = (G2 W2^T) . [h1 > 0] over h1
+    GFNX_TIMED("gemm_nt_g1", st);
+    if (s.H2 <= 256) {
+      const int gx = row_tiles < 256 / pt2 ? row_tiles : 256 / pt2;
       auto k = gemm_nt2_kernel<false>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(gx, 1), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
+      hipLaunchKernelGGL(k, dim3(gx, pt2), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
                          at<unsigned long long>(ws, L.m1), s.mw1, coef, B, rows, hdr);
-    }
-  } else {
-    {
-      GFNX_TIMED("scale_rows", st);
-      hipLaunchKernelGGL(scale_rows_kernel, dim3(1024), dim3(256), 0, st, ebuf, s.A16, coef, B, rows, hdr);
-    }
-    // layer 3: dW3, db3, then G2 over h2
-    {
-      const dim3 grid((s.H2 + 127) / 128, s.qtot3 / s.qt3, s.s3);
-      float* part = at<float>(ws, L.part3);
-      float* dbp = at<float>(ws, L.dbp3);
-      {
-        GFNX_TIMED("gemm_tn_w3", st);
-        if (s.qt3 == 32)
-          hipLaunchKernelGGL(gemm_tn_kernel<32>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
-        else
-          hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h2buf, s.H2, ebuf, s.A16, rows, hdr, s.H2, s.qtot3, part, dbp);
-      }
-      GFNX_TIMED("reduce_w3", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part, s.s3, s.H2, s.qtot3, s.A, grads->dW3, (const int*)nullptr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp, s.s3, 1, s.qtot3, s.A, grads->db3, (const int*)nullptr);
-    }
-    const int gx = row_tiles < 2048 ? row_tiles : 2048;
-    {
-      GFNX_TIMED("gemm_nt_g2", st);
-      hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H2 + 127) / 128), dim3(256), 0, st, ebuf, s.A16, mlp->W3, s.A,
-                         h2buf, s.H2, s.H2, rows, hdr);
-    }
-    // layer 2: dW2, db2, then G1 over h1
-    {
-      const dim3 grid((s.H1 + 127) / 128, s.qtot2 / 128, s.s2);
-      float* part = at<float>(ws, L.part2);
-      float* dbp = at<float>(ws, L.dbp2);
-      {
-        GFNX_TIMED("gemm_tn_w2", st);
-        hipLaunchKernelGGL(gemm_tn_kernel<128>, grid, dim3(256), 0, st, h1buf, s.H1, h2buf, s.H2, rows, hdr, s.H1, s.qtot2, part, dbp);
-      }
-      GFNX_TIMED("reduce_w2", st);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, (const int*)nullptr);
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp, s.s2, 1, s.qtot2, s.H2, grads->db2, (const int*)nullptr);
-    }
-    {
-      GFNX_TIMED("gemm_nt_g1", st);
-      hipLaunchKernelGGL(gemm_nt_mask_kernel, dim3(gx, (s.H1 + 127) / 128), dim3(256), 0, st, h2buf, s.H2, mlp->W2, s.H2,
-                         h1buf, s.H1, s.H1, rows, hdr);
+    } else {
+      const int ctiles = (s.H1 + 127) / 128, rt32 = (int)((s.rows + 31) / 32);
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
+      const int lds = (int)gemm_nt2k_lds_bytes();
+      auto k = gemm_nt2k_kernel;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf,
+                         s.H1, s.H1, (const unsigned long long*)at<unsigned long long>(ws, L.m1), s.mw1, (const int*)rows,
+                         (const int*)hdr);
     }
   }
   // layer 1
@@ -506,27 +469,28 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     float* dbp1 = at<float>(ws, L.dbp1);
     const uint8_t* sbuf = at<uint8_t>(ws, L.sb);
     const int lds = (int)dw1_onehot_lds_bytes();
+    const dim3 grid1(s.s1, s.qtot1 / 256);
     {
       GFNX_TIMED("dw1", st);
       if (s.onehot == 1) {
         auto k = dw1_onehot_kernel<1>;
         if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-        hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes,
-                           (int)env->grid_side, s.p1, part1, dbp1);
+        hipLaunchKernelGGL(k, grid1, dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes,
+                           (int)env->grid_side, s.p1, s.qtot1, part1, dbp1);
       } else {
         auto k = dw1_onehot_kernel<2>;
         if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-        hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes, 1, s.p1,
-                           part1, dbp1);
+        hipLaunchKernelGGL(k, grid1, dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes, 1, s.p1,
+                           s.qtot1, part1, dbp1);
       }
     }
     GFNX_TIMED("reduce_w1", st);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((256 / 4 + 63) / 64), dim3(256), 0, st, dbp1, 256, 1, 256, s.H1, grads->db1, hdr);
+    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot1 / 4 + 63) / 64), dim3(256), 0, st, dbp1, s.s1, 1, s.qtot1, s.H1, grads->db1, hdr);
     if (s.onehot == 1)
-      hipLaunchKernelGGL(reduce2_kernel, dim3(s.p1), dim3(256), 0, st, part1, 256, s.p1, 256, s.H1, grads->dW1, hdr);
+      hipLaunchKernelGGL(reduce2_kernel, dim3((s.p1 * s.qtot1 / 4 + 63) / 64), dim3(256), 0, st, part1, s.s1, s.p1, s.qtot1, s.H1, grads->dW1, hdr);
     else
-      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 63) / 64), dim3(256), 0, st, part1, 256, s.p1,
-                         256, s.H1, hdr, grads->db1, grads->dW1);
+      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 63) / 64), dim3(256), 0, st, part1, s.s1, s.p1,
+                         s.qtot1, s.H1, hdr, grads->db1, grads->dW1);
   } else {
     // segment sums along each trajectory with atomics (large observation spaces: bit sequences)
     {

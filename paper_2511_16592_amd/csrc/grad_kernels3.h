@@ -34,13 +34,15 @@ constexpr int kDw1Round = 64;  // transition rows per round
 // XSRC 1 (grid):  one-hot column p = H*i + x is 1 iff coordinate i equals x;
 // XSRC 2 (Ising): column p = 2*site + s is 1 iff the site holds spin 2s-1 (the "unassigned" rows follow from the
 //                 column sums, see reduce_dw1_ising_kernel).
-// G: rows of ldg floats (ldg <= 256 columns used); part: [S][P][QTOT = 256]; dbpart: [S][256].
+// G: rows of ldg floats; blockIdx.y selects a tile of 256 of its columns; part: [S][P][QTOT]; dbpart: [S][QTOT];
+// QTOT = 256 * gridDim.y.
 template <int XSRC>
 __global__ __launch_bounds__(512) void dw1_onehot_kernel(const float* __restrict__ G, int ldg,
                                                          const int* __restrict__ rows, const int* __restrict__ hdr,
                                                          const uint8_t* __restrict__ sbuf, int SB, int envH, int P,
-                                                         float* __restrict__ part, float* __restrict__ dbpart) {
-  constexpr int R = kDw1Round, QTOT = 256;
+                                                         int QTOT, float* __restrict__ part,
+                                                         float* __restrict__ dbpart) {
+  constexpr int R = kDw1Round;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   int* ids = (int*)smem_raw;                              // [3][R] row ids of three consecutive rounds
   unsigned char* SBs = smem_raw + 3 * R * 4;              // [R][SB] state bytes of the round being built
@@ -55,7 +57,7 @@ __global__ __launch_bounds__(512) void dw1_onehot_kernel(const float* __restrict
   const int row0 = 32 * c0, row1 = min(n, 32 * c1);      // this part's slice of the row list
   const int rounds = (row1 - row0 + R - 1) / R;
   const int PB = (P + 31) >> 5;                          // 32-column blocks of the one-hot operand in use
-  const int q = 32 * w + (lane & 31), kg = lane >> 5;
+  const int q = 256 * blockIdx.y + 32 * w + (lane & 31), kg = lane >> 5;
   const bool qok = q < ldg;
 
   f32x16 acc[8];
