@@ -397,13 +397,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       const int lds = 2 * 32 * (256 + 32) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                         s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
+                         s.qtot3, part3, dbp3);
     } else {
       auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
       const int lds = 2 * 32 * (256 + 256) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
-                         s.qtot3, part3, dbp3, (const uint8_t*)nullptr, 0, 1);
+                         s.qtot3, part3, dbp3);
     }
   }
   {
@@ -435,7 +435,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     const int lds = 2 * 32 * (256 + 256) * 4;
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
     hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
-                       s.qtot2, part2, dbp2, (const uint8_t*)nullptr, 0, 1);
+                       s.qtot2, part2, dbp2);
   }
   {
     GFNX_TIMED("reduce_w2", st);

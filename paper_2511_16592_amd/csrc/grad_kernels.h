@@ -1,14 +1,16 @@
-// Gradient pass of the Trajectory-Balance loss over the transitions recorded by the rollout.
+// Gradient pass of the Trajectory-Balance loss over the transitions recorded by the rollout: bookkeeping kernels
+// and the layer-1 fallback.
 //
-// The live transitions (t < length[b]) are listed in (t, b) order; every kernel below works on that
-// list, so padded steps cost nothing.  With coef_b = 2 delta_b / B the chain is
-//   G3 = coef * (onehot(a) - p)                      (scale_rows_kernel, in place)
-//   dW3 = H2^T G3, db3 = colsum G3                   (gemm_tn_kernel, split over the transitions)
-//   G2 = (G3 W3^T) . [h2 > 0]   written over h2      (gemm_nt_mask_kernel)
-//   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn_kernel)
-//   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt_mask_kernel)
-//   dW1, db1 from G1 by prefix sums along each trajectory (dw1_kernel)
-// All contractions run on the fp32 matrix cores (32x32x2 tiles) from LDS-staged operands.
+// The live transitions (t < length[b]) are listed in (t, b) order; every kernel of the pass works on that list,
+// so padded steps cost nothing.  With coef_b = 2 delta_b / B the chain is
+//   G3 = coef * (onehot(a) - p)                      (formed on load, never stored)
+//   dW3 = H2^T G3, db3 = colsum G3                   (gemm_tn2_kernel, split over the transitions)
+//   G2 = (G3 W3^T) . [h2 > 0]   written over h2      (gemm_nt2_kernel; both in logit_bwd_narrow_kernel for <= 16 logits)
+//   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn2_kernel)
+//   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt2_kernel / gemm_nt2k_kernel)
+//   dW1, db1 from G1                                 (dw1_onehot_kernel; dw1_kernel below for wide one-hot inputs)
+// This file: prep_kernel (residuals, loss, list offsets), build_rows_kernel (the list), fill kernels, dw1_kernel
+// (per-trajectory segment sums with atomics).
 #pragma once
 #include "gfnx_device.h"
 
@@ -96,175 +98,10 @@ __global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict_
   }
 }
 
-// E rows (onehot - p) -> G3 = coef_b * E, in place, live rows only.
-__global__ void scale_rows_kernel(float* __restrict__ ebuf, int A16, const float* __restrict__ coef, int B,
-                                  const int* __restrict__ rows, const int* __restrict__ hdr) {
-  const int n = hdr[kHdrNLive];
-  const int per = A16 >> 2;
-  const size_t total = (size_t)n * per;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-    const int r = rows[i / per];
-    f32x4* p = (f32x4*)&ebuf[(size_t)r * A16 + 4 * (i % per)];
-    *p = *p * coef[r % B];
-  }
-}
-
-// part[s][p][q] = sum over this split's live rows i of X[i][p] * G[i][q]   (dW = X^T G)
-// dbpart[s][q]  = sum over the same rows of G[i][q]                         (written by the p-tile 0 groups)
-// grid = (P/128, QTOT/QT, S); tile 128 x QT, K-chunks of 32 rows gathered through the row list.
-template <int QT>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ X, int ldx, const float* __restrict__ G,
-                                                      int ldg, const int* __restrict__ rows,
-                                                      const int* __restrict__ hdr, int P, int QTOT,
-                                                      float* __restrict__ part, float* __restrict__ dbpart) {
-  constexpr int KC = 32;
-  __shared__ float XS[KC][128];
-  __shared__ float GS[KC][QT];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int ptile = blockIdx.x, qtile = blockIdx.y, s = blockIdx.z, S = gridDim.z;
-  const int n = hdr[kHdrNLive];
-  const int chunks = (n + KC - 1) / KC;
-  const int per = (chunks + S - 1) / S;
-  const int c0 = s * per, c1 = min(chunks, c0 + per);
-
-  constexpr int PB = (QT == 128) ? 2 : 1;  // 32-row blocks per wave along p
-  constexpr int QB = (QT == 128) ? 2 : 1;
-  const int pbase = (QT == 128) ? 64 * (w >> 1) : 32 * w;
-  const int qbase = (QT == 128) ? 64 * (w & 1) : 0;
-  f32x16 acc[PB][QB];
-#pragma unroll
-  for (int a = 0; a < PB; ++a)
-#pragma unroll
-    for (int b = 0; b < QB; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-  float dbacc = 0.f;
-
-  for (int c = c0; c < c1; ++c) {
-    for (int i = tid; i < KC * 32; i += 256) {
-      const int r = i >> 5, c4 = i & 31;
-      const int li = c * KC + r;
-      f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (li < n && ptile * 128 + 4 * c4 < P) v = *(const f32x4*)&X[(size_t)rows[li] * ldx + ptile * 128 + 4 * c4];
-      *(f32x4*)&XS[r][4 * c4] = v;
-    }
-    for (int i = tid; i < KC * (QT / 4); i += 256) {
-      const int r = i / (QT / 4), c4 = i % (QT / 4);
-      const int li = c * KC + r;
-      const int col = qtile * QT + 4 * c4;
-      f32x4 v = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (li < n && col < ldg) v = *(const f32x4*)&G[(size_t)rows[li] * ldg + col];
-      *(f32x4*)&GS[r][4 * c4] = v;
-    }
-    __syncthreads();
-#pragma unroll 4
-    for (int k = 0; k < KC; k += 2) {
-      float av[PB], bv[QB];
-#pragma unroll
-      for (int a = 0; a < PB; ++a) av[a] = XS[k + (lane >> 5)][pbase + 32 * a + (lane & 31)];
-#pragma unroll
-      for (int b = 0; b < QB; ++b) bv[b] = GS[k + (lane >> 5)][qbase + 32 * b + (lane & 31)];
-#pragma unroll
-      for (int a = 0; a < PB; ++a)
-#pragma unroll
-        for (int b = 0; b < QB; ++b) acc[a][b] = mfma32(av[a], bv[b], acc[a][b]);
-    }
-    if (ptile == 0 && tid < QT) {
-#pragma unroll 8
-      for (int k = 0; k < KC; ++k) dbacc += GS[k][tid];
-    }
-    __syncthreads();
-  }
-  float* out = part + (size_t)s * P * QTOT;
-#pragma unroll
-  for (int a = 0; a < PB; ++a)
-#pragma unroll
-    for (int b = 0; b < QB; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int pi = ptile * 128 + pbase + 32 * a + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int qi = qtile * QT + qbase + 32 * b + (lane & 31);
-        if (pi < P) out[(size_t)pi * QTOT + qi] = acc[a][b][r];
-      }
-  if (ptile == 0 && tid < QT) dbpart[(size_t)s * QTOT + qtile * QT + tid] = dbacc;
-}
-
-// out[p*Q + q] = sum_s part[s][p][q] for q < Q (fixed order: reproducible); rows of `part` have QTOT columns.
-__global__ void reduce_partials_kernel(const float* __restrict__ part, int S, int P, int QTOT, int Q,
-                                       float* __restrict__ out) {
-  const size_t total = (size_t)P * Q;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-    const int p = (int)(i / Q), q = (int)(i % Q);
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc += part[((size_t)s * P + p) * QTOT + q];
-    out[i] = acc;
-  }
-}
-
-// For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [Out[i][p] > 0], in place over the stored
-// activation.  Gin rows have ldgi floats (zero beyond Q), W is row-major [P][Q].
-// grid = (row tiles (grid-stride), P/128); tile 64 rows x 128 columns, K-chunks of 32.
-__global__ __launch_bounds__(256) void gemm_nt_mask_kernel(const float* __restrict__ Gin, int ldgi,
-                                                           const float* __restrict__ W, int Q,
-                                                           float* __restrict__ ActOut, int ldo, int P,
-                                                           const int* __restrict__ rows,
-                                                           const int* __restrict__ hdr) {
-  constexpr int KC = 32, KP = KC + 1;
-  __shared__ float GS[64 * KP];
-  __shared__ float WS[128 * KP];
-  __shared__ int rid[64];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int n = hdr[kHdrNLive];
-  const int tiles = (n + 63) >> 6;
-  const int pt = blockIdx.y;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    __syncthreads();
-    if (tid < 64) rid[tid] = (tile * 64 + tid < n) ? rows[tile * 64 + tid] : -1;
-    __syncthreads();
-    f32x16 acc[2];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
-    for (int k0 = 0; k0 < Q; k0 += KC) {
-      for (int i = tid; i < 64 * KC; i += 256) {
-        const int r = i >> 5, k = i & 31;
-        float v = 0.f;
-        if (rid[r] >= 0 && k0 + k < ldgi) v = Gin[(size_t)rid[r] * ldgi + k0 + k];
-        GS[r * KP + k] = v;
-      }
-      for (int i = tid; i < 128 * KC; i += 256) {
-        const int r = i >> 5, k = i & 31;
-        float v = 0.f;
-        if (k0 + k < Q && pt * 128 + r < P) v = W[(size_t)(pt * 128 + r) * Q + k0 + k];
-        WS[r * KP + k] = v;
-      }
-      __syncthreads();
-#pragma unroll 4
-      for (int k = 0; k < KC; k += 2) {
-        const int kk = k + (lane >> 5);
-        const float bv = WS[(32 * w + (lane & 31)) * KP + kk];
-        const float a0 = GS[(lane & 31) * KP + kk];
-        const float a1 = GS[(32 + (lane & 31)) * KP + kk];
-        acc[0] = mfma32(a0, bv, acc[0]);
-        acc[1] = mfma32(a1, bv, acc[1]);
-      }
-      __syncthreads();
-    }
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = 32 * ib + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (rid[i] >= 0 && pt * 128 + 32 * w + (lane & 31) < P) {
-          float* o = &ActOut[(size_t)rid[i] * ldo + pt * 128 + 32 * w + (lane & 31)];
-          *o = (*o > 0.f) ? acc[ib][r] : 0.f;
-        }
-      }
-  }
-}
-
 __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
+
 // bytes [0, n) <- v, as 32-bit words where aligned (p is 4-byte aligned)
 __global__ void fill_bytes_kernel(uint8_t* __restrict__ p, size_t n, uint8_t v) {
   const size_t words = n >> 2;
@@ -273,10 +110,6 @@ __global__ void fill_bytes_kernel(uint8_t* __restrict__ p, size_t n, uint8_t v) 
     ((uint32_t*)p)[i] = vv;
   if (blockIdx.x == 0 && threadIdx.x < (n & 3)) p[(words << 2) + threadIdx.x] = v;
 }
-__global__ void fill_int_kernel(int* __restrict__ p, size_t n, int v) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
-}
-
 struct Dw1Params {
   EnvParams env;
   int H1, B;

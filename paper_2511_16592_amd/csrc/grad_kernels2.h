@@ -1,13 +1,15 @@
-// Gradient-pass kernels for hidden widths up to 256 (one workgroup covers a whole 256-wide operand).
+// Matrix-core kernels of the gradient pass (binary32 MFMA, operands staged in LDS).
 //
-//   gemm_tn2_kernel   dW = X^T G over the live transitions: 8 waves hold a (up to) 256 x 256 accumulator tile
-//                     in registers, transition rows are gathered through the row list in chunks of 32, staged
-//                     in LDS, the next chunk's global loads are in flight while the matrix cores work;
-//                     column sums of G (the bias gradient) ride along.
-//   gemm_nt2_kernel   Out = (G W^T) . [act > 0]: each wave keeps a 32-column slice of W in registers as the
-//                     MFMA B operand for the whole kernel; tiles of 64 transition rows stream through LDS.
-//   reduce_dw1_ising_kernel  Ising layer-1 weight gradient from the partial tiles of the one-hot contraction.
-//   reduce2_kernel    fixed-order sum of the split partials.
+//   gemm_tn2_kernel   dW = X^T G over the live transitions: 8 waves hold a 256 x 256 (or 256 x 32) accumulator
+//                     tile in registers (blockIdx.x / .y pick the tile of wider operands), transition rows are
+//                     gathered through the row list in chunks of 32 and staged in double-buffered LDS, the rows
+//                     two chunks ahead are in flight while the matrix cores work; column sums of G (the bias
+//                     gradient) ride along.
+//   gemm_nt2_kernel   Out = (G W^T) . [act > 0], contraction length <= 256: each wave keeps a 32-column slice of W
+//                     in registers as the MFMA B operand for the whole kernel; tiles of 64 transition rows stream
+//                     through LDS.   gemm_nt2k_kernel: the same for contraction lengths up to 512.
+//   transpose_kernel  W^T, so that those register slices load coalesced.
+//   reduce2_kernel, reduce_dw1_ising_kernel   fixed-order sums of the split partial tiles.
 // With SCALE the G operand is (2 delta_b / B) * e, formed while the rows are loaded, so the logit-gradient rows
 // are never rewritten in HBM.
 #pragma once
@@ -23,20 +25,13 @@ __device__ __forceinline__ int split_chunks_per_part(int chunks, int S) {
   return per < 4 ? 4 : per;
 }
 
-// XSRC selects the left operand: 0 = rows of the matrix X; 1, 2 = the one-hot observation of the transition,
-// rebuilt from the state bytes the rollout recorded (sbuf, SB bytes per row), never stored as floats:
-//   1 (grid)  column p = H*i + x is 1 iff coordinate i equals x;
-//   2 (Ising) column p = 2*site + s is 1 iff the site holds spin 2s-1 (the "unassigned" rows follow from the
-//             column sums: every site has exactly one active row per transition).
-// This turns the layer-1 weight gradient dW1 = onehot^T G1 into the same matrix-core contraction as dW2.
-template <int WP, int WQ, int PBW, int QBW, bool SCALE, int XSRC = 0>
+template <int WP, int WQ, int PBW, int QBW, bool SCALE>
 __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__ X, int ldx, int P,
                                                        const float* __restrict__ G, int ldg,
                                                        const float* __restrict__ coef, int B,
                                                        const int* __restrict__ rows, const int* __restrict__ hdr,
                                                        int QTOT, float* __restrict__ part,
-                                                       float* __restrict__ dbpart,
-                                                       const uint8_t* __restrict__ sbuf, int SB, int envH) {
+                                                       float* __restrict__ dbpart) {
   constexpr int PT = WP * PBW * 32, QT = WQ * QBW * 32, KC = 32;
   constexpr int XV = KC * PT / 4 / 512, GV = (KC * QT / 4 + 511) / 512;  // f32x4 per thread per chunk
   static_assert(WP * WQ == 8, "eight waves");
@@ -76,42 +71,12 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
       gid[m] = (c < c1 && i < KC * QT / 4 && li < n) ? rows[li] : -1;
     }
   };
-  // one-hot sources: this thread's four columns are the same for every row it loads
-  int oh_word[4] = {0, 0, 0, 0}, oh_shift[4] = {0, 0, 0, 0}, oh_val[4] = {-1, -1, -1, -1};
-  if (XSRC == 1) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int col = ptile * PT + 4 * (tid % (PT / 4)) + k;
-      if (col < P) {
-        const int i = col / envH;
-        oh_word[k] = i >> 2; oh_shift[k] = 8 * (i & 3); oh_val[k] = col - i * envH;
-      }
-    }
-  }
   auto load_rows = [&]() {
 #pragma unroll
     for (int m = 0; m < XV; ++m) {
       const int c4 = (tid + 512 * m) % (PT / 4);
       xr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      if (XSRC == 0) {
-        if (xid[m] >= 0 && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)xid[m] * ldx + ptile * PT + 4 * c4];
-      } else if (XSRC == 1) {
-        if (xid[m] >= 0) {
-          const uint4 sv = *(const uint4*)&sbuf[(size_t)xid[m] * SB];  // the (up to 16) coordinates of the state
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const uint32_t wd = oh_word[k] == 0 ? sv.x : (oh_word[k] == 1 ? sv.y : (oh_word[k] == 2 ? sv.z : sv.w));
-            xr[m][k] = ((int)((wd >> oh_shift[k]) & 255u) == oh_val[k]) ? 1.f : 0.f;
-          }
-        }
-      } else {
-        const int p0 = ptile * PT + 4 * c4;  // sites p0/2 and p0/2 + 1
-        if (xid[m] >= 0 && p0 < P) {
-          const uint32_t sv = *(const uint16_t*)&sbuf[(size_t)xid[m] * SB + (p0 >> 1)];
-          const uint32_t s0 = sv & 255u, s1 = sv >> 8;
-          xr[m] = (f32x4){s0 == 255u ? 1.f : 0.f, s0 == 1u ? 1.f : 0.f, s1 == 255u ? 1.f : 0.f, s1 == 1u ? 1.f : 0.f};
-        }
-      }
+      if (xid[m] >= 0 && ptile * PT + 4 * c4 < P) xr[m] = *(const f32x4*)&X[(size_t)xid[m] * ldx + ptile * PT + 4 * c4];
     }
 #pragma unroll
     for (int m = 0; m < GV; ++m) {
