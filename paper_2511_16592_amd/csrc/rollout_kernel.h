@@ -204,15 +204,43 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   // partial logits of a split contraction are summed across lanes when (parts x chunks) is exactly the 32
   // lanes of a slot (1, 2 or 4 logit tiles); otherwise by the owning lane
   const bool lane_sum = KS > 1 && KS * nchunk == 32;
+  // Every register loaded above is read here once, so the wait for those loads sits before the step loop: inside
+  // the loop a wait placed at their first use would also wait for the kernel's own recent stores each step.
+#pragma unroll
+  for (int n = 0; n < (STAT ? 2 : 1); ++n)
+#pragma unroll
+    for (int q = 0; q < (STAT ? kW2RegQ : 1); ++q) asm volatile("" ::"v"(w2r[n][q]));
+#pragma unroll
+  for (int n = 0; n < (STAT ? 2 : 1); ++n) asm volatile("" ::"v"(w3r[n]));
+#pragma unroll
+  for (int n = 0; n < NTW; ++n) asm volatile("" ::"v"(b2r[n]));
+#pragma unroll
+  for (int n = 0; n < NCH; ++n) asm volatile("" ::"v"(b3r[n]));
   lds_barrier();
 
   // list-scheduling bound on the number of steps: (sum of lengths) / kSlots + longest trajectory
   const int max_iters = e.max_steps * ((p.tpw + kSlots - 1) / kSlots + 1);
   for (int iter = 0; iter < max_iters; ++iter) {
+    // ---- slot flags and row indices of this step, fetched once and together: all 16 flags (any trajectory
+    // left?), the two slots whose h1 / h2 rows this wave writes out, and the slot this lane serves in L2
+    int sa[2], sr[2];
+    int my_alive, my_row;
+    {
+      const int4* av = (const int4*)alive;
+      const int4 a0 = av[0], a1 = av[1], a2 = av[2], a3 = av[3];
+      sa[0] = alive[w]; sa[1] = alive[w + 8];
+      sr[0] = srow[w]; sr[1] = srow[w + 8];
+      my_alive = alive[j16]; my_row = srow[j16];
+      const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
+                      a3.y | a3.z | a3.w;
+      if (!any) break;
+    }
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
-    for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
-      if (!alive[jj]) continue;
-      const size_t row = (size_t)srow[jj];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {  // h1 rows and sign masks of slots w and w + 8
+      if (!sa[hh]) continue;
+      const int jj = w + 8 * hh;
+      const size_t row = (size_t)sr[hh];
       float* dst = p.h1buf + row * H1;
       for (int it = 0; it * 64 < (H1 >> 2); ++it) {
         const int fg = lane + 64 * it;
@@ -264,38 +292,103 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
 #undef GFNX_L2_STEP
       } else if (w * NTW < NT2) {
-        // tiles w*NTW .. w*NTW+NTW-1 (clamped: a clamped tile is computed twice and stored once)
+        // tiles w*NTW .. w*NTW+NTW-1 (clamped: a clamped tile is computed twice and stored once); the weights
+        // stream from L2 cache in operand order, two contraction steps ahead of their use
         const f32x4* wp = (const f32x4*)p.W2p + lane;
-        int tn[NTW];
+        const f32x4* wt[NTW];
 #pragma unroll
-        for (int n = 0; n < NTW; ++n) tn[n] = min(w * NTW + n, NT2 - 1);
-        f32x4 cur[NTW];
+        for (int n = 0; n < NTW; ++n) wt[n] = wp + (size_t)min(w * NTW + n, NT2 - 1) * Q1 * 64;
+        f32x4 r[2][NTW];
 #pragma unroll
-        for (int n = 0; n < NTW; ++n) cur[n] = wp[((size_t)tn[n] * Q1) * 64];
-        for (int q = 0; q < Q1; ++q) {
-          const int qn = q + 1 < Q1 ? q + 1 : q;
-          f32x4 nxt[NTW];
+        for (int d = 0; d < 2; ++d)
 #pragma unroll
-          for (int n = 0; n < NTW; ++n) nxt[n] = wp[((size_t)tn[n] * Q1 + qn) * 64];
-          const f32x4 bv = relu4(*(const f32x4*)&z1s[(4 * q + g) * kPitch + j16 * 4]);
+          for (int n = 0; n < NTW; ++n) r[d][n] = wt[n][min(d, Q1 - 1) * 64];
+        f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
+#pragma nounroll
+        for (int q0 = 0; q0 < Q1; q0 += 2) {  // Q1 is a multiple of 4
 #pragma unroll
-          for (int n = 0; n < NTW; ++n) { GFNX_MFMA4(acc[n], cur[n], bv); }
+          for (int d = 0; d < 2; ++d) {
+            const int q = q0 + d;
+            f32x4 cur[NTW];
 #pragma unroll
-          for (int n = 0; n < NTW; ++n) cur[n] = nxt[n];
+            for (int n = 0; n < NTW; ++n) cur[n] = r[d][n];
+            const int qn = min(q + 2, Q1 - 1);
+#pragma unroll
+            for (int n = 0; n < NTW; ++n) r[d][n] = wt[n][qn * 64];
+            const f32x4 bv = relu4(bvn);
+            bvn = *(const f32x4*)&z1s[(4 * min(q + 1, Q1 - 1) + g) * kPitch + j16 * 4];
+#pragma unroll
+            for (int n = 0; n < NTW; ++n) acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
+#pragma unroll
+            for (int n = 0; n < NTW; ++n) acc[n] = mfma16(cur[n].y, bv.y, acc[n]);
+#pragma unroll
+            for (int n = 0; n < NTW; ++n) acc[n] = mfma16(cur[n].z, bv.z, acc[n]);
+#pragma unroll
+            for (int n = 0; n < NTW; ++n) acc[n] = mfma16(cur[n].w, bv.w, acc[n]);
+            __builtin_amdgcn_sched_group_barrier(0x020, NTW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * NTW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          }
         }
       }
+      if constexpr (STAT) {
+        // This lane holds h2 of slot j16 for units 16 nt + 4 g .. + 3 of its two tiles: the row piece and its share
+        // of the sign masks go to HBM from registers (unit 16 nt + 4 g + r is bit 4 (nt % 2) + g of byte nt / 2
+        // = w of mask word r: one byte per slot, word and wave).
+        f32x4 hv[2];
 #pragma unroll
-      for (int n = 0; n < NTW; ++n) {
-        const int nt = w * NTW + n;
-        if (nt < NT2) *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + b2r[n]);
+        for (int n = 0; n < 2; ++n) hv[n] = relu4(acc[n] + b2r[n]);
+        const int alv = my_alive;
+        const size_t row = (size_t)my_row;
+        unsigned long long bal[2][4];
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+          if (alv) *(f32x4*)&p.h2buf[row * 256 + 16 * (2 * w + n) + 4 * g] = hv[n];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) bal[n][r] = __ballot(alv && hv[n][r] > 0.f);
+        }
+        {
+          // lane (j16, g) assembles the byte of mask word r = g: bit 4 n + g' comes from lane 16 g' + j16 of tile n
+          uint32_t byte = 0;
+#pragma unroll
+          for (int n = 0; n < 2; ++n) {
+            const unsigned long long b =
+                g == 0 ? bal[n][0] : (g == 1 ? bal[n][1] : (g == 2 ? bal[n][2] : bal[n][3]));
+            const unsigned long long x = b >> j16;
+            const uint32_t nib = (uint32_t)(x & 1ull) | (uint32_t)((x >> 15) & 2ull) | (uint32_t)((x >> 30) & 4ull) |
+                                 (uint32_t)((x >> 45) & 8ull);
+            byte |= nib << (4 * n);
+          }
+          if (alv) ((uint8_t*)p.m2buf)[(row * p.MW2 + g) * 8 + w] = (uint8_t)byte;
+        }
+        if (NT3 == 1) {
+          // a single logit tile (grids): the contraction is split by wave, and wave w's part runs over exactly
+          // the 32 units it has just produced - the logits phase needs no LDS round trip and no barrier
+          f32x4 acc3 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int n = 0; n < 2; ++n) { GFNX_MFMA4(acc3, w3r[n], hv[n]); }
+          *(f32x4*)&lgs[(w * nchunk + g) * kPitch + j16 * 4] = acc3;
+        } else {
+#pragma unroll
+          for (int n = 0; n < 2; ++n) *(f32x4*)&h2s[(4 * (2 * w + n) + g) * kPitch + j16 * 4] = hv[n];
+        }
+      } else {
+#pragma unroll
+        for (int n = 0; n < NTW; ++n) {
+          const int nt = w * NTW + n;
+          if (nt < NT2) *(f32x4*)&h2s[(4 * nt + g) * kPitch + j16 * 4] = relu4(acc[n] + b2r[n]);
+        }
       }
     }
     lds_barrier();
 
     // ================= L3: logits = W3^T h2 (+ b3 added in SU)
-    for (int jj = w; jj < kSlots; jj += kRolloutWaves) {
-      if (!alive[jj]) continue;
-      const size_t row = (size_t)srow[jj];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {  // (the resident-W2 variant has written h2 out of registers above)
+      if (STAT || !sa[hh]) continue;
+      const int jj = w + 8 * hh;
+      const size_t row = (size_t)sr[hh];
       float* dst = p.h2buf + row * H2;
       for (int it = 0; it * 64 < (H2 >> 2); ++it) {
         const int fg = lane + 64 * it;
@@ -307,7 +400,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
       }
     }
-    if (ENV != 0 && KS == 1) {
+    const bool logits_done = STAT && NT3 == 1;  // computed at the end of L2 above
+    if (logits_done) {
+    } else if (ENV != 0 && KS == 1) {
       // whole tiles: w and w + 8 (a wave without a second tile repeats its first: two independent accumulator
       // chains either way); the weights stream from L2 cache kL3Ahead contraction steps ahead of their use.
       // Grids have at most two logit tiles and never take this path.
@@ -357,24 +452,16 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       if (nt < NT3) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         const int qn = Q2 / KS;
-        if (STAT && NT3 == 1 && KS == 8) {
-#pragma unroll
-          for (int q = 0; q < (STAT ? 2 : 1); ++q) {
-            const f32x4 bv = *(const f32x4*)&h2s[(4 * (w * 2 + q) + g) * kPitch + j16 * 4];
-            GFNX_MFMA4(acc, w3r[q], bv);
-          }
-        } else {
-          const f32x4* wp = (const f32x4*)p.W3p + lane;
-          for (int q = ks * qn; q < (ks + 1) * qn; ++q) {
-            const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
-            const f32x4 av = wp[((size_t)nt * Q2 + q) * 64];
-            GFNX_MFMA4(acc, av, bv);
-          }
+        const f32x4* wp = (const f32x4*)p.W3p + lane;
+        for (int q = ks * qn; q < (ks + 1) * qn; ++q) {
+          const f32x4 bv = *(const f32x4*)&h2s[(4 * q + g) * kPitch + j16 * 4];
+          const f32x4 av = wp[((size_t)nt * Q2 + q) * 64];
+          GFNX_MFMA4(acc, av, bv);
         }
         *(f32x4*)&lgs[(ks * nchunk + 4 * nt + g) * kPitch + j16 * 4] = acc;
       }
     }
-    lds_barrier();
+    if (!logits_done) lds_barrier();
 
     // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (LPS lanes per slot)
     if (su_wave && alive[sj]) {
@@ -660,15 +747,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         for (int fg = si + LPS * kPre; fg < (H1 >> 2); fg += LPS)
           update(fg, *(const f32x4*)&wo_row[4 * fg], *(const f32x4*)&wn_row[4 * fg]);
       }
+      // the W1 rows were requested on every path but are consumed only when the trajectory goes on: read them
+      // here, so that the wait for these loads (not for the stores issued after them) closes the phase and the
+      // next phase does not start by waiting for everything outstanding
+#pragma unroll
+      for (int it = 0; it < kPre; ++it) asm volatile("" ::"v"(wo[it]), "v"(wn[it]));
     }
     lds_barrier();
-    {
-      const int4* av = (const int4*)alive;
-      const int4 a0 = av[0], a1 = av[1], a2 = av[2], a3 = av[3];
-      const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
-                      a3.y | a3.z | a3.w;
-      if (!any) break;
-    }
   }
 }
 
