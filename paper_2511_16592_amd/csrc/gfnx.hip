@@ -396,13 +396,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
       const int lds = 2 * 32 * (256 + 32) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     } else {
       auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
       const int lds = 2 * 32 * (256 + 256) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, coef, B, rows, hdr,
+      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     }
   }
@@ -411,7 +411,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
     hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
   }
-  const int nt_lds = (64 * 258 + 192 + 512) * 4;
+  const int nt_lds = (64 * 258 + 192 + 512 + 192) * 4;
   float* w2t = at<float>(ws, L.w2t);
   float* w3t = at<float>(ws, L.w3t);
   {
@@ -426,7 +426,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     auto k = gemm_nt2_kernel<true>;
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
     hipLaunchKernelGGL(k, dim3(gx, pt3), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
-                       at<unsigned long long>(ws, L.m2), s.mw2, coef, B, rows, hdr);
+                       at<unsigned long long>(ws, L.m2), s.mw2, (const float*)crow, rows, hdr);
   }
   {
     // layer 2: dW2 = H1^T G2, db2
@@ -434,7 +434,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
     const int lds = 2 * 32 * (256 + 256) * 4;
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
-    hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, coef, B, rows, hdr,
+    hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, (const float*)crow, rows, hdr,
                        s.qtot2, part2, dbp2);
   }
   {
@@ -450,7 +450,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       auto k = gemm_nt2_kernel<false>;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(gx, pt2), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
-                         at<unsigned long long>(ws, L.m1), s.mw1, coef, B, rows, hdr);
+                         at<unsigned long long>(ws, L.m1), s.mw1, (const float*)crow, rows, hdr);
     } else {
       const int ctiles = (s.H1 + 127) / 128, rt32 = (int)((s.rows + 31) / 32);
       const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);

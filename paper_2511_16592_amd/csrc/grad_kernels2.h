@@ -28,7 +28,7 @@ __device__ __forceinline__ int split_chunks_per_part(int chunks, int S) {
 template <int WP, int WQ, int PBW, int QBW, bool SCALE>
 __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__ X, int ldx, int P,
                                                        const float* __restrict__ G, int ldg,
-                                                       const float* __restrict__ coef, int B,
+                                                       const float* __restrict__ crow,
                                                        const int* __restrict__ rows, const int* __restrict__ hdr,
                                                        int QTOT, float* __restrict__ part,
                                                        float* __restrict__ dbpart) {
@@ -58,6 +58,7 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
   // software pipeline: row ids of chunk c+2 and rows of chunk c+1 are in flight while chunk c is multiplied
   f32x4 xr[XV], gr[GV];
   int xid[XV], gid[GV];
+  float gcf[GV];  // SCALE: coefficient of the row, from the list that runs parallel to the row list
   auto load_ids = [&](int c) {
 #pragma unroll
     for (int m = 0; m < XV; ++m) {
@@ -68,7 +69,9 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
     for (int m = 0; m < GV; ++m) {
       const int i = tid + 512 * m;
       const int li = c * KC + i / (QT / 4);
-      gid[m] = (c < c1 && i < KC * QT / 4 && li < n) ? rows[li] : -1;
+      const bool on = c < c1 && i < KC * QT / 4 && li < n;
+      gid[m] = on ? rows[li] : -1;
+      if (SCALE) gcf[m] = on ? crow[li] : 0.f;
     }
   };
   auto load_rows = [&]() {
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
       gr[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if (gid[m] >= 0 && col < ldg) {
         f32x4 v = *(const f32x4*)&G[(size_t)gid[m] * ldg + col];
-        if (SCALE) v = v * coef[gid[m] % B];
+        if (SCALE) v = v * gcf[m];
         gr[m] = v;
       }
     }
@@ -212,13 +215,14 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
                                                        const float* __restrict__ Wt, int Kvalid,
                                                        float* __restrict__ ActOut, int ldo, int P,
                                                        const unsigned long long* __restrict__ mask, int MW,
-                                                       const float* __restrict__ coef, int B,
+                                                       const float* __restrict__ crow,
                                                        const int* __restrict__ rows, const int* __restrict__ hdr) {
   constexpr int KP = 258;  // LDS row pitch in floats: even (8-byte reads) and 2 mod 32 (conflict-free rows)
   extern __shared__ float smem[];
   float* GS = smem;                    // [64][KP]
   int* ridb = (int*)(smem + 64 * KP);  // [3][64] physical row ids of three consecutive tiles
   uint32_t* MS = (uint32_t*)(ridb + 192);  // [64 rows][8]: the four 64-bit mask words of this column tile
+  float* cfb = (float*)(MS + 512);         // [3][64] coefficients of the same rows (SCALE)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = hdr[kHdrNLive];
   const int tiles = (n + 63) >> 6;
@@ -241,10 +245,15 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
   f32x4 pre[8];
   uint32_t mpre = 0;
   int idreg = -1;
+  float cfreg = 0.f;
   auto fetch_ids = [&](int tile) {  // threads 0..63
-    if (tid < 64) idreg = (tile < tiles && tile * 64 + tid < n) ? rows[tile * 64 + tid] : -1;
+    if (tid < 64) {
+      const bool on = tile < tiles && tile * 64 + tid < n;
+      idreg = on ? rows[tile * 64 + tid] : -1;
+      if (SCALE) cfreg = on ? crow[tile * 64 + tid] : 0.f;
+    }
   };
-  auto load_rows = [&](const int* ids) {
+  auto load_rows = [&](const int* ids, const float* cfs) {
     {
       const int rr = ids[tid >> 3];    // mask tile: 64 rows x 8 words of 32 bits, one per thread
       mpre = rr >= 0 ? mask32[(size_t)rr * MW * 2 + (tid & 7)] : 0u;
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
       pre[m] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if (rr >= 0 && c4 < kv) {
         f32x4 v = *(const f32x4*)&Gin[(size_t)rr * ldgi + 4 * c4];
-        if (SCALE) v = v * coef[rr % B];
+        if (SCALE) v = v * cfs[i >> 6];
         pre[m] = v;
       }
     }
@@ -264,13 +273,14 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
 
   int tile = blockIdx.x;
   fetch_ids(tile);
-  if (tid < 64) ridb[tid] = idreg;
+  if (tid < 64) { ridb[tid] = idreg; cfb[tid] = cfreg; }
   lds_barrier();
-  load_rows(ridb);
+  load_rows(ridb, cfb);
   fetch_ids(tile + gridDim.x);
   for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
     const int* rid = ridb + 64 * (it % 3);
     int* rid_next = ridb + 64 * ((it + 1) % 3);
+    float* cf_next = cfb + 64 * ((it + 1) % 3);
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       const int i = tid + 512 * m;
@@ -279,9 +289,9 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
       *(float2*)(d + 2) = make_float2(pre[m].z, pre[m].w);
     }
     MS[tid] = mpre;
-    if (tid < 64) rid_next[tid] = idreg;
+    if (tid < 64) { rid_next[tid] = idreg; cf_next[tid] = cfreg; }
     lds_barrier();
-    load_rows(rid_next);
+    load_rows(rid_next, cf_next);
     fetch_ids(tile + 2 * (int)gridDim.x);
     // the 64 rows of the tile as two passes of 32, one accumulator block live at a time
     const int pl = 32 * w + (lane & 31);
