@@ -66,7 +66,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, coef, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, total;
+  size_t hdr, w2p, w3p, w2t, w3t, coef, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -153,6 +153,7 @@ Layout make_layout(const Shapes& s) {
   L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
   L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
   L.dbp3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.qtot3);
+  L.cs = o; o += align256(s.onehot ? 0 : sizeof(float) * (size_t)s.max_steps * s.H1);  // per-step column sums of G1
   L.total = o;
   return L;
 }
@@ -501,7 +502,18 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     GFNX_TIMED("dw1", st);
     switch (env->kind) {
       case GFNX_ENV_GRID: hipLaunchKernelGGL(dw1_kernel<0>, dim3(B), dim3(256), 0, st, dp); break;
-      case GFNX_ENV_BITSEQ: hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp); break;
+      case GFNX_ENV_BITSEQ: {
+        // token rows: suffix sums per trajectory; the shared "empty" rows and db1: per-step column sums
+        float* cs = at<float>(ws, L.cs);
+        dp.suffix_only = 1;
+        hipLaunchKernelGGL(fill_kernel, dim3(64), dim3(256), 0, st, cs, (size_t)T * s.H1, 0.f);
+        hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp);
+        hipLaunchKernelGGL(colsum_steps_kernel, dim3(T, 16), dim3(256), 0, st, (const float*)h1buf, s.H1, (const int*)rows,
+                           (const int*)hdr, cs);
+        hipLaunchKernelGGL(bitseq_empty_rows_kernel, dim3(s.state_dim), dim3(256), 0, st, (const float*)cs, s.H1,
+                           s.state_dim, T, 1 << env->k_bits, grads->dW1, grads->db1);
+        break;
+      }
       default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
     }
   }

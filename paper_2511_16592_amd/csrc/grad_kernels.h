@@ -118,6 +118,7 @@ struct Dw1Params {
   const int8_t* term;
   const float* g1;  // rows t*B + b, H1 floats
   float *dW1, *db1;
+  int suffix_only;  // bit sequences: the "empty" rows and db1 come from the per-step column sums instead
 };
 
 // One workgroup per trajectory; dW1[r] += sum of g1_t over the steps t at which one-hot row r is active.
@@ -196,13 +197,15 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
         if (i < e.d) atomicAdd(&p.dW1[(size_t)rend[i] * H1 + f], acc[i]);
       atomicAdd(&p.db1[f], total);
     } else {
-      float P = 0.f;
-      for (int t = 0; t < len; ++t) {
-        P += g1[t * stride];
-        if (t + 1 < len) atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], P);
+      if (!p.suffix_only) {
+        float P = 0.f;
+        for (int t = 0; t < len; ++t) {
+          P += g1[t * stride];
+          if (t + 1 < len) atomicAdd(&p.dW1[(size_t)rold[t] * H1 + f], P);
+        }
+        for (int i = 0; i < nend; ++i) atomicAdd(&p.dW1[(size_t)rend[i] * H1 + f], P);
+        atomicAdd(&p.db1[f], P);
       }
-      for (int i = 0; i < nend; ++i) atomicAdd(&p.dW1[(size_t)rend[i] * H1 + f], P);
-      atomicAdd(&p.db1[f], P);
       float S = 0.f;
       for (int t = len - 1; t >= 1; --t) {
         S += g1[t * stride];
@@ -210,6 +213,52 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
       }
     }
   }
+}
+
+// Bit sequences: every trajectory shares the same "empty" rows, so their gradient is not scattered per trajectory.
+// The empty row of position s is active at step t' iff t' <= s, for every trajectory alive at t': its gradient is
+// the sum over t' <= s of the column sums cs[t'] of G1 over the live rows of step t', and db1 is the sum of all.
+//   colsum_steps_kernel  grid (steps, parts): partial column sums of a slab of one step's rows, added to cs[t]
+//                        (cs zeroed before; at most `parts` atomics meet on an address)
+//   bitseq_empty_rows_kernel  grid (positions): prefix over the steps, plain stores to dW1; block 0 also writes db1
+__global__ __launch_bounds__(256) void colsum_steps_kernel(const float* __restrict__ g1, int H1,
+                                                           const int* __restrict__ rows, const int* __restrict__ hdr,
+                                                           float* __restrict__ cs) {
+  const int t = blockIdx.x, part = blockIdx.y, parts = gridDim.y;
+  const int cnt = hdr[kHdrCnt + t];
+  if (cnt == 0) return;
+  const int off = hdr[kHdrOff + t];
+  const int per = (cnt + parts - 1) / parts;
+  const int i0 = part * per, i1 = min(cnt, i0 + per);
+  for (int f = threadIdx.x; f < H1; f += 256) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int i = i0;
+    for (; i + 4 <= i1; i += 4) {
+      a0 += g1[(size_t)rows[off + i] * H1 + f];
+      a1 += g1[(size_t)rows[off + i + 1] * H1 + f];
+      a2 += g1[(size_t)rows[off + i + 2] * H1 + f];
+      a3 += g1[(size_t)rows[off + i + 3] * H1 + f];
+    }
+    for (; i < i1; ++i) a0 += g1[(size_t)rows[off + i] * H1 + f];
+    if (i0 < i1) atomicAdd(&cs[(size_t)t * H1 + f], (a0 + a1) + (a2 + a3));
+  }
+}
+
+__global__ __launch_bounds__(256) void bitseq_empty_rows_kernel(const float* __restrict__ cs, int H1, int L, int T,
+                                                                int tokens, float* __restrict__ dW1,
+                                                                float* __restrict__ db1) {
+  const int s = blockIdx.x;  // position
+  for (int f = threadIdx.x; f < H1; f += 256) {
+    float acc = 0.f;
+    for (int t = 0; t <= s && t < T; ++t) acc += cs[(size_t)t * H1 + f];
+    dW1[((size_t)(tokens + 1) * s + tokens) * H1 + f] = acc;
+    if (s == 0) {
+      float tot = 0.f;
+      for (int t = 0; t < T; ++t) tot += cs[(size_t)t * H1 + f];
+      db1[f] = tot;
+    }
+  }
+  (void)L;
 }
 
 }  // namespace gfnx
