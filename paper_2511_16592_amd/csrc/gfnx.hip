@@ -250,14 +250,6 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
 
-  {
-    GFNX_TIMED("pack_weights", st);
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, s.H2 / 16,
-                       at<float>(ws, L.w2p));
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(128), dim3(256), 0, st, mlp->W3, s.H2, s.A, s.A16 / 16,
-                       at<float>(ws, L.w3p));
-  }
-
   RolloutParams p = {};
   p.env = env_params(env, s);
   p.In = s.obs_dim; p.H1 = s.H1; p.H2 = s.H2; p.A = s.A; p.A16 = s.A16;
@@ -283,10 +275,16 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   const dim3 grid((s.B + tpw - 1) / tpw);
   const size_t lds = rollout_lds_bytes(s);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
-  if (!replay) {
-    // every action byte starts as the 0xFF padding; the rollout overwrites the transitions it takes
-    GFNX_TIMED("pad_actions", st);
-    hipLaunchKernelGGL(fill_bytes_kernel, dim3(256), dim3(256), 0, st, traj->actions, (size_t)traj->max_steps * s.B, (uint8_t)0xFF);
+  {
+    // packed and transposed weights, and (free-running rollout) every action byte preset to the 0xFF padding
+    GFNX_TIMED("prepare", st);
+    PrepareParams pp = {};
+    pp.W2 = mlp->W2; pp.W3 = mlp->W3; pp.H1 = s.H1; pp.H2 = s.H2; pp.A = s.A; pp.A16 = s.A16;
+    pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
+    pp.W2t = at<float>(ws, L.w2t); pp.W3t = at<float>(ws, L.w3t);
+    pp.actions = replay ? nullptr : traj->actions;
+    pp.action_bytes = (size_t)traj->max_steps * s.B;
+    hipLaunchKernelGGL(prepare_kernel, dim3(kPrepareBlocks), dim3(256), 0, st, pp);
   }
   {
     GFNX_TIMED("rollout", st);
@@ -376,6 +374,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
   const int row_tiles = (int)((s.rows + 63) / 64);
 
+  // the split partial tiles of every weight / bias gradient are summed by one launch at the end of the pass
+  ReduceJobs jobs = {};
+  auto add_job = [&](const float* part, int S, int P, int QTOT, int Q, float* out) {
+    const int j = jobs.n++;
+    jobs.part[j] = part; jobs.out[j] = out; jobs.S[j] = S; jobs.P[j] = P; jobs.QTOT[j] = QTOT; jobs.Q[j] = Q;
+    jobs.first[j + 1] = jobs.first[j] + (P * (QTOT / 4) + 63) / 64;
+  };
   float* part3 = at<float>(ws, L.part3);
   float* dbp3 = at<float>(ws, L.dbp3);
   float* part2 = at<float>(ws, L.part2);
@@ -407,19 +412,11 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                          s.qtot3, part3, dbp3);
     }
   }
-  {
-    GFNX_TIMED("reduce_w3", st);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((s.H2 * s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3, hdr);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot3 / 4 + 63) / 64), dim3(256), 0, st, dbp3, s.s3, 1, s.qtot3, s.A, grads->db3, hdr);
-  }
+  add_job(part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
+  add_job(dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
   const int nt_lds = (64 * 258 + 192 + 512 + 192) * 4;
   float* w2t = at<float>(ws, L.w2t);
   float* w3t = at<float>(ws, L.w3t);
-  {
-    GFNX_TIMED("transpose_w", st);
-    hipLaunchKernelGGL(transpose_kernel, dim3(64), dim3(256), 0, st, mlp->W3, s.H2, s.A, w3t);
-    hipLaunchKernelGGL(transpose_kernel, dim3(256), dim3(256), 0, st, mlp->W2, s.H1, s.H2, w2t);
-  }
   if (!narrow) {
     // G2 = ((coef * e) W3^T) . [h2 > 0] over h2; persistent: about one workgroup per CU
     GFNX_TIMED("gemm_nt_g2", st);
@@ -438,11 +435,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, (const float*)crow, rows, hdr,
                        s.qtot2, part2, dbp2);
   }
-  {
-    GFNX_TIMED("reduce_w2", st);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((s.H1 * s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2, hdr);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot2 / 4 + 63) / 64), dim3(256), 0, st, dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2, hdr);
-  }
+  add_job(part2, s.s2, s.H1, s.qtot2, s.H2, grads->dW2);
+  add_job(dbp2, s.s2, 1, s.qtot2, s.H2, grads->db2);
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
@@ -485,13 +479,8 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                            s.qtot1, part1, dbp1);
       }
     }
-    GFNX_TIMED("reduce_w1", st);
-    hipLaunchKernelGGL(reduce2_kernel, dim3((s.qtot1 / 4 + 63) / 64), dim3(256), 0, st, dbp1, s.s1, 1, s.qtot1, s.H1, grads->db1, hdr);
-    if (s.onehot == 1)
-      hipLaunchKernelGGL(reduce2_kernel, dim3((s.p1 * s.qtot1 / 4 + 63) / 64), dim3(256), 0, st, part1, s.s1, s.p1, s.qtot1, s.H1, grads->dW1, hdr);
-    else
-      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 63) / 64), dim3(256), 0, st, part1, s.s1, s.p1,
-                         s.qtot1, s.H1, hdr, grads->db1, grads->dW1);
+    add_job(dbp1, s.s1, 1, s.qtot1, s.H1, grads->db1);
+    if (s.onehot == 1) add_job(part1, s.s1, s.p1, s.qtot1, s.H1, grads->dW1);
   } else {
     // segment sums along each trajectory with atomics (large observation spaces: bit sequences)
     {
@@ -516,6 +505,13 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       }
       default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
     }
+  }
+  {
+    GFNX_TIMED("reduce", st);
+    hipLaunchKernelGGL(reduce_jobs_kernel, dim3(jobs.first[jobs.n]), dim3(256), 0, st, jobs, (const int*)hdr);
+    if (s.onehot == 2)  // needs db1 from the launch above
+      hipLaunchKernelGGL(reduce_dw1_ising_kernel, dim3((s.p1 / 2 * (s.H1 / 4) + 63) / 64), dim3(256), 0, st,
+                         (const float*)at<float>(ws, L.part1), s.s1, s.p1, s.qtot1, s.H1, (const int*)hdr, grads->db1, grads->dW1);
   }
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
 }

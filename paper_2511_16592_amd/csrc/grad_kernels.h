@@ -9,7 +9,7 @@
 //   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn2_kernel)
 //   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt2_kernel / gemm_nt2k_kernel)
 //   dW1, db1 from G1                                 (dw1_onehot_kernel; dw1_kernel below for wide one-hot inputs)
-// This file: prep_kernel (residuals, loss, list offsets), build_rows_kernel (the list), fill kernels, dw1_kernel
+// This file: prep_kernel (residuals, loss, list offsets), build_rows_kernel (the list), fill_kernel, dw1_kernel
 // (per-trajectory segment sums with atomics).
 #pragma once
 #include "gfnx_device.h"
@@ -102,14 +102,6 @@ __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-// bytes [0, n) <- v, as 32-bit words where aligned (p is 4-byte aligned)
-__global__ void fill_bytes_kernel(uint8_t* __restrict__ p, size_t n, uint8_t v) {
-  const size_t words = n >> 2;
-  const uint32_t vv = 0x01010101u * v;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
-    ((uint32_t*)p)[i] = vv;
-  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) p[(words << 2) + threadIdx.x] = v;
-}
 struct Dw1Params {
   EnvParams env;
   int H1, B;

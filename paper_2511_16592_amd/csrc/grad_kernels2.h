@@ -8,8 +8,8 @@
 //   gemm_nt2_kernel   Out = (G W^T) . [act > 0], contraction length <= 256: each wave keeps a 32-column slice of W
 //                     in registers as the MFMA B operand for the whole kernel; tiles of 64 transition rows stream
 //                     through LDS.   gemm_nt2k_kernel: the same for contraction lengths up to 512.
-//   transpose_kernel  W^T, so that those register slices load coalesced.
-//   reduce2_kernel, reduce_dw1_ising_kernel   fixed-order sums of the split partial tiles.
+//                     (W comes transposed, prepared with the rollout's weights, so that those slices load coalesced)
+//   reduce_jobs_kernel, reduce_dw1_ising_kernel   fixed-order sums of the split partial tiles.
 // With SCALE the G operand is (2 delta_b / B) * e, formed while the rows are loaded, so the logit-gradient rows
 // are never rewritten in HBM.
 #pragma once
@@ -157,9 +157,9 @@ __global__ __launch_bounds__(512) void gemm_tn2_kernel(const float* __restrict__
 // out[p*Q + q] = sum_s part[s][p][q], q < Q.  A block of 256 threads finishes 64 groups of four outputs: thread
 // (o, sg) sums the parts sg, sg+4, sg+8, ... of group o (four loads in flight), and the four sub-sums meet in LDS in
 // a fixed order, so the result does not depend on the launch.  grid = ceil(P * QTOT / 4 / 64) blocks.
-__global__ __launch_bounds__(256) void reduce2_kernel(const float* __restrict__ part, int S, int P, int QTOT, int Q,
-                                                      float* __restrict__ out, const int* __restrict__ hdr) {
-  __shared__ f32x4 red[3][64];
+__device__ __forceinline__ void reduce2_block(const float* __restrict__ part, int S, int P, int QTOT, int Q,
+                                              float* __restrict__ out, const int* __restrict__ hdr, int block,
+                                              f32x4 (*red)[64]) {
   if (hdr) {  // partials come from a split over the live transitions: only the parts that hold some were written
     const int chunks = (hdr[kHdrNLive] + 31) / 32;
     const int per = split_chunks_per_part(chunks, S);
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void reduce2_kernel(const float* __restrict__ 
   const size_t total = (size_t)P * qv;
   const size_t stride = (size_t)P * QTOT;
   const int o = threadIdx.x & 63, sg = threadIdx.x >> 6;
-  const size_t i = (size_t)blockIdx.x * 64 + o;
+  const size_t i = (size_t)block * 64 + o;
   const bool live = i < total;
   const int p = live ? (int)(i / qv) : 0, q4 = live ? (int)(i % qv) * 4 : 0;
   f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
@@ -195,14 +195,22 @@ __global__ __launch_bounds__(256) void reduce2_kernel(const float* __restrict__ 
   }
 }
 
-// Wt[q][p] = W[p][q] for a row-major W of P rows and Q columns: the weight slices gemm_nt2_kernel keeps in
-// registers are then read with consecutive lanes on consecutive addresses.
-__global__ void transpose_kernel(const float* __restrict__ W, int P, int Q, float* __restrict__ Wt) {
-  const int total = P * Q;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-    const int q = i / P, p = i - q * P;
-    Wt[i] = W[(size_t)p * Q + q];
-  }
+// Several such reductions in one launch (the weight and bias gradients of all layers at the end of the pass):
+// job j owns the blocks [first[j], first[j+1]).
+constexpr int kMaxReduceJobs = 6;
+struct ReduceJobs {
+  const float* part[kMaxReduceJobs];
+  float* out[kMaxReduceJobs];
+  int S[kMaxReduceJobs], P[kMaxReduceJobs], QTOT[kMaxReduceJobs], Q[kMaxReduceJobs];
+  int first[kMaxReduceJobs + 1];
+  int n;
+};
+__global__ __launch_bounds__(256) void reduce_jobs_kernel(const ReduceJobs jobs, const int* __restrict__ hdr) {
+  __shared__ f32x4 red[3][64];
+  int j = 0;
+  while (j + 1 < jobs.n && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
+  reduce2_block(jobs.part[j], jobs.S[j], jobs.P[j], jobs.QTOT[j], jobs.Q[j], jobs.out[j], hdr,
+                (int)blockIdx.x - jobs.first[j], red);
 }
 
 // For each live row i: Out[i][p] = (sum_q Gin[i][q] * W[p][q]) * [act[i][p] > 0], written over the stored
@@ -457,7 +465,7 @@ __global__ __launch_bounds__(256) void reduce_dw1_ising_kernel(const float* __re
   const size_t stride = (size_t)P * QTOT;
   const int qv = H1 >> 2;
   const size_t total = (size_t)(P / 2) * qv;
-  const int o = threadIdx.x & 63, sg = threadIdx.x >> 6;  // as in reduce2_kernel: 64 outputs x 4 groups of parts
+  const int o = threadIdx.x & 63, sg = threadIdx.x >> 6;  // as in reduce2_block: 64 outputs x 4 groups of parts
   const size_t i = (size_t)blockIdx.x * 64 + o;
   const bool live = i < total;
   const int u = live ? (int)(i / qv) : 0, q = live ? (int)(i % qv) * 4 : 0;

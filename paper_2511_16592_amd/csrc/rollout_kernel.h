@@ -757,17 +757,54 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   }
 }
 
-// W[K][N] row-major -> MFMA A-operand order: out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
-// zero beyond column N.
-__global__ void pack_weights_kernel(const float* __restrict__ W, int K, int N, int NT, float* __restrict__ out) {
+// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 32 / 64
+// blocks of 256 threads):
+//   W2p, W3p  W[K][N] row-major -> MFMA A-operand order, out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
+//             zero beyond column N (the rollout's layer-2 and logit weights);
+//   W2t, W3t  transposes Wt[n][k] = W[k][n] (register slices of the input-gradient kernels load coalesced);
+//   actions   every action byte <- 0xFF padding, as 32-bit words (the buffer is 4-byte aligned); skipped when null.
+struct PrepareParams {
+  const float *W2, *W3;
+  int H1, H2, A, A16;
+  float *W2p, *W3p, *W2t, *W3t;
+  uint8_t* actions;
+  size_t action_bytes;
+};
+__device__ __forceinline__ void pack_weights_part(const float* __restrict__ W, int K, int N, int NT,
+                                                  float* __restrict__ out, int block, int blocks) {
   const int Q = K >> 4;
   const size_t total = (size_t)NT * Q * 256;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+  for (size_t i = (size_t)block * 256 + threadIdx.x; i < total; i += (size_t)blocks * 256) {
     const int s = (int)(i & 3), ln = (int)((i >> 2) & 63);
     const size_t r = i >> 8;
     const int q = (int)(r % Q), nt = (int)(r / Q);
     const int k = 16 * q + 4 * (ln >> 4) + s, n = 16 * nt + (ln & 15);
     out[i] = n < N ? W[(size_t)k * N + n] : 0.f;
+  }
+}
+__device__ __forceinline__ void transpose_part(const float* __restrict__ W, int P, int Q, float* __restrict__ Wt,
+                                               int block, int blocks) {
+  const int total = P * Q;
+  for (int i = block * 256 + threadIdx.x; i < total; i += blocks * 256) {
+    const int q = i / P, pp = i - q * P;
+    Wt[i] = W[(size_t)pp * Q + q];
+  }
+}
+constexpr int kPrepareBlocks = 128 + 64 + 128 + 32 + 64;
+__global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
+  int b = blockIdx.x;
+  if (b < 128) { pack_weights_part(p.W2, p.H1, p.H2, p.H2 >> 4, p.W2p, b, 128); return; }
+  b -= 128;
+  if (b < 64) { pack_weights_part(p.W3, p.H2, p.A, p.A16 >> 4, p.W3p, b, 64); return; }
+  b -= 64;
+  if (b < 128) { transpose_part(p.W2, p.H1, p.H2, p.W2t, b, 128); return; }
+  b -= 128;
+  if (b < 32) { transpose_part(p.W3, p.H2, p.A, p.W3t, b, 32); return; }
+  b -= 32;
+  if (p.actions) {
+    const size_t words = p.action_bytes >> 2;
+    for (size_t i = (size_t)b * 256 + threadIdx.x; i < words; i += (size_t)64 * 256) ((uint32_t*)p.actions)[i] = 0xFFFFFFFFu;
+    if (b == 0 && threadIdx.x < (p.action_bytes & 3)) p.actions[(words << 2) + threadIdx.x] = 0xFF;
   }
 }
 
