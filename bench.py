@@ -178,7 +178,10 @@ def main():
                     "traffic": measured_traffic(args.workload, r["dominant"]),
                     "avg_kernel_ms": avg_ms, "launches": launches,
                     "algorithmic_flops_per_launch": share * per_step * (args.steps / launches),
-                    "whole_step_frac": head["whole_step_mfma_frac"]}
+                    "whole_step_frac": head["whole_step_mfma_frac"],
+                    "note": "the rollout's duration is bounded below by (longest trajectory of the batch) x (per-step "
+                            "latency of a workgroup): short walks (c2, c5) are latency-bound, long walks and Ising "
+                            "(see extra) are matrix-core-bound"}
 
     out = {
         "metric": "env transitions/s for rollout+TB-grad step",

@@ -18,11 +18,11 @@
 
 namespace gfnx {
 
-// The live transitions are cut into chunks of 32 rows and the chunks into at most S parts of at least 4
+// The live transitions are cut into chunks of 32 rows and the chunks into at most S parts of at least 3
 // chunks each, so that short batches do not pay for S partial tiles.
 __device__ __forceinline__ int split_chunks_per_part(int chunks, int S) {
   const int per = (chunks + S - 1) / S;
-  return per < 4 ? 4 : per;
+  return per < 3 ? 3 : per;
 }
 
 template <int WP, int WQ, int PBW, int QBW, bool SCALE>
