@@ -201,6 +201,68 @@ def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
     assert (a.trajectories()["actions"] != ta["actions"]).any()
 
 
+def test_longest_supported_walks(gfnx, oracle32, oracle64):
+    """15-D grid of side 18: 256 steps at most (the supported maximum), 270 one-hot inputs (more than the 256 the
+    one-hot contraction takes: the per-trajectory segment-sum path of the layer-1 gradient), stop bias -8."""
+    env = grid_env(15, 18)
+    assert env.dims()[3] == 256
+    w = xavier_mlp(270, 64, 64, 16, seed=41)
+    w["b3"][15] = -8.0
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, 24, seed=12, iteration=1, log_z=0.0, name="grid15x18")
+    assert traj["length"].max() >= 200
+
+
+def test_kernel_timing_interface(gfnx):
+    """gfnx_timing_*: per-label launch counts and times; the label filter keeps only the chosen kernel."""
+    import torch
+    wl = workloads()["c1"]
+    sess = gfnx.Session(wl.env, wl.mlp(), wl.batch)
+    timer = gfnx.KernelTimer()
+    timer.enable(True)
+    for i in range(3):
+        sess.rollout(wl.seed, i)
+        sess.tb_loss_grad(0.0)
+    torch.cuda.synchronize()
+    rec = timer.collect()
+    assert rec["rollout"][0] == 3 and rec["rollout"][1] > 0.0
+    assert {"prepare", "prep", "build_rows", "reduce"} <= set(rec)
+    timer.enable(True, only="rollout")
+    sess.rollout(wl.seed, 9)
+    sess.tb_loss_grad(0.0)
+    torch.cuda.synchronize()
+    rec = timer.collect()
+    assert set(rec) == {"rollout"} and rec["rollout"][0] == 1
+    timer.enable(False)
+    sess.rollout(wl.seed, 10)
+    torch.cuda.synchronize()
+    assert timer.collect() == {}
+
+
+def test_replay_cuts_a_trajectory_at_an_impossible_action(gfnx, oracle64):
+    """A given action that is impossible in its state ends that trajectory there (no fault, no effect on the
+    others); the other trajectories match the reference as usual."""
+    env = grid_env(2, 4)
+    trajs = enumerate_grid_trajectories(2, 4)[:32]
+    actions, length = pack_trajectories(trajs, 7)
+    w = random_mlp(8, 64, 64, 3, seed=37, scale=2.0)
+    sess = gfnx.Session(env, w, len(trajs))
+    sess.replay(actions, length)
+    good = sess.trajectories()
+    bad_actions = actions.copy()
+    victim = int(np.argmax(length))
+    bad_actions[1, victim] = 200  # not an action of this environment
+    sess.replay(bad_actions, length)
+    got = sess.trajectories()
+    others = np.arange(len(trajs)) != victim
+    for k in ("log_pf", "log_pb", "log_reward"):
+        assert (got[k][others] == good[k][others]).all(), k
+    assert (got["terminal_state"][:, others] == good["terminal_state"][:, others]).all()
+    assert np.isfinite(got["log_pf"][victim]) and np.isfinite(got["log_reward"][victim])
+    sess.tb_loss_grad(0.1)
+    g = sess.gradients()
+    assert all(np.isfinite(g[k]).all() for k in KEYS) and np.isfinite(g["loss"])
+
+
 # ------------------------------------------------------------------ teacher-forced pass and the DP-optimal policy
 def test_replay_of_all_trajectories_and_optimal_policy(gfnx, oracle64):
     """All 69 complete trajectories of the 2-D side-4 grid, teacher-forced: with the proper forward policy
