@@ -66,7 +66,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, coef, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs, total;
+  size_t hdr, w2p, w3p, w2t, w3t, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs, total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -138,7 +138,6 @@ Layout make_layout(const Shapes& s) {
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
   L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T, W3^T for the gradient pass
   L.w3t = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
-  L.coef = o; o += align256(sizeof(float) * (size_t)s.B);
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
@@ -350,7 +349,6 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
 
   int* hdr = at<int>(ws, L.hdr);
   int* rows = at<int>(ws, L.rows);
-  float* coef = at<float>(ws, L.coef);
   float* crow = at<float>(ws, L.crow);
   float* h1buf = at<float>(ws, L.h1);
   float* h2buf = at<float>(ws, L.h2);
@@ -359,13 +357,9 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   if ((size_t)traj->max_steps * B > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
 
   {
-    GFNX_TIMED("prep", st);
-    hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb,
-                       traj->log_reward, log_z, B, T, coef, loss_dev, dlogz_dev, hdr);
-  }
-  {
-    GFNX_TIMED("build_rows", st);
-    hipLaunchKernelGGL(build_rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, B, hdr, rows, (const float*)coef, crow);
+    GFNX_TIMED("rows", st);
+    hipLaunchKernelGGL(rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb, traj->log_reward,
+                       log_z, B, T, loss_dev, dlogz_dev, hdr, rows, crow);
   }
   Dw1Params dp = {};
   dp.env = env_params(env, s);

@@ -9,7 +9,7 @@
 //   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn2_kernel)
 //   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt2_kernel / gemm_nt2k_kernel)
 //   dW1, db1 from G1                                 (dw1_onehot_kernel; dw1_kernel below for wide one-hot inputs)
-// This file: prep_kernel (residuals, loss, list offsets), build_rows_kernel (the list), fill_kernel, dw1_kernel
+// This file: rows_kernel (residuals, loss, the list), fill_kernel, dw1_kernel
 // (per-trajectory segment sums with atomics).
 #pragma once
 #include "gfnx_device.h"
@@ -22,63 +22,69 @@ constexpr int kHdrCnt = 16;     // cnt[t] = number of trajectories longer than t
 constexpr int kHdrOff = 16 + 256;  // off[t] = first list position of step t
 constexpr int kHdrWords = 16 + 512;
 
-// One workgroup: TB residuals, loss, dloss/dlogZ, per-trajectory gradient scale, and the histogram of
-// lengths that positions each step's live transitions in the list.
-__global__ __launch_bounds__(1024) void prep_kernel(const int* __restrict__ length, const float* __restrict__ lpf,
+// Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b, and next to each
+// the coefficient of its trajectory, crow[off[t] + rank] = 2 delta_b / B with the TB residual
+// delta_b = log Z + log P_F - log R - log P_B.  Every workgroup derives the list offsets itself from the histogram
+// of the lengths (B integers: cheaper than a launch of its own); workgroup 0 also writes them to the header for
+// the kernels that follow, together with the loss (mean delta^2) and dloss/dlogZ (2 mean delta).
+__global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ length, const float* __restrict__ lpf,
                                                     const float* __restrict__ lpb, const float* __restrict__ logr,
-                                                    float log_z, int B, int T, float* __restrict__ coef,
-                                                    float* __restrict__ loss, float* __restrict__ dlogz,
-                                                    int* __restrict__ hdr) {
+                                                    float log_z, int B, int T, float* __restrict__ loss,
+                                                    float* __restrict__ dlogz, int* __restrict__ hdr,
+                                                    int* __restrict__ rows, float* __restrict__ crow) {
   __shared__ int hist[258];
   __shared__ float red2[1024], red1[1024];
-  const int tid = threadIdx.x;
+  __shared__ int wsum[16];
+  __shared__ int base, mycnt;
+  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   for (int i = tid; i < 258; i += 1024) hist[i] = 0;
   __syncthreads();
   float s2 = 0.f, s1 = 0.f;
   for (int b = tid; b < B; b += 1024) {
-    const float delta = log_z + lpf[b] - logr[b] - lpb[b];
-    coef[b] = 2.f * delta / (float)B;
-    s2 += delta * delta;
-    s1 += delta;
+    if (t == 0) {
+      const float delta = log_z + lpf[b] - logr[b] - lpb[b];
+      s2 += delta * delta;
+      s1 += delta;
+    }
     int len = length[b];
     len = len < 0 ? 0 : (len > T ? T : len);
     atomicAdd(&hist[len], 1);
   }
-  red2[tid] = s2;
-  red1[tid] = s1;
-  __syncthreads();
-  for (int o = 512; o > 0; o >>= 1) {
-    if (tid < o) { red2[tid] += red2[tid + o]; red1[tid] += red1[tid + o]; }
+  if (t == 0) {
+    red2[tid] = s2;
+    red1[tid] = s1;
     __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+      if (tid < o) { red2[tid] += red2[tid + o]; red1[tid] += red1[tid + o]; }
+      __syncthreads();
+    }
   }
+  __syncthreads();
   if (tid == 0) {
-    *loss = red2[0] / (float)B;
-    *dlogz = 2.f * red1[0] / (float)B;
-    // cnt[t] = #{b : len_b > t} = sum_{l > t} hist[l]
-    int run = 0, maxlen = 0;
+    // cnt[u] = #{b : len_b > u} = sum_{l > u} hist[l]; off[u] = sum_{v < u} cnt[v]
+    int off = 0, run = 0, maxlen = 0, off_t = 0, cnt_t = 0;
     for (int l = T; l >= 1; --l) {
       run += hist[l];
-      hdr[kHdrCnt + l - 1] = run;
-      if (hist[l] && maxlen == 0) maxlen = l;
+      hist[l] = run;  // now cnt[l - 1]
+      if (run && maxlen == 0) maxlen = l;
     }
-    int off = 0;
-    for (int t = 0; t < T; ++t) { hdr[kHdrOff + t] = off; off += hdr[kHdrCnt + t]; }
-    hdr[kHdrNLive] = off;
-    hdr[kHdrMaxLen] = maxlen;
+    for (int u = 0; u < T; ++u) {
+      const int c = hist[u + 1];
+      if (u == t) { off_t = off; cnt_t = c; }
+      if (t == 0) { hdr[kHdrCnt + u] = c; hdr[kHdrOff + u] = off; }
+      off += c;
+    }
+    if (t == 0) {
+      hdr[kHdrNLive] = off;
+      hdr[kHdrMaxLen] = maxlen;
+      *loss = red2[0] / (float)B;
+      *dlogz = 2.f * red1[0] / (float)B;
+    }
+    base = off_t;
+    mycnt = cnt_t;
   }
-}
-
-// Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b, and next to
-// each its trajectory's coefficient crow[off[t] + rank] = coef[b].
-__global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict__ length, int B,
-                                                          const int* __restrict__ hdr, int* __restrict__ rows,
-                                                          const float* __restrict__ coef, float* __restrict__ crow) {
-  __shared__ int wsum[16];
-  __shared__ int base;
-  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (hdr[kHdrCnt + t] == 0) return;
-  if (tid == 0) base = hdr[kHdrOff + t];
   __syncthreads();
+  if (mycnt == 0) return;
   for (int b0 = 0; b0 < B; b0 += 1024) {
     const int b = b0 + tid;
     const bool on = b < B && length[b] > t;
@@ -90,7 +96,7 @@ __global__ __launch_bounds__(1024) void build_rows_kernel(const int* __restrict_
     for (int k = 0; k < 16; ++k) { if (k < wv) woff += wsum[k]; tot += wsum[k]; }
     if (on) {
       rows[base + woff + before] = t * B + b;
-      crow[base + woff + before] = coef[b];
+      crow[base + woff + before] = 2.f * (log_z + lpf[b] - logr[b] - lpb[b]) / (float)B;
     }
     __syncthreads();
     if (tid == 0) base += tot;

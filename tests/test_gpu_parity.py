@@ -225,7 +225,7 @@ def test_kernel_timing_interface(gfnx):
     torch.cuda.synchronize()
     rec = timer.collect()
     assert rec["rollout"][0] == 3 and rec["rollout"][1] > 0.0
-    assert {"prepare", "prep", "build_rows", "reduce"} <= set(rec)
+    assert {"prepare", "rows", "reduce"} <= set(rec)
     timer.enable(True, only="rollout")
     sess.rollout(wl.seed, 9)
     sess.tb_loss_grad(0.0)
