@@ -408,7 +408,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   }
   add_job(part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
   add_job(dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
-  const int nt_lds = (64 * 258 + 192 + 512 + 192) * 4;
+  const int nt_lds = (2 * 64 * 258 + 256 + 1024 + 256) * 4;
   float* w2t = at<float>(ws, L.w2t);
   float* w3t = at<float>(ws, L.w3t);
   if (!narrow) {

@@ -227,10 +227,10 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
                                                        const int* __restrict__ rows, const int* __restrict__ hdr) {
   constexpr int KP = 258;  // LDS row pitch in floats: even (8-byte reads) and 2 mod 32 (conflict-free rows)
   extern __shared__ float smem[];
-  float* GS = smem;                    // [64][KP]
-  int* ridb = (int*)(smem + 64 * KP);  // [3][64] physical row ids of three consecutive tiles
-  uint32_t* MS = (uint32_t*)(ridb + 192);  // [64 rows][8]: the four 64-bit mask words of this column tile
-  float* cfb = (float*)(MS + 512);         // [3][64] coefficients of the same rows (SCALE)
+  float* GSb = smem;                         // [2][64][KP] row tiles, double-buffered
+  int* ridb = (int*)(smem + 2 * 64 * KP);    // [4][64] physical row ids of four consecutive tiles
+  uint32_t* MSb = (uint32_t*)(ridb + 256);   // [2][64 rows][8]: the four 64-bit mask words of this column tile
+  float* cfb = (float*)(MSb + 1024);         // [4][64] coefficients of the same rows (SCALE)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = hdr[kHdrNLive];
   const int tiles = (n + 63) >> 6;
@@ -247,9 +247,6 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
   }
 
   const int kv = K >> 2;               // f32x4 per row
-  // Software pipeline over the row tiles of this workgroup (it = 0, 1, ...): the row ids of tile it+2 (one
-  // register on 64 threads) and the rows + mask words of tile it+1 are in flight during the MFMAs of tile it.
-  // Row ids live in LDS, three tiles deep: ridb[it % 3].
   f32x4 pre[8];
   uint32_t mpre = 0;
   int idreg = -1;
@@ -279,16 +276,13 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
     }
   };
 
-  int tile = blockIdx.x;
-  fetch_ids(tile);
-  if (tid < 64) { ridb[tid] = idreg; cfb[tid] = cfreg; }
-  lds_barrier();
-  load_rows(ridb, cfb);
-  fetch_ids(tile + gridDim.x);
-  for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
-    const int* rid = ridb + 64 * (it % 3);
-    int* rid_next = ridb + 64 * ((it + 1) % 3);
-    float* cf_next = cfb + 64 * ((it + 1) % 3);
+  // Tile k of this workgroup is row tile blockIdx.x + k * gridDim.x.  In iteration it the matrix cores work on
+  // LDS buffer it % 2 while the rows of tile it+1 (in registers since the previous iteration) go to the other
+  // buffer, the rows of tile it+2 are requested and the row ids of tile it+4 are fetched: one barrier per tile.
+  // Row ids (and coefficients) live in LDS four tiles deep, from the request of a tile's rows to its epilogue.
+  const int t0 = blockIdx.x, dt = gridDim.x;
+  auto store_tile = [&](int buf) {
+    float* GS = GSb + buf * 64 * KP;
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       const int i = tid + 512 * m;
@@ -296,11 +290,28 @@ __global__ __launch_bounds__(512) void gemm_nt2_kernel(const float* __restrict__
       *(float2*)d = make_float2(pre[m].x, pre[m].y);
       *(float2*)(d + 2) = make_float2(pre[m].z, pre[m].w);
     }
-    MS[tid] = mpre;
-    if (tid < 64) { rid_next[tid] = idreg; cf_next[tid] = cfreg; }
-    lds_barrier();
-    load_rows(rid_next, cf_next);
-    fetch_ids(tile + 2 * (int)gridDim.x);
+    MSb[buf * 512 + tid] = mpre;
+  };
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    fetch_ids(t0 + k * dt);
+    if (tid < 64) { ridb[64 * k + tid] = idreg; cfb[64 * k + tid] = cfreg; }
+  }
+  lds_barrier();
+  load_rows(ridb, cfb);
+  store_tile(0);
+  load_rows(ridb + 64, cfb + 64);
+  fetch_ids(t0 + 3 * dt);
+  lds_barrier();
+  int it = 0;
+  for (int tile = t0; tile < tiles; tile += dt, ++it) {
+    const int* rid = ridb + 64 * (it & 3);
+    const float* GS = GSb + (it & 1) * 64 * KP;
+    const uint32_t* MS = MSb + (it & 1) * 512;
+    store_tile((it + 1) & 1);
+    if (tid < 64) { ridb[64 * ((it + 3) & 3) + tid] = idreg; cfb[64 * ((it + 3) & 3) + tid] = cfreg; }
+    load_rows(ridb + 64 * ((it + 2) & 3), cfb + 64 * ((it + 2) & 3));
+    fetch_ids(tile + 4 * dt);
     // the 64 rows of the tile as two passes of 32, one accumulator block live at a time
     const int pl = 32 * w + (lane & 31);
     const int mk = pl & 3, ml = pl >> 2;  // unit p = 4l + k of this column tile: bit l of mask word k
