@@ -84,9 +84,12 @@ def cpu_baseline(wl, w, seconds_target=12.0):
             break
         if dt < seconds_target / 8 and batch < wl.batch:
             batch = min(wl.batch, batch * 4)
+    sizes = sorted(set(batches))
+    mix = ", ".join("%d x %d" % (batches.count(b), b) for b in sizes)
     return {"value": done_tr / used, "unit": "transitions/s", "cores": cores, "kind": "oracle",
-            "sample": "%d passes (rollout + TB gradient, binary32 build, %d threads) over batches %s of the same "
-                      "workload: %d transitions in %.1f s" % (len(batches), cores, batches, done_tr, used)}
+            "sample": "%d passes (rollout + TB gradient, binary32 build, %d threads) over batches of the same "
+                      "workload (passes x trajectories: %s): %d transitions in %.1f s"
+                      % (len(batches), cores, mix, done_tr, used)}
 
 
 def run_workload(name, steps, warmup, events=True):
