@@ -188,3 +188,15 @@ class Oracle:
         g.update(loss=float(loss.value), dlogz=float(dlogz.value), delta=delta, n_kink=int(n_kink.value),
                  slack=dict(zip(("dW1", "db1", "dW2", "db2", "dW3", "db3"), slack.astype(np.float64))))
         return g
+
+    # ---- optimiser -------------------------------------------------------------
+    def adam_step(self, theta: np.ndarray, grad: np.ndarray, m: np.ndarray, v: np.ndarray, t: int, lr: float,
+                  beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+        """One Adam update of `theta`, `m`, `v` in place (arrays of this oracle's precision); t counts from 1."""
+        for a in (theta, m, v):
+            assert a.dtype == self.real and a.flags.c_contiguous and a.shape == theta.shape
+        g = np.ascontiguousarray(grad, dtype=self.real)
+        assert g.shape == theta.shape
+        rc = self.lib.oracle_adam_step(_ptr(theta), _ptr(g), _ptr(m), _ptr(v), C.c_int64(theta.size), C.c_int64(t),
+                                       self.creal(lr), self.creal(beta1), self.creal(beta2), self.creal(eps))
+        assert rc == 0, rc

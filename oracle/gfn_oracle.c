@@ -24,7 +24,11 @@
  *   - Ising partial assignments: Appendix "Ising model" (energy equation,
  *     state / action description);
  *   - environments emit log-reward only on the terminal transition: "Library
- *     Details", implementation notes.
+ *     Details", implementation notes;
+ *   - the optimiser step of a training iteration: Adam with the settings of the
+ *     hypergrid hyperparameter table (Appendix "Hypergrid": learning rate 1e-3,
+ *     1e-1 for log Z, betas (0.9, 0.999), epsilon 1e-8, no weight decay), the
+ *     update itself as published by Kingma & Ba (2015), Algorithm 1.
  *
  * Conventions fixed here where the paper is silent (they are listed in full in
  * the design document of the repository):
@@ -47,7 +51,9 @@
  * Parity pins (tests/test_oracle_*.py): exhaustive enumeration on the 2-D side-4
  * grid, closed-form normalising constants, the DP-optimal policy with zero
  * residual, closed-form rewards, finite differences, an independent big-integer
- * Philox and the published known-answer vectors, chi-square tests of the sampler.
+ * Philox and the published known-answer vectors, chi-square tests of the sampler;
+ * for the optimiser step a library Adam, the constant-gradient closed form, and a
+ * training run on the side-4 grid whose terminal distribution must approach R/Z.
  * Free-running sampled actions have no external reference ("parity unpinned"
  * beyond those statistical pins): the counter layout above is this build's own.
  */
@@ -657,6 +663,30 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
   if (n_kink_out) { *n_kink_out = 0; for (int k = 0; k < nthreads; ++k) *n_kink_out += jobs[k].n_kink; }
   free(delta); free(priv); free(th); free(jobs);
   return status;
+}
+
+/* ------------------------------------------------------------------ optimiser */
+
+static real rsqrt_(real x) { return sizeof(real) == 4 ? (real)sqrtf((float)x) : (real)sqrt((double)x); }
+
+/* One Adam update of n parameters in place (Kingma & Ba 2015, Algorithm 1; settings: Appendix "Hypergrid",
+ * hyperparameter table).  t is the 1-based count of this update; m and v are the running first and second
+ * moments (zero before the first update):
+ *   m <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2,
+ *   theta <- theta - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps). */
+int oracle_adam_step(real* theta, const real* g, real* m, real* v, int64_t n, int64_t t, real lr, real beta1,
+                     real beta2, real eps) {
+  if (!theta || !g || !m || !v || n < 0 || t < 1) return -1;
+  const real c1 = (real)1 - (real)pow((double)beta1, (double)t);
+  const real c2 = (real)1 - (real)pow((double)beta2, (double)t);
+  for (int64_t i = 0; i < n; ++i) {
+    m[i] = beta1 * m[i] + ((real)1 - beta1) * g[i];
+    v[i] = beta2 * v[i] + ((real)1 - beta2) * (g[i] * g[i]);
+    const real mhat = m[i] / c1;
+    const real vhat = v[i] / c2;
+    theta[i] = theta[i] - lr * mhat / (rsqrt_(vhat) + eps);
+  }
+  return 0;
 }
 
 int oracle_real_bytes(void) { return (int)sizeof(real); }

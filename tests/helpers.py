@@ -102,3 +102,65 @@ def optimal_policy_mlp_2d(side, dtype=np.float64, **kw):
 def chi2_sf(stat, dof):
     from scipy.stats import chi2
     return float(chi2.sf(stat, dof))
+
+
+def grid_terminal_distribution(policy, dim, side):
+    """Exact distribution over terminal states induced by a forward policy on the hypergrid DAG:
+    visit(s0) = 1, visit(x + e_i) += visit(x) P_F(+e_i | x), P_T(x) = visit(x) P_F(stop | x).
+    `policy(x)` returns (log_probs[dim+1], valid[dim+1]); stop is the last action."""
+    visit = {tuple([0] * dim): 1.0}
+    term = {}
+    for x in sorted(itertools.product(range(side), repeat=dim), key=lambda s: sum(s)):
+        v = visit.get(x, 0.0)
+        logp, valid = policy(x)
+        term[x] = v * math.exp(float(logp[dim]))
+        for i in range(dim):
+            if x[i] < side - 1:
+                assert valid[i]
+                y = list(x)
+                y[i] += 1
+                y = tuple(y)
+                visit[y] = visit.get(y, 0.0) + v * math.exp(float(logp[i]))
+            else:
+                assert not valid[i]
+    return term
+
+
+def grid_tv_to_reward(term, side, **kw):
+    """Total variation distance between a terminal distribution and R / Z."""
+    z = sum(grid_reward(x, side, **kw) for x in term)
+    return 0.5 * sum(abs(p - grid_reward(x, side, **kw) / z) for x, p in term.items())
+
+
+PARAM_KEYS = ("W1", "b1", "W2", "b2", "W3", "b3")
+
+
+class OracleTrainer:
+    """A whole training iteration composed from the CPU reference: on-policy rollout, TB loss and gradient along
+    the sampled actions, one Adam update of every weight tensor and of log Z (Appendix "Hypergrid",
+    hyperparameter table: learning rate 1e-3, 1e-1 for log Z)."""
+
+    def __init__(self, oracle, env, weights, log_z=0.0, lr=1e-3, lr_log_z=1e-1, beta1=0.9, beta2=0.999, eps=1e-8):
+        self.o, self.env = oracle, env
+        self.w = {k: np.array(weights[k], dtype=oracle.real) for k in PARAM_KEYS}
+        self.log_z = np.array([log_z], dtype=oracle.real)
+        self.m = {k: np.zeros_like(v) for k, v in self.w.items()}
+        self.v = {k: np.zeros_like(v) for k, v in self.w.items()}
+        self.mz, self.vz = np.zeros(1, dtype=oracle.real), np.zeros(1, dtype=oracle.real)
+        self.hp = dict(beta1=beta1, beta2=beta2, eps=eps)
+        self.lr, self.lr_log_z = lr, lr_log_z
+        self.t = 0
+
+    def step(self, seed, iteration, batch, nthreads=1):
+        out = self.o.rollout(self.env, self.w, seed, iteration, batch, nthreads=nthreads)
+        g = self.o.tb_loss_grad(self.env, self.w, out["actions"], out["length"], log_z=float(self.log_z[0]),
+                                nthreads=nthreads)
+        self.apply(g)
+        return out, g
+
+    def apply(self, g):
+        self.t += 1
+        for k in PARAM_KEYS:
+            self.o.adam_step(self.w[k], g["d" + k], self.m[k], self.v[k], self.t, self.lr, **self.hp)
+        self.o.adam_step(self.log_z, np.array([g["dlogz"]], dtype=self.o.real), self.mz, self.vz, self.t,
+                         self.lr_log_z, **self.hp)
