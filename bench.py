@@ -3,6 +3,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-extra] [--no-cpu-baseline]
 
+(--no-extra skips the short runs of the other workloads and of whole training iterations.)
+
 A step is one pass of the whole hot path over one batch of synthetic input: gfnx_rollout (fresh
 Philox iteration counter each step) followed by gfnx_tb_loss_grad, inputs and outputs resident in
 HBM.  Prints one JSON line: environment transitions per second (valid transitions only), the roofline
@@ -138,6 +140,45 @@ def run_workload(name, steps, warmup, events=True):
                 breakdown={k: v[1] / max(1, warmup - cold) for k, v in breakdown.items()})
 
 
+def run_training(name, steps, warmup, batch=None):
+    """Whole training iterations (rollout, TB loss and gradient, Adam update of the weights and of log Z on the
+    device, no host round trip) from the workload's initial weights.  The policy changes from one iteration to the
+    next, so the transitions are counted inside the loop: one 4-byte-per-trajectory device copy per iteration."""
+    import torch
+    from paper_2511_16592_amd import gfnx
+    from paper_2511_16592_amd.workloads import workloads
+
+    wl = workloads()[name]
+    if batch is not None:
+        wl = wl.with_batch(batch)
+    sess = gfnx.Session(wl.env, wl.mlp(), wl.batch)
+    sess.init_optimizer(log_z=wl.log_z, lr=1e-3, lr_log_z=1e-1)
+    lengths = torch.zeros((steps, wl.batch), dtype=torch.int32, device=sess.device)
+    timer = gfnx.KernelTimer()
+    for i in range(warmup):
+        sess.train_step(wl.seed, i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        sess.train_step(wl.seed, warmup + i)
+        lengths[i].copy_(sess.length)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timer.enable(True, only="adam")
+    for i in range(5):
+        sess.train_step(wl.seed, warmup + steps + i)
+    torch.cuda.synchronize()
+    launches, adam_ms = timer.collect().get("adam", (1, float("nan")))
+    timer.enable(False)
+    n_par = sum(int(v.numel()) for v in sess.w.values()) + 1
+    transitions = int(lengths.sum().item())
+    return {"batch": wl.batch, "iterations": steps, "ms_per_iteration": elapsed / steps * 1e3,
+            "iterations_per_s": steps / elapsed, "transitions_per_s": transitions / elapsed,
+            "transitions_per_iteration": transitions / steps,
+            "adam_kernel": {"avg_ms": adam_ms / launches, "parameters": n_par,
+                            "achieved_GBps": 28.0 * n_par / (adam_ms / launches * 1e-3) / 1e9, "peak_GBps": 8000.0}}
+
+
 def summary(name, r, steps):
     wl = r["wl"]
     a = wl.env.dims()[2]
@@ -207,6 +248,13 @@ def main():
             steps = 5 if name == "c5_long" else 20
             extra[name] = summary(name, run_workload(name, steps, 3, events=False), steps)
         out["extra"] = extra
+        # the next stage of the same path: whole training iterations (optimiser step included)
+        train = {args.workload: run_training(args.workload, 50, 5), "c3": run_training("c3", 20, 3)}
+        paper = run_training("c2", 300, 20, batch=16)
+        paper["context"] = ("the paper's own hypergrid setting (4-D side 20, TB, MLP 2x256, batch 16, Adam): it "
+                            "reports 1463.3 it/s on an Intel Core i7-10700F CPU")
+        train["c2_batch16"] = paper
+        out["train"] = train
     print(json.dumps(out))
 
 

@@ -149,6 +149,42 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                       float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/* Optimiser settings of a training iteration: Adam (Kingma & Ba 2015, Algorithm 1) as the paper trains with
+ * (Appendix "Hypergrid", hyperparameter table: lr 1e-3, lr_log_z 1e-1, beta1 0.9, beta2 0.999, eps 1e-8, no
+ * weight decay).  Host struct. */
+typedef struct {
+  float lr;       /* learning rate of the six weight tensors */
+  float lr_log_z; /* learning rate of log Z */
+  float beta1, beta2, eps;
+} gfnx_adam_cfg;
+
+/* Optimiser state: running first (m) and second (v) moments, shaped like the weights, and those of log Z.
+ * Device pointers, caller-allocated, all zero before the first update. */
+typedef struct {
+  gfnx_mlp_grad m, v;
+  float* log_z_mv; /* two floats: m and v of log Z */
+} gfnx_adam_state;
+
+/* One Adam update, in place, of the six weight tensors `mlp` points at (the const of gfnx_mlp's pointer types is
+ * dropped for this call) and of *log_z_dev, from `grads` and *dlogz_dev:
+ *   m <- beta1 m + (1-beta1) g,  v <- beta2 v + (1-beta2) g^2,
+ *   theta <- theta - lr (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps),
+ * `step` = 1-based count of this update (>= 1).  log_z_dev, dlogz_dev and state->log_z_mv may all be NULL to
+ * leave log Z out.  One elementwise launch; nothing but the named buffers is read or written.
+ * Errors: NULL pointers, non-positive sizes, step < 1, beta outside [0, 1), lr or eps negative. */
+int gfnx_adam_step(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* grads, const float* dlogz_dev,
+                   const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* hip_stream);
+
+/* One whole on-policy training iteration (the loop the paper's speed table counts: rollout, objective, backward
+ * pass, optimiser step), enqueued without any host round trip: gfnx_rollout with (seed, iteration), then
+ * gfnx_tb_loss_grad with log Z read from *log_z_dev, then gfnx_adam_step with `step`.  Outputs as for those
+ * calls: traj, *loss_dev and *dlogz_dev (of the weights BEFORE the update), grads; weights, *log_z_dev and the
+ * optimiser state are updated in place.  Errors: the union of the three calls'. */
+int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                    uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                    const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the method; not thread-safe).  While enabled, every kernel (or small group
  * of kernels) the library launches is bracketed by HIP events recorded on the launch stream, labelled
  * "rollout", "gemm_tn_w2", ...  gfnx_timing_enable(on) also discards the records taken so far;

@@ -9,6 +9,7 @@
 #include "grad_kernels3.h"
 #include "rollout_kernel.h"
 
+#include <cmath>
 #include <string>
 #include <vector>
 
@@ -332,9 +333,14 @@ int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, 
   return rollout_impl(env, mlp, 0, 0, traj, workspace, workspace_bytes, hip_stream, true);
 }
 
-int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
-                      float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes,
-                      void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// log Z by value, or read from device memory when log_z_dev is not NULL
+int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
+                      const float* log_z_dev, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws,
+                      size_t ws_bytes, void* hip_stream) {
   Shapes s;
   if (!traj || !grads || !loss_dev || !dlogz_dev) return GFNX_E_NULL;
   int rc = check_shapes(env, mlp, traj->batch, &s);
@@ -359,7 +365,7 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     GFNX_TIMED("rows", st);
     hipLaunchKernelGGL(rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb, traj->log_reward,
-                       log_z, B, T, loss_dev, dlogz_dev, hdr, rows, crow);
+                       log_z, log_z_dev, B, T, loss_dev, dlogz_dev, hdr, rows, crow);
   }
   Dw1Params dp = {};
   dp.env = env_params(env, s);
@@ -508,6 +514,84 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                          (const float*)at<float>(ws, L.part1), s.s1, s.p1, s.qtot1, s.H1, (const int*)hdr, grads->db1, grads->dW1);
   }
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+int check_adam(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* grads, const float* dlogz_dev,
+               const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step) {
+  if (!mlp || !grads || !state || !cfg) return GFNX_E_NULL;
+  if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2 || !mlp->W3 || !mlp->b3) return GFNX_E_NULL;
+  if (!grads->dW1 || !grads->db1 || !grads->dW2 || !grads->db2 || !grads->dW3 || !grads->db3) return GFNX_E_NULL;
+  for (const gfnx_mlp_grad* q : {&state->m, &state->v})
+    if (!q->dW1 || !q->db1 || !q->dW2 || !q->db2 || !q->dW3 || !q->db3) return GFNX_E_NULL;
+  const int nz = (log_z_dev != nullptr) + (dlogz_dev != nullptr) + (state->log_z_mv != nullptr);
+  if (nz != 0 && nz != 3) return GFNX_E_NULL;
+  if (mlp->in_dim <= 0 || mlp->h1 <= 0 || mlp->h2 <= 0 || mlp->n_actions <= 0) return GFNX_E_BAD_SHAPE;
+  if ((uint64_t)mlp->in_dim * mlp->h1 > 0x7fffffffull || (uint64_t)mlp->h1 * mlp->h2 > 0x7fffffffull ||
+      (uint64_t)mlp->h2 * mlp->n_actions > 0x7fffffffull)
+    return GFNX_E_UNSUPPORTED;
+  if (step < 1) return GFNX_E_BAD_SHAPE;
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f)) return GFNX_E_BAD_SHAPE;
+  if (!(cfg->lr >= 0.f) || !(cfg->lr_log_z >= 0.f) || !(cfg->eps >= 0.f)) return GFNX_E_BAD_SHAPE;
+  return GFNX_OK;
+}
+
+int adam_impl(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* grads, const float* dlogz_dev,
+              const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* hip_stream) {
+  const int rc = check_adam(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  AdamJobs a = {};
+  auto add = [&](const float* theta, const float* g, float* m, float* v, size_t n, float lr) {
+    const int j = a.jobs++;
+    a.theta[j] = const_cast<float*>(theta); a.g[j] = g; a.m[j] = m; a.v[j] = v; a.n[j] = (unsigned)n; a.lr[j] = lr;
+    a.first[j + 1] = a.first[j] + (int)((n + 1023) / 1024);
+  };
+  const size_t In = mlp->in_dim, H1 = mlp->h1, H2 = mlp->h2, A = mlp->n_actions;
+  add(mlp->W1, grads->dW1, state->m.dW1, state->v.dW1, In * H1, cfg->lr);
+  add(mlp->b1, grads->db1, state->m.db1, state->v.db1, H1, cfg->lr);
+  add(mlp->W2, grads->dW2, state->m.dW2, state->v.dW2, H1 * H2, cfg->lr);
+  add(mlp->b2, grads->db2, state->m.db2, state->v.db2, H2, cfg->lr);
+  add(mlp->W3, grads->dW3, state->m.dW3, state->v.dW3, H2 * A, cfg->lr);
+  add(mlp->b3, grads->db3, state->m.db3, state->v.db3, A, cfg->lr);
+  if (log_z_dev) add(log_z_dev, dlogz_dev, state->log_z_mv, state->log_z_mv + 1, 1, cfg->lr_log_z);
+  a.beta1 = cfg->beta1; a.beta2 = cfg->beta2; a.eps = cfg->eps;
+  a.c1 = 1.f - (float)pow((double)cfg->beta1, (double)step);
+  a.c2 = 1.f - (float)pow((double)cfg->beta2, (double)step);
+  {
+    GFNX_TIMED("adam", st);
+    hipLaunchKernelGGL(adam_kernel, dim3(a.first[a.jobs]), dim3(256), 0, st, a);
+  }
+  return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
+                      float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes,
+                      void* hip_stream) {
+  return tb_loss_grad_impl(env, mlp, traj, log_z, nullptr, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
+}
+
+int gfnx_adam_step(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* grads, const float* dlogz_dev,
+                   const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* hip_stream) {
+  return adam_impl(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step, hip_stream);
+}
+
+int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                    uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                    const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* ws, size_t ws_bytes,
+                    void* hip_stream) {
+  // every argument is checked before the first launch, so a rejected call leaves all buffers untouched
+  if (!log_z_dev || !loss_dev || !dlogz_dev || !grads || !traj) return GFNX_E_NULL;
+  int rc = check_adam(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step);
+  if (rc) return rc;
+  rc = rollout_impl(env, mlp, seed, iteration, traj, ws, ws_bytes, hip_stream, false);
+  if (rc) return rc;
+  rc = tb_loss_grad_impl(env, mlp, traj, 0.f, log_z_dev, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
+  if (rc) return rc;
+  return adam_impl(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step, hip_stream);
 }
 
 int gfnx_timing_enable(int on) {

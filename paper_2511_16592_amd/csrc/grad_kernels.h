@@ -9,7 +9,7 @@
 //   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn2_kernel)
 //   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt2_kernel / gemm_nt2k_kernel)
 //   dW1, db1 from G1                                 (dw1_onehot_kernel; dw1_kernel below for wide one-hot inputs)
-// This file: rows_kernel (residuals, loss, the list), fill_kernel, dw1_kernel
+// This file: rows_kernel (residuals, loss, the list), adam_kernel (optimiser step), fill_kernel, dw1_kernel
 // (per-trajectory segment sums with atomics).
 #pragma once
 #include "gfnx_device.h"
@@ -29,9 +29,11 @@ constexpr int kHdrWords = 16 + 512;
 // the kernels that follow, together with the loss (mean delta^2) and dloss/dlogZ (2 mean delta).
 __global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ length, const float* __restrict__ lpf,
                                                     const float* __restrict__ lpb, const float* __restrict__ logr,
-                                                    float log_z, int B, int T, float* __restrict__ loss,
-                                                    float* __restrict__ dlogz, int* __restrict__ hdr,
-                                                    int* __restrict__ rows, float* __restrict__ crow) {
+                                                    float log_z, const float* __restrict__ log_z_dev, int B, int T,
+                                                    float* __restrict__ loss, float* __restrict__ dlogz,
+                                                    int* __restrict__ hdr, int* __restrict__ rows,
+                                                    float* __restrict__ crow) {
+  if (log_z_dev) log_z = *log_z_dev;  // log Z kept on the device (training loop) instead of passed by value
   __shared__ int hist[258];
   __shared__ float red2[1024], red1[1024];
   __shared__ int wsum[16];
@@ -101,6 +103,55 @@ __global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ leng
     __syncthreads();
     if (tid == 0) base += tot;
     __syncthreads();
+  }
+}
+
+// Adam update (Kingma & Ba 2015, Algorithm 1) of up to kAdamMaxJobs tensors in one elementwise launch.  c1, c2 are
+// the bias corrections 1 - beta1^t, 1 - beta2^t of this update.  Workgroup i serves 1024 consecutive elements of
+// the tensor whose block range [first[j], first[j+1]) holds i, four per lane.  HBM-bound: 16 B read + 12 B written per parameter.
+constexpr int kAdamMaxJobs = 8;
+struct AdamJobs {
+  float* theta[kAdamMaxJobs];
+  const float* g[kAdamMaxJobs];
+  float* m[kAdamMaxJobs];
+  float* v[kAdamMaxJobs];
+  unsigned n[kAdamMaxJobs];
+  float lr[kAdamMaxJobs];
+  int first[kAdamMaxJobs + 1];
+  int jobs;
+  float beta1, beta2, eps, c1, c2;
+};
+
+__device__ __forceinline__ void adam_one(float& theta, float g, float& m, float& v, float lr, const AdamJobs& a) {
+  m = a.beta1 * m + (1.f - a.beta1) * g;
+  v = a.beta2 * v + (1.f - a.beta2) * (g * g);
+  theta = theta - lr * (m / a.c1) / (sqrtf(v / a.c2) + a.eps);
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(AdamJobs a) {
+  int j = 0;
+  while (j + 1 < a.jobs && (int)blockIdx.x >= a.first[j + 1]) ++j;
+  float* __restrict__ theta = a.theta[j];
+  const float* __restrict__ g = a.g[j];
+  float* __restrict__ m = a.m[j];
+  float* __restrict__ v = a.v[j];
+  const unsigned n = a.n[j];
+  const float lr = a.lr[j];
+  const unsigned i0 = ((unsigned)((int)blockIdx.x - a.first[j]) * 256u + threadIdx.x) * 4u;  // four elements per lane
+  if (i0 >= n) return;
+  const bool aligned = ((((uintptr_t)theta) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)v)) & 15) == 0;
+  if (aligned && i0 + 4 <= n) {
+    float4 t4 = *(const float4*)(theta + i0), m4 = *(const float4*)(m + i0), v4 = *(const float4*)(v + i0);
+    const float4 g4 = *(const float4*)(g + i0);
+    adam_one(t4.x, g4.x, m4.x, v4.x, lr, a);
+    adam_one(t4.y, g4.y, m4.y, v4.y, lr, a);
+    adam_one(t4.z, g4.z, m4.z, v4.z, lr, a);
+    adam_one(t4.w, g4.w, m4.w, v4.w, lr, a);
+    *(float4*)(theta + i0) = t4;
+    *(float4*)(m + i0) = m4;
+    *(float4*)(v + i0) = v4;
+  } else {
+    for (unsigned i = i0; i < n && i < i0 + 4; ++i) adam_one(theta[i], g[i], m[i], v[i], lr, a);
   }
 }
 

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
-           "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
+           "gfnx_adam_step", "gfnx_train_step", "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
 
 class EnvDesc(C.Structure):
@@ -34,6 +34,15 @@ class Mlp(C.Structure):
 
 class MlpGrad(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("dW1", "db1", "dW2", "db2", "dW3", "db3")]
+
+
+class AdamCfg(C.Structure):
+    _fields_ = [("lr", C.c_float), ("lr_log_z", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float)]
+
+
+class AdamState(C.Structure):
+    _fields_ = [("m", MlpGrad), ("v", MlpGrad), ("log_z_mv", C.c_void_p)]
 
 
 class Traj(C.Structure):
@@ -72,6 +81,14 @@ def load_library() -> C.CDLL:
         lib.gfnx_tb_loss_grad.restype = C.c_int
         lib.gfnx_tb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
                                           C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_adam_step.restype = C.c_int
+        lib.gfnx_adam_step.argtypes = [C.POINTER(Mlp), C.c_void_p, C.POINTER(MlpGrad), C.c_void_p,
+                                       C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p]
+        lib.gfnx_train_step.restype = C.c_int
+        lib.gfnx_train_step.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_void_p, C.c_uint64, C.c_uint64,
+                                        C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
+                                        C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p, C.c_size_t,
+                                        C.c_void_p]
         lib.gfnx_timing_enable.restype = C.c_int
         lib.gfnx_timing_enable.argtypes = [C.c_int]
         lib.gfnx_timing_only.restype = C.c_int
@@ -191,6 +208,41 @@ class Session:
         _check(self.lib.gfnx_tb_loss_grad(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), float(log_z),
                                           _ptr(self.loss), _ptr(self.dlogz), C.byref(self.cgrads),
                                           _ptr(self.workspace), self.workspace_bytes, self._stream()))
+
+    # ---- training iterations -------------------------------------------------------
+    def init_optimizer(self, log_z: float = 0.0, lr: float = 1e-3, lr_log_z: float = 1e-1, beta1: float = 0.9,
+                       beta2: float = 0.999, eps: float = 1e-8) -> None:
+        """Device-resident log Z and zeroed Adam moments; the update count restarts at zero."""
+        torch = self.torch
+        self.log_z = torch.full((1,), float(log_z), dtype=torch.float32, device=self.device)
+        self.adam_m = {k: torch.zeros_like(v) for k, v in self.w.items()}
+        self.adam_v = {k: torch.zeros_like(v) for k, v in self.w.items()}
+        self.log_z_mv = torch.zeros(2, dtype=torch.float32, device=self.device)
+        keys = ("W1", "b1", "W2", "b2", "W3", "b3")
+        self.adam_state = AdamState(MlpGrad(*[_ptr(self.adam_m[k]) for k in keys]),
+                                    MlpGrad(*[_ptr(self.adam_v[k]) for k in keys]), _ptr(self.log_z_mv))
+        self.adam_cfg = AdamCfg(lr, lr_log_z, beta1, beta2, eps)
+        self.updates = 0
+
+    def adam_step(self) -> None:
+        """One Adam update of the weights and log Z from the gradients of the last tb_loss_grad."""
+        self.updates += 1
+        _check(self.lib.gfnx_adam_step(C.byref(self.mlp), _ptr(self.log_z), C.byref(self.cgrads), _ptr(self.dlogz),
+                                       C.byref(self.adam_state), C.byref(self.adam_cfg), self.updates,
+                                       self._stream()))
+
+    def train_step(self, seed: int, iteration: int) -> None:
+        """Rollout, TB loss and gradient (log Z read on the device), Adam update: one call, no host round trip."""
+        self.updates += 1
+        _check(self.lib.gfnx_train_step(C.byref(self.desc), C.byref(self.mlp), _ptr(self.log_z), seed, iteration,
+                                        C.byref(self.traj), _ptr(self.loss), _ptr(self.dlogz), C.byref(self.cgrads),
+                                        C.byref(self.adam_state), C.byref(self.adam_cfg), self.updates,
+                                        _ptr(self.workspace), self.workspace_bytes, self._stream()))
+
+    def weights(self) -> Dict:
+        """Host copies (numpy) of the six weight tensors."""
+        self.torch.cuda.synchronize(self.device)
+        return {k: v.cpu().numpy() for k, v in self.w.items()}
 
     def trajectories(self) -> Dict:
         """Host copies (numpy) of the trajectory arrays."""

@@ -103,3 +103,36 @@ def test_workspace_sizes_of_the_benchmark_configurations(lib):
         d = gfnx.env_desc(wl.env, 0x1000)
         need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(od, wl.h1, wl.h2, na)), wl.batch)
         assert 0 < need < limit, (name, need)
+
+
+def test_optimiser_argument_validation(lib):
+    """gfnx_adam_step / gfnx_train_step reject bad arguments on the host, before any launch."""
+    p = 0x1000
+    m = _mlp(16, 64, 64, 3)
+    g = gfnx.MlpGrad(p, p, p, p, p, p)
+    st = gfnx.AdamState(gfnx.MlpGrad(p, p, p, p, p, p), gfnx.MlpGrad(p, p, p, p, p, p), p)
+    cfg = gfnx.AdamCfg(1e-3, 1e-1, 0.9, 0.999, 1e-8)
+    call = lambda mm, lz, gg, dz, ss, cc, step: lib.gfnx_adam_step(mm, lz, gg, dz, ss, cc, step, None)
+    assert call(None, p, C.byref(g), p, C.byref(st), C.byref(cfg), 1) == -1
+    assert call(C.byref(m), p, None, p, C.byref(st), C.byref(cfg), 1) == -1
+    assert call(C.byref(m), p, C.byref(g), p, None, C.byref(cfg), 1) == -1
+    assert call(C.byref(m), p, C.byref(g), p, C.byref(st), None, 1) == -1
+    assert call(C.byref(m), p, C.byref(gfnx.MlpGrad(p, p, p, 0, p, p)), p, C.byref(st), C.byref(cfg), 1) == -1
+    bad_state = gfnx.AdamState(gfnx.MlpGrad(p, p, p, p, p, p), gfnx.MlpGrad(p, 0, p, p, p, p), p)
+    assert call(C.byref(m), p, C.byref(g), p, C.byref(bad_state), C.byref(cfg), 1) == -1
+    assert call(C.byref(m), p, C.byref(g), None, C.byref(st), C.byref(cfg), 1) == -1   # log Z given only in part
+    assert call(C.byref(m), p, C.byref(g), p, C.byref(st), C.byref(cfg), 0) == -3      # updates count from 1
+    assert call(C.byref(_mlp(16, 0, 64, 3)), p, C.byref(g), p, C.byref(st), C.byref(cfg), 1) == -3
+    for bad in (gfnx.AdamCfg(1e-3, 1e-1, 1.0, 0.999, 1e-8), gfnx.AdamCfg(1e-3, 1e-1, 0.9, -0.1, 1e-8),
+                gfnx.AdamCfg(-1e-3, 1e-1, 0.9, 0.999, 1e-8), gfnx.AdamCfg(1e-3, 1e-1, 0.9, 0.999, float("nan"))):
+        assert call(C.byref(m), p, C.byref(g), p, C.byref(st), C.byref(bad), 1) == -3
+    # the fused iteration: its own pointers, then the same checks, then those of the rollout
+    d = gfnx.env_desc(grid_env(2, 8))
+    t = _traj(16, 15)
+    need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 16)
+    train = lambda lz, step, ws_bytes: lib.gfnx_train_step(C.byref(d), C.byref(m), lz, 0, 0, C.byref(t), p, p,
+                                                          C.byref(g), C.byref(st), C.byref(cfg), step, 0x10000,
+                                                          ws_bytes, None)
+    assert train(None, 1, need) == -1
+    assert train(p, 0, need) == -3
+    assert train(p, 1, need - 1) == -4
