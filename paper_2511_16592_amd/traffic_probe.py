@@ -26,6 +26,9 @@ def main():
         sess.rollout(wl.seed, i)
         sess.tb_loss_grad(wl.log_z)
         torch.add(src, 1.0, out=dst)  # a plain elementwise kernel: reads COPY_BYTES, writes COPY_BYTES
+    sess.init_optimizer()
+    for i in range(steps):
+        sess.adam_step()  # the optimiser update alone, on the gradients of the last step
     torch.cuda.synchronize()
     print("traffic_probe", name, steps, "steps; copy bytes", COPY_BYTES, "transitions/step", int(sess.length.sum().item()))
 
