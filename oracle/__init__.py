@@ -189,6 +189,33 @@ class Oracle:
                  slack=dict(zip(("dW1", "db1", "dW2", "db2", "dW3", "db3"), slack.astype(np.float64))))
         return g
 
+    # ---- backward rollouts ------------------------------------------------------
+    def backward_rollout(self, env, seed: int, iteration: int, terminal_state: np.ndarray, b_offset: int = 0,
+                         max_steps: Optional[int] = None) -> Dict[str, np.ndarray]:
+        """Trajectories tau ~ P_B(. | x) for the terminal states terminal_state[state_dim, batch], in forward order."""
+        e, _k1 = self._env(env)
+        ts = np.ascontiguousarray(terminal_state, dtype=np.int8)
+        sd, batch = ts.shape
+        assert sd == env.dims()[0]
+        T = env.dims()[3] if max_steps is None else max_steps
+        out = dict(actions=np.zeros((T, batch), dtype=np.uint8), length=np.zeros(batch, dtype=np.int32),
+                   log_pb=np.zeros(batch, dtype=self.real))
+        rc = self.lib.oracle_backward_rollout(C.byref(e), C.c_uint64(seed), C.c_uint64(iteration), C.c_int32(b_offset),
+                                              C.c_int32(batch), C.c_int32(T), _ptr(ts), _ptr(out["actions"]),
+                                              _ptr(out["length"]), _ptr(out["log_pb"]))
+        assert rc == 0, rc
+        return out
+
+    def log_prob_estimate(self, log_pf: np.ndarray, log_pb: np.ndarray, n_states: int, n_samples: int) -> np.ndarray:
+        """log of the mean over the n_samples trajectories of each state of P_F / P_B (samples of a state adjacent)."""
+        f = np.ascontiguousarray(log_pf, dtype=self.real)
+        bk = np.ascontiguousarray(log_pb, dtype=self.real)
+        assert f.shape == bk.shape == (n_states * n_samples,)
+        out = np.zeros(n_states, dtype=self.real)
+        rc = self.lib.oracle_log_prob_estimate(_ptr(f), _ptr(bk), C.c_int32(n_states), C.c_int32(n_samples), _ptr(out))
+        assert rc == 0, rc
+        return out
+
     # ---- optimiser -------------------------------------------------------------
     def adam_step(self, theta: np.ndarray, grad: np.ndarray, m: np.ndarray, v: np.ndarray, t: int, lr: float,
                   beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:

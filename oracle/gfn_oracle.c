@@ -25,6 +25,11 @@
  *     state / action description);
  *   - environments emit log-reward only on the terminal transition: "Library
  *     Details", implementation notes;
+ *   - backward rollouts and the Monte-Carlo estimate of the probability P_theta(x) of
+ *     sampling a terminal state x: "Library Details" (a backward rollout is a rollout
+ *     started at terminal states with the backward step in place of the step; backward
+ *     actions are the structural choices only) and Appendix "Bit sequences" (estimator
+ *     equation: mean over tau^i ~ P_B(.|x) of P_F(tau^i) / P_B(tau^i | x));
  *   - the optimiser step of a training iteration: Adam with the settings of the
  *     hypergrid hyperparameter table (Appendix "Hypergrid": learning rate 1e-3,
  *     1e-1 for log Z, betas (0.9, 0.999), epsilon 1e-8, no weight decay), the
@@ -45,6 +50,11 @@
  *            serves action a.  u = ((w>>9)+0.5)*2^-23,  g = -log(-log(u)).
  *   log P_B  grid increment: -log #{i : child_i > 0}; grid stop: 0; bitseq: 0;
  *            Ising: -log(#assigned sites of the child) = -log(t+1).
+ *   backward the parents of a state in increasing index order (grid: coordinates > 0;
+ *            Ising: assigned sites; bitseq: the last position only); the j-th is taken,
+ *            j = floor(w * n / 2^32), w = word 0 of Philox(counter = (b, k, 0xFFFFFFFF,
+ *            iteration lo)), k = index of the backward move (the grid's un-stop move has
+ *            one parent and draws nothing).
  *   loss     mean over the batch of the squared residual
  *            delta_b = log Z + log P_F(tau_b) - log R(x_b) - log P_B(tau_b).
  *
@@ -663,6 +673,82 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
   if (n_kink_out) { *n_kink_out = 0; for (int k = 0; k < nthreads; ++k) *n_kink_out += jobs[k].n_kink; }
   free(delta); free(priv); free(th); free(jobs);
   return status;
+}
+
+/* ------------------------------------------------------------------ backward rollout */
+
+/* Parents of state s under the structural backward actions, in increasing index order. */
+static int env_backward_choices(const oracle_env* e, const int* s, int sd, int* choice) {
+  int n = 0;
+  if (e->kind == ENV_GRID) {
+    for (int i = 0; i < sd; ++i) if (s[i] > 0) choice[n++] = i;
+  } else if (e->kind == ENV_BITSEQ) {
+    int last = -1; /* left-to-right scheme: only the last written position can be emptied */
+    for (int i = 0; i < sd; ++i) if (s[i] != (1 << e->k_bits)) last = i;
+    if (last >= 0) choice[n++] = last;
+  } else {
+    for (int i = 0; i < sd; ++i) if (s[i] != 0) choice[n++] = i;
+  }
+  return n;
+}
+
+/* Undoes the forward move that produced s at index c; returns that forward action. */
+static int env_backward_step(const oracle_env* e, int* s, int c) {
+  if (e->kind == ENV_GRID) { s[c] -= 1; return c; }
+  if (e->kind == ENV_BITSEQ) { int a = s[c]; s[c] = 1 << e->k_bits; return a; }
+  { int a = 2 * c + (s[c] > 0 ? 1 : 0); s[c] = 0; return a; }
+}
+
+/* Backward rollouts ("Library Details": start at terminal states, backward step in place of the step) under
+ * the fixed uniform backward policy: for trajectory b, starting from terminal_state[:, b], parents are drawn
+ * until s_0 is reached.  Outputs the trajectory in FORWARD order (actions[t][b], 0xFF padding, length[b]) and
+ * log P_B(tau | x) summed in the order the moves are drawn. */
+int oracle_backward_rollout(const oracle_env* env, uint64_t seed, uint64_t iteration, int32_t b_offset,
+                            int32_t batch, int32_t max_steps, const int8_t* terminal_state, uint8_t* actions,
+                            int32_t* length, real* log_pb) {
+  int32_t sd, od, na, ms;
+  if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
+  if (sd > MAX_STATE || max_steps < ms) return -3;
+  const uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
+  for (int b = 0; b < batch; ++b) {
+    int s[MAX_STATE], choice[MAX_STATE], rev[MAX_STATE + 1];
+    for (int i = 0; i < sd; ++i) s[i] = terminal_state[(size_t)i * batch + b];
+    int k = 0, draws = 0;
+    real lpb = 0;
+    if (env->kind == ENV_GRID) rev[k++] = env->grid_dim; /* un-stop: the terminal copy has one parent */
+    for (;;) {
+      const int n = env_backward_choices(env, s, sd, choice);
+      if (n == 0) break; /* s_0 reached */
+      if (k >= max_steps) return -4;
+      uint32_t ctr[4] = {(uint32_t)(b_offset + b), (uint32_t)draws, 0xFFFFFFFFu, (uint32_t)(iteration & 0xFFFFFFFFu)};
+      uint32_t out[4];
+      oracle_philox4x32_10(ctr, key, out);
+      const int j = (int)(((uint64_t)out[0] * (uint64_t)n) >> 32);
+      lpb += -rlog((real)n);
+      rev[k++] = env_backward_step(env, s, choice[j]);
+      ++draws;
+    }
+    length[b] = k;
+    for (int t = 0; t < max_steps; ++t) actions[(size_t)t * batch + b] = t < k ? (uint8_t)rev[k - 1 - t] : 0xFF;
+    log_pb[b] = lpb;
+  }
+  return 0;
+}
+
+/* Monte-Carlo estimate of log P_theta(x) (Appendix "Bit sequences", estimator equation): for state x with
+ * samples i = 0..N-1 stored at index x * N + i,  out[x] = log( (1/N) sum_i exp(log_pf - log_pb) ). */
+int oracle_log_prob_estimate(const real* log_pf, const real* log_pb, int32_t n_states, int32_t n_samples, real* out) {
+  if (n_states < 0 || n_samples < 1) return -1;
+  for (int x = 0; x < n_states; ++x) {
+    const real* f = log_pf + (size_t)x * n_samples;
+    const real* bk = log_pb + (size_t)x * n_samples;
+    real mx = f[0] - bk[0];
+    for (int i = 1; i < n_samples; ++i) if (f[i] - bk[i] > mx) mx = f[i] - bk[i];
+    real acc = 0;
+    for (int i = 0; i < n_samples; ++i) acc += rexp((f[i] - bk[i]) - mx);
+    out[x] = mx + rlog(acc / (real)n_samples);
+  }
+  return 0;
 }
 
 /* ------------------------------------------------------------------ optimiser */

@@ -1,0 +1,159 @@
+"""Pins for the backward rollout and the Monte-Carlo estimate of P_theta(x) of the CPU reference."""
+import math
+from collections import Counter
+
+import numpy as np
+import pytest
+
+from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, random_mlp
+from tests.helpers import (chi2_sf, enumerate_grid_trajectories, grid_reward, grid_terminal_distribution,
+                           optimal_policy_mlp_2d)
+
+
+def _random_terminal_states(env, batch, rng):
+    sd = env.dims()[0]
+    if env.kind == 0:
+        return rng.integers(0, env.grid_side, size=(sd, batch)).astype(np.int8)
+    if env.kind == 1:
+        return rng.integers(0, 1 << env.k_bits, size=(sd, batch)).astype(np.uint8).view(np.int8)
+    return (2 * rng.integers(0, 2, size=(sd, batch)) - 1).astype(np.int8)
+
+
+@pytest.mark.parametrize("env", [grid_env(3, 5), grid_env(2, 8), bitseq_env(24, 4, 7, mode_seed=2),
+                                 bitseq_env(120, 8, 60, mode_seed=3), ising_env(3), ising_env(5)],
+                         ids=["grid3x5", "grid2x8", "bitseq24", "bitseq120", "ising3", "ising5"])
+def test_backward_rollout_inverts_the_forward_steps(oracle32, oracle64, env):
+    """The paper's own check ("Library Details", usage listing): a backward step undoes the forward step.  Replaying
+    the actions of a backward rollout forwards from s_0 must end in the terminal state the rollout started from,
+    with the same log P_B."""
+    rng = np.random.default_rng(3)
+    batch = 40
+    sd, od, na, ms = env.dims()
+    ts = _random_terminal_states(env, batch, rng)
+    back = oracle64.backward_rollout(env, 17, 2, ts)
+    w = random_mlp(od, 64, 64, na, seed=5)
+    rep = oracle64.replay(env, w, 0, 0, back["actions"], back["length"], tie_tol=1e30)
+    assert (rep["terminal_state"] == ts).all()
+    np.testing.assert_allclose(back["log_pb"], rep["log_pb"], rtol=1e-12, atol=1e-12)
+    if env.kind == 0:
+        assert (back["length"] == ts.astype(int).sum(0) + 1).all()
+        for b in range(batch):
+            assert back["actions"][back["length"][b] - 1, b] == env.grid_dim       # stop is the last action
+    else:
+        assert (back["length"] == ms).all()
+    for b in range(batch):
+        assert (back["actions"][back["length"][b]:, b] == 0xFF).all()
+    # binary32 build: the integer decisions are the same
+    back32 = oracle32.backward_rollout(env, 17, 2, ts)
+    assert (back32["actions"] == back["actions"]).all() and (back32["length"] == back["length"]).all()
+    # trajectory b depends on (seed, iteration, global index) only
+    part = oracle64.backward_rollout(env, 17, 2, np.ascontiguousarray(ts[:, 10:25]), b_offset=10)
+    assert (part["actions"] == back["actions"][:, 10:25]).all()
+    other = oracle64.backward_rollout(env, 17, 3, ts)
+    if env.kind != 1:
+        assert (other["actions"] != back["actions"]).any()
+    else:
+        assert (other["actions"] == back["actions"]).all()   # one parent per state: nothing is drawn
+
+
+def test_bitseq_backward_path_is_the_token_sequence(oracle64):
+    env = bitseq_env(24, 4, 7, mode_seed=2)
+    ts = np.array([[3, 0], [15, 1], [0, 2], [7, 3], [8, 4], [1, 5]], dtype=np.int8)
+    back = oracle64.backward_rollout(env, 1, 0, ts)
+    assert (back["actions"] == ts.view(np.uint8)).all()
+    assert (back["log_pb"] == 0).all()
+
+
+def test_grid_backward_paths_follow_the_uniform_backward_policy(oracle64):
+    """Sampled backward paths from one terminal state against P_B(tau | x) = prod 1 / #{i : y_i > 0} computed from
+    the enumeration of all forward trajectories that end there (chi-square); sum_tau P_B(tau | x) = 1."""
+    side, x = 4, (2, 1)
+    env = grid_env(2, side)
+    probs = {}
+    for acts, term in enumerate_grid_trajectories(2, side):
+        if term != x:
+            continue
+        y, p = [0, 0], 1.0
+        for a in acts[:-1]:
+            y[a] += 1
+            p /= sum(1 for c in y if c > 0)
+        probs[tuple(acts)] = p
+    assert len(probs) == 3 and abs(sum(probs.values()) - 1.0) < 1e-12
+    n = 30000
+    ts = np.repeat(np.array(x, dtype=np.int8)[:, None], n, axis=1)
+    back = oracle64.backward_rollout(env, 5, 0, ts)
+    seen = Counter(tuple(int(a) for a in back["actions"][:back["length"][b], b]) for b in range(n))
+    assert set(seen) == set(probs)
+    stat = sum((seen[k] - n * p) ** 2 / (n * p) for k, p in probs.items())
+    assert chi2_sf(stat, len(probs) - 1) > 1e-4
+    for b in range(0, n, 997):
+        path = tuple(int(a) for a in back["actions"][:back["length"][b], b])
+        assert abs(math.exp(back["log_pb"][b]) - probs[path]) < 1e-12
+
+
+def test_ising_backward_paths_are_uniform_orders(oracle64):
+    env = ising_env(3)
+    n = 18000
+    rng = np.random.default_rng(4)
+    x = (2 * rng.integers(0, 2, size=9) - 1).astype(np.int8)
+    ts = np.repeat(x[:, None], n, axis=1)
+    back = oracle64.backward_rollout(env, 6, 1, ts)
+    acts = back["actions"].astype(int)
+    assert (np.sort(acts // 2, axis=0) == np.arange(9)[:, None]).all()          # every site exactly once
+    assert (2 * (acts % 2) - 1 == x[acts // 2]).all()                            # with the spin it has in x
+    np.testing.assert_allclose(back["log_pb"], -math.lgamma(10), rtol=1e-12)
+    for t in (0, 4, 8):   # the site assigned at forward step t is uniform over the sites
+        counts = np.bincount(acts[t] // 2, minlength=9)
+        stat = float(((counts - n / 9) ** 2 / (n / 9)).sum())
+        assert chi2_sf(stat, 8) > 1e-4
+    pairs = np.bincount((acts[7] // 2) * 9 + acts[8] // 2, minlength=81).reshape(9, 9)   # last two removed: ordered pairs
+    assert (np.diag(pairs) == 0).all()
+    off = pairs[~np.eye(9, dtype=bool)]
+    assert chi2_sf(float(((off - n / 72) ** 2 / (n / 72)).sum()), 71) > 1e-4
+
+
+@pytest.mark.parametrize("side", [4, 8])
+def test_estimate_is_exact_under_the_proper_policy(oracle64, side):
+    """For the policy that satisfies the trajectory balance constraint, P_F(tau) / P_B(tau | x) = R(x) / Z on EVERY
+    trajectory, so the estimate equals R(x)/Z whatever paths are drawn and however few."""
+    env = grid_env(2, side)
+    w, log_z = optimal_policy_mlp_2d(side)
+    states = [(i, j) for i in range(side) for j in range(side)]
+    n_samples = 3
+    ts = np.repeat(np.array(states, dtype=np.int8).T, n_samples, axis=1)
+    back = oracle64.backward_rollout(env, 8, 0, ts)
+    rep = oracle64.replay(env, w, 0, 0, back["actions"], back["length"], tie_tol=1e30)
+    est = oracle64.log_prob_estimate(rep["log_pf"], back["log_pb"], len(states), n_samples)
+    want = np.array([math.log(grid_reward(x, side)) - log_z for x in states])
+    np.testing.assert_allclose(est, want, rtol=0, atol=1e-10)
+
+
+def test_estimate_converges_to_the_exact_terminal_probability(oracle64):
+    """Arbitrary policy: the mean of P_F / P_B over backward samples is P_theta(x), computed exactly by pushing
+    visit probabilities through the grid."""
+    side = 5
+    env = grid_env(2, side)
+    w = random_mlp(2 * side, 64, 64, 3, seed=9, scale=2.0, dtype=np.float64)
+    exact = grid_terminal_distribution(lambda x: oracle64.policy(env, w, list(x))[1:], 2, side)
+    states = [(4, 4), (2, 3), (0, 0), (1, 4), (3, 1)]
+    n_samples = 4000
+    ts = np.repeat(np.array(states, dtype=np.int8).T, n_samples, axis=1)
+    back = oracle64.backward_rollout(env, 10, 0, ts)
+    rep = oracle64.replay(env, w, 0, 0, back["actions"], back["length"], tie_tol=1e30)
+    est = np.exp(oracle64.log_prob_estimate(rep["log_pf"], back["log_pb"], len(states), n_samples))
+    ratio = np.exp(rep["log_pf"] - back["log_pb"]).reshape(len(states), n_samples)
+    for i, x in enumerate(states):
+        sigma = ratio[i].std() / math.sqrt(n_samples)
+        assert abs(est[i] - exact[x]) <= 4.5 * sigma + 1e-15, (x, est[i], exact[x], sigma)
+    assert abs(est[2] - exact[(0, 0)]) < 1e-12          # one path only: no variance
+    # averaging several small-N estimates is unbiased too (N = 2 here, as the paper's N = 10 would be)
+    small = np.exp(oracle64.log_prob_estimate(rep["log_pf"], back["log_pb"], len(states) * n_samples // 2, 2))
+    np.testing.assert_allclose(small.reshape(len(states), -1).mean(1), est, rtol=1e-10)
+
+
+def test_estimate_is_stable_for_tiny_probabilities(oracle64, oracle32):
+    lpf = np.array([-1000.0, -1001.0, -1002.0, -50.0, -50.0, -50.0])
+    lpb = np.array([-3.0, -3.0, -3.0, 0.0, 0.0, 0.0])
+    want = np.array([-997.0 + math.log((1 + math.exp(-1) + math.exp(-2)) / 3), -50.0])
+    np.testing.assert_allclose(oracle64.log_prob_estimate(lpf, lpb, 2, 3), want, rtol=1e-13)
+    np.testing.assert_allclose(oracle32.log_prob_estimate(lpf, lpb, 2, 3), want, rtol=1e-6)
