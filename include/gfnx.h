@@ -149,6 +149,28 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                       float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/* Backward rollout ("Library Details": a rollout started at terminal states with the backward step in place of
+ * the step) under the fixed uniform backward policy.  INPUT: traj->terminal_state [state_dim][batch] (grid
+ * coordinates, clamped into 0..H-1; token bytes; spins, anything not positive counting as -1).  OUTPUT, for a
+ * trajectory tau_b ~ P_B(. | x_b) drawn parent by parent until s_0: traj->actions in FORWARD order with 0xFF
+ * padding, traj->length, traj->log_pb = log P_B(tau_b | x_b).  traj->log_pf and traj->log_reward are not touched
+ * (they may be NULL); gfnx_replay on the same `traj` then evaluates log P_F along these trajectories.  Parents are
+ * taken in increasing index order (grid: coordinates > 0; Ising: assigned sites), the j-th with
+ * j = floor(w * n / 2^32), w = word 0 of Philox4x32-10(counter = (b, k, 0xFFFFFFFF, iteration lo32), key = seed),
+ * k = index of the backward move; moves with a single parent (the grid's un-stop, every move of the left-to-right
+ * bit sequences) draw nothing.  No workspace and no network are needed; env->modes_dev is not read.
+ * Errors: NULL pointers, bad descriptor, traj->max_steps below the environment's, unsupported sizes. */
+int gfnx_backward_rollout(const gfnx_env_desc* env, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
+                          void* hip_stream);
+
+/* Monte-Carlo estimate of the probability of sampling a terminal state (Appendix "Bit sequences", estimator
+ * equation): with the n_samples trajectories of state x stored at indices x * n_samples + i,
+ *   log_p_dev[x] = log( (1 / n_samples) sum_i exp(log_pf_dev[.] - log_pb_dev[.]) ),  x = 0 .. n_states-1.
+ * Device pointers; log_pf from gfnx_replay, log_pb from gfnx_backward_rollout (or gfnx_replay: same value).
+ * Errors: NULL pointers, n_states < 1, n_samples < 1, n_states * n_samples beyond 2^31-1. */
+int gfnx_log_prob_estimate(const float* log_pf_dev, const float* log_pb_dev, int32_t n_states, int32_t n_samples,
+                           float* log_p_dev, void* hip_stream);
+
 /* Optimiser settings of a training iteration: Adam (Kingma & Ba 2015, Algorithm 1) as the paper trains with
  * (Appendix "Hypergrid", hyperparameter table: lr 1e-3, lr_log_z 1e-1, beta1 0.9, beta2 0.999, eps 1e-8, no
  * weight decay).  Host struct. */

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "gfnx_device.h"
+#include "backward_kernel.h"
 #include "grad_kernels.h"
 #include "grad_kernels2.h"
 #include "grad_kernels3.h"
@@ -572,6 +573,48 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                       float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes,
                       void* hip_stream) {
   return tb_loss_grad_impl(env, mlp, traj, log_z, nullptr, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
+}
+
+int gfnx_backward_rollout(const gfnx_env_desc* env, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
+                          void* hip_stream) {
+  if (!env || !traj) return GFNX_E_NULL;
+  int sd, od, na, ms;
+  const int rc = env_dims(env, &sd, &od, &na, &ms);
+  if (rc) return rc;
+  if (!traj->actions || !traj->length || !traj->terminal_state || !traj->log_pb) return GFNX_E_NULL;
+  if (traj->batch <= 0 || traj->max_steps < ms) return GFNX_E_BAD_SHAPE;
+  if (na > 256 || ms > 256 || sd > kMaxStateDim) return GFNX_E_UNSUPPORTED;  // the limits of the forward kernels
+  if (env->kind == GFNX_ENV_GRID && sd > 16) return GFNX_E_UNSUPPORTED;
+  if ((size_t)traj->max_steps * (size_t)traj->batch > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  BackwardParams p = {};
+  Shapes s = {};
+  s.state_dim = sd; s.obs_dim = od; s.n_actions = na; s.max_steps = ms;
+  p.env = env_params(env, s);
+  p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
+  p.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFull);
+  p.B = traj->batch; p.T = traj->max_steps;
+  p.term = traj->terminal_state; p.actions = traj->actions; p.length = traj->length; p.lpb = traj->log_pb;
+  {
+    GFNX_TIMED("backward", st);
+    hipLaunchKernelGGL(backward_rollout_kernel, dim3((p.B + kBackwardThreads - 1) / kBackwardThreads),
+                       dim3(kBackwardThreads), 0, st, p);
+  }
+  return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+}
+
+int gfnx_log_prob_estimate(const float* log_pf_dev, const float* log_pb_dev, int32_t n_states, int32_t n_samples,
+                           float* log_p_dev, void* hip_stream) {
+  if (!log_pf_dev || !log_pb_dev || !log_p_dev) return GFNX_E_NULL;
+  if (n_states < 1 || n_samples < 1) return GFNX_E_BAD_SHAPE;
+  if ((uint64_t)n_states * (uint64_t)n_samples > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)hip_stream;
+  {
+    GFNX_TIMED("estimate", st);
+    hipLaunchKernelGGL(log_prob_estimate_kernel, dim3((n_states + 3) / 4), dim3(256), 0, st, log_pf_dev, log_pb_dev,
+                       n_states, n_samples, log_p_dev);
+  }
+  return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
 }
 
 int gfnx_adam_step(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* grads, const float* dlogz_dev,

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
-           "gfnx_adam_step", "gfnx_train_step", "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
+           "gfnx_adam_step", "gfnx_train_step", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
+           "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
 
 class EnvDesc(C.Structure):
@@ -81,6 +82,10 @@ def load_library() -> C.CDLL:
         lib.gfnx_tb_loss_grad.restype = C.c_int
         lib.gfnx_tb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
                                           C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_backward_rollout.restype = C.c_int
+        lib.gfnx_backward_rollout.argtypes = [C.POINTER(EnvDesc), C.c_uint64, C.c_uint64, C.POINTER(Traj), C.c_void_p]
+        lib.gfnx_log_prob_estimate.restype = C.c_int
+        lib.gfnx_log_prob_estimate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         lib.gfnx_adam_step.restype = C.c_int
         lib.gfnx_adam_step.argtypes = [C.POINTER(Mlp), C.c_void_p, C.POINTER(MlpGrad), C.c_void_p,
                                        C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p]
@@ -208,6 +213,37 @@ class Session:
         _check(self.lib.gfnx_tb_loss_grad(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), float(log_z),
                                           _ptr(self.loss), _ptr(self.dlogz), C.byref(self.cgrads),
                                           _ptr(self.workspace), self.workspace_bytes, self._stream()))
+
+    # ---- backward rollouts and the estimate of P_theta(x) --------------------------
+    def backward_rollout(self, seed: int, iteration: int, terminal_state=None) -> None:
+        """Trajectories tau_b ~ P_B(. | x_b) for the terminal states in self.terminal_state (or the given host
+        array [state_dim, batch]); fills actions (forward order), length, log_pb."""
+        if terminal_state is not None:
+            self.terminal_state.copy_(self.torch.as_tensor(terminal_state, dtype=self.torch.int8))
+        _check(self.lib.gfnx_backward_rollout(C.byref(self.desc), seed, iteration, C.byref(self.traj), self._stream()))
+
+    def replay_device(self) -> None:
+        """Teacher-forced pass along the action bytes and lengths already on the device."""
+        _check(self.lib.gfnx_replay(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), _ptr(self.workspace),
+                                    self.workspace_bytes, self._stream()))
+
+    def log_prob_estimate(self, n_states: int, n_samples: int):
+        """Device tensor [n_states] of log P_theta(x) estimated from this batch's log_pf and log_pb (the samples of
+        state x at trajectory indices x * n_samples + i; n_states * n_samples = batch)."""
+        assert n_states * n_samples == self.batch
+        out = self.torch.empty(n_states, dtype=self.torch.float32, device=self.device)
+        _check(self.lib.gfnx_log_prob_estimate(_ptr(self.log_pf), _ptr(self.log_pb), n_states, n_samples, _ptr(out),
+                                               self._stream()))
+        return out
+
+    def estimate_log_prob(self, states, n_samples: int, seed: int, iteration: int):
+        """log P_theta(x) for the host array states [n_states, state_dim]: backward rollouts, forward evaluation, mean."""
+        torch = self.torch
+        st = torch.as_tensor(states, dtype=torch.int8)
+        n_states = int(st.shape[0])
+        self.backward_rollout(seed, iteration, st.t().repeat_interleave(n_samples, dim=1).contiguous())
+        self.replay_device()
+        return self.log_prob_estimate(n_states, n_samples)
 
     # ---- training iterations -------------------------------------------------------
     def init_optimizer(self, log_z: float = 0.0, lr: float = 1e-3, lr_log_z: float = 1e-1, beta1: float = 0.9,

@@ -136,3 +136,22 @@ def test_optimiser_argument_validation(lib):
     assert train(None, 1, need) == -1
     assert train(p, 0, need) == -3
     assert train(p, 1, need - 1) == -4
+
+
+def test_backward_rollout_and_estimate_argument_validation(lib):
+    p = 0x1000
+    d = gfnx.env_desc(grid_env(2, 8))
+    t = _traj(16, 15)
+    call = lambda dd, tt: lib.gfnx_backward_rollout(dd, 0, 0, tt, None)
+    assert call(None, C.byref(t)) == -1
+    assert call(C.byref(d), None) == -1
+    assert call(C.byref(d), C.byref(gfnx.Traj(16, 15, p, p, 0, p, p, p))) == -1       # no terminal states
+    assert call(C.byref(d), C.byref(gfnx.Traj(16, 15, p, p, p, p, 0, p))) == -1       # no log_pb
+    assert call(C.byref(d), C.byref(_traj(16, 14))) == -3
+    assert call(C.byref(d), C.byref(_traj(0, 15))) == -3
+    assert call(C.byref(gfnx.env_desc(grid_env(2, 1))), C.byref(t)) == -2
+    assert call(C.byref(gfnx.env_desc(grid_env(16, 100))), C.byref(_traj(16, 1600))) == -5   # walks longer than 256
+    est = lambda f, b, ns, n, o: lib.gfnx_log_prob_estimate(f, b, ns, n, o, None)
+    assert est(None, p, 4, 4, p) == -1 and est(p, None, 4, 4, p) == -1 and est(p, p, 4, 4, None) == -1
+    assert est(p, p, 0, 4, p) == -3 and est(p, p, 4, 0, p) == -3
+    assert est(p, p, 1 << 20, 1 << 20, p) == -5
