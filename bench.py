@@ -3,7 +3,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-extra] [--no-cpu-baseline]
 
-(--no-extra skips the short runs of the other workloads and of whole training iterations.)
+(--no-extra skips the short runs of the other workloads, of whole training iterations and of the estimate of
+P_theta(x).)
 
 A step is one pass of the whole hot path over one batch of synthetic input: gfnx_rollout (fresh
 Philox iteration counter each step) followed by gfnx_tb_loss_grad, inputs and outputs resident in
@@ -34,7 +35,8 @@ DESCRIPTIONS = {
     "c5": "10-D grid H=20, MLP 200-256-256-11 (seeded Xavier), batch 16384, max 191 steps",
     "c5_long": "10-D grid H=20, MLP 200-256-256-11 with stop bias -8 (long walks), batch 16384",
 }
-KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "gfnx_device.h", "gfnx.hip")
+KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "backward_kernel.h",
+                  "gfnx_device.h", "gfnx.hip")
 
 
 def kernel_source_hash():
@@ -179,6 +181,55 @@ def run_training(name, steps, warmup, batch=None):
                             "achieved_GBps": 28.0 * n_par / (adam_ms / launches * 1e-3) / 1e9, "peak_GBps": 8000.0}}
 
 
+def run_estimate(name, steps, n_samples=10):
+    """Monte-Carlo estimate of log P_theta(x) for batch / n_samples seeded random terminal states: backward rollouts,
+    teacher-forced forward evaluation along them, log-mean of P_F / P_B (the paper's evaluation uses 10 samples)."""
+    import numpy as np
+    import torch
+    from paper_2511_16592_amd import gfnx
+    from paper_2511_16592_amd.workloads import workloads
+
+    wl = workloads()[name]
+    n_states = wl.batch // n_samples
+    wl = wl.with_batch(n_states * n_samples)
+    sd = wl.env.dims()[0]
+    rng = np.random.default_rng(wl.seed)
+    if wl.env.kind == 0:
+        states = rng.integers(0, wl.env.grid_side, size=(n_states, sd))
+    elif wl.env.kind == 1:
+        states = rng.integers(0, 1 << wl.env.k_bits, size=(n_states, sd)).astype(np.uint8).view(np.int8)
+    else:
+        states = 2 * rng.integers(0, 2, size=(n_states, sd)) - 1
+    sess = gfnx.Session(wl.env, wl.mlp(), wl.batch)
+    ts = torch.as_tensor(states, dtype=torch.int8).t().repeat_interleave(n_samples, dim=1).contiguous().to(sess.device)
+    timer = gfnx.KernelTimer()
+
+    def one(i):
+        sess.terminal_state.copy_(ts)
+        sess.backward_rollout(wl.seed, i)
+        sess.replay_device()
+        return sess.log_prob_estimate(n_states, n_samples)
+
+    for i in range(3):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(3 + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timer.enable(True)
+    for i in range(5):
+        one(3 + steps + i)
+    torch.cuda.synchronize()
+    bd = {k: v[1] / 5 for k, v in timer.collect().items()}
+    timer.enable(False)
+    transitions = int(sess.length.sum().item())
+    return {"states": n_states, "samples_per_state": n_samples, "ms_per_evaluation": elapsed / steps * 1e3,
+            "states_per_s": n_states * steps / elapsed, "transitions_per_s": transitions * steps / elapsed,
+            "kernels_ms": {k: round(v, 5) for k, v in sorted(bd.items(), key=lambda kv: -kv[1])}}
+
+
 def summary(name, r, steps):
     wl = r["wl"]
     a = wl.env.dims()[2]
@@ -255,6 +306,8 @@ def main():
                             "reports 1463.3 it/s on an Intel Core i7-10700F CPU")
         train["c2_batch16"] = paper
         out["train"] = train
+        # evaluation side of the same kernels: backward rollouts + forward evaluation + estimate of P_theta(x)
+        out["estimate"] = {name: run_estimate(name, 20) for name in ("c2", "c4")}
     print(json.dumps(out))
 
 

@@ -29,7 +29,10 @@ constexpr int kBackwardThreads = 64;
 
 __global__ __launch_bounds__(kBackwardThreads) void backward_rollout_kernel(BackwardParams p) {
   __shared__ int8_t coord[16][kBackwardThreads];  // grid coordinates of this lane's state
+  __shared__ float neg_log[129];                  // -log n for the number of parents n
   const int lane = threadIdx.x;
+  for (int n = 1 + lane; n <= 128; n += kBackwardThreads) neg_log[n] = -logf((float)n);
+  __syncthreads();
   const int b = blockIdx.x * kBackwardThreads + lane;
   if (b >= p.B) return;  // no barrier below: every lane works on its own column
   const EnvParams& e = p.env;
@@ -78,11 +81,15 @@ __global__ __launch_bounds__(kBackwardThreads) void backward_rollout_kernel(Back
     int q = 0;
     if (j >= c0) { j -= c0; q = 1; if (j >= c1) { j -= c1; q = 2; if (j >= c2) { j -= c2; q = 3; } } }
     uint32_t word = q == 0 ? m0 : q == 1 ? m1 : q == 2 ? m2 : m3;
-    for (int z = 0; z < j; ++z) word &= word - 1;  // drop the j lowest set bits
-    const int bitpos = __ffs(word) - 1;
+    int bitpos = 0;  // position of the j-th set bit of the word: halve the range five times
+    int c = __popc(word & 0xFFFFu); if (j >= c) { j -= c; bitpos += 16; word >>= 16; }
+    c = __popc(word & 0xFFu); if (j >= c) { j -= c; bitpos += 8; word >>= 8; }
+    c = __popc(word & 0xFu); if (j >= c) { j -= c; bitpos += 4; word >>= 4; }
+    c = __popc(word & 0x3u); if (j >= c) { j -= c; bitpos += 2; word >>= 2; }
+    if (j >= (int)(word & 1u)) bitpos += 1;
     const uint32_t bit = 1u << bitpos;
     const int idx = 32 * q + bitpos;
-    lpb += -logf((float)n);
+    lpb += neg_log[n];
     int a;
     bool clear;
     if (e.kind == 0) {
