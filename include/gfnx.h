@@ -30,8 +30,9 @@
  *   sampling  Gumbel-max over the valid actions: argmax_a (logit_a + g_a), lowest index on ties,
  *             g = -log(-log(u)), u = ((w >> 9) + 0.5) * 2^-23, w = word (a % 4) of
  *             Philox4x32-10(counter = (b, t, a / 4, iteration lo32), key = (seed lo32, seed hi32)),
- *             b = global trajectory index, t = step.  Results do not depend on how the batch is
- *             split over workgroups.
+ *             b = global trajectory index, t = step.  The random draws of a trajectory do not depend
+ *             on the batch it is in; its floating-point sums may be rounded in a different order
+ *             (relative differences of 1e-7) when the trajectories running beside it differ.
  *   log P_B   uniform over parents: grid increment -log #{i : child_i > 0}, grid stop 0,
  *             bitseq 0, Ising -log(t+1).
  */

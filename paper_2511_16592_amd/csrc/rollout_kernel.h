@@ -7,7 +7,9 @@
 //   L2  hidden layer 2 on the matrix cores, computed transposed: D[feature][slot] = W2^T * relu(z1); the
 //       eight waves split the output features; weights are MFMA A-operands (resident in registers when the
 //       layer is 256 x 256: 128 registers per lane, or streamed from L2 cache in operand order with the next
-//       step's loads in flight), activations come from LDS in B-operand order;
+//       step's loads in flight), activations come from LDS in B-operand order; on grids, a workgroup left with
+//       at most four running trajectories (the tail of a batch of unequal walks) switches to the 4x4x1 matrix
+//       instruction, which contracts the same resident operands against four slots at a quarter of the cost;
 //   L3  logits the same way: output tiles split over the waves, and the contraction split as well when there
 //       are fewer than eight tiles;
 //   SU  per slot, 16 (grids) or 32 lanes of one wave: action mask, softmax weights, Philox draw and argmin by DPP row
@@ -89,6 +91,12 @@ __host__ __device__ inline int logits_ksplit(int nt3, int q2) {
   ACC = mfma16((AV).z, (BV).z, ACC);       \
   ACC = mfma16((AV).w, (BV).w, ACC)
 
+#define GFNX_MFMA4S(ACC, AV, BV)                                             \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).x, (BV).x, ACC, 0, 0, 0);      \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).y, (BV).y, ACC, 0, 0, 0);      \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).z, (BV).z, ACC, 0, 0, 0);      \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).w, (BV).w, ACC, 0, 0, 0)
+
 constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile held in registers; the rest sit in LDS
 
 // Byte offsets of the kernel's LDS regions (shared by the launch code, which sizes the allocation).
@@ -144,6 +152,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   const int bend = min(B, b0 + p.tpw);
   // roles in the SU phase: LPS lanes (sub-lane si) of one wave per slot sj.  Grids have at most 32 logits, so 16
   // lanes per slot are enough and four waves (one per SIMD, with the vector unit to itself) serve all slots.
+  // Grids with the resident layer 2: steps with at most kTailSlots running trajectories take the four-slot path
+  constexpr bool kTail = STAT && ENV == 0;
+  constexpr int kTailSlots = 4;
   constexpr int LPS = ENV == 0 ? 16 : 32;
   constexpr int kSuWaves = kSlots / (64 / LPS);
   const int sj = (64 / LPS) * (w % kSuWaves) + lane / LPS, si = lane % LPS;
@@ -165,6 +176,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     z1i[H1 + f] = lo;
   }
   for (int i = tid; 4 * i < SBL * kSlots; i += kRolloutThreads) ((uint32_t*)st)[i] = 0u;
+  if constexpr (kTail)  // the four-slot path reads back whole h2 tiles of which it has written four columns
+    for (int i = tid; i < (H2 >> 2) * kPitch; i += kRolloutThreads) h2s[i] = 0.f;
   if (tid < kSlots) {
     alive[tid] = (b0 + tid < bend) ? 1 : 0;
     srow[tid] = b0 + tid;
@@ -225,6 +238,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     // left?), the two slots whose h1 / h2 rows this wave writes out, and the slot this lane serves in L2
     int sa[2], sr[2];
     int my_alive, my_row;
+    uint32_t live_mask = 0;  // bit j: slot j is running (all flags are 0 or 1)
     {
       const int4* av = (const int4*)alive;
       const int4 a0 = av[0], a1 = av[1], a2 = av[2], a3 = av[3];
@@ -234,6 +248,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
                       a3.y | a3.z | a3.w;
       if (!any) break;
+      if constexpr (kTail)
+        live_mask = a0.x | (a0.y << 1) | (a0.z << 2) | (a0.w << 3) | (a1.x << 4) | (a1.y << 5) | (a1.z << 6) |
+                    (a1.w << 7) | (a2.x << 8) | (a2.y << 9) | (a2.z << 10) | (a2.w << 11) | (a3.x << 12) |
+                    (a3.y << 13) | (a3.z << 14) | (a3.w << 15);
     }
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
 #pragma unroll
@@ -258,14 +276,14 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       for (int n = 0; n < NTW; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
       if constexpr (STAT) {
         const f32x4* wl = w2l + (size_t)(w * 2) * (16 - kW2RegQ) * 64 + lane;
-        f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
         // One contraction step; NEXT_READS = LDS reads of the following step (activations, plus the two weight
         // operands once past the register-resident part), which are issued before this step's eight matrix
-        // instructions so that their latency is covered.
-#define GFNX_L2_STEP(NEXT_READS)                                                                     \
+        // instructions so that their latency is covered.  MFMA4 / SLOT: the matrix instruction and the slot whose
+        // activations this lane feeds it.
+#define GFNX_L2_STEP(NEXT_READS, MFMA4, SLOT)                                                        \
         {                                                                                            \
           const f32x4 bv = relu4(bvn);                                                               \
-          if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + j16 * 4];           \
+          if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + (SLOT) * 4];        \
           f32x4 a0, a1;                                                                              \
           if (q < kW2RegQ) {                                                                         \
             a0 = w2r[0][q];                                                                          \
@@ -274,21 +292,68 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             a0 = wl[(q - kW2RegQ) * 64];                                                             \
             a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];                                          \
           }                                                                                          \
-          GFNX_MFMA4(acc[0], a0, bv);                                                                \
-          GFNX_MFMA4(acc[1], a1, bv);                                                                \
+          MFMA4(acc[0], a0, bv);                                                                     \
+          MFMA4(acc[1], a1, bv);                                                                     \
           __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                                \
           __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                         \
           __builtin_amdgcn_sched_group_barrier(0x002, 4, 0); /* relu of the next step's activations */ \
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the read of step 0 above
-        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // and its relu
+        bool tail = false;
+        if constexpr (kTail) tail = __popc(live_mask) <= kTailSlots;  // the same in every wave
+        if (tail) {
+          // Four-slot path.  The 4x4x1 instruction multiplies, in each of 16 blocks of four lanes, a 4-vector of
+          // A (one value per lane of the block) with a 4-vector of B: D[r] of lane l = A(lane 4 (l / 4) + r) * B(l).
+          // Fed with the same resident W2 operands, lane l = 16 g + 4 m + j therefore accumulates, for the slot it
+          // picks for j, units 16 tile + 4 m + r over the contraction indices of lane group g; the four groups
+          // are summed across lanes, the four columns go to LDS and come back in the layout of the 16-slot path.
+          int jj = lane & 3;
+          if (jj >= __popc(live_mask)) jj = 0;
+          uint32_t wd = live_mask;
+          int sl = 0;  // jj-th running slot
+          int c = __popc(wd & 0xFFu); if (jj >= c) { jj -= c; sl += 8; wd >>= 8; }
+          c = __popc(wd & 0xFu); if (jj >= c) { jj -= c; sl += 4; wd >>= 4; }
+          c = __popc(wd & 0x3u); if (jj >= c) { jj -= c; sl += 2; wd >>= 2; }
+          if (jj >= (int)(wd & 1u)) sl += 1;
+          f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + sl * 4];
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
 #pragma unroll
-        for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1)
+          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4S, sl)
 #pragma unroll
-        for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3)
-        {
-          constexpr int q = 15;
-          GFNX_L2_STEP(0)
+          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4S, sl)
+          {
+            constexpr int q = 15;
+            GFNX_L2_STEP(0, GFNX_MFMA4S, sl)
+          }
+#pragma unroll
+          for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              float v = acc[n][r];
+              v += __shfl_xor(v, 16);
+              v += __shfl_xor(v, 32);
+              acc[n][r] = v;
+            }
+          const int m4 = (lane >> 2) & 3;
+          if (g == 0) {
+#pragma unroll
+            for (int n = 0; n < 2; ++n) *(f32x4*)&h2s[(4 * (2 * w + n) + m4) * kPitch + sl * 4] = acc[n];
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's own columns, written above
+#pragma unroll
+          for (int n = 0; n < 2; ++n) acc[n] = *(const f32x4*)&h2s[(4 * (2 * w + n) + g) * kPitch + j16 * 4];
+        } else {
+          f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the read of step 0 above
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // and its relu
+#pragma unroll
+          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4, j16)
+#pragma unroll
+          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4, j16)
+          {
+            constexpr int q = 15;
+            GFNX_L2_STEP(0, GFNX_MFMA4, j16)
+          }
         }
 #undef GFNX_L2_STEP
       } else if (w * NTW < NT2) {

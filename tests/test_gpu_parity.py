@@ -201,6 +201,38 @@ def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
     assert (a.trajectories()["actions"] != ta["actions"]).any()
 
 
+@pytest.mark.parametrize("batch", [3, 4, 5, 21, 260])
+def test_wide_grid_few_running_trajectories(gfnx, oracle32, oracle64, batch):
+    """256-wide grid policies switch to the four-slot matrix path whenever a workgroup has at most four running
+    trajectories: batches of 3 and 4 never leave it, 5 enters it as soon as one walk ends, 21 and 260 mix full and
+    nearly empty workgroups; long walks (stop bias -3) keep the tail long."""
+    env = grid_env(3, 9)
+    w = random_mlp(27, 256, 256, 4, seed=37, scale=1.5)
+    w["b3"][3] -= 3.0
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, batch, seed=14, iteration=2, log_z=0.1,
+                          name=f"grid3x9_256_b{batch}")
+    assert traj["length"].max() >= 10
+
+
+def test_wide_grid_batch_split_changes_rounding_only(gfnx):
+    """The path a step takes depends on how many trajectories of the workgroup still run, so the same trajectory in
+    a different batch sees sums rounded in a different order: same actions (no near-tie here), floats to 1e-6."""
+    env = grid_env(3, 9)
+    w = random_mlp(27, 256, 256, 4, seed=37, scale=1.5)
+    a = gfnx.Session(env, w, 64)
+    a.rollout(3, 5)
+    ta = a.trajectories()
+    small = gfnx.Session(env, w, 3)
+    small.rollout(3, 5)
+    ts = small.trajectories()
+    assert (ts["actions"] == ta["actions"][:, :3]).all() and (ts["length"] == ta["length"][:3]).all()
+    np.testing.assert_allclose(ts["log_pf"], ta["log_pf"][:3], rtol=1e-6, atol=1e-6)
+    a.rollout(3, 5)
+    tb = a.trajectories()
+    for k in ta:
+        assert (ta[k] == tb[k]).all()   # the same launch twice is bit-identical
+
+
 def test_longest_supported_walks(gfnx, oracle32, oracle64):
     """15-D grid of side 18: 256 steps at most (the supported maximum), 270 one-hot inputs (more than the 256 the
     one-hot contraction takes: the per-trajectory segment-sum path of the layer-1 gradient), stop bias -8."""
