@@ -129,7 +129,7 @@ class Oracle:
 
     # ---- rollout / replay ----------------------------------------------------
     def rollout(self, env, w, seed: int, iteration: int, batch: int, b_offset: int = 0,
-                max_steps: Optional[int] = None, nthreads: int = 1) -> Dict[str, np.ndarray]:
+                max_steps: Optional[int] = None, nthreads: int = 1, epsilon: float = 0.0) -> Dict[str, np.ndarray]:
         e, _k1 = self._env(env)
         m, _k2 = self._mlp(w)
         sd, _, _, ms = env.dims()
@@ -142,12 +142,12 @@ class Oracle:
                                      C.c_int32(b_offset), C.c_int32(batch), C.c_int32(T),
                                      _ptr(out["actions"]), _ptr(out["length"]), _ptr(out["terminal_state"]),
                                      _ptr(out["log_pf"]), _ptr(out["log_pb"]), _ptr(out["log_reward"]),
-                                     _ptr(out["min_margin"]), C.c_int(nthreads))
+                                     _ptr(out["min_margin"]), self.creal(epsilon), C.c_int(nthreads))
         assert rc == 0, rc
         return out
 
     def replay(self, env, w, seed: int, iteration: int, actions: np.ndarray, length: np.ndarray,
-               b_offset: int = 0, tie_tol: float = 1e-5, nthreads: int = 1) -> Dict[str, np.ndarray]:
+               b_offset: int = 0, tie_tol: float = 1e-5, nthreads: int = 1, epsilon: float = 0.0) -> Dict[str, np.ndarray]:
         e, _k1 = self._env(env)
         m, _k2 = self._mlp(w)
         sd = env.dims()[0]
@@ -162,7 +162,8 @@ class Oracle:
                                     C.c_int32(b_offset), C.c_int32(batch), C.c_int32(T), _ptr(actions), _ptr(length),
                                     _ptr(out["terminal_state"]), _ptr(out["log_pf"]), _ptr(out["log_pb"]),
                                     _ptr(out["log_reward"]), self.creal(tie_tol), _ptr(out["near_ties"]),
-                                    _ptr(out["violations"]), _ptr(out["min_margin"]), C.c_int(nthreads))
+                                    _ptr(out["violations"]), _ptr(out["min_margin"]), self.creal(epsilon),
+                                    C.c_int(nthreads))
         assert rc == 0, rc
         return out
 

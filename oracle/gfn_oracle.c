@@ -50,6 +50,9 @@
  *            serves action a.  u = ((w>>9)+0.5)*2^-23,  g = -log(-log(u)).
  *   log P_B  grid increment: -log #{i : child_i > 0}; grid stop: 0; bitseq: 0;
  *            Ising: -log(#assigned sites of the child) = -log(t+1).
+ *   explore  epsilon-uniform exploration: one more Philox call per step, counter (b, t,
+ *            0xFFFFFFFE, iteration lo); word 0 -> u, explore iff u < epsilon (binary32);
+ *            word 1 -> the j-th valid action in increasing order, j = floor(w * n / 2^32).
  *   backward the parents of a state in increasing index order (grid: coordinates > 0;
  *            Ising: assigned sites; bitseq: the last position only); the j-th is taken,
  *            j = floor(w * n / 2^32), w = word 0 of Philox(counter = (b, k, 0xFFFFFFFF,
@@ -356,6 +359,7 @@ typedef struct {
   int32_t* length;          /* [batch] */
   int8_t* terminal_state;   /* [state_dim][batch] */
   real *log_pf, *log_pb, *log_reward;
+  real epsilon;             /* probability of replacing the policy's draw by a uniform one over the valid actions */
   /* replay only */
   int replay;
   real tie_tol;
@@ -395,12 +399,33 @@ static void* rollout_worker(void* arg) {
         if (best < 0 || pert[a] > pert[best]) { second = best; best = a; }
         else if (second < 0 || pert[a] > pert[second]) second = a;
       }
-      if (second >= 0 && pert[best] - pert[second] < minmargin) minmargin = pert[best] - pert[second];
-      int act = best;
+      /* epsilon-uniform exploration (Appendix "Bit sequences", experimental setting): with probability epsilon
+       * the action is uniform over the valid ones instead of drawn from P_F.  Both draws come from one more
+       * Philox call per step, counter (b, t, 0xFFFFFFFE, iteration): word 0 decides (u < epsilon, compared in
+       * binary32), word 1 picks the j-th valid action in increasing order, j = floor(w * n / 2^32). */
+      int forced = -1;
+      if (J->epsilon > 0) {
+        uint32_t ctr[4] = {b, (uint32_t)t, 0xFFFFFFFEu, (uint32_t)(J->iteration & 0xFFFFFFFFu)};
+        uint32_t key[2] = {(uint32_t)(J->seed & 0xFFFFFFFFu), (uint32_t)(J->seed >> 32)};
+        uint32_t out[4];
+        oracle_philox4x32_10(ctr, key, out);
+        const float u = ((float)(out[0] >> 9) + 0.5f) * (1.0f / 8388608.0f);
+        if (u < (float)J->epsilon) {
+          int nvalid = 0;
+          for (int a = 0; a < na; ++a) nvalid += valid[a] != 0;
+          int j = (int)(((uint64_t)out[1] * (uint64_t)nvalid) >> 32);
+          for (int a = 0; a < na; ++a)
+            if (valid[a] && j-- == 0) { forced = a; break; }
+        }
+      }
+      if (forced < 0 && second >= 0 && pert[best] - pert[second] < minmargin) minmargin = pert[best] - pert[second];
+      int act = forced >= 0 ? forced : best;
       if (J->replay) {
         act = J->actions[(size_t)t * J->batch + col];
         if (act >= na || !valid[act]) { viol++; break; }
-        if (act != best) {
+        if (forced >= 0) {
+          if (act != forced) viol++; /* an integer decision: no tolerance */
+        } else if (act != best) {
           if (pert[best] - pert[act] < J->tie_tol) ties++; else viol++;
         }
       } else {
@@ -456,30 +481,32 @@ static int run_rollout(rollout_job* base, int nthreads) {
 /* Samples `batch` trajectories with global indices b_offset .. b_offset+batch-1. */
 int oracle_rollout(const oracle_env* env, const oracle_mlp* mlp, uint64_t seed, uint64_t iteration, int32_t b_offset,
                    int32_t batch, int32_t max_steps, uint8_t* actions, int32_t* length, int8_t* terminal_state,
-                   real* log_pf, real* log_pb, real* log_reward, real* min_margin, int nthreads) {
+                   real* log_pf, real* log_pb, real* log_reward, real* min_margin, real epsilon, int nthreads) {
   rollout_job J;
   memset(&J, 0, sizeof(J));
   J.env = env; J.mlp = mlp; J.seed = seed; J.iteration = iteration; J.b_offset = b_offset;
   J.batch = batch; J.max_steps = max_steps; J.actions = actions; J.length = length;
   J.terminal_state = terminal_state; J.log_pf = log_pf; J.log_pb = log_pb; J.log_reward = log_reward;
-  J.min_margin = min_margin;
+  J.min_margin = min_margin; J.epsilon = epsilon;
   return run_rollout(&J, nthreads);
 }
 
 /* Follows the given actions (length[] steps per column) and reports, per column, the
  * trajectory scalars along THOSE actions, the number of steps where the given action is
  * not this implementation's argmax but within tie_tol of it (near ties), and the number
- * of steps where it is invalid or further away (violations). */
+ * of steps where it is invalid or further away (violations).  With epsilon > 0 the steps
+ * where the exploration draw decides must carry exactly the action it picks. */
 int oracle_replay(const oracle_env* env, const oracle_mlp* mlp, uint64_t seed, uint64_t iteration, int32_t b_offset,
                   int32_t batch, int32_t max_steps, const uint8_t* actions, const int32_t* length,
                   int8_t* terminal_state, real* log_pf, real* log_pb, real* log_reward, real tie_tol,
-                  int32_t* near_ties, int32_t* violations, real* min_margin, int nthreads) {
+                  int32_t* near_ties, int32_t* violations, real* min_margin, real epsilon, int nthreads) {
   rollout_job J;
   memset(&J, 0, sizeof(J));
   J.env = env; J.mlp = mlp; J.seed = seed; J.iteration = iteration; J.b_offset = b_offset;
   J.batch = batch; J.max_steps = max_steps; J.actions = (uint8_t*)actions; J.length = (int32_t*)length;
   J.terminal_state = terminal_state; J.log_pf = log_pf; J.log_pb = log_pb; J.log_reward = log_reward;
   J.replay = 1; J.tie_tol = tie_tol; J.near_ties = near_ties; J.violations = violations; J.min_margin = min_margin;
+  J.epsilon = epsilon;
   return run_rollout(&J, nthreads);
 }
 
