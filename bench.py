@@ -96,7 +96,7 @@ def cpu_baseline(wl, w, seconds_target=12.0):
                       % (len(batches), cores, mix, done_tr, used)}
 
 
-def run_workload(name, steps, warmup, events=True):
+def run_workload(name, steps, warmup, events=True, epsilon=None):
     import torch
     from paper_2511_16592_amd import gfnx
     from paper_2511_16592_amd.workloads import workloads
@@ -110,12 +110,12 @@ def run_workload(name, steps, warmup, events=True):
     # the per-kernel breakdown when there is more than one warm-up step
     cold = 1 if warmup >= 2 else 0
     for i in range(cold):
-        sess.rollout(wl.seed, i)
+        sess.rollout(wl.seed, i, epsilon)
         sess.tb_loss_grad(wl.log_z)
     torch.cuda.synchronize()
     timer.enable(events)
     for i in range(cold, warmup):
-        sess.rollout(wl.seed, i)
+        sess.rollout(wl.seed, i, epsilon)
         sess.tb_loss_grad(wl.log_z)
     torch.cuda.synchronize()
     breakdown = timer.collect() if events else {}
@@ -125,7 +125,7 @@ def run_workload(name, steps, warmup, events=True):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        sess.rollout(wl.seed, warmup + i)
+        sess.rollout(wl.seed, warmup + i, epsilon)
         sess.tb_loss_grad(wl.log_z)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -135,7 +135,7 @@ def run_workload(name, steps, warmup, events=True):
     # valid transitions of the timed steps (the rollout is a pure function of seed and iteration)
     transitions = 0
     for i in range(steps):
-        sess.rollout(wl.seed, warmup + i)
+        sess.rollout(wl.seed, warmup + i, epsilon)
         transitions += int(sess.length.sum().item())
     torch.cuda.synchronize()
     return dict(wl=wl, weights=w, elapsed=elapsed, transitions=transitions, dominant=dominant, dom=dom,
@@ -299,6 +299,9 @@ def main():
             steps = 5 if name == "c5_long" else 20
             extra[name] = summary(name, run_workload(name, steps, 3, events=False), steps)
         out["extra"] = extra
+        # the same step with epsilon-uniform exploration at the paper's rate
+        out["explore_eps_1e-3"] = {name: summary(name, run_workload(name, 20, 3, events=False, epsilon=1e-3), 20)
+                                   for name in ("c2", "c4", "c3")}
         # the next stage of the same path: whole training iterations (optimiser step included)
         train = {args.workload: run_training(args.workload, 50, 5), "c3": run_training("c3", 20, 3)}
         paper = run_training("c2", 300, 20, batch=16)

@@ -129,6 +129,16 @@ size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32
 int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration,
                  gfnx_traj* traj, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* gfnx_rollout with epsilon-uniform exploration (Appendix "Bit sequences", experimental setting; the paper uses
+ * epsilon = 1e-3): at every step, with probability epsilon the action is uniform over the valid actions instead of
+ * drawn from P_F.  One more Philox call per step, counter (b, t, 0xFFFFFFFE, iteration lo32): word 0 -> u as above,
+ * explore iff u < epsilon (binary32 comparison); word 1 picks the j-th valid action in increasing order,
+ * j = floor(w * n / 2^32).  log_pf remains the log-probability under P_F of the actions taken (what the
+ * Trajectory-Balance objective needs for off-policy trajectories).  epsilon = 0 is gfnx_rollout bit for bit.
+ * Errors: as gfnx_rollout; epsilon outside [0, 1] or NaN is GFNX_E_BAD_SHAPE. */
+int gfnx_rollout_explore(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration,
+                         float epsilon, gfnx_traj* traj, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Teacher-forced rollout: follows the given traj->actions / traj->length (inputs) instead of
  * sampling, and fills log_pf, log_pb, log_reward, terminal_state and the workspace exactly as
  * gfnx_rollout would (off-policy trajectories, the trajectory distributions of eq.

@@ -202,11 +202,11 @@ size_t rollout_lds_bytes(const Shapes& s) {
   return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), s.H1 == 256 && s.H2 == 256).total;
 }
 
-template <int ENV, bool REPLAY, int NCH>
+template <int ENV, bool REPLAY, int NCH, bool EXPLORE>
 int launch_rollout_ntw(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st) {
 #define GFNX_LAUNCH(N, STATIONARY)                                                                          \
   {                                                                                                         \
-    auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH>;                                               \
+    auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH, EXPLORE>;                                      \
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
       return GFNX_E_HIP;                                                                                    \
     hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, p);                                         \
@@ -226,22 +226,25 @@ int launch_rollout_ntw(const RolloutParams& p, dim3 grid, size_t lds, hipStream_
   return GFNX_OK;
 }
 
-template <bool REPLAY>
+template <bool REPLAY, bool EXPLORE>
 int launch_rollout(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st) {
   const bool wide = p.A16 > 128;  // more than one chunk of four logits per sampling lane
   switch (p.env.kind) {
-    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY, 1>(p, grid, lds, st);
+    case GFNX_ENV_GRID: return launch_rollout_ntw<0, REPLAY, 1, EXPLORE>(p, grid, lds, st);
     case GFNX_ENV_BITSEQ:
-      return wide ? launch_rollout_ntw<1, REPLAY, 2>(p, grid, lds, st) : launch_rollout_ntw<1, REPLAY, 1>(p, grid, lds, st);
+      return wide ? launch_rollout_ntw<1, REPLAY, 2, EXPLORE>(p, grid, lds, st)
+                  : launch_rollout_ntw<1, REPLAY, 1, EXPLORE>(p, grid, lds, st);
     default:
-      return wide ? launch_rollout_ntw<2, REPLAY, 2>(p, grid, lds, st) : launch_rollout_ntw<2, REPLAY, 1>(p, grid, lds, st);
+      return wide ? launch_rollout_ntw<2, REPLAY, 2, EXPLORE>(p, grid, lds, st)
+                  : launch_rollout_ntw<2, REPLAY, 1, EXPLORE>(p, grid, lds, st);
   }
 }
 
 int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
-                 void* ws, size_t ws_bytes, void* hip_stream, bool replay) {
+                 void* ws, size_t ws_bytes, void* hip_stream, bool replay, float epsilon = 0.f) {
   Shapes s;
   if (!traj) return GFNX_E_NULL;
+  if (!(epsilon >= 0.f && epsilon <= 1.f)) return GFNX_E_BAD_SHAPE;
   int rc = check_shapes(env, mlp, traj->batch, &s);
   if (rc) return rc;
   rc = check_traj(traj, s);
@@ -267,6 +270,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.sbuf = s.onehot ? at<uint8_t>(ws, L.sb) : nullptr;
   p.SB = s.sbytes;
   p.SBL = rollout_state_pitch(s);
+  p.eps = epsilon;
 
   // Each workgroup owns a contiguous range of trajectories and runs them 16 at a time; ranges longer than 16
   // (large batches) let a slot start the next trajectory as soon as its current one ends.
@@ -289,7 +293,9 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   }
   {
     GFNX_TIMED("rollout", st);
-    rc = replay ? launch_rollout<true>(p, grid, lds, st) : launch_rollout<false>(p, grid, lds, st);
+    rc = replay ? launch_rollout<true, false>(p, grid, lds, st)
+                : (epsilon > 0.f ? launch_rollout<false, true>(p, grid, lds, st)
+                                 : launch_rollout<false, false>(p, grid, lds, st));
   }
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
@@ -327,6 +333,11 @@ size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32
 int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   return rollout_impl(env, mlp, seed, iteration, traj, workspace, workspace_bytes, hip_stream, false);
+}
+
+int gfnx_rollout_explore(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration,
+                         float epsilon, gfnx_traj* traj, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rollout_impl(env, mlp, seed, iteration, traj, workspace, workspace_bytes, hip_stream, false, epsilon);
 }
 
 int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, void* workspace,

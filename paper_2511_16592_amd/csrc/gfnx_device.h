@@ -43,6 +43,7 @@ struct RolloutParams {
   uint8_t* sbuf;  // state bytes of every transition (SB per row), or null when the gradient pass needs none
   int SB;
   int SBL;        // bytes per slot of the state kept in LDS: a multiple of 16, >= max(state_dim, SB)
+  float eps;      // epsilon-uniform exploration: probability of a uniform draw over the valid actions (0 = off)
 };
 
 // D(16x16) += A(16x4) * B(4x16).  Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];

@@ -124,7 +124,8 @@ __host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16
 //        kW2RegQ/16 of them in registers and the rest in LDS; with a single logit tile (grids) its eighth of
 //        W3 as well.
 // NCH  = chunks of four logits a lane may own in SU: 1 up to 128 actions, else 2.
-template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH>
+// EXPLORE = epsilon-uniform exploration compiled in (free-running rollouts with epsilon > 0 only).
+template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH, bool EXPLORE>
 __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const EnvParams& e = p.env;
@@ -625,6 +626,44 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
         best = grp_min_u64<LPS>(best);
         act = (int)(uint32_t)best;
+        if constexpr (EXPLORE) {
+          // epsilon-uniform exploration (Appendix "Bit sequences", experimental setting): one more Philox call
+          // per step, counter (b, t, 0xFFFFFFFE, iteration); word 0 decides, the same in every lane of the slot;
+          // word 1 picks the j-th valid action in increasing order, j = floor(w n / 2^32).  Chunks are owned in
+          // the order (pass, lane), so the rank of a lane's first valid action is a prefix sum over the lanes.
+          uint32_t we[4];
+          philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, 0xFFFFFFFEu, p.iter_lo, p.seed_lo, p.seed_hi, we);
+          if (uniform_from_bits(we[0]) < p.eps) {
+            int pre[NCH], cnt[NCH], total = 0;
+#pragma unroll
+            for (int n = 0; n < NCH; ++n) {
+              cnt[n] = __popc(vm[n]);
+              int incl = cnt[n];
+#pragma unroll
+              for (int d = 1; d < LPS; d <<= 1) {
+                const int o = __shfl_up(incl, d, LPS);
+                if (si >= d) incl += o;
+              }
+              pre[n] = total + incl - cnt[n];
+              total += __shfl(incl, LPS - 1, LPS);
+            }
+            const int j = (int)__umulhi(we[1], (uint32_t)total);
+            int cand = 0x7fffffff;
+#pragma unroll
+            for (int n = 0; n < NCH; ++n) {
+              int jl = j - pre[n];
+              if (jl >= 0 && jl < cnt[n]) {
+                uint32_t bb = vm[n];
+                int k = 0;
+                const int c2 = __popc(bb & 3u);
+                if (jl >= c2) { jl -= c2; k = 2; bb >>= 2; }
+                if (jl >= (int)(bb & 1u)) k += 1;
+                cand = 4 * (si + LPS * n) + k;
+              }
+            }
+            act = grp_min<LPS>(cand);
+          }
+        }
       } else {
         act = p.actions[(size_t)t * B + sb];
       }

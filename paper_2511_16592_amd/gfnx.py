@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
-EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_replay", "gfnx_tb_loss_grad",
+EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
+           "gfnx_tb_loss_grad",
            "gfnx_adam_step", "gfnx_train_step", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
            "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
@@ -76,6 +77,9 @@ def load_library() -> C.CDLL:
         lib.gfnx_rollout.restype = C.c_int
         lib.gfnx_rollout.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_uint64, C.c_uint64, C.POINTER(Traj),
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_rollout_explore.restype = C.c_int
+        lib.gfnx_rollout_explore.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_uint64, C.c_uint64, C.c_float,
+                                             C.POINTER(Traj), C.c_void_p, C.c_size_t, C.c_void_p]
         lib.gfnx_replay.restype = C.c_int
         lib.gfnx_replay.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_void_p, C.c_size_t,
                                     C.c_void_p]
@@ -197,9 +201,15 @@ class Session:
         for k, v in weights.items():
             self.w[k].copy_(self.torch.as_tensor(v, dtype=self.torch.float32))
 
-    def rollout(self, seed: int, iteration: int) -> None:
-        _check(self.lib.gfnx_rollout(C.byref(self.desc), C.byref(self.mlp), seed, iteration, C.byref(self.traj),
-                                     _ptr(self.workspace), self.workspace_bytes, self._stream()))
+    def rollout(self, seed: int, iteration: int, epsilon: float = None) -> None:
+        """Samples the batch; with `epsilon`, through gfnx_rollout_explore (epsilon-uniform exploration)."""
+        if epsilon is None:
+            _check(self.lib.gfnx_rollout(C.byref(self.desc), C.byref(self.mlp), seed, iteration, C.byref(self.traj),
+                                         _ptr(self.workspace), self.workspace_bytes, self._stream()))
+        else:
+            _check(self.lib.gfnx_rollout_explore(C.byref(self.desc), C.byref(self.mlp), seed, iteration,
+                                                 float(epsilon), C.byref(self.traj), _ptr(self.workspace),
+                                                 self.workspace_bytes, self._stream()))
 
     def replay(self, actions, length) -> None:
         """Teacher-forced pass along the given host arrays actions [T, B] (uint8) and length [B]."""

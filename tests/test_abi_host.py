@@ -93,6 +93,9 @@ def test_workspace_size_and_argument_validation(lib):
     assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(m), C.byref(t), 0.0, 0x1000, 0x1000, C.byref(g), ws, need, None) == -1
     assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(m), C.byref(t), 0.0, None, 0x1000, C.byref(g), ws, need, None) == -1
     assert lib.gfnx_replay(C.byref(d), C.byref(m), C.byref(t), ws, need - 1, None) == -4
+    explore = lambda eps, n: lib.gfnx_rollout_explore(C.byref(d), C.byref(m), 0, 0, eps, C.byref(t), ws, n, None)
+    assert explore(-0.01, need) == -3 and explore(1.01, need) == -3 and explore(float("nan"), need) == -3
+    assert explore(0.5, need - 1) == -4
 
 
 def test_workspace_sizes_of_the_benchmark_configurations(lib):
