@@ -190,6 +190,23 @@ class Oracle:
                  slack=dict(zip(("dW1", "db1", "dW2", "db2", "dW3", "db3"), slack.astype(np.float64))))
         return g
 
+    def subtb_loss_grad(self, env, w, actions: np.ndarray, length: np.ndarray, lam: float) -> Dict[str, np.ndarray]:
+        """SubTB(lambda) loss (lambda = 0: DB) and gradient for a network whose last output is log F(s)."""
+        e, _k1 = self._env(env)
+        m, arrs = self._mlp(w)
+        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        length = np.ascontiguousarray(length, dtype=np.int32)
+        T, batch = actions.shape
+        g = {("d" + k): np.zeros_like(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
+        gs = _Grad(*[_ptr(g[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
+        loss = self.creal()
+        u = np.zeros((T + 1, batch), dtype=self.real)
+        rc = self.lib.oracle_subtb_loss_grad(C.byref(e), C.byref(m), C.c_int32(batch), C.c_int32(T), _ptr(actions),
+                                             _ptr(length), self.creal(lam), C.byref(loss), C.byref(gs), _ptr(u))
+        assert rc == 0, rc
+        g.update(loss=float(loss.value), u=u)
+        return g
+
     # ---- backward rollouts ------------------------------------------------------
     def backward_rollout(self, env, seed: int, iteration: int, terminal_state: np.ndarray, b_offset: int = 0,
                          max_steps: Optional[int] = None) -> Dict[str, np.ndarray]:

@@ -25,6 +25,9 @@
  *     state / action description);
  *   - environments emit log-reward only on the terminal transition: "Library
  *     Details", implementation notes;
+ *   - Detailed Balance and Subtrajectory Balance objectives with a learned state flow: Background section,
+ *     eq. (DB_loss) and eq. (SubTB_loss) (weights lambda^(k-j) normalised to sum to one, flow of a terminal
+ *     state replaced by its reward);
  *   - backward rollouts and the Monte-Carlo estimate of the probability P_theta(x) of
  *     sampling a terminal state x: "Library Details" (a backward rollout is a rollout
  *     started at terminal states with the backward step in place of the step; backward
@@ -699,6 +702,126 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
     for (int q = 0; q < 6; ++q) { slack_out[q] = 0; for (int k = 0; k < nthreads; ++k) slack_out[q] += jobs[k].slack[q]; }
   if (n_kink_out) { *n_kink_out = 0; for (int k = 0; k < nthreads; ++k) *n_kink_out += jobs[k].n_kink; }
   free(delta); free(priv); free(th); free(jobs);
+  return status;
+}
+
+/* ------------------------------------------------------- SubTB / DB loss + gradient */
+
+/* Adds to G the gradient of a scalar whose derivative w.r.t. the network outputs of this step is g3[0..n_out). */
+static void backprop_outputs(const oracle_mlp* m, const act_buf* A, const int* rows, int nr, const real* g3,
+                             oracle_grad* G, real* g2, real* g1) {
+  const int no = m->n_actions;
+  for (int k = 0; k < m->h2; ++k) {
+    real acc = 0;
+    for (int a = 0; a < no; ++a) {
+      G->dW3[(size_t)k * no + a] += A->h2[k] * g3[a];
+      acc += m->W3[(size_t)k * no + a] * g3[a];
+    }
+    g2[k] = A->z2[k] > 0 ? acc : 0;
+  }
+  for (int a = 0; a < no; ++a) G->db3[a] += g3[a];
+  for (int i = 0; i < m->h1; ++i) {
+    real acc = 0;
+    for (int k = 0; k < m->h2; ++k) {
+      G->dW2[(size_t)i * m->h2 + k] += A->h1[i] * g2[k];
+      acc += m->W2[(size_t)i * m->h2 + k] * g2[k];
+    }
+    g1[i] = A->z1[i] > 0 ? acc : 0;
+  }
+  for (int k = 0; k < m->h2; ++k) G->db2[k] += g2[k];
+  for (int r = 0; r < nr; ++r)
+    for (int i = 0; i < m->h1; ++i) G->dW1[(size_t)rows[r] * m->h1 + i] += g1[i];
+  for (int i = 0; i < m->h1; ++i) G->db1[i] += g1[i];
+}
+
+/* Subtrajectory Balance (Background, eq. SubTB_loss) along given trajectories, for a network with one output more
+ * than the environment has actions: outputs 0..A-1 are the policy logits, output A is log F_theta(s).
+ * With phi_t = log F(s_t) for t < n and phi_n = log R(s_n), and c_t = sum_{i<=t} (log P_F(s_i|s_i-1) -
+ * log P_B(s_i-1|s_i)), the residual of the pair j < k is (phi_j - c_j) - (phi_k - c_k) = u_j - u_k, so
+ *   L(tau) = sum_{j<k} w_jk (u_j - u_k)^2,  w_jk = lambda^(k-j-1) / sum_{j<k} lambda^(k-j-1)
+ * (the paper's lambda^(k-j) normalised to sum to one; written this way lambda = 0 is defined and keeps exactly the
+ * single-transition pairs: the Detailed Balance objective, eq. DB_loss, averaged over the transitions).
+ * loss = mean over the batch; grads (overwritten) hold its gradient; P_B is fixed.
+ * u_out, optional: [max_steps + 1][batch], u_t of every trajectory (0 beyond its length). */
+int oracle_subtb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
+                           const uint8_t* actions, const int32_t* length, real lambda, real* loss,
+                           oracle_grad* grads, real* u_out) {
+  int32_t sd, od, na, ms;
+  if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
+  if (na + 1 != mlp->n_actions || od != mlp->in_dim) return -2;
+  if (sd > MAX_STATE || na + 1 > MAX_ACT || max_steps > MAX_STATE) return -3;
+  const int no = na + 1;
+  memset(grads->dW1, 0, sizeof(real) * n_w1(mlp)); memset(grads->db1, 0, sizeof(real) * mlp->h1);
+  memset(grads->dW2, 0, sizeof(real) * n_w2(mlp)); memset(grads->db2, 0, sizeof(real) * mlp->h2);
+  memset(grads->dW3, 0, sizeof(real) * n_w3(mlp)); memset(grads->db3, 0, sizeof(real) * no);
+  if (u_out) memset(u_out, 0, sizeof(real) * (size_t)(max_steps + 1) * batch);
+  act_buf A = act_alloc(mlp);
+  real* g3 = (real*)malloc(sizeof(real) * no);
+  real* g2 = (real*)malloc(sizeof(real) * mlp->h2);
+  real* g1 = (real*)malloc(sizeof(real) * mlp->h1);
+  real u[MAX_STATE + 2], g[MAX_STATE + 2];
+  int s[MAX_STATE], rows[MAX_STATE], valid[MAX_ACT];
+  real total = 0;
+  int status = 0;
+  for (int col = 0; col < batch && !status; ++col) {
+    const int n = length[col];
+    if (n < 1 || n > max_steps) { status = -4; break; }
+    /* pass 1: u_t along the trajectory */
+    env_reset(env, s, sd);
+    real c = 0;
+    int terminal = 0;
+    for (int t = 0; t < n; ++t) {
+      const int act = actions[(size_t)t * batch + col];
+      const int nr = env_obs_rows(env, s, sd, rows);
+      mlp_forward(mlp, rows, nr, &A);
+      env_valid(env, s, t, na, valid);
+      if (act >= na || !valid[act]) { status = -5; break; }
+      masked_log_softmax(A.logit, valid, na, A.logp);
+      u[t] = A.logit[na] - c;
+      terminal = env_step(env, s, sd, t, act);
+      c += A.logp[act] - env_log_pb(env, s, sd, t, act);
+      if (terminal && t + 1 != n) { status = -6; break; }
+    }
+    if (status) break;
+    if (!terminal) { status = -6; break; }
+    u[n] = env_log_reward(env, s, sd) - c;
+    /* pair sum and its derivative with respect to every u_t */
+    real wsum = 0;
+    for (int j = 0; j < n; ++j) { real w = 1; for (int k = j + 1; k <= n; ++k) { wsum += w; w *= lambda; } }
+    real L = 0;
+    for (int t = 0; t <= n; ++t) g[t] = 0;
+    for (int j = 0; j < n; ++j) {
+      real w = 1;
+      for (int k = j + 1; k <= n; ++k) {
+        const real d = u[j] - u[k];
+        L += (w / wsum) * d * d;
+        g[j] += (real)2 * (w / wsum) * d;
+        g[k] -= (real)2 * (w / wsum) * d;
+        w *= lambda;
+      }
+    }
+    total += L;
+    if (u_out) for (int t = 0; t <= n; ++t) u_out[(size_t)t * batch + col] = u[t];
+    /* pass 2: u_t = phi_t - c_t; log P_F of transition t -> t+1 enters c_k for every k > t with sign -1 */
+    env_reset(env, s, sd);
+    for (int t = 0; t < n; ++t) {
+      const int act = actions[(size_t)t * batch + col];
+      const int nr = env_obs_rows(env, s, sd, rows);
+      mlp_forward(mlp, rows, nr, &A);
+      env_valid(env, s, t, na, valid);
+      masked_log_softmax(A.logit, valid, na, A.logp);
+      real kappa = 0;
+      for (int k = t + 1; k <= n; ++k) kappa -= g[k];
+      for (int a = 0; a < na; ++a)
+        g3[a] = valid[a] ? (kappa / (real)batch) * ((real)(a == act) - rexp(A.logp[a])) : 0;
+      g3[na] = g[t] / (real)batch;
+      backprop_outputs(mlp, &A, rows, nr, g3, grads, g2, g1);
+      env_step(env, s, sd, t, act);
+    }
+  }
+  *loss = total / (real)batch;
+  free(g3); free(g2); free(g1);
+  act_free(&A);
   return status;
 }
 
