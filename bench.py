@@ -181,6 +181,38 @@ def run_training(name, steps, warmup, batch=None):
                             "achieved_GBps": 28.0 * n_par / (adam_ms / launches * 1e-3) / 1e9, "peak_GBps": 8000.0}}
 
 
+def run_subtb(name, steps, lam):
+    """The same step with the Subtrajectory Balance objective (lambda = 0: Detailed Balance): the network gets one
+    more output, the state flow; rollout + gfnx_subtb_loss_grad."""
+    import numpy as np
+    import torch
+    from paper_2511_16592_amd import gfnx
+    from paper_2511_16592_amd.workloads import workloads, xavier_mlp
+
+    wl = workloads()[name]
+    _, obs_dim, n_actions, _ = wl.env.dims()
+    w = xavier_mlp(obs_dim, wl.h1, wl.h2, n_actions + 1, wl.weight_seed)
+    if wl.stop_bias:
+        w["b3"][n_actions - 1] += np.float32(wl.stop_bias)
+    sess = gfnx.Session(wl.env, w, wl.batch)
+    for i in range(3):
+        sess.rollout(wl.seed, i)
+        sess.subtb_loss_grad(lam)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        sess.rollout(wl.seed, 3 + i)
+        sess.subtb_loss_grad(lam)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    transitions = 0
+    for i in range(steps):
+        sess.rollout(wl.seed, 3 + i)
+        transitions += int(sess.length.sum().item())
+    return {"lambda": lam, "ms_per_step": elapsed / steps * 1e3, "transitions_per_s": transitions / elapsed,
+            "transitions_per_step": transitions / steps}
+
+
 def run_estimate(name, steps, n_samples=10):
     """Monte-Carlo estimate of log P_theta(x) for batch / n_samples seeded random terminal states: backward rollouts,
     teacher-forced forward evaluation along them, log-mean of P_F / P_B (the paper's evaluation uses 10 samples)."""
@@ -309,6 +341,9 @@ def main():
                             "reports 1463.3 it/s on an Intel Core i7-10700F CPU")
         train["c2_batch16"] = paper
         out["train"] = train
+        # the other two objectives of the paper's hypergrid benchmark, on the same kernels
+        out["subtb"] = {"c2_db": run_subtb("c2", 20, 0.0), "c2_subtb0.9": run_subtb("c2", 20, 0.9),
+                        "c2_long_subtb0.9": run_subtb("c2_long", 10, 0.9), "c5_long_subtb0.9": run_subtb("c5_long", 5, 0.9)}
         # evaluation side of the same kernels: backward rollouts + forward evaluation + estimate of P_theta(x)
         out["estimate"] = {name: run_estimate(name, 20) for name in ("c2", "c4")}
     print(json.dumps(out))

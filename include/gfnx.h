@@ -88,6 +88,11 @@ typedef struct {
   const float *W1, *b1, *W2, *b2, *W3, *b3;
 } gfnx_mlp;
 
+/* Networks with a flow output (hypergrid only): n_actions may be the environment's number of actions PLUS ONE.
+ * The last output is then log F_theta(s), the state flow of the Detailed / Subtrajectory Balance objectives
+ * (Background, eq. DB_loss, eq. SubTB_loss); sampling ignores it, gfnx_rollout / gfnx_rollout_explore / gfnx_replay
+ * record it per transition in the workspace, and gfnx_subtb_loss_grad (not gfnx_tb_loss_grad) consumes it. */
+
 /* Gradient buffers, same shapes as the weights, device pointers; OVERWRITTEN (not accumulated). */
 typedef struct {
   float *dW1, *db1, *dW2, *db2, *dW3, *db3;
@@ -159,6 +164,20 @@ int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, 
 int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
                       float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
+
+/* Subtrajectory Balance loss (Background, eq. SubTB_loss) and its gradient, for a network with a flow output
+ * (see gfnx_mlp) on the hypergrid, along the trajectories of the immediately preceding gfnx_rollout /
+ * gfnx_rollout_explore / gfnx_replay on the same stream and workspace (consumed, as by gfnx_tb_loss_grad):
+ *   phi_t = log F(s_t) for t < n, phi_n = log R(s_n);  S_jk = sum_{t=j+1..k} (log P_F(s_t|s_t-1) - log P_B(s_t-1|s_t));
+ *   L(tau) = sum_{0<=j<k<=n} w_jk (phi_j - phi_k + S_jk)^2,  w_jk = lambda^(k-j-1) / sum_{j<k} lambda^(k-j-1)
+ * (the paper's lambda^(k-j) normalised to sum to one; in this form lambda = 0 is defined and keeps the single
+ * transitions only: the Detailed Balance objective, eq. DB_loss, averaged over the transitions of a trajectory);
+ * *loss_dev = mean over the batch, grads = its gradient (W3 / b3 gradients include the flow column), P_B fixed.
+ * lambda in [0, 1].  Errors: as gfnx_tb_loss_grad; a network without a flow output, or another environment than
+ * the hypergrid, is GFNX_E_BAD_SHAPE. */
+int gfnx_subtb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float lambda,
+                         float* loss_dev, gfnx_mlp_grad* grads, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
 
 /* Backward rollout ("Library Details": a rollout started at terminal states with the backward step in place of
  * the step) under the fixed uniform backward policy.  INPUT: traj->terminal_state [state_dim][batch] (grid

@@ -8,6 +8,7 @@
 #include "grad_kernels.h"
 #include "grad_kernels2.h"
 #include "grad_kernels3.h"
+#include "subtb_kernels.h"
 #include "rollout_kernel.h"
 
 #include <cmath>
@@ -62,13 +63,16 @@ struct Shapes {
   int qt3, qtot3, s3, s2, qtot2;  // output tiling / split factors of dW3 and dW2
   int s1, qtot1;                  // ... of the one-hot dW1 contraction
   int mw1, mw2; // 64-bit sign-mask words per transition row for h1 / h2
+  int flow;     // the network has one output more than the environment has actions: log F(s) (grids only)
   int onehot;   // layer-1 weight gradient as a one-hot contraction: 0 no, 1 grid, 2 Ising
   int sbytes;   // state bytes recorded per transition row for it
   int p1;       // rows of that contraction's output tile
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs, total;
+  size_t hdr, w2p, w3p, w2t, w3t, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
+  size_t total;
 };
 
 int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
@@ -107,11 +111,13 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   if (env->kind == GFNX_ENV_BITSEQ && !env->modes_dev) return GFNX_E_NULL;
   if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2 || !mlp->W3 || !mlp->b3) return GFNX_E_NULL;
   if (batch <= 0) return GFNX_E_BAD_SHAPE;
-  if (mlp->in_dim != s->obs_dim || mlp->n_actions != s->n_actions) return GFNX_E_BAD_SHAPE;
+  if (mlp->in_dim != s->obs_dim) return GFNX_E_BAD_SHAPE;
+  s->flow = (env->kind == GFNX_ENV_GRID && mlp->n_actions == s->n_actions + 1) ? 1 : 0;
+  if (!s->flow && mlp->n_actions != s->n_actions) return GFNX_E_BAD_SHAPE;
   if (mlp->h1 <= 0 || mlp->h2 <= 0) return GFNX_E_BAD_SHAPE;
   if (mlp->h1 % 64 || mlp->h2 % 64 || mlp->h1 > 512 || mlp->h2 > 512) return GFNX_E_UNSUPPORTED;
   if (s->n_actions > 256 || s->max_steps > 256 || s->state_dim > kMaxStateDim) return GFNX_E_UNSUPPORTED;
-  s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = s->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
+  s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = mlp->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
   s->rows = (size_t)s->max_steps * (size_t)batch;
   if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
   s->mw1 = 4 * ((s->H1 + 255) / 256);
@@ -155,6 +161,9 @@ Layout make_layout(const Shapes& s) {
   L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
   L.dbp3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.qtot3);
   L.cs = o; o += align256(s.onehot ? 0 : sizeof(float) * (size_t)s.max_steps * s.H1);  // per-step column sums of G1
+  L.phi = o; o += align256(s.flow ? sizeof(float) * s.rows : 0);
+  L.dl = o; o += align256(s.flow ? sizeof(float) * s.rows : 0);
+  L.lossb = o; o += align256(s.flow ? sizeof(float) * (size_t)(s.B + 2) : 0);
   L.total = o;
   return L;
 }
@@ -271,6 +280,8 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.SB = s.sbytes;
   p.SBL = rollout_state_pitch(s);
   p.eps = epsilon;
+  p.phibuf = s.flow ? at<float>(ws, L.phi) : nullptr;
+  p.dlbuf = s.flow ? at<float>(ws, L.dl) : nullptr;
 
   // Each workgroup owns a contiguous range of trajectories and runs them 16 at a time; ranges longer than 16
   // (large batches) let a slot start the next trajectory as soon as its current one ends.
@@ -350,13 +361,16 @@ int gfnx_replay(const gfnx_env_desc* env, const gfnx_mlp* mlp, gfnx_traj* traj, 
 namespace {
 
 // log Z by value, or read from device memory when log_z_dev is not NULL
+// With subtb_lambda >= 0: the Subtrajectory Balance objective of a network with a flow output instead of TB.
 int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float log_z,
                       const float* log_z_dev, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws,
-                      size_t ws_bytes, void* hip_stream) {
+                      size_t ws_bytes, void* hip_stream, float subtb_lambda = -1.f) {
   Shapes s;
-  if (!traj || !grads || !loss_dev || !dlogz_dev) return GFNX_E_NULL;
+  const bool subtb = subtb_lambda >= 0.f;
+  if (!traj || !grads || !loss_dev || (!subtb && !dlogz_dev)) return GFNX_E_NULL;
   int rc = check_shapes(env, mlp, traj->batch, &s);
   if (rc) return rc;
+  if (subtb != (s.flow != 0)) return GFNX_E_BAD_SHAPE;  // TB takes a plain policy network, SubTB one with a flow output
   rc = check_traj(traj, s);
   if (rc) return rc;
   if (!grads->dW1 || !grads->db1 || !grads->dW2 || !grads->db2 || !grads->dW3 || !grads->db3) return GFNX_E_NULL;
@@ -374,10 +388,25 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   const int T = s.max_steps, B = s.B;
   if ((size_t)traj->max_steps * B > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
 
-  {
+  if (!subtb) {
     GFNX_TIMED("rows", st);
     hipLaunchKernelGGL(rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb, traj->log_reward,
                        log_z, log_z_dev, B, T, loss_dev, dlogz_dev, hdr, rows, crow);
+  } else {
+    // the same list of live rows (the TB scalars it also computes go to two scratch floats), then the per-transition
+    // coefficients of the pair sum, which are folded into the logit-gradient rows so that every kernel below runs
+    // unchanged with unit row coefficients
+    float* lossb = at<float>(ws, L.lossb);
+    float* phi = at<float>(ws, L.phi);
+    float* dl = at<float>(ws, L.dl);
+    GFNX_TIMED("rows", st);
+    hipLaunchKernelGGL(rows_kernel, dim3(T), dim3(1024), 0, st, traj->length, traj->log_pf, traj->log_pb, traj->log_reward,
+                       0.f, (const float*)nullptr, B, T, lossb + B, lossb + B + 1, hdr, rows, crow);
+    hipLaunchKernelGGL(subtb_coef_kernel, dim3((B + 3) / 4), dim3(256), 0, st, (const int*)traj->length,
+                       (const float*)traj->log_reward, phi, dl, B, T, subtb_lambda, lossb);
+    hipLaunchKernelGGL(subtb_apply_kernel, dim3(512), dim3(256), 0, st, (const int*)rows, (const int*)hdr,
+                       (const float*)dl, (const float*)phi, s.n_actions, s.A16, ebuf, crow, (const float*)lossb, B,
+                       loss_dev);
   }
   Dw1Params dp = {};
   dp.env = env_params(env, s);
@@ -584,6 +613,12 @@ int gfnx_tb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                       float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes,
                       void* hip_stream) {
   return tb_loss_grad_impl(env, mlp, traj, log_z, nullptr, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
+}
+
+int gfnx_subtb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_traj* traj, float lambda,
+                         float* loss_dev, gfnx_mlp_grad* grads, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!(lambda >= 0.f && lambda <= 1.f)) return GFNX_E_BAD_SHAPE;
+  return tb_loss_grad_impl(env, mlp, traj, 0.f, nullptr, loss_dev, nullptr, grads, ws, ws_bytes, hip_stream, lambda);
 }
 
 int gfnx_backward_rollout(const gfnx_env_desc* env, uint64_t seed, uint64_t iteration, gfnx_traj* traj,

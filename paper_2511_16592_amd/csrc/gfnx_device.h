@@ -44,6 +44,8 @@ struct RolloutParams {
   int SB;
   int SBL;        // bytes per slot of the state kept in LDS: a multiple of 16, >= max(state_dim, SB)
   float eps;      // epsilon-uniform exploration: probability of a uniform draw over the valid actions (0 = off)
+  // networks with a flow output (grids): log F(s_t) and log P_F - log P_B of every transition, row t*B + b; or null
+  float *phibuf, *dlbuf;
 };
 
 // D(16x16) += A(16x4) * B(4x16).  Lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];

@@ -687,6 +687,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
       }
       lpf += (alogit - m) - lse;
+      // network with a flow output: output d + 1 is log F of the state the policy was evaluated at (never a valid
+      // action: the validity bits of a grid stop at d); its owner lane hands it to the slot
+      float phi_here = 0.f;
+      if (ENV == 0 && p.phibuf) {
+        const int fa = e.d + 1, fk = fa & 3;
+        const float mine = fk == 0 ? lg[0].x : (fk == 1 ? lg[0].y : (fk == 2 ? lg[0].z : lg[0].w));
+        phi_here = __shfl(mine, fa >> 2, LPS);
+      }
+      const float lpb_before = lpb;
 
       // the one-hot row that leaves / enters the input with this action (known to all lanes of the slot); the
       // two rows of W1 are requested now so that their latency overlaps the bookkeeping below
@@ -792,6 +801,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       }
       if (REPLAY) term = term || (t + 1 >= len_given);
       if (!REPLAY && si == 0) p.actions[(size_t)t * B + sb] = (uint8_t)act;
+      if (ENV == 0 && p.phibuf && si == 0) {
+        p.phibuf[(size_t)t * B + sb] = phi_here;
+        p.dlbuf[(size_t)t * B + sb] = ((alogit - m) - lse) - (lpb - lpb_before);
+      }
       if (term) {
         if (si == 0) {
           if (!REPLAY) p.length[sb] = t + 1;

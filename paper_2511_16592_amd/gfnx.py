@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
-           "gfnx_tb_loss_grad",
+           "gfnx_tb_loss_grad", "gfnx_subtb_loss_grad",
            "gfnx_adam_step", "gfnx_train_step", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
            "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
@@ -86,6 +86,9 @@ def load_library() -> C.CDLL:
         lib.gfnx_tb_loss_grad.restype = C.c_int
         lib.gfnx_tb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
                                           C.c_void_p, C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.gfnx_subtb_loss_grad.restype = C.c_int
+        lib.gfnx_subtb_loss_grad.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.POINTER(Traj), C.c_float, C.c_void_p,
+                                             C.POINTER(MlpGrad), C.c_void_p, C.c_size_t, C.c_void_p]
         lib.gfnx_backward_rollout.restype = C.c_int
         lib.gfnx_backward_rollout.argtypes = [C.POINTER(EnvDesc), C.c_uint64, C.c_uint64, C.POINTER(Traj), C.c_void_p]
         lib.gfnx_log_prob_estimate.restype = C.c_int
@@ -289,6 +292,12 @@ class Session:
         """Host copies (numpy) of the six weight tensors."""
         self.torch.cuda.synchronize(self.device)
         return {k: v.cpu().numpy() for k, v in self.w.items()}
+
+    def subtb_loss_grad(self, lam: float) -> None:
+        """SubTB(lambda) (lambda = 0: DB) loss and gradient; the network must have the flow output."""
+        _check(self.lib.gfnx_subtb_loss_grad(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), float(lam),
+                                             _ptr(self.loss), C.byref(self.cgrads), _ptr(self.workspace),
+                                             self.workspace_bytes, self._stream()))
 
     def trajectories(self) -> Dict:
         """Host copies (numpy) of the trajectory arrays."""

@@ -68,7 +68,7 @@ def test_workspace_size_and_argument_validation(lib):
     need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 16)
     assert need > 0 and need % 256 == 0
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 32) > need
-    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 64, 64, 4)), 16) == 0   # n_actions != env's
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 64, 64, 5)), 16) == 0   # neither env's n_actions nor +1
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(15, 64, 64, 3)), 16) == 0   # in_dim != obs_dim
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 48, 64, 3)), 16) == 0   # h1 not a multiple of 64
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 0) == 0
@@ -158,3 +158,23 @@ def test_backward_rollout_and_estimate_argument_validation(lib):
     assert est(None, p, 4, 4, p) == -1 and est(p, None, 4, 4, p) == -1 and est(p, p, 4, 4, None) == -1
     assert est(p, p, 0, 4, p) == -3 and est(p, p, 4, 0, p) == -3
     assert est(p, p, 1 << 20, 1 << 20, p) == -5
+
+
+def test_flow_network_shapes_are_validated_on_the_host(lib):
+    """A network with one output more than the environment has actions is a flow network: grids only, and only the
+    matching objective accepts it."""
+    p = 0x1000
+    d = gfnx.env_desc(grid_env(2, 8))
+    flow, plain = _mlp(16, 64, 64, 4), _mlp(16, 64, 64, 3)
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(flow), 16) > lib.gfnx_workspace_bytes(C.byref(d), C.byref(plain), 16)
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16, 64, 64, 5)), 16) == 0
+    ising = gfnx.env_desc(ising_env(3))
+    assert lib.gfnx_workspace_bytes(C.byref(ising), C.byref(_mlp(27, 64, 64, 19)), 16) == 0   # no flow output there
+    t = _traj(16, 15)
+    g = gfnx.MlpGrad(p, p, p, p, p, p)
+    need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(flow), 16)
+    sub = lambda mm, lam, n: lib.gfnx_subtb_loss_grad(C.byref(d), C.byref(mm), C.byref(t), lam, p, C.byref(g), 0x10000, n, None)
+    assert sub(plain, 0.9, need) == -3
+    assert sub(flow, -0.1, need) == -3 and sub(flow, 1.1, need) == -3 and sub(flow, float("nan"), need) == -3
+    assert sub(flow, 0.9, need - 1) == -4
+    assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(flow), C.byref(t), 0.0, p, p, C.byref(g), 0x10000, need, None) == -3
