@@ -181,6 +181,38 @@ def run_training(name, steps, warmup, batch=None):
                             "achieved_GBps": 28.0 * n_par / (adam_ms / launches * 1e-3) / 1e9, "peak_GBps": 8000.0}}
 
 
+def run_training_subtb(name, steps, warmup, lam, batch):
+    """Training iterations with the DB / SubTB objective: rollout, gfnx_subtb_loss_grad, Adam (three calls, no host
+    round trip; no log Z: the flow output at s_0 plays its part)."""
+    import ctypes as C
+    import torch
+    from paper_2511_16592_amd import gfnx
+    from paper_2511_16592_amd.workloads import workloads, xavier_mlp
+
+    wl = workloads()[name].with_batch(batch)
+    _, obs_dim, n_actions, _ = wl.env.dims()
+    sess = gfnx.Session(wl.env, xavier_mlp(obs_dim, wl.h1, wl.h2, n_actions + 1, wl.weight_seed), wl.batch)
+    sess.init_optimizer(lr=1e-3)
+    state = gfnx.AdamState(sess.adam_state.m, sess.adam_state.v, None)
+
+    def one(i):
+        sess.rollout(wl.seed, i)
+        sess.subtb_loss_grad(lam)
+        gfnx._check(sess.lib.gfnx_adam_step(C.byref(sess.mlp), None, C.byref(sess.cgrads), None, C.byref(state),
+                                            C.byref(sess.adam_cfg), i + 1, sess._stream()))
+
+    for i in range(warmup):
+        one(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        one(warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    return {"batch": wl.batch, "lambda": lam, "iterations": steps, "ms_per_iteration": elapsed / steps * 1e3,
+            "iterations_per_s": steps / elapsed}
+
+
 def run_subtb(name, steps, lam):
     """The same step with the Subtrajectory Balance objective (lambda = 0: Detailed Balance): the network gets one
     more output, the state flow; rollout + gfnx_subtb_loss_grad."""
@@ -340,6 +372,10 @@ def main():
         paper["context"] = ("the paper's own hypergrid setting (4-D side 20, TB, MLP 2x256, batch 16, Adam): it "
                             "reports 1463.3 it/s on an Intel Core i7-10700F CPU")
         train["c2_batch16"] = paper
+        for key, lam, ref in (("c2_batch16_db", 0.0, "1560.0"), ("c2_batch16_subtb0.9", 0.9, "596.0")):
+            train[key] = run_training_subtb("c2", 300, 20, lam, 16)
+            train[key]["context"] = "same setting, %s objective: the paper reports %s it/s on that CPU" % (
+                "DB" if lam == 0.0 else "SubTB(0.9)", ref)
         out["train"] = train
         # the other two objectives of the paper's hypergrid benchmark, on the same kernels
         out["subtb"] = {"c2_db": run_subtb("c2", 20, 0.0), "c2_subtb0.9": run_subtb("c2", 20, 0.9),

@@ -676,6 +676,12 @@ int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_
   if (!log_z_dev || !loss_dev || !dlogz_dev || !grads || !traj) return GFNX_E_NULL;
   int rc = check_adam(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step);
   if (rc) return rc;
+  {
+    Shapes s;
+    rc = check_shapes(env, mlp, traj->batch, &s);
+    if (rc) return rc;
+    if (s.flow) return GFNX_E_BAD_SHAPE;  // the Trajectory-Balance iteration takes a plain policy network
+  }
   rc = rollout_impl(env, mlp, seed, iteration, traj, ws, ws_bytes, hip_stream, false);
   if (rc) return rc;
   rc = tb_loss_grad_impl(env, mlp, traj, 0.f, log_z_dev, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
