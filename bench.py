@@ -314,7 +314,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: this library has no multi-GPU path (run with --gpus 1)")
 
     import torch
     if not torch.cuda.is_available():

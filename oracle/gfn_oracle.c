@@ -71,7 +71,7 @@
  * for the optimiser step a library Adam, the constant-gradient closed form, and a
  * training run on the side-4 grid whose terminal distribution must approach R/Z.
  * Free-running sampled actions have no external reference ("parity unpinned"
- * beyond those statistical pins): the counter layout above is this build's own.
+ * beyond those statistical pins): the counter layout above is this implementation's own.
  */
 #include <math.h>
 #include <pthread.h>
