@@ -84,7 +84,7 @@ def cpu_baseline(wl, w, seconds_target=12.0):
         used += dt
         done_tr += int(out["length"].sum())
         batches.append(batch)
-        if used >= seconds_target or len(batches) >= 64:
+        if used >= seconds_target or len(batches) >= 160:
             break
         if dt < seconds_target / 8 and batch < wl.batch:
             batch = min(wl.batch, batch * 4)
