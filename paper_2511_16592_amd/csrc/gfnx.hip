@@ -274,7 +274,10 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.actions = traj->actions; p.length = traj->length; p.term = traj->terminal_state;
   p.lpf = traj->log_pf; p.lpb = traj->log_pb; p.logr = traj->log_reward;
   p.h1buf = at<float>(ws, L.h1); p.h2buf = at<float>(ws, L.h2); p.ebuf = at<float>(ws, L.e);
-  p.m1buf = at<unsigned long long>(ws, L.m1); p.m2buf = at<unsigned long long>(ws, L.m2);
+  p.m1buf = at<unsigned long long>(ws, L.m1);
+  // sign masks of h2: read by the input-gradient GEMM of layer 3 only; the one-sweep logit backward of narrow action
+  // spaces (same condition as in the gradient pass) takes the ReLU derivative from h2 itself
+  p.m2buf = (s.A16 == 16 && s.H2 == 256) ? nullptr : at<unsigned long long>(ws, L.m2);
   p.MW1 = s.mw1; p.MW2 = s.mw2;
   p.sbuf = s.onehot ? at<uint8_t>(ws, L.sb) : nullptr;
   p.SB = s.sbytes;

@@ -407,14 +407,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         for (int n = 0; n < 2; ++n) hv[n] = relu4(acc[n] + b2r[n]);
         const int alv = my_alive;
         const size_t row = (size_t)my_row;
-        unsigned long long bal[2][4];
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
+        for (int n = 0; n < 2; ++n)
           if (alv) *(f32x4*)&p.h2buf[row * 256 + 16 * (2 * w + n) + 4 * g] = hv[n];
+        if (p.m2buf) {  // (no consumer when the gradient pass takes the ReLU derivative from h2 itself)
+          unsigned long long bal[2][4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) bal[n][r] = __ballot(alv && hv[n][r] > 0.f);
-        }
-        {
+          for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bal[n][r] = __ballot(alv && hv[n][r] > 0.f);
           // lane (j16, g) assembles the byte of mask word r = g: bit 4 n + g' comes from lane 16 g' + j16 of tile n
           uint32_t byte = 0;
 #pragma unroll
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           v = *(const f32x4*)&h2s[fg * kPitch + jj * 4];
           *(f32x4*)&dst[fg * 4] = v;
         }
-        store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
+        if (p.m2buf) store_sign_mask(p.m2buf + (row * p.MW2 + 4 * it), v, lane);
       }
     }
     const bool logits_done = STAT && NT3 == 1;  // computed at the end of L2 above
