@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     // ---- slot flags and row indices of this step, fetched once and together: all 16 flags (any trajectory
     // left?), the two slots whose h1 / h2 rows this wave writes out, and the slot this lane serves in L2
     int sa[2], sr[2];
-    int my_alive, my_row;
+    int my_alive, my_row, su_alive;
     uint32_t live_mask = 0;  // bit j: slot j is running (all flags are 0 or 1)
     {
       const int4* av = (const int4*)alive;
@@ -246,6 +246,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       sa[0] = alive[w]; sa[1] = alive[w + 8];
       sr[0] = srow[w]; sr[1] = srow[w + 8];
       my_alive = alive[j16]; my_row = srow[j16];
+      su_alive = alive[sj];
       const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
                       a3.y | a3.z | a3.w;
       if (!any) break;
@@ -531,12 +532,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     if (!logits_done) lds_barrier();
 
     // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (LPS lanes per slot)
-    if (su_wave && alive[sj]) {
+    if (su_wave && su_alive) {
       const int t = ts;
-      if (p.sbuf) {  // the state the policy is evaluated at, for the one-hot contraction of the gradient pass
-        uint32_t* srowp = (uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB);  // SB is a multiple of 16, <= SBL
-        for (int s4 = si; 4 * s4 < p.SB; s4 += LPS) srowp[s4] = ((const uint32_t*)stj)[s4];
-      }
+      // word si of the slot's state bytes: the validity bits of a grid lane's actions, and this lane's piece of
+      // the state row kept for the gradient pass.  Read here, together with the partial logits below, so that the
+      // phase starts with one round of LDS reads instead of a chain of them.
+      const uint32_t stw = ((const uint32_t*)stj)[min(si, (SBL >> 2) - 1)];
       // ---- logits of this lane's chunks, validity bits, running maximum
       f32x4 lg[NCH];
       uint32_t vm[NCH];
@@ -564,7 +565,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         lg[n] = v;
         // state bytes that decide the validity of actions 4c .. 4c+3, fetched as one word at a clamped index
         uint32_t sw = 0;
-        if (ENV == 0) sw = ((const uint32_t*)stj)[min(c, (SBL >> 2) - 1)];
+        if (ENV == 0) sw = stw;  // one chunk per lane on grids: c = si
         if (ENV == 2) sw = ((const uint16_t*)stj)[min(c, (SBL >> 1) - 1)];
         uint32_t bits = 0;
 #pragma unroll
@@ -586,6 +587,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         vm[n] = bits;
       }
       m = grp_max<LPS>(m);
+      if (p.sbuf && 4 * si < p.SB)  // the state the policy is evaluated at (SB <= 4 LPS bytes, a multiple of 16)
+        ((uint32_t*)(p.sbuf + ((size_t)t * B + sb) * p.SB))[si] = stw;
       // ---- softmax weights exp(l - m) of the valid actions (0 elsewhere) and their sum
       f32x4 wv[NCH];
       float sum = 0.f;
