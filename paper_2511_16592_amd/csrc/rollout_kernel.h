@@ -91,11 +91,12 @@ __host__ __device__ inline int logits_ksplit(int nt3, int q2) {
   ACC = mfma16((AV).z, (BV).z, ACC);       \
   ACC = mfma16((AV).w, (BV).w, ACC)
 
-#define GFNX_MFMA4S(ACC, AV, BV)                                             \
-  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).x, (BV).x, ACC, 0, 0, 0);      \
-  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).y, (BV).y, ACC, 0, 0, 0);      \
-  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).z, (BV).z, ACC, 0, 0, 0);      \
-  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).w, (BV).w, ACC, 0, 0, 0)
+// (two accumulators per tile: an 8-cycle instruction leaves too little distance between dependent ones otherwise)
+#define GFNX_MFMA4S(ACC, AV, BV)                                                           \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).x, (BV).x, ACC, 0, 0, 0);                    \
+  ACC##b = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).y, (BV).y, ACC##b, 0, 0, 0);              \
+  ACC = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).z, (BV).z, ACC, 0, 0, 0);                    \
+  ACC##b = __builtin_amdgcn_mfma_f32_4x4x1f32((AV).w, (BV).w, ACC##b, 0, 0, 0)
 
 constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile held in registers; the rest sit in LDS
 
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         // operands once past the register-resident part), which are issued before this step's eight matrix
         // instructions so that their latency is covered.  MFMA4 / SLOT: the matrix instruction and the slot whose
         // activations this lane feeds it.
-#define GFNX_L2_STEP(NEXT_READS, MFMA4, SLOT)                                                        \
+#define GFNX_L2_STEP(NEXT_READS, MFMA4, SLOT, ACC0, ACC1)                                                      \
         {                                                                                            \
           const f32x4 bv = relu4(bvn);                                                               \
           if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + (SLOT) * 4];        \
@@ -294,8 +295,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             a0 = wl[(q - kW2RegQ) * 64];                                                             \
             a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];                                          \
           }                                                                                          \
-          MFMA4(acc[0], a0, bv);                                                                     \
-          MFMA4(acc[1], a1, bv);                                                                     \
+          MFMA4(ACC0, a0, bv);                                                                       \
+          MFMA4(ACC1, a1, bv);                                                                       \
           __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                                \
           __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                         \
           __builtin_amdgcn_sched_group_barrier(0x002, 4, 0); /* relu of the next step's activations */ \
@@ -317,16 +318,19 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           c = __popc(wd & 0x3u); if (jj >= c) { jj -= c; sl += 2; wd >>= 2; }
           if (jj >= (int)(wd & 1u)) sl += 1;
           f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + sl * 4];
+          f32x4 ta0 = {0.f, 0.f, 0.f, 0.f}, ta0b = ta0, ta1 = ta0, ta1b = ta0;
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
 #pragma unroll
-          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4S, sl)
+          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4S, sl, ta0, ta1)
 #pragma unroll
-          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4S, sl)
+          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4S, sl, ta0, ta1)
           {
             constexpr int q = 15;
-            GFNX_L2_STEP(0, GFNX_MFMA4S, sl)
+            GFNX_L2_STEP(0, GFNX_MFMA4S, sl, ta0, ta1)
           }
+          acc[0] = ta0 + ta0b;
+          acc[1] = ta1 + ta1b;
 #pragma unroll
           for (int n = 0; n < 2; ++n)
 #pragma unroll
@@ -349,12 +353,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the read of step 0 above
           __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // and its relu
 #pragma unroll
-          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4, j16)
+          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4, j16, acc[0], acc[1])
 #pragma unroll
-          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4, j16)
+          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4, j16, acc[0], acc[1])
           {
             constexpr int q = 15;
-            GFNX_L2_STEP(0, GFNX_MFMA4, j16)
+            GFNX_L2_STEP(0, GFNX_MFMA4, j16, acc[0], acc[1])
           }
         }
 #undef GFNX_L2_STEP
