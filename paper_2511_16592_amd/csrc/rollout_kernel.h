@@ -113,7 +113,7 @@ __host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16
   L.h2s = o; o += (H2 >> 2) * kPitch * 4;
   L.lgs = o; o += ks * (A16 >> 2) * kPitch * 4;      // [KS][A16 / 4] partial logits
   L.z1i = o; o += 2 * H1 * 4;                        // z1(s_0): high and low parts, for slots that restart
-  L.flags = o; o += (2 * kSlots + 4) * 4;            // alive[kSlots], srow[kSlots], qnext
+  L.flags = o; o += (kSlots + 4) * 4;                // srow[kSlots], qnext, live
   L.st = o; o += kSlots * SBL;                       // state bytes, SBL per slot (a multiple of 16)
   L.w2l = o; if (stat) o += (16 - kW2RegQ) * 16 * 64 * 16;  // 16 tiles x (16 - kW2RegQ) steps x 64 lanes x 16 bytes
   L.total = o;
@@ -144,9 +144,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   float* h2s = (float*)(smem_raw + L.h2s);
   float* lgs = (float*)(smem_raw + L.lgs);
   float* z1i = (float*)(smem_raw + L.z1i);
-  int* alive = (int*)(smem_raw + L.flags);    // [kSlots] slot is running a trajectory
-  int* srow = alive + kSlots;                 // [kSlots] row t*B + b of the slot's current transition
+  int* srow = (int*)(smem_raw + L.flags);     // [kSlots] row t*B + b of the slot's current transition
   int* qnext = srow + kSlots;                 // next trajectory of this workgroup's range to start
+  uint32_t* live = (uint32_t*)(qnext + 1);    // bit j: slot j is running a trajectory
   int8_t* st = (int8_t*)(smem_raw + L.st);
   const f32x4* w2l = (const f32x4*)(smem_raw + L.w2l);
 
@@ -180,11 +180,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   for (int i = tid; 4 * i < SBL * kSlots; i += kRolloutThreads) ((uint32_t*)st)[i] = 0u;
   if constexpr (kTail)  // the four-slot path reads back whole h2 tiles of which it has written four columns
     for (int i = tid; i < (H2 >> 2) * kPitch; i += kRolloutThreads) h2s[i] = 0.f;
-  if (tid < kSlots) {
-    alive[tid] = (b0 + tid < bend) ? 1 : 0;
-    srow[tid] = b0 + tid;
+  if (tid < kSlots) srow[tid] = b0 + tid;
+  if (tid == 0) {
+    *qnext = b0 + kSlots;
+    const int n0 = bend - b0;  // at least one: the grid has no empty workgroup
+    *live = n0 >= kSlots ? 0xFFFFu : ((1u << n0) - 1u);
   }
-  if (tid == 0) *qnext = b0 + kSlots;
   float lpf = 0.f, lpb = 0.f;
   int len_given = 0;
   if (REPLAY && sb < bend) len_given = p.length[sb];
@@ -236,26 +237,16 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   // list-scheduling bound on the number of steps: (sum of lengths) / kSlots + longest trajectory
   const int max_iters = e.max_steps * ((p.tpw + kSlots - 1) / kSlots + 1);
   for (int iter = 0; iter < max_iters; ++iter) {
-    // ---- slot flags and row indices of this step, fetched once and together: all 16 flags (any trajectory
-    // left?), the two slots whose h1 / h2 rows this wave writes out, and the slot this lane serves in L2
+    // ---- the running slots (one word, the same in every lane: kept on the scalar unit) and the row indices of this
+    // step: of the two slots whose h1 / h2 rows this wave writes out and of the slot this lane serves in L2
     int sa[2], sr[2];
     int my_alive, my_row, su_alive;
-    uint32_t live_mask = 0;  // bit j: slot j is running (all flags are 0 or 1)
-    {
-      const int4* av = (const int4*)alive;
-      const int4 a0 = av[0], a1 = av[1], a2 = av[2], a3 = av[3];
-      sa[0] = alive[w]; sa[1] = alive[w + 8];
-      sr[0] = srow[w]; sr[1] = srow[w + 8];
-      my_alive = alive[j16]; my_row = srow[j16];
-      su_alive = alive[sj];
-      const int any = a0.x | a0.y | a0.z | a0.w | a1.x | a1.y | a1.z | a1.w | a2.x | a2.y | a2.z | a2.w | a3.x |
-                      a3.y | a3.z | a3.w;
-      if (!any) break;
-      if constexpr (kTail)
-        live_mask = a0.x | (a0.y << 1) | (a0.z << 2) | (a0.w << 3) | (a1.x << 4) | (a1.y << 5) | (a1.z << 6) |
-                    (a1.w << 7) | (a2.x << 8) | (a2.y << 9) | (a2.z << 10) | (a2.w << 11) | (a3.x << 12) |
-                    (a3.y << 13) | (a3.z << 14) | (a3.w << 15);
-    }
+    const uint32_t live_mask = __builtin_amdgcn_readfirstlane(*live);
+    if (live_mask == 0u) break;
+    sa[0] = (live_mask >> w) & 1u; sa[1] = (live_mask >> (w + 8)) & 1u;
+    sr[0] = srow[w]; sr[1] = srow[w + 8];
+    my_alive = (live_mask >> j16) & 1u; my_row = srow[j16];
+    su_alive = (live_mask >> sj) & 1u;
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {  // h1 rows and sign masks of slots w and w + 8
@@ -844,7 +835,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           }
           if (si == 0) srow[sj] = sb;
         } else if (si == 0) {
-          alive[sj] = 0;
+          atomicAnd(live, ~(1u << sj));
         }
       } else {
         ts = t + 1;
