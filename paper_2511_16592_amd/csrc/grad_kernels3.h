@@ -192,7 +192,7 @@ inline size_t dw1_onehot_lds_bytes() { return 3 * kDw1Round * 4 + kDw1Round * 11
 // Transitions are split over the workgroups as in gemm_tn2_kernel and the partial tiles / column sums have its
 // layout (part[s][unit][QTOT], dbpart[s][QTOT]), so the same reduction finishes dW3 and db3.
 // crow[i] is the coefficient 2 delta_b / B of live transition i.
-constexpr int kNarrowInFlight = 4;
+constexpr int kNarrowInFlight = 8;
 constexpr int kNarrowLdsBytes = 8 * 16 * 64 * 16;
 __global__ __launch_bounds__(512) void logit_bwd_narrow_kernel(float* __restrict__ h2buf, const float* __restrict__ ebuf,
                                                                const float* __restrict__ crow,
@@ -224,12 +224,13 @@ __global__ __launch_bounds__(512) void logit_bwd_narrow_kernel(float* __restrict
 
   const int wu = __builtin_amdgcn_readfirstlane(w);
   for (int base = row0 + wu * U; base < row1; base += 8 * U) {
-    // row id, coefficient and the 16 values of e are the same for every lane: they are fetched through the
-    // scalar cache and stay in scalar registers; per lane only the 16 bytes of h2 and one value of e (for db3)
+    // row id and coefficient are the same for every lane (scalar loads); per lane the 16 bytes of h2 and one value
+    // of e: lane l holds e[l % 16], scaled into g3[l % 16] once the data is there, and the sixteen values reach the
+    // multiply-adds as scalar operands read from lanes 0..15.  Little state per transition, so eight are in flight per
+    // wave: the sweep is bound by HBM latency x bytes in flight.
     int id[U];
     float c[U], el[U];
     f32x4 h[U];
-    const float* er[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int li = base + u;
@@ -240,16 +241,17 @@ __global__ __launch_bounds__(512) void logit_bwd_narrow_kernel(float* __restrict
     for (int u = 0; u < U; ++u) {
       const size_t r = (size_t)(id[u] < 0 ? 0 : id[u]);
       h[u] = *(const f32x4*)&h2buf[r * 256 + 4 * lane];
-      er[u] = ebuf + r * 16;
-      el[u] = er[u][lane & 15];
+      el[u] = ebuf[r * 16 + (lane & 15)];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (id[u] < 0) continue;  // uniform: the row index does not depend on the lane
+      const float gl = c[u] * el[u];
       float g3[16];
 #pragma unroll
-      for (int k = 0; k < 16; ++k) g3[k] = c[u] * er[u][k];
-      if (lane < 16) dbl += c[u] * el[u];
+      for (int k = 0; k < 16; ++k)
+        g3[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gl), k));
+      if (lane < 16) dbl += gl;
       f32x4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j)
