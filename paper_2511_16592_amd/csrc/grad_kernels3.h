@@ -186,7 +186,7 @@ inline size_t dw1_onehot_lds_bytes() { return 3 * kDw1Round * 4 + kDw1Round * 11
 // Backward pass of the logit layer for narrow action spaces (at most 16 logits, 256 hidden units), one sweep
 // over the live transitions instead of two GEMM kernels whose contraction / output width would be 16:
 //   g3 = c_b * e (16 values), dW3 += h2^T g3, db3 += g3, G2 = (W3 g3) . [h2 > 0] written over h2.
-// A wave takes one transition at a time (four in flight): lane l owns hidden units 4l .. 4l+3, i.e. 16 bytes of
+// A wave takes one transition at a time (eight in flight): lane l owns hidden units 4l .. 4l+3, i.e. 16 bytes of
 // the 1 KiB row it reads and writes, its 4 x 16 slice of W3 and a 4 x 16 accumulator of dW3 in registers.  The
 // work is HBM-bound (read h2, write G2: 2 KiB per transition); the 128 multiply-adds per lane hide under it.
 // Transitions are split over the workgroups as in gemm_tn2_kernel and the partial tiles / column sums have its

@@ -17,10 +17,10 @@
 //       transition, terminal log-reward, action byte; then the same lanes update the layer-1
 //       pre-activation: layer 1 is a one-hot gather and a transition swaps exactly one active row, so z1 is
 //       kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
-// The post-ReLU activations h1, h2, their sign masks (1 bit per unit), the state bytes and the logit-gradient
-// direction (onehot(a) - p) of every transition are written to HBM rows t*B + b for the gradient pass.  Nothing the
-// kernel writes to global memory is read back by it, so the three barriers per step order LDS traffic only
-// (no wait for stores to land).
+// The post-ReLU activations h1, h2, their sign masks (1 bit per unit; those of h2 only where the gradient pass
+// reads them), the state bytes and the logit-gradient direction (onehot(a) - p) of every transition are written to
+// HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is read back by it, so the
+// two (single logit tile) or three barriers per step order LDS traffic only (no wait for stores to land).
 #pragma once
 #include "gfnx_device.h"
 

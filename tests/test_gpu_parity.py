@@ -233,6 +233,35 @@ def test_wide_grid_batch_split_changes_rounding_only(gfnx):
         assert (ta[k] == tb[k]).all()   # the same launch twice is bit-identical
 
 
+def test_trajectory_buffer_longer_than_the_environment_needs(gfnx, oracle32, oracle64):
+    """traj->max_steps may exceed the environment's: the extra steps stay 0xFF padding and nothing else moves."""
+    import torch
+    env = grid_env(3, 5)
+    w = random_mlp(15, 64, 128, 4, seed=38, scale=1.5)
+    sess = gfnx.Session(env, w, 90)
+    extra = 6
+    T = sess.max_steps + extra
+    sess.actions = torch.zeros((T, 90), dtype=torch.uint8, device=sess.device)
+    sess.traj = gfnx.Traj(90, T, int(sess.actions.data_ptr()), int(sess.length.data_ptr()),
+                          int(sess.terminal_state.data_ptr()), int(sess.log_pf.data_ptr()),
+                          int(sess.log_pb.data_ptr()), int(sess.log_reward.data_ptr()))
+    sess.rollout(15, 2)
+    sess.tb_loss_grad(0.3)
+    traj, grads = sess.trajectories(), sess.gradients()
+    assert (traj["actions"][sess.max_steps:] == 0xFF).all()
+    ref = gfnx.Session(env, w, 90)
+    ref.rollout(15, 2)
+    ref.tb_loss_grad(0.3)
+    t2, g2 = ref.trajectories(), ref.gradients()
+    assert (traj["actions"][:sess.max_steps] == t2["actions"]).all()
+    for k in ("length", "terminal_state", "log_pf", "log_pb", "log_reward"):
+        assert (traj[k] == t2[k]).all()
+    for k in KEYS:
+        assert np.array_equal(grads[k], g2[k])
+    check_trajectories(oracle32, oracle64, env, w, 15, 2, traj)
+    check_gradients(oracle64, env, w, traj, grads, 0.3)
+
+
 def test_longest_supported_walks(gfnx, oracle32, oracle64):
     """15-D grid of side 18: 256 steps at most (the supported maximum), 270 one-hot inputs (more than the 256 the
     one-hot contraction takes: the per-trajectory segment-sum path of the layer-1 gradient), stop bias -8."""
