@@ -207,8 +207,8 @@ int rollout_state_pitch(const Shapes& s) {
   return r > s.sbytes ? r : s.sbytes;
 }
 
-size_t rollout_lds_bytes(const Shapes& s) {
-  return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), s.H1 == 256 && s.H2 == 256).total;
+size_t rollout_lds_bytes(const Shapes& s, bool grid) {
+  return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), s.H1 == 256 && s.H2 == 256, grid).total;
 }
 
 template <int ENV, bool REPLAY, int NCH, bool EXPLORE>
@@ -292,7 +292,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   if (tpw > 128) tpw = 128;
   p.tpw = tpw;
   const dim3 grid((s.B + tpw - 1) / tpw);
-  const size_t lds = rollout_lds_bytes(s);
+  const size_t lds = rollout_lds_bytes(s, env->kind == GFNX_ENV_GRID);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
   {
     // packed and transposed weights, and (free-running rollout) every action byte preset to the 0xFF padding

@@ -102,13 +102,15 @@ constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile 
 
 // Byte offsets of the kernel's LDS regions (shared by the launch code, which sizes the allocation).
 struct RolloutLds {
-  int z1s, z1l, h2s, lgs, z1i, flags, st, w2l, total;
+  int z1s, z1s2, z1l, h2s, lgs, z1i, flags, st, w2l, total;
 };
-__host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16, int SBL, bool stat) {
+// grid: the high part of z1 is double-buffered (read by the step in progress, written for the next one)
+__host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16, int SBL, bool stat, bool grid) {
   const int ks = logits_ksplit(A16 >> 4, H2 >> 4);
   RolloutLds L;
   int o = 0;
   L.z1s = o; o += (H1 >> 2) * kPitch * 4;            // pre-activation of layer 1, high part
+  L.z1s2 = grid ? o : L.z1s; if (grid) o += (H1 >> 2) * kPitch * 4;
   L.z1l = o; o += (H1 >> 2) * kPitch * 4;            // ... low part (z1 = hi + lo carries the sum to ~48 bits)
   L.h2s = o; o += (H2 >> 2) * kPitch * 4;
   L.lgs = o; o += ks * (A16 >> 2) * kPitch * 4;      // [KS][A16 / 4] partial logits
@@ -138,8 +140,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   const int NT2 = H2 >> 4, NT3 = A16 >> 4, nchunk = A16 >> 2;
   const int KS = logits_ksplit(NT3, Q2);
 
-  const RolloutLds L = rollout_lds_layout(H1, H2, A16, SBL, STAT);
-  float* z1s = (float*)(smem_raw + L.z1s);
+  const RolloutLds L = rollout_lds_layout(H1, H2, A16, SBL, STAT, ENV == 0);
+  float* z1a = (float*)(smem_raw + L.z1s);
+  float* z1b = (float*)(smem_raw + L.z1s2);
   float* z1l = (float*)(smem_raw + L.z1l);
   float* h2s = (float*)(smem_raw + L.h2s);
   float* lgs = (float*)(smem_raw + L.lgs);
@@ -155,6 +158,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   // roles in the SU phase: LPS lanes (sub-lane si) of one wave per slot sj.  Grids have at most 32 logits, so 16
   // lanes per slot are enough and four waves (one per SIMD, with the vector unit to itself) serve all slots.
   // Grids with the resident layer 2: steps with at most kTailSlots running trajectories take the four-slot path
+  // Grids: SU occupies four of the eight waves, so the other four write the h1 rows and sign masks of the step during
+  // SU instead of all eight doing it at the head of the L2 phase.  They read the z1 the step was computed from while
+  // SU writes the next one, hence the two buffers (z1a / z1b, swapped every step; one buffer otherwise).
+  constexpr bool kRowsInSU = ENV == 0;
   constexpr bool kTail = STAT && ENV == 0;
   constexpr int kTailSlots = 4;
   constexpr int LPS = ENV == 0 ? 16 : 32;
@@ -170,10 +177,11 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     double z = (double)p.b1[f];
     for (int s = 0; s < e.state_dim; ++s) z += (double)p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
     const float hi = (float)z, lo = (float)(z - (double)hi);
-    float* dh = z1s + (f >> 2) * kPitch + (f & 3);
+    float* dh = z1a + (f >> 2) * kPitch + (f & 3);
+    float* dh2 = z1b + (f >> 2) * kPitch + (f & 3);
     float* dl = z1l + (f >> 2) * kPitch + (f & 3);
 #pragma unroll
-    for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dl[j * 4] = lo; }
+    for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dh2[j * 4] = hi; dl[j * 4] = lo; }
     z1i[f] = hi;
     z1i[H1 + f] = lo;
   }
@@ -247,10 +255,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     sr[0] = srow[w]; sr[1] = srow[w + 8];
     my_alive = (live_mask >> j16) & 1u; my_row = srow[j16];
     su_alive = (live_mask >> sj) & 1u;
+    const float* z1s = (iter & 1) ? z1b : z1a;  // z1 of this step
+    float* z1n = (iter & 1) ? z1a : z1b;        // ... of the next one (the same buffer unless double-buffered)
+    int srk[4];                                 // rows of the four slots a non-SU wave writes out on grids
+#pragma unroll
+    for (int k = 0; k < 4; ++k) srk[k] = kRowsInSU ? srow[4 * (w & 3) + k] : 0;
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {  // h1 rows and sign masks of slots w and w + 8
-      if (!sa[hh]) continue;
+      if (kRowsInSU || !sa[hh]) continue;
       const int jj = w + 8 * hh;
       const size_t row = (size_t)sr[hh];
       float* dst = p.h1buf + row * H1;
@@ -527,6 +540,25 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     if (!logits_done) lds_barrier();
 
     // ================= SU: mask, softmax, sample, bookkeeping, transition, z1 update (LPS lanes per slot)
+    if (kRowsInSU && !su_wave) {
+      // h1 rows and sign masks of this step, slots 4 (w - 4) .. + 3, while the other four waves are in SU
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int jj = 4 * (w & 3) + k;
+        if (!((live_mask >> jj) & 1u)) continue;
+        const size_t row = (size_t)srk[k];
+        float* dst = p.h1buf + row * H1;
+        for (int it = 0; it * 64 < (H1 >> 2); ++it) {
+          const int fg = lane + 64 * it;
+          f32x4 v = {0.f, 0.f, 0.f, 0.f};
+          if (fg < (H1 >> 2)) {
+            v = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
+            *(f32x4*)&dst[fg * 4] = v;
+          }
+          store_sign_mask(p.m1buf + (row * p.MW1 + 4 * it), v, lane);
+        }
+      }
+    }
     if (su_wave && su_alive) {
       const int t = ts;
       // word si of the slot's state bytes: the validity bits of a grid lane's actions, and this lane's piece of
@@ -830,7 +862,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           if (REPLAY) len_given = p.length[sb];
           for (int s4 = si; 4 * s4 < SBL; s4 += LPS) ((uint32_t*)stj)[s4] = 0u;
           for (int fg = si; fg < (H1 >> 2); fg += LPS) {
-            *(f32x4*)&z1s[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
+            *(f32x4*)&z1n[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
             *(f32x4*)&z1l[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[H1 + 4 * fg];
           }
           if (si == 0) srow[sj] = sb;
@@ -845,16 +877,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         const float* wo_row = p.W1 + (size_t)rold * H1;
         const float* wn_row = p.W1 + (size_t)rnew * H1;
         auto update = [&](int fg, f32x4 o, f32x4 n) {
-          f32x4* zp = (f32x4*)&z1s[fg * kPitch + sj * 4];
           f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
-          f32x4 hi = *zp, lo = *lp;
+          f32x4 hi = *(const f32x4*)&z1s[fg * kPitch + sj * 4], lo = *lp;
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             const double z = ((double)hi[k] + (double)lo[k]) - (double)o[k] + (double)n[k];
             hi[k] = (float)z;
             lo[k] = (float)(z - (double)hi[k]);
           }
-          *zp = hi;
+          *(f32x4*)&z1n[fg * kPitch + sj * 4] = hi;
           *lp = lo;
         };
 #pragma unroll
