@@ -69,7 +69,11 @@
  * residual, closed-form rewards, finite differences, an independent big-integer
  * Philox and the published known-answer vectors, chi-square tests of the sampler;
  * for the optimiser step a library Adam, the constant-gradient closed form, and a
- * training run on the side-4 grid whose terminal distribution must approach R/Z.
+ * training run on the side-4 grid whose terminal distribution must approach R/Z;
+ * for backward rollouts reversibility, path frequencies against the enumeration and
+ * the estimate being exactly R(x)/Z under the proper policy; for exploration the
+ * uniform and mixture frequencies; for DB / SubTB zero loss under the proper policy
+ * with the true state flows, the pair sum written out, and finite differences.
  * Free-running sampled actions have no external reference ("parity unpinned"
  * beyond those statistical pins): the counter layout above is this implementation's own.
  */
