@@ -182,9 +182,8 @@ def run_training(name, steps, warmup, batch=None):
 
 
 def run_training_subtb(name, steps, warmup, lam, batch):
-    """Training iterations with the DB / SubTB objective: rollout, gfnx_subtb_loss_grad, Adam (three calls, no host
-    round trip; no log Z: the flow output at s_0 plays its part)."""
-    import ctypes as C
+    """Training iterations with the DB / SubTB objective (gfnx_train_step_opts: rollout, gfnx_subtb_loss_grad, Adam;
+    no log Z: the flow output at s_0 plays its part)."""
     import torch
     from paper_2511_16592_amd import gfnx
     from paper_2511_16592_amd.workloads import workloads, xavier_mlp
@@ -193,20 +192,12 @@ def run_training_subtb(name, steps, warmup, lam, batch):
     _, obs_dim, n_actions, _ = wl.env.dims()
     sess = gfnx.Session(wl.env, xavier_mlp(obs_dim, wl.h1, wl.h2, n_actions + 1, wl.weight_seed), wl.batch)
     sess.init_optimizer(lr=1e-3)
-    state = gfnx.AdamState(sess.adam_state.m, sess.adam_state.v, None)
-
-    def one(i):
-        sess.rollout(wl.seed, i)
-        sess.subtb_loss_grad(lam)
-        gfnx._check(sess.lib.gfnx_adam_step(C.byref(sess.mlp), None, C.byref(sess.cgrads), None, C.byref(state),
-                                            C.byref(sess.adam_cfg), i + 1, sess._stream()))
-
     for i in range(warmup):
-        one(i)
+        sess.train_step(wl.seed, i, subtb_lambda=lam)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        one(warmup + i)
+        sess.train_step(wl.seed, warmup + i, subtb_lambda=lam)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     return {"batch": wl.batch, "lambda": lam, "iterations": steps, "ms_per_iteration": elapsed / steps * 1e3,

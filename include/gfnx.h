@@ -237,6 +237,23 @@ int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_
                     const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* workspace,
                     size_t workspace_bytes, void* hip_stream);
 
+/* Variants of a training iteration. */
+typedef struct {
+  float epsilon;      /* epsilon-uniform exploration in the rollout (gfnx_rollout_explore); 0 = on-policy */
+  float subtb_lambda; /* negative: Trajectory Balance; in [0, 1]: gfnx_subtb_loss_grad with this lambda (0 = Detailed
+                         Balance), for a network with a flow output on the hypergrid */
+} gfnx_train_opts;
+
+/* gfnx_train_step with the rollout and the objective chosen by `opts` (the settings the paper trains with besides
+ * on-policy TB: epsilon-uniform exploration; DB and SubTB on the hypergrid).  With a Subtrajectory Balance objective
+ * there is no log Z: log_z_dev, dlogz_dev and state->log_z_mv are ignored and may be NULL.
+ * gfnx_train_step is this call with opts = {0, -1}.  Errors: the union of the calls it is made of; an objective
+ * that does not fit the network (flow output or not) is GFNX_E_BAD_SHAPE. */
+int gfnx_train_step_opts(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                         uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                         const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, const gfnx_train_opts* opts,
+                         int64_t step, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Measurement aid (not part of the method; not thread-safe).  While enabled, every kernel (or small group
  * of kernels) the library launches is bracketed by HIP events recorded on the launch stream, labelled
  * "rollout", "gemm_tn_w2", ...  gfnx_timing_enable(on) also discards the records taken so far;

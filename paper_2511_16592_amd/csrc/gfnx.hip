@@ -671,25 +671,47 @@ int gfnx_adam_step(const gfnx_mlp* mlp, float* log_z_dev, const gfnx_mlp_grad* g
   return adam_impl(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step, hip_stream);
 }
 
-int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
-                    uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
-                    const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* ws, size_t ws_bytes,
-                    void* hip_stream) {
+int gfnx_train_step_opts(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                         uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                         const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, const gfnx_train_opts* opts,
+                         int64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
   // every argument is checked before the first launch, so a rejected call leaves all buffers untouched
-  if (!log_z_dev || !loss_dev || !dlogz_dev || !grads || !traj) return GFNX_E_NULL;
-  int rc = check_adam(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step);
+  if (!opts || !loss_dev || !grads || !traj || !state) return GFNX_E_NULL;
+  if (!(opts->epsilon >= 0.f && opts->epsilon <= 1.f)) return GFNX_E_BAD_SHAPE;
+  const bool subtb = opts->subtb_lambda >= 0.f;
+  if (subtb && !(opts->subtb_lambda <= 1.f)) return GFNX_E_BAD_SHAPE;
+  if (!subtb && !(opts->subtb_lambda < 0.f)) return GFNX_E_BAD_SHAPE;  // NaN
+  gfnx_adam_state st = *state;
+  if (subtb) {  // no log Z in this objective: the flow output at s_0 plays its part
+    log_z_dev = nullptr;
+    dlogz_dev = nullptr;
+    st.log_z_mv = nullptr;
+  } else if (!log_z_dev || !dlogz_dev) {
+    return GFNX_E_NULL;
+  }
+  int rc = check_adam(mlp, log_z_dev, grads, dlogz_dev, &st, cfg, step);
   if (rc) return rc;
   {
     Shapes s;
     rc = check_shapes(env, mlp, traj->batch, &s);
     if (rc) return rc;
-    if (s.flow) return GFNX_E_BAD_SHAPE;  // the Trajectory-Balance iteration takes a plain policy network
+    if (subtb != (s.flow != 0)) return GFNX_E_BAD_SHAPE;  // TB: plain policy network; SubTB: one with a flow output
   }
-  rc = rollout_impl(env, mlp, seed, iteration, traj, ws, ws_bytes, hip_stream, false);
+  rc = rollout_impl(env, mlp, seed, iteration, traj, ws, ws_bytes, hip_stream, false, opts->epsilon);
   if (rc) return rc;
-  rc = tb_loss_grad_impl(env, mlp, traj, 0.f, log_z_dev, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream);
+  rc = tb_loss_grad_impl(env, mlp, traj, 0.f, log_z_dev, loss_dev, dlogz_dev, grads, ws, ws_bytes, hip_stream,
+                         subtb ? opts->subtb_lambda : -1.f);
   if (rc) return rc;
-  return adam_impl(mlp, log_z_dev, grads, dlogz_dev, state, cfg, step, hip_stream);
+  return adam_impl(mlp, log_z_dev, grads, dlogz_dev, &st, cfg, step, hip_stream);
+}
+
+int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                    uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                    const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* ws, size_t ws_bytes,
+                    void* hip_stream) {
+  const gfnx_train_opts opts = {0.f, -1.f};
+  return gfnx_train_step_opts(env, mlp, log_z_dev, seed, iteration, traj, loss_dev, dlogz_dev, grads, state, cfg, &opts,
+                              step, ws, ws_bytes, hip_stream);
 }
 
 int gfnx_timing_enable(int on) {

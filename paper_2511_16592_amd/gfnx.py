@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
            "gfnx_tb_loss_grad", "gfnx_subtb_loss_grad",
-           "gfnx_adam_step", "gfnx_train_step", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
+           "gfnx_adam_step", "gfnx_train_step", "gfnx_train_step_opts", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
            "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
 
@@ -41,6 +41,10 @@ class MlpGrad(C.Structure):
 class AdamCfg(C.Structure):
     _fields_ = [("lr", C.c_float), ("lr_log_z", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float)]
+
+
+class TrainOpts(C.Structure):
+    _fields_ = [("epsilon", C.c_float), ("subtb_lambda", C.c_float)]
 
 
 class AdamState(C.Structure):
@@ -101,6 +105,11 @@ def load_library() -> C.CDLL:
                                         C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
                                         C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p, C.c_size_t,
                                         C.c_void_p]
+        lib.gfnx_train_step_opts.restype = C.c_int
+        lib.gfnx_train_step_opts.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_void_p, C.c_uint64, C.c_uint64,
+                                             C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
+                                             C.POINTER(AdamState), C.POINTER(AdamCfg), C.POINTER(TrainOpts),
+                                             C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.gfnx_timing_enable.restype = C.c_int
         lib.gfnx_timing_enable.argtypes = [C.c_int]
         lib.gfnx_timing_only.restype = C.c_int
@@ -280,13 +289,23 @@ class Session:
                                        C.byref(self.adam_state), C.byref(self.adam_cfg), self.updates,
                                        self._stream()))
 
-    def train_step(self, seed: int, iteration: int) -> None:
-        """Rollout, TB loss and gradient (log Z read on the device), Adam update: one call, no host round trip."""
+    def train_step(self, seed: int, iteration: int, epsilon: float = 0.0, subtb_lambda: float = None) -> None:
+        """Rollout, loss and gradient, Adam update: one call, no host round trip.  Default: on-policy Trajectory
+        Balance (log Z read on the device); epsilon > 0 explores; subtb_lambda in [0, 1] trains a flow network with
+        SubTB (0 = DB) instead."""
         self.updates += 1
-        _check(self.lib.gfnx_train_step(C.byref(self.desc), C.byref(self.mlp), _ptr(self.log_z), seed, iteration,
-                                        C.byref(self.traj), _ptr(self.loss), _ptr(self.dlogz), C.byref(self.cgrads),
-                                        C.byref(self.adam_state), C.byref(self.adam_cfg), self.updates,
-                                        _ptr(self.workspace), self.workspace_bytes, self._stream()))
+        if epsilon == 0.0 and subtb_lambda is None:
+            _check(self.lib.gfnx_train_step(C.byref(self.desc), C.byref(self.mlp), _ptr(self.log_z), seed, iteration,
+                                            C.byref(self.traj), _ptr(self.loss), _ptr(self.dlogz),
+                                            C.byref(self.cgrads), C.byref(self.adam_state), C.byref(self.adam_cfg),
+                                            self.updates, _ptr(self.workspace), self.workspace_bytes, self._stream()))
+            return
+        opts = TrainOpts(float(epsilon), -1.0 if subtb_lambda is None else float(subtb_lambda))
+        _check(self.lib.gfnx_train_step_opts(C.byref(self.desc), C.byref(self.mlp), _ptr(self.log_z), seed, iteration,
+                                             C.byref(self.traj), _ptr(self.loss), _ptr(self.dlogz),
+                                             C.byref(self.cgrads), C.byref(self.adam_state), C.byref(self.adam_cfg),
+                                             C.byref(opts), self.updates, _ptr(self.workspace), self.workspace_bytes,
+                                             self._stream()))
 
     def weights(self) -> Dict:
         """Host copies (numpy) of the six weight tensors."""

@@ -178,3 +178,28 @@ def test_flow_network_shapes_are_validated_on_the_host(lib):
     assert sub(flow, -0.1, need) == -3 and sub(flow, 1.1, need) == -3 and sub(flow, float("nan"), need) == -3
     assert sub(flow, 0.9, need - 1) == -4
     assert lib.gfnx_tb_loss_grad(C.byref(d), C.byref(flow), C.byref(t), 0.0, p, p, C.byref(g), 0x10000, need, None) == -3
+
+
+def test_train_step_options_are_validated_on_the_host(lib):
+    p = 0x1000
+    d = gfnx.env_desc(grid_env(2, 8))
+    flow, plain = _mlp(16, 64, 64, 4), _mlp(16, 64, 64, 3)
+    t = _traj(16, 15)
+    g = gfnx.MlpGrad(p, p, p, p, p, p)
+    st = gfnx.AdamState(gfnx.MlpGrad(p, p, p, p, p, p), gfnx.MlpGrad(p, p, p, p, p, p), p)
+    cfg = gfnx.AdamCfg(1e-3, 1e-1, 0.9, 0.999, 1e-8)
+
+    def call(mm, opts, lz=p, need_of=None):
+        need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(need_of or mm), 16)
+        return lib.gfnx_train_step_opts(C.byref(d), C.byref(mm), lz, 0, 0, C.byref(t), p, lz, C.byref(g), C.byref(st),
+                                        C.byref(cfg), None if opts is None else C.byref(opts), 1, 0x10000, need - 1,
+                                        None)
+
+    assert call(plain, None) == -1
+    assert call(plain, gfnx.TrainOpts(-0.1, -1.0)) == -3 and call(plain, gfnx.TrainOpts(1.1, -1.0)) == -3
+    assert call(plain, gfnx.TrainOpts(0.0, 1.5)) == -3 and call(plain, gfnx.TrainOpts(0.0, float("nan"))) == -3
+    assert call(plain, gfnx.TrainOpts(0.0, 0.9)) == -3           # SubTB needs the flow output
+    assert call(flow, gfnx.TrainOpts(0.0, -1.0)) == -3           # TB must not have it
+    assert call(plain, gfnx.TrainOpts(0.1, -1.0), lz=None) == -1  # TB needs log Z
+    assert call(plain, gfnx.TrainOpts(0.1, -1.0)) == -4          # everything else fine: only the workspace is short
+    assert call(flow, gfnx.TrainOpts(0.1, 0.9), lz=None) == -4   # SubTB: log Z pointers may be NULL

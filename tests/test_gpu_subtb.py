@@ -166,3 +166,48 @@ def test_training_with_db_and_subtb_converges(gfnx, oracle64, lam):
     say(f"[converge lambda={lam}] total variation {tv0:.3f} -> {tv1:.4f}; log F(s0) {phi0:.3f} (log Z {math.log(16.064):.3f})")
     assert tv0 > 0.5 and tv1 < 0.03
     assert abs(phi0 - math.log(16.064)) < 0.06
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.9])
+def test_train_step_with_options_equals_its_three_calls(gfnx, lam):
+    """gfnx_train_step_opts with exploration and a SubTB objective against rollout_explore + subtb_loss_grad + adam."""
+    import ctypes as C
+    env = grid_env(3, 7)
+    w = xavier_mlp(21, 256, 256, 5, seed=95)
+    a = gfnx.Session(env, w, 150)
+    b = gfnx.Session(env, w, 150)
+    a.init_optimizer()
+    b.init_optimizer()
+    state = gfnx.AdamState(b.adam_state.m, b.adam_state.v, None)
+    for it in range(4):
+        a.train_step(8, it, epsilon=0.05, subtb_lambda=lam)
+        b.rollout(8, it, epsilon=0.05)
+        b.subtb_loss_grad(lam)
+        assert b.lib.gfnx_adam_step(C.byref(b.mlp), None, C.byref(b.cgrads), None, C.byref(state),
+                                    C.byref(b.adam_cfg), it + 1, b._stream()) == 0
+        ta, tb = a.trajectories(), b.trajectories()
+        for k in ta:
+            assert (ta[k] == tb[k]).all(), (it, k)
+        wa, wb = a.weights(), b.weights()
+        for k in wa:
+            assert np.array_equal(wa[k], wb[k]), (it, k)
+        assert float(a.loss.item()) == float(b.loss.item())
+    assert float(a.log_z.item()) == 0.0   # untouched by this objective
+
+
+def test_train_step_with_exploration_equals_its_three_calls(gfnx):
+    env = grid_env(3, 7)
+    w = xavier_mlp(21, 256, 256, 4, seed=96)
+    a = gfnx.Session(env, w, 150)
+    b = gfnx.Session(env, w, 150)
+    a.init_optimizer(log_z=0.2)
+    b.init_optimizer(log_z=0.2)
+    for it in range(3):
+        a.train_step(8, it, epsilon=0.1)
+        b.rollout(8, it, epsilon=0.1)
+        b.tb_loss_grad(float(b.log_z.item()))
+        b.adam_step()
+        wa, wb = a.weights(), b.weights()
+        for k in wa:
+            assert np.array_equal(wa[k], wb[k]), (it, k)
+        assert float(a.log_z.item()) == float(b.log_z.item())
