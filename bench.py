@@ -88,9 +88,15 @@ def cpu_baseline(wl, w, seconds_target=12.0):
             break
         if dt < seconds_target / 8 and batch < wl.batch:
             batch = min(wl.batch, batch * 4)
+    # the same reference on one thread, on a small batch (per-transition cost does not depend on the batch)
+    t0 = time.perf_counter()
+    one = o32.rollout(wl.env, w, wl.seed, 0, batch=min(wl.batch, 256), nthreads=1)
+    o32.tb_loss_grad(wl.env, w, one["actions"], one["length"], wl.log_z, nthreads=1)
+    single = int(one["length"].sum()) / (time.perf_counter() - t0)
     sizes = sorted(set(batches))
     mix = ", ".join("%d x %d" % (batches.count(b), b) for b in sizes)
     return {"value": done_tr / used, "unit": "transitions/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": single,
             "sample": "%d passes (rollout + TB gradient, binary32 build, %d threads) over batches of the same "
                       "workload (passes x trajectories: %s): %d transitions in %.1f s"
                       % (len(batches), cores, mix, done_tr, used)}
