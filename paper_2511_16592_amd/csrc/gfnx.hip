@@ -130,7 +130,7 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   const int pt2 = (s->H1 + 255) / 256, qn2 = (s->H2 + 255) / 256, pt3 = (s->H2 + 255) / 256;
   s->qtot2 = 256 * qn2;
   s->s2 = 256 / (pt2 * qn2);
-  s->qt3 = s->A16 <= 32 ? 32 : 256;
+  s->qt3 = s->A16 <= 32 ? 32 : ((s->A16 > 192 && s->A16 <= 224) ? 224 : 256);  // 224: seven 32-column blocks per wave
   s->qtot3 = s->qt3;
   s->s3 = 256 / pt3;
   s->qtot1 = 256 * pt2;
@@ -445,6 +445,14 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     if (s.qt3 == 32) {
       auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
       const int lds = 2 * 32 * (256 + 32) * 4;
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
+                         s.qtot3, part3, dbp3);
+    } else if (s.qt3 == 224) {
+      // 193..224 logits (Ising 10 x 10: 200): a 256 x 224 tile, each wave 32 rows by seven column blocks, instead
+      // of a 256 x 256 one an eighth of which would be padding
+      auto k = gemm_tn2_kernel<8, 1, 1, 7, true>;
+      const int lds = 2 * 32 * (256 + 224) * 4;
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
