@@ -240,3 +240,47 @@ def test_training_converges_to_the_reward_distribution(gfnx, oracle64):
     from tests.helpers import grid_reward
     target = np.array([grid_reward((i, j), side) for i in range(side) for j in range(side)]) / 16.064
     assert 0.5 * np.abs(probs - target).sum() < 0.05
+
+
+def test_paper_hypergrid_experiment(gfnx):
+    """The paper's own hypergrid experiment (Appendix "Hypergrid"): 4-D grid of side 20, TB, MLP 2 x 256, batch 16,
+    Adam 1e-3 (1e-1 for log Z), 10^6 training trajectories; metric: total variation between R/Z and the empirical
+    distribution of the last 2 * 10^5 terminal states sampled during training, next to the same metric of a perfect
+    sampler (which is not zero at that sample size).  The run must reach the perfect sampler's level, and log Z the
+    closed-form log 5672."""
+    import torch
+    d, side, batch = 4, 20, 16
+    env = grid_env(d, side)
+    sess = gfnx.Session(env, xavier_mlp(d * side, 256, 256, d + 1, seed=7), batch)
+    sess.init_optimizer(log_z=0.0, lr=1e-3, lr_log_z=1e-1)
+    v = np.abs(np.arange(side) / (side - 1) - 0.5)
+    in1, in2 = (0.25 < v).astype(float), ((0.3 < v) & (v < 0.4)).astype(float)
+    reward = (1e-3 + 0.5 * np.einsum("a,b,c,d->abcd", in1, in1, in1, in1)
+              + 2.0 * np.einsum("a,b,c,d->abcd", in2, in2, in2, in2))
+    assert abs(reward.sum() - 5672.0) < 1e-6
+    target = (reward / reward.sum()).reshape(-1)
+
+    def tv_of(states):
+        idx = ((states[:, 0] * side + states[:, 1]) * side + states[:, 2]) * side + states[:, 3]
+        return 0.5 * np.abs(np.bincount(idx, minlength=side ** d) / len(idx) - target).sum()
+
+    keep = 200000 // batch
+    rng = np.random.default_rng(0)
+    perfect = np.stack(np.unravel_index(rng.choice(side ** d, size=keep * batch, p=target), (side,) * d), 1)
+    tv_perfect = tv_of(perfect)
+    ring = torch.zeros((keep, d, batch), dtype=torch.int8, device=sess.device)
+    iters = 1000000 // batch
+    tv_early = None
+    for it in range(iters):
+        sess.train_step(11, it)
+        ring[it % keep].copy_(sess.terminal_state)
+        if it + 1 == keep:
+            tv_early = tv_of(ring.permute(0, 2, 1).reshape(-1, d).cpu().numpy().astype(int))
+            say(f"[paper grid] after {it + 1} iterations: TV {tv_early:.3f}")
+    tv_final = tv_of(ring.permute(0, 2, 1).reshape(-1, d).cpu().numpy().astype(int))
+    log_z = float(sess.log_z.item())
+    say(f"[paper grid] TV of the last 2e5 terminal states {tv_final:.4f} (perfect sampler {tv_perfect:.4f}); "
+        f"log Z {log_z:.3f} (exact {math.log(5672):.3f})")
+    assert tv_early > 0.5
+    assert tv_final < tv_perfect + 0.02
+    assert abs(log_z - math.log(5672)) < 0.05
