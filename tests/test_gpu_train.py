@@ -284,3 +284,77 @@ def test_paper_hypergrid_experiment(gfnx):
     assert tv_early > 0.5
     assert tv_final < tv_perfect + 0.02
     assert abs(log_z - math.log(5672)) < 0.05
+
+
+def test_training_on_bit_sequences_reaches_the_reward_distribution(gfnx, oracle64):
+    """Left-to-right bit sequences small enough to enumerate (n = 12, k = 4: 4096 strings, one trajectory each): after
+    TB training, the exact P_theta(x) (teacher-forced log P_F of every string) is close to R/Z in total variation, the
+    log-probabilities correlate with the log-rewards (the paper's metric for this environment is that Pearson
+    correlation, Appendix "Bit sequences"), and log Z is the log of the true normalising constant."""
+    import itertools
+    from paper_2511_16592_amd.workloads import bitseq_env
+    env = bitseq_env(12, 4, 3, mode_seed=5, uniform_bits=True)
+    sd, od, na, ms = env.dims()
+    sess = gfnx.Session(env, xavier_mlp(od, 64, 64, na, seed=8), 64)
+    sess.init_optimizer(log_z=0.0)
+    allx = np.array(list(itertools.product(range(16), repeat=3)), dtype=np.uint8)
+    logr = np.array([oracle64.log_reward(env, list(map(int, x))) for x in allx])
+    log_z_true = float(np.logaddexp.reduce(logr))
+    target = np.exp(logr - log_z_true)
+    ev = gfnx.Session(env, sess.weights(), 4096)
+
+    def exact_log_p():
+        ev.set_weights(sess.weights())
+        ev.replay(np.ascontiguousarray(allx.T), np.full(4096, 3, np.int32))
+        return ev.trajectories()["log_pf"].astype(np.float64)
+
+    lp0 = exact_log_p()
+    assert abs(np.exp(lp0).sum() - 1.0) < 1e-5           # the policy's terminal distribution is normalised
+    tv0 = 0.5 * np.abs(np.exp(lp0) - target).sum()
+    for it in range(6000):
+        sess.train_step(3, it)
+    lp = exact_log_p()
+    tv = 0.5 * np.abs(np.exp(lp) - target).sum()
+    pearson = float(np.corrcoef(lp, logr)[0, 1])
+    log_z = float(sess.log_z.item())
+    say(f"[bitseq training] TV {tv0:.3f} -> {tv:.4f}; Pearson {pearson:.4f}; log Z {log_z:.3f} (true {log_z_true:.3f})")
+    assert tv0 > 0.1 and tv < 0.03
+    assert pearson > 0.99
+    assert abs(log_z - log_z_true) < 0.02
+
+
+def test_training_on_ising_with_estimated_terminal_probabilities(gfnx, oracle64):
+    """3 x 3 Ising assignments (512 terminal states, 9! orders each): after TB training, P_theta(x) of EVERY state,
+    estimated from 32 backward rollouts each (gfnx_backward_rollout + gfnx_replay + gfnx_log_prob_estimate), sums to
+    one, is close to R/Z and correlates with the log-reward."""
+    import itertools
+    env = ising_env(3)
+    sd, od, na, ms = env.dims()
+    sess = gfnx.Session(env, xavier_mlp(od, 64, 64, na, seed=9), 64)
+    sess.init_optimizer(log_z=0.0)
+    allx = np.array(list(itertools.product((-1, 1), repeat=9)), dtype=np.int8)
+    logr = np.array([oracle64.log_reward(env, list(map(int, x))) for x in allx])
+    log_z_true = float(np.logaddexp.reduce(logr))
+    target = np.exp(logr - log_z_true)
+    n_samples = 32
+    ev = gfnx.Session(env, sess.weights(), 512 * n_samples)
+
+    def estimated_log_p():
+        ev.set_weights(sess.weights())
+        return ev.estimate_log_prob(allx, n_samples, seed=4, iteration=0).cpu().numpy().astype(np.float64)
+
+    lp0 = estimated_log_p()
+    assert abs(np.exp(lp0).sum() - 1.0) < 0.03            # unbiased estimates of a normalised distribution
+    tv0 = 0.5 * np.abs(np.exp(lp0) - target).sum()
+    for it in range(6000):
+        sess.train_step(3, it)
+    lp = estimated_log_p()
+    tv = 0.5 * np.abs(np.exp(lp) - target).sum()
+    pearson = float(np.corrcoef(lp, logr)[0, 1])
+    log_z = float(sess.log_z.item())
+    say(f"[ising training] sum of estimates {np.exp(lp).sum():.4f}; TV {tv0:.3f} -> {tv:.4f}; Pearson {pearson:.4f}; "
+        f"log Z {log_z:.3f} (true {log_z_true:.3f})")
+    assert abs(np.exp(lp).sum() - 1.0) < 0.03
+    assert tv0 > 0.5 and tv < 0.06
+    assert pearson > 0.98
+    assert abs(log_z - log_z_true) < 0.06
