@@ -190,6 +190,37 @@ class Oracle:
                  slack=dict(zip(("dW1", "db1", "dW2", "db2", "dW3", "db3"), slack.astype(np.float64))))
         return g
 
+    def tb_loss_grad_follow(self, env, w, actions: np.ndarray, length: np.ndarray, relu1: np.ndarray,
+                            relu2: np.ndarray, log_z: float = 0.0, kink_tol: float = 2e-6,
+                            nthreads: int = 1) -> Dict[str, np.ndarray]:
+        """TB loss and gradient with ReLU' taken from the given decisions where binary32 cannot decide it.
+
+        relu1 [n, h1], relu2 [n, h2]: 0 / 1 per hidden unit, the n = sum(length) transitions ordered by column, then
+        step.  Returns the gradients plus `followed`, `flipped`, `mismatched` (see oracle_tb_loss_grad_follow)."""
+        e, _k1 = self._env(env)
+        m, arrs = self._mlp(w)
+        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        length = np.ascontiguousarray(length, dtype=np.int32)
+        T, batch = actions.shape
+        relu1 = np.ascontiguousarray(relu1, dtype=np.uint8)
+        relu2 = np.ascontiguousarray(relu2, dtype=np.uint8)
+        n = int(length.sum())
+        assert relu1.shape == (n, m.h1) and relu2.shape == (n, m.h2), (relu1.shape, relu2.shape, n)
+        first = np.zeros(batch, dtype=np.int64)
+        first[1:] = np.cumsum(length.astype(np.int64))[:-1]
+        g = {("d" + k): np.zeros_like(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
+        gs = _Grad(*[_ptr(g[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
+        loss, dlogz = self.creal(), self.creal()
+        counts = np.zeros(3, dtype=np.int64)
+        rc = self.lib.oracle_tb_loss_grad_follow(C.byref(e), C.byref(m), C.c_int32(batch), C.c_int32(T), _ptr(actions),
+                                                 _ptr(length), self.creal(log_z), C.byref(loss), C.byref(dlogz),
+                                                 C.byref(gs), self.creal(kink_tol), _ptr(relu1), _ptr(relu2),
+                                                 _ptr(first), _ptr(counts), C.c_int(nthreads))
+        assert rc == 0, rc
+        g.update(loss=float(loss.value), dlogz=float(dlogz.value), followed=int(counts[0]), flipped=int(counts[1]),
+                 mismatched=int(counts[2]))
+        return g
+
     def subtb_loss_grad(self, env, w, actions: np.ndarray, length: np.ndarray, lam: float) -> Dict[str, np.ndarray]:
         """SubTB(lambda) loss (lambda = 0: DB) and gradient for a network whose last output is log F(s)."""
         e, _k1 = self._env(env)

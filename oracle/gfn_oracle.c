@@ -234,11 +234,16 @@ static real env_log_pb(const oracle_env* e, const int* s, int sd, int t, int a) 
 
 static real env_log_reward(const oracle_env* e, const int* s, int sd) {
   if (e->kind == ENV_GRID) {
+    /* The indicators of the reward equation compare v = |x / (H-1) - 1/2| with 1/4, 3/10 and 2/5, strictly.  A
+     * coordinate can sit exactly on a threshold (H-1 a multiple of 4, 5 or 10), so the comparisons are made on
+     * integers, where they are exact:  1/4 < v  <=>  H-1 < |4x - 2(H-1)|;   3/10 < v < 2/5  <=>
+     * 3(H-1) < |10x - 5(H-1)| < 4(H-1). */
     int in1 = 1, in2 = 1;
+    const int h = e->grid_side - 1;
     for (int i = 0; i < sd; ++i) {
-      real v = rabs((real)s[i] / (real)(e->grid_side - 1) - (real)0.5);
-      in1 = in1 && ((real)0.25 < v);
-      in2 = in2 && ((real)0.3 < v) && (v < (real)0.4);
+      const int q = abs(4 * s[i] - 2 * h), r = abs(10 * s[i] - 5 * h);
+      in1 = in1 && (h < q);
+      in2 = in2 && (3 * h < r) && (r < 4 * h);
     }
     real r = (real)e->r0 + (real)e->r1 * (real)in1 + (real)e->r2 * (real)in2;
     return rlog(r);
@@ -533,11 +538,36 @@ typedef struct {
   real kink_tol;   /* hidden units with |z| < kink_tol * (|bias| + sum |terms of z|) sit on the ReLU kink */
   real slack[6];   /* per tensor (dW1,db1,dW2,db2,dW3,db3): bound on the change if those units' masks flipped */
   int64_t n_kink;
+  /* ReLU' decisions of another implementation, one byte (0 / 1) per (transition, hidden unit): transition t of
+   * column col is row first[col] + t of relu1 [.][h1] and relu2 [.][h2].  NULL: this implementation's own. */
+  const uint8_t *relu1, *relu2;
+  const int64_t* first;
+  int64_t followed, flipped, mismatched;
 } grad_job;
 
 static size_t n_w1(const oracle_mlp* m) { return (size_t)m->in_dim * m->h1; }
 static size_t n_w2(const oracle_mlp* m) { return (size_t)m->h1 * m->h2; }
 static size_t n_w3(const oracle_mlp* m) { return (size_t)m->h2 * m->n_actions; }
+
+/* ReLU'(z) of one hidden unit.  Own decision: z > 0.  A decision given by another implementation is followed only
+ * where the sign of z is not decidable in binary32, |z| < kink_tol * mag with mag = |bias| + sum |terms of z|
+ * (the scale of the rounding error of the dot product); elsewhere the given decision must equal z > 0 and a
+ * different one is counted in *mismatched and ignored.  mag is only evaluated (by the caller-supplied lazily
+ * computed value) when it can matter: the given bit differs, or |z| < 1e-3. */
+typedef struct { int64_t followed, flipped, mismatched; } relu_counts;
+
+static int relu_decision(real z, int given, int have_given, real kink_tol, real mag, relu_counts* c) {
+  const int own = z > 0;
+  if (!have_given) return own;
+  const int in_zone = rabs(z) < kink_tol * mag;
+  if (in_zone) {
+    c->followed++;
+    if (given != own) c->flipped++;
+    return given;
+  }
+  if (given != own) c->mismatched++;
+  return own;
+}
 
 static void* grad_worker(void* arg) {
   grad_job* J = (grad_job*)arg;
@@ -549,6 +579,9 @@ static void* grad_worker(void* arg) {
   real* g3 = (real*)malloc(sizeof(real) * na);
   real* g2 = (real*)malloc(sizeof(real) * m->h2);
   real* g1 = (real*)malloc(sizeof(real) * m->h1);
+  uint8_t* d1 = (uint8_t*)malloc((size_t)m->h1);
+  uint8_t* d2 = (uint8_t*)malloc((size_t)m->h2);
+  relu_counts rc = {0, 0, 0};
   int s[MAX_STATE], rows[MAX_STATE], valid[MAX_ACT];
   for (int col = J->b_begin; col < J->b_end; ++col) {
     int len = J->length[col];
@@ -580,6 +613,27 @@ static void* grad_worker(void* arg) {
       mlp_forward(m, rows, nr, &A);
       env_valid(e, s, t, na, valid);
       masked_log_softmax(A.logit, valid, na, A.logp);
+      /* ReLU' of every hidden unit on this transition (see relu_decision) */
+      for (int k = 0; k < m->h2; ++k) {
+        const int have = J->relu2 != NULL;
+        const int given = have ? (J->relu2[(size_t)(J->first[col] + t) * m->h2 + k] != 0) : 0;
+        real mag = 0;
+        if (have && (given != (A.z2[k] > 0) || rabs(A.z2[k]) < (real)1e-3)) {
+          mag = rabs(m->b2[k]);
+          for (int i = 0; i < m->h1; ++i) mag += rabs(A.h1[i] * m->W2[(size_t)i * m->h2 + k]);
+        }
+        d2[k] = (uint8_t)relu_decision(A.z2[k], given, have, J->kink_tol, mag, &rc);
+      }
+      for (int i = 0; i < m->h1; ++i) {
+        const int have = J->relu1 != NULL;
+        const int given = have ? (J->relu1[(size_t)(J->first[col] + t) * m->h1 + i] != 0) : 0;
+        real mag = 0;
+        if (have && (given != (A.z1[i] > 0) || rabs(A.z1[i]) < (real)1e-3)) {
+          mag = rabs(m->b1[i]);
+          for (int r = 0; r < nr; ++r) mag += rabs(m->W1[(size_t)rows[r] * m->h1 + i]);
+        }
+        d1[i] = (uint8_t)relu_decision(A.z1[i], given, have, J->kink_tol, mag, &rc);
+      }
       for (int a = 0; a < na; ++a) g3[a] = valid[a] ? coef * ((real)(a == act) - rexp(A.logp[a])) : 0;
       for (int k = 0; k < m->h2; ++k) {
         real acc = 0;
@@ -587,7 +641,7 @@ static void* grad_worker(void* arg) {
           J->g.dW3[(size_t)k * na + a] += A.h2[k] * g3[a];
           acc += m->W3[(size_t)k * na + a] * g3[a];
         }
-        g2[k] = A.z2[k] > 0 ? acc : 0;
+        g2[k] = d2[k] ? acc : 0;
       }
       for (int a = 0; a < na; ++a) J->g.db3[a] += g3[a];
       for (int i = 0; i < m->h1; ++i) {
@@ -596,10 +650,10 @@ static void* grad_worker(void* arg) {
           J->g.dW2[(size_t)i * m->h2 + k] += A.h1[i] * g2[k];
           acc += m->W2[(size_t)i * m->h2 + k] * g2[k];
         }
-        g1[i] = A.z1[i] > 0 ? acc : 0;
+        g1[i] = d1[i] ? acc : 0;
       }
       for (int k = 0; k < m->h2; ++k) J->g.db2[k] += g2[k];
-      if (J->kink_tol > 0) {
+      if (J->kink_tol > 0 && !J->relu1) {
         /* ReLU'(z) is decided by the sign of z; an implementation in another precision may decide a unit
          * with |z| < kink_tol the other way.  Bound, per tensor, what such a flip changes (max-norm). */
         for (int k = 0; k < m->h2; ++k) {
@@ -639,7 +693,8 @@ static void* grad_worker(void* arg) {
     }
   }
 done:
-  free(g3); free(g2); free(g1);
+  J->followed = rc.followed; J->flipped = rc.flipped; J->mismatched = rc.mismatched;
+  free(g3); free(g2); free(g1); free(d1); free(d2);
   act_free(&A);
   return NULL;
 }
@@ -651,10 +706,11 @@ done:
  * of the rounding error of a dot product), and slack[6], a per-tensor bound (max-norm, order
  * dW1 db1 dW2 db2 dW3 db3) on what the gradient would change by if ReLU' were decided the other way on
  * those units -- the analogue, for the derivative of the ReLU, of the near-tie margin of the sampler. */
-int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
-                        const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
-                        oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out, int64_t* n_kink_out,
-                        int nthreads) {
+static int tb_loss_grad_impl(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
+                             const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                             oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out,
+                             int64_t* n_kink_out, const uint8_t* relu1, const uint8_t* relu2, const int64_t* first,
+                             int64_t* counts_out, int nthreads) {
   int32_t sd, od, na, ms;
   if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
   if (na != mlp->n_actions || od != mlp->in_dim) return -2;
@@ -678,6 +734,8 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
     jobs[k].b_end = (int)((int64_t)batch * (k + 1) / nthreads);
     jobs[k].status = 0;
     jobs[k].kink_tol = kink_tol; jobs[k].n_kink = 0;
+    jobs[k].relu1 = relu1; jobs[k].relu2 = relu2; jobs[k].first = first;
+    jobs[k].followed = jobs[k].flipped = jobs[k].mismatched = 0;
     for (int q = 0; q < 6; ++q) jobs[k].slack[q] = 0;
     if (nthreads == 1) grad_worker(&jobs[k]);
     else pthread_create(&th[k], NULL, grad_worker, &jobs[k]);
@@ -705,8 +763,38 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
   if (slack_out)
     for (int q = 0; q < 6; ++q) { slack_out[q] = 0; for (int k = 0; k < nthreads; ++k) slack_out[q] += jobs[k].slack[q]; }
   if (n_kink_out) { *n_kink_out = 0; for (int k = 0; k < nthreads; ++k) *n_kink_out += jobs[k].n_kink; }
+  if (counts_out) {
+    counts_out[0] = counts_out[1] = counts_out[2] = 0;
+    for (int k = 0; k < nthreads; ++k) {
+      counts_out[0] += jobs[k].followed; counts_out[1] += jobs[k].flipped; counts_out[2] += jobs[k].mismatched;
+    }
+  }
   free(delta); free(priv); free(th); free(jobs);
   return status;
+}
+
+int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
+                        const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                        oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out, int64_t* n_kink_out,
+                        int nthreads) {
+  return tb_loss_grad_impl(env, mlp, batch, max_steps, actions, length, log_z, loss, dlogz, grads, delta_out,
+                           kink_tol, slack_out, n_kink_out, NULL, NULL, NULL, NULL, nthreads);
+}
+
+/* The same loss and gradient with the derivative of the ReLU taken from another implementation's decisions where,
+ * and only where, binary32 cannot decide it -- the analogue for ReLU' of following given actions in oracle_replay.
+ * relu1 / relu2: one byte (0 / 1) per (transition, hidden unit of layer 1 / 2), transition t of column col at row
+ * first[col] + t.  A given decision is used iff |z| < kink_tol * (|bias| + sum |terms of z|); everywhere else this
+ * implementation's own z > 0 is used and a given decision that differs from it is a disagreement.
+ * counts_out[3] = {units whose given decision was followed (counted among units with |z| < 1e-3), of which the given
+ * decision differs from z > 0, disagreements outside the margin (must be 0 for a correct implementation)}. */
+int oracle_tb_loss_grad_follow(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
+                               const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                               oracle_grad* grads, real kink_tol, const uint8_t* relu1, const uint8_t* relu2,
+                               const int64_t* first, int64_t* counts_out, int nthreads) {
+  if (!relu1 || !relu2 || !first || !counts_out) return -7;
+  return tb_loss_grad_impl(env, mlp, batch, max_steps, actions, length, log_z, loss, dlogz, grads, NULL, kink_tol,
+                           NULL, NULL, relu1, relu2, first, counts_out, nthreads);
 }
 
 /* ------------------------------------------------------- SubTB / DB loss + gradient */

@@ -58,6 +58,31 @@ def test_grid_threshold_is_strict_side5(oracle32, oracle64):
         assert abs(o.log_reward(env, [0, 4, 0]) - math.log(0.501)) < 1e-6
 
 
+def test_grid_reward_is_exact_on_every_threshold(oracle32, oracle64):
+    """Whenever H-1 is a multiple of 4, 5 or 10 some coordinate sits exactly on 1/4, 3/10 or 2/5 of the reward
+    equation's strict inequalities (side 11: x = 2, 8 on 0.3 and x = 1, 9 on 0.4), where rounding of x/(H-1) - 0.5
+    would decide the indicator.  Both builds must give the value of the equation evaluated in exact rationals, for
+    every coordinate of every side from 2 to 127 and for products over two coordinates on the sides with thresholds."""
+    for side in range(2, 128):
+        env1 = grid_env(1, side)
+        for x in range(side):
+            want = math.log(grid_reward((x,), side))
+            assert abs(oracle64.log_reward(env1, [x]) - want) < 1e-12, (side, x)
+            assert abs(oracle32.log_reward(env1, [x]) - want) < 1e-6, (side, x)
+    for side in (5, 6, 11, 21):
+        env2 = grid_env(2, side)
+        for x in range(side):
+            for y in range(side):
+                want = math.log(grid_reward((x, y), side))
+                assert abs(oracle64.log_reward(env2, [x, y]) - want) < 1e-12, (side, x, y)
+                assert abs(oracle32.log_reward(env2, [x, y]) - want) < 1e-6, (side, x, y)
+    # the edge cells of the side-11 grid named above: on the threshold means outside the band
+    assert abs(oracle64.log_reward(grid_env(2, 11), [9, 9]) - math.log(0.501)) < 1e-12
+    assert abs(oracle64.log_reward(grid_env(2, 11), [8, 8]) - math.log(0.501)) < 1e-12
+    assert abs(oracle32.log_reward(grid_env(2, 11), [9, 9]) - math.log(0.501)) < 1e-6
+    assert abs(oracle32.log_reward(grid_env(2, 11), [8, 8]) - math.log(0.501)) < 1e-6
+
+
 def test_worked_example_of_the_paper(oracle64):
     """Usage listing in "Library Details": dim 3, side 5; action 0 is not terminal and earns log-reward 0,
     the stop action is the LAST index and yields the log-reward of the state reached, here (1,0,0)."""
@@ -272,3 +297,49 @@ def test_replay_reproduces_free_run_and_flags_wrong_actions(oracle32):
     r2 = oracle32.replay(env, w, 2, 3, bad, out["length"])
     assert r2["violations"][b] >= 1
     assert (np.delete(r2["violations"], b) == 0).all()
+
+
+def test_replay_near_tie_margin_is_absolute_on_the_perturbed_logits(oracle32):
+    """The near-tie rule of the replay: an action other than the argmax is a near tie iff its perturbed logit is
+    within tie_tol (absolute) of the best one, otherwise a violation.  One-step bit sequences (a single 4-bit token,
+    16 actions, no mask): the perturbed logits are rebuilt here from the policy's logits, an independent big-integer
+    Philox and numpy's binary32 logarithm; the runner-up is handed to the replay with tie_tol just above and just
+    below the gap.  A comparison on the raw logits, a relative one, or one against another operand fails this."""
+    from tests.test_oracle_rng import philox_bigint
+    env = bitseq_env(4, 4, 3, mode_seed=5, uniform_bits=True)
+    w = random_mlp(17, 32, 32, 16, seed=51, scale=3.0)
+    seed, iteration, batch = 77, 6, 24
+    out = oracle32.rollout(env, w, seed=seed, iteration=iteration, batch=batch)
+    assert (out["length"] == 1).all()
+    logits, _, valid = oracle32.policy(env, w, [16])  # the empty string: the state of step 0
+    assert valid.all()
+    checked = 0
+    for b in range(batch):
+        pert = np.zeros(16, dtype=np.float32)
+        for a in range(16):
+            word = philox_bigint([b, 0, a // 4, iteration], [seed, 0])[a % 4]
+            u = np.float32((word >> 9) + 0.5) * np.float32(2.0 ** -23)
+            pert[a] = np.float32(logits[a]) + (-np.log(-np.log(u, dtype=np.float32), dtype=np.float32))
+        order = np.argsort(-pert, kind="stable")
+        best, second = int(order[0]), int(order[1])
+        gap = float(pert[best] - pert[second])
+        assert out["actions"][0, b] == best
+        assert abs(out["min_margin"][b] - gap) <= 2e-6
+        if gap < 1e-4 or abs(abs(float(pert[best])) - 1.0) < 0.2:
+            continue  # keep clear of rounding in the gap itself, and of |best| ~ 1 where relative = absolute
+        raw_gap = float(logits[best] - logits[second])
+        given = out["actions"].copy()
+        given[0, b] = second
+        above = oracle32.replay(env, w, seed, iteration, given, out["length"], tie_tol=gap * 1.01)
+        below = oracle32.replay(env, w, seed, iteration, given, out["length"], tie_tol=gap * 0.99)
+        assert above["near_ties"][b] == 1 and above["violations"][b] == 0, (b, gap, raw_gap)
+        assert below["near_ties"][b] == 0 and below["violations"][b] == 1, (b, gap, raw_gap)
+        others = np.arange(batch) != b
+        assert (above["near_ties"][others] == 0).all() and (above["violations"][others] == 0).all()
+        # the third-best action is further away than the runner-up: a violation under the same tolerance
+        given[0, b] = int(order[2])
+        if float(pert[best] - pert[order[2]]) > gap * 1.02:
+            third = oracle32.replay(env, w, seed, iteration, given, out["length"], tie_tol=gap * 1.01)
+            assert third["near_ties"][b] == 0 and third["violations"][b] == 1
+        checked += 1
+    assert checked >= 12

@@ -152,3 +152,83 @@ def test_relu_kink_slack_bounds_a_planted_flip(oracle64):
             differs = differs or diff > 1e-6
             assert diff <= min(grads[0]["slack"][k], grads[1]["slack"][k]) + 1e-7, (layer, k, diff)
         assert differs  # the planted flip really changes the gradient
+
+
+def _grid_hidden_signs(env, w, actions, length):
+    """ReLU' decisions (z > 0) of both hidden layers along grid trajectories, from a dense numpy forward pass over
+    states rebuilt here in Python; rows ordered column by column, step by step."""
+    d, side = env.grid_dim, env.grid_side
+    r1, r2 = [], []
+    for b in range(actions.shape[1]):
+        x = [0] * d
+        for t in range(int(length[b])):
+            onehot = np.zeros(d * side)
+            for i in range(d):
+                onehot[side * i + x[i]] = 1.0
+            z1 = w["b1"] + onehot @ w["W1"]
+            z2 = w["b2"] + np.maximum(z1, 0) @ w["W2"]
+            r1.append(z1 > 0)
+            r2.append(z2 > 0)
+            a = int(actions[t, b])
+            if a < d:
+                x[a] += 1
+    return np.array(r1, dtype=np.uint8), np.array(r2, dtype=np.uint8)
+
+
+def test_following_given_relu_decisions(oracle64):
+    """The mask-following mode of the gradient: (i) given the decisions z > 0 of an independent dense forward pass it
+    reproduces the plain gradient and reports no disagreement; (ii) a decision given the other way on a unit far from
+    the kink is ignored and counted as a disagreement; (iii) on a unit placed 1e-9 above zero (through its bias) the
+    given decision "off" is followed, and the result is the plain gradient of the network whose bias puts that unit
+    1e-9 below zero -- for a unit of either hidden layer."""
+    env = grid_env(2, 4)
+    w = random_mlp(8, 32, 32, 3, seed=41, scale=2.0, dtype=np.float64)
+    out = oracle64.rollout(env, w, seed=3, iteration=0, batch=12)
+    actions, length = out["actions"], out["length"]
+    plain = oracle64.tb_loss_grad(env, w, actions, length, 0.2)
+    r1, r2 = _grid_hidden_signs(env, w, actions, length)
+    assert r1.shape == (int(length.sum()), 32) and 0 < r1.mean() < 1 and 0 < r2.mean() < 1
+    same = oracle64.tb_loss_grad_follow(env, w, actions, length, r1, r2, 0.2, kink_tol=1e-6)
+    assert (same["followed"], same["flipped"], same["mismatched"]) == (0, 0, 0)
+    assert same["loss"] == plain["loss"] and same["dlogz"] == plain["dlogz"]
+    threaded = oracle64.tb_loss_grad_follow(env, w, actions, length, r1, r2, 0.2, kink_tol=1e-6, nthreads=3)
+    for k in KEYS:
+        assert np.array_equal(same[k], plain[k]), k
+        assert np.allclose(threaded[k], plain[k], rtol=1e-13, atol=1e-15), k
+    # (ii) far from the kink a given decision changes nothing
+    for layer, arr in ((1, r1), (2, r2)):
+        bad1, bad2 = r1.copy(), r2.copy()
+        (bad1 if layer == 1 else bad2)[3, 9] ^= 1
+        res = oracle64.tb_loss_grad_follow(env, w, actions, length, bad1, bad2, 0.2, kink_tol=1e-6)
+        assert (res["followed"], res["flipped"], res["mismatched"]) == (0, 0, 1)
+        for k in KEYS:
+            assert np.array_equal(res[k], same[k]), k
+    # (iii) inside the margin the given decision decides
+    for layer, unit in ((1, 5), (2, 7)):
+        ws = {}
+        for sign in (+1, -1):
+            w2 = {k: v.copy() for k, v in w.items()}
+            if layer == 1:
+                z0 = w2["b1"][unit] + w2["W1"][0, unit] + w2["W1"][4, unit]  # s_0 = (0,0): rows 0 and 4
+                w2["b1"][unit] += -z0 + sign * 1e-9
+            else:
+                z1 = np.maximum(w2["b1"] + w2["W1"][0] + w2["W1"][4], 0)
+                z0 = w2["b2"][unit] + z1 @ w2["W2"][:, unit]
+                w2["b2"][unit] += -z0 + sign * 1e-9
+            ws[sign] = w2
+        up1, up2 = _grid_hidden_signs(env, ws[+1], actions, length)
+        dn1, dn2 = _grid_hidden_signs(env, ws[-1], actions, length)
+        changed = (up1 != dn1).sum() + (up2 != dn2).sum()
+        assert changed == 12  # the unit at s_0 of every trajectory, nothing else
+        below = oracle64.tb_loss_grad(env, ws[-1], actions, length, 0.2)
+        above = oracle64.tb_loss_grad(env, ws[+1], actions, length, 0.2)
+        assert max(np.abs(below[k] - above[k]).max() for k in KEYS) > 1e-6  # the decision matters
+        res = oracle64.tb_loss_grad_follow(env, ws[+1], actions, length, dn1, dn2, 0.2, kink_tol=1e-6, nthreads=2)
+        assert (res["followed"], res["flipped"], res["mismatched"]) == (12, 12, 0)
+        for k in KEYS:
+            assert np.abs(res[k] - below[k]).max() <= 1e-7 * max(1.0, np.abs(below[k]).max()), (layer, k)
+        # with a margin too small to cover the unit, the same given decisions are disagreements and are ignored
+        res = oracle64.tb_loss_grad_follow(env, ws[+1], actions, length, dn1, dn2, 0.2, kink_tol=1e-12)
+        assert (res["followed"], res["flipped"], res["mismatched"]) == (0, 0, 12)
+        for k in KEYS:
+            assert np.allclose(res[k], above[k], rtol=1e-13, atol=1e-15), (layer, k)
