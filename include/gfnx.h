@@ -126,6 +126,23 @@ int gfnx_env_dims(const gfnx_env_desc* env, int32_t* state_dim, int32_t* obs_dim
  * per-transition activations the rollout keeps for the gradient pass, and reduction partials. */
 size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t batch);
 
+/* Host-only: where, inside the workspace, a rollout (gfnx_rollout / gfnx_rollout_explore / gfnx_replay) leaves the
+ * derivative of the ReLU it used on every transition -- for tools that check the gradient of eq. TB_loss against
+ * another implementation, which must take the same float-decided derivative where a pre-activation is zero to
+ * within binary32 rounding.  The region starts at byte *offset of the workspace and holds one row of *row_bytes
+ * bytes per (step t, trajectory b) at row index t * batch + b; rows of steps t >= length[b] are undefined.  The
+ * contents are valid from the end of the rollout until the next gfnx_tb_loss_grad / gfnx_subtb_loss_grad (which
+ * consumes the workspace) on the same stream.
+ *   GFNX_REGION_H1_SIGNS, GFNX_REGION_H2_SIGNS   one bit per hidden unit of layer 1 / 2, set iff the unit's
+ *       pre-activation was > 0: unit u is bit (u % 256) / 4 of the 64-bit little-endian word 4 * (u / 256) + u % 4
+ *       of the row.  GFNX_REGION_H2_SIGNS is GFNX_E_UNSUPPORTED for networks of at most 16 outputs with h2 = 256,
+ *       which record no such bits: there the sign is that of the stored activation, GFNX_REGION_H2_ROWS.
+ *   GFNX_REGION_H2_ROWS   h2 binary32 values per row: the post-ReLU activations of layer 2.
+ * Errors: NULL pointers, descriptor / shape errors as gfnx_workspace_bytes, unknown region (GFNX_E_BAD_SHAPE). */
+typedef enum { GFNX_REGION_H1_SIGNS = 0, GFNX_REGION_H2_SIGNS = 1, GFNX_REGION_H2_ROWS = 2 } gfnx_region;
+int gfnx_workspace_region(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t batch, int32_t region,
+                          size_t* offset, size_t* row_bytes);
+
 /* Forward rollout (the paper's forward_rollout utility, "Library Details"): samples `traj->batch`
  * complete trajectories from P_F given by `mlp`, starting at s_0, and fills every array of `traj`.
  * Trajectory b uses the Philox counters (b, t, ., iteration).  Also leaves in `workspace` what

@@ -201,6 +201,18 @@ EnvParams env_params(const gfnx_env_desc* env, const Shapes& s) {
 template <typename T>
 inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
+// Raises a kernel's dynamic-LDS limit; the runtime call is made once per kernel instantiation and size (the
+// largest size asked for so far is remembered per call site through `granted`).
+template <typename K>
+inline bool allow_lds(K kernel, int bytes, int* granted) {
+  if (bytes <= *granted) return true;
+  if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+  *granted = bytes;
+  return true;
+}
+#define GFNX_ALLOW_LDS(kernel, bytes) \
+  { static int granted_lds = 0; if (!allow_lds(kernel, (int)(bytes), &granted_lds)) return GFNX_E_HIP; }
+
 // bytes per slot of the state kept in LDS by the rollout kernel
 int rollout_state_pitch(const Shapes& s) {
   const int r = (s.state_dim + 15) / 16 * 16;
@@ -216,8 +228,7 @@ int launch_rollout_ntw(const RolloutParams& p, dim3 grid, size_t lds, hipStream_
 #define GFNX_LAUNCH(N, STATIONARY)                                                                          \
   {                                                                                                         \
     auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH, EXPLORE>;                                      \
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
-      return GFNX_E_HIP;                                                                                    \
+    GFNX_ALLOW_LDS(k, lds)                                                                                  \
     hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, p);                                         \
   }
   if (p.H1 == 256 && p.H2 == 256) {  // layer 2 resident in registers
@@ -344,6 +355,28 @@ size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32
   return make_layout(s).total;
 }
 
+int gfnx_workspace_region(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t batch, int32_t region,
+                          size_t* offset, size_t* row_bytes) {
+  if (!env || !mlp || !offset || !row_bytes) return GFNX_E_NULL;
+  Shapes s;
+  gfnx_mlp m = *mlp;  // as in gfnx_workspace_bytes: the shapes only
+  static const float dummy = 0.f;
+  m.W1 = m.b1 = m.W2 = m.b2 = m.W3 = m.b3 = &dummy;
+  gfnx_env_desc e = *env;
+  if (e.kind == GFNX_ENV_BITSEQ && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
+  const int rc = check_shapes(&e, &m, batch, &s);
+  if (rc) return rc;
+  const Layout L = make_layout(s);
+  switch (region) {
+    case GFNX_REGION_H1_SIGNS: *offset = L.m1; *row_bytes = 8 * (size_t)s.mw1; return GFNX_OK;
+    case GFNX_REGION_H2_SIGNS:
+      if (s.A16 == 16 && s.H2 == 256) return GFNX_E_UNSUPPORTED;  // not recorded: the gradient pass reads h2 itself
+      *offset = L.m2; *row_bytes = 8 * (size_t)s.mw2; return GFNX_OK;
+    case GFNX_REGION_H2_ROWS: *offset = L.h2; *row_bytes = sizeof(float) * (size_t)s.H2; return GFNX_OK;
+    default: return GFNX_E_BAD_SHAPE;
+  }
+}
+
 int gfnx_rollout(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, uint64_t iteration, gfnx_traj* traj,
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   return rollout_impl(env, mlp, seed, iteration, traj, workspace, workspace_bytes, hip_stream, false);
@@ -436,7 +469,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   if (narrow) {
     GFNX_TIMED("logit_bwd", st);
     auto k = logit_bwd_narrow_kernel;
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess) return GFNX_E_HIP;
+    GFNX_ALLOW_LDS(k, kNarrowLdsBytes)
     hipLaunchKernelGGL(k, dim3(s.s3), dim3(512), kNarrowLdsBytes, st, h2buf, (const float*)ebuf, (const float*)crow,
                        mlp->W3, s.A, (const int*)rows, (const int*)hdr, part3, s.qtot3, dbp3);
   } else {
@@ -445,7 +478,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     if (s.qt3 == 32) {
       auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
       const int lds = 2 * 32 * (256 + 32) * 4;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     } else if (s.qt3 == 224) {
@@ -453,13 +486,13 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       // of a 256 x 256 one an eighth of which would be padding
       auto k = gemm_tn2_kernel<8, 1, 1, 7, true>;
       const int lds = 2 * 32 * (256 + 224) * 4;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     } else {
       auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
       const int lds = 2 * 32 * (256 + 256) * 4;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     }
@@ -474,7 +507,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     GFNX_TIMED("gemm_nt_g2", st);
     const int gx = row_tiles < 256 / pt3 ? row_tiles : 256 / pt3;
     auto k = gemm_nt2_kernel<true>;
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
+    GFNX_ALLOW_LDS(k, nt_lds)
     hipLaunchKernelGGL(k, dim3(gx, pt3), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
                        at<unsigned long long>(ws, L.m2), s.mw2, (const float*)crow, rows, hdr);
   }
@@ -483,7 +516,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     GFNX_TIMED("gemm_tn_w2", st);
     auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
     const int lds = 2 * 32 * (256 + 256) * 4;
-    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+    GFNX_ALLOW_LDS(k, lds)
     hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, (const float*)crow, rows, hdr,
                        s.qtot2, part2, dbp2);
   }
@@ -495,7 +528,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     if (s.H2 <= 256) {
       const int gx = row_tiles < 256 / pt2 ? row_tiles : 256 / pt2;
       auto k = gemm_nt2_kernel<false>;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, nt_lds) != hipSuccess) return GFNX_E_HIP;
+      GFNX_ALLOW_LDS(k, nt_lds)
       hipLaunchKernelGGL(k, dim3(gx, pt2), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
                          at<unsigned long long>(ws, L.m1), s.mw1, (const float*)crow, rows, hdr);
     } else {
@@ -503,7 +536,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
       const int lds = (int)gemm_nt2k_lds_bytes();
       auto k = gemm_nt2k_kernel;
-      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+      GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf,
                          s.H1, s.H1, (const unsigned long long*)at<unsigned long long>(ws, L.m1), s.mw1, (const int*)rows,
                          (const int*)hdr);
@@ -521,12 +554,12 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       GFNX_TIMED("dw1", st);
       if (s.onehot == 1) {
         auto k = dw1_onehot_kernel<1>;
-        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+        GFNX_ALLOW_LDS(k, lds)
         hipLaunchKernelGGL(k, grid1, dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes,
                            (int)env->grid_side, s.p1, s.qtot1, part1, dbp1);
       } else {
         auto k = dw1_onehot_kernel<2>;
-        if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return GFNX_E_HIP;
+        GFNX_ALLOW_LDS(k, lds)
         hipLaunchKernelGGL(k, grid1, dim3(512), lds, st, (const float*)h1buf, s.H1, rows, hdr, sbuf, s.sbytes, 1, s.p1,
                            s.qtot1, part1, dbp1);
       }

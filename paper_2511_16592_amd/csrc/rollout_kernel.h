@@ -784,9 +784,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           const int cnt = grp_sum<LPS>((si < e.d && xi > 0) ? 1 : 0);
           lpb -= __builtin_amdgcn_logf((float)cnt) * 0.693147180559945f;
         } else {
-          const float v = fabsf((float)xi / (float)(e.H - 1) - 0.5f);
-          const int bad1 = grp_sum<LPS>((si < e.d && !(0.25f < v)) ? 1 : 0);
-          const int bad2 = grp_sum<LPS>((si < e.d && !((0.3f < v) && (v < 0.4f))) ? 1 : 0);
+          // v = |x / (H-1) - 1/2| against the strict thresholds 1/4, 3/10 and 2/5 of the reward equation, decided on
+          // integers (a coordinate sits exactly on a threshold whenever H-1 is a multiple of 4, 5 or 10):
+          // 1/4 < v <=> H-1 < |4x - 2(H-1)|;  3/10 < v < 2/5 <=> 3(H-1) < |10x - 5(H-1)| < 4(H-1)
+          const int hm = e.H - 1;
+          const int q4 = abs(4 * xi - 2 * hm), q10 = abs(10 * xi - 5 * hm);
+          const int bad1 = grp_sum<LPS>((si < e.d && !(hm < q4)) ? 1 : 0);
+          const int bad2 = grp_sum<LPS>((si < e.d && !((3 * hm < q10) && (q10 < 4 * hm))) ? 1 : 0);
           const float r = e.r0 + e.r1 * (bad1 == 0 ? 1.f : 0.f) + e.r2 * (bad2 == 0 ? 1.f : 0.f);
           logr = logf(r);
           term = true;

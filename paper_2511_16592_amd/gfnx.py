@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 
 GFNX_OK = 0
-EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
+EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_workspace_region", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
            "gfnx_tb_loss_grad", "gfnx_subtb_loss_grad",
            "gfnx_adam_step", "gfnx_train_step", "gfnx_train_step_opts", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
            "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
@@ -78,6 +78,9 @@ def load_library() -> C.CDLL:
         lib.gfnx_env_dims.argtypes = [C.POINTER(EnvDesc)] + [C.POINTER(C.c_int32)] * 4
         lib.gfnx_workspace_bytes.restype = C.c_size_t
         lib.gfnx_workspace_bytes.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_int32]
+        lib.gfnx_workspace_region.restype = C.c_int
+        lib.gfnx_workspace_region.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_int32, C.c_int32,
+                                              C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         lib.gfnx_rollout.restype = C.c_int
         lib.gfnx_rollout.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_uint64, C.c_uint64, C.POINTER(Traj),
                                      C.c_void_p, C.c_size_t, C.c_void_p]
@@ -177,7 +180,7 @@ class Session:
         self.torch = torch
         self.lib = load_library()
         self.env, self.batch, self.device = env, int(batch), torch.device(device)
-        self.state_dim, self.obs_dim, self.n_actions, self.max_steps = env.dims()
+        self.state_dim, self.obs_dim, self.n_actions, self.max_steps = env_dims(env)  # gfnx_env_dims
         dev = self.device
         self.modes = None
         if env.modes is not None:
@@ -230,6 +233,19 @@ class Session:
         self.length.copy_(torch.as_tensor(length, dtype=torch.int32))
         _check(self.lib.gfnx_replay(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), _ptr(self.workspace),
                                     self.workspace_bytes, self._stream()))
+
+    def workspace_rows(self, region: int, rows):
+        """Device tensor [len(rows), row_bytes] (uint8) of the given rows (index t * batch + b, a device int64
+        tensor) of a workspace region (gfnx_workspace_region); None where the region is not recorded."""
+        off, rb = C.c_size_t(), C.c_size_t()
+        rc = self.lib.gfnx_workspace_region(C.byref(self.desc), C.byref(self.mlp), self.batch, region,
+                                            C.byref(off), C.byref(rb))
+        if rc == -5:
+            return None
+        _check(rc)
+        n_rows = self.max_steps * self.batch
+        view = self.workspace[off.value:off.value + n_rows * rb.value].view(n_rows, rb.value)
+        return view.index_select(0, rows)
 
     def tb_loss_grad(self, log_z: float = 0.0) -> None:
         _check(self.lib.gfnx_tb_loss_grad(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), float(log_z),

@@ -203,3 +203,30 @@ def test_train_step_options_are_validated_on_the_host(lib):
     assert call(plain, gfnx.TrainOpts(0.1, -1.0), lz=None) == -1  # TB needs log Z
     assert call(plain, gfnx.TrainOpts(0.1, -1.0)) == -4          # everything else fine: only the workspace is short
     assert call(flow, gfnx.TrainOpts(0.1, 0.9), lz=None) == -4   # SubTB: log Z pointers may be NULL
+
+
+def test_workspace_regions(lib):
+    """gfnx_workspace_region: the recorded ReLU' bits lie inside the workspace, rows of 32 bytes per 256 hidden
+    units; networks of at most 16 outputs with h2 = 256 record no h2 bits (GFNX_E_UNSUPPORTED) but do have h2 rows."""
+    off, rb = C.c_size_t(), C.c_size_t()
+    cases = [(grid_env(4, 20), _mlp(80, 256, 256, 5), 4096, 77, False),
+             (ising_env(10), _mlp(300, 256, 256, 200), 512, 100, True),
+             (bitseq_env(120, 8, 4, 1), _mlp(3855, 512, 512, 256), 64, 15, True),
+             (grid_env(2, 8), _mlp(16, 64, 128, 3), 16, 15, True)]
+    for env, m, batch, steps, has_h2_bits in cases:
+        d = gfnx.env_desc(env, 0x1000)
+        need = lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), batch)
+        rows = steps * batch
+        assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 0, C.byref(off), C.byref(rb)) == 0
+        assert rb.value == 32 * ((m.h1 + 255) // 256) and off.value % 256 == 0
+        assert off.value + rows * rb.value <= need
+        rc = lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 1, C.byref(off), C.byref(rb))
+        assert rc == (0 if has_h2_bits else -5)
+        if has_h2_bits:
+            assert rb.value == 32 * ((m.h2 + 255) // 256) and off.value + rows * rb.value <= need
+        assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 2, C.byref(off), C.byref(rb)) == 0
+        assert rb.value == 4 * m.h2 and off.value + rows * rb.value <= need
+        assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 3, C.byref(off), C.byref(rb)) == -3
+        assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 0, None, C.byref(rb)) == -1
+        assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), 0, 0, C.byref(off), C.byref(rb)) == -3
+    assert lib.gfnx_workspace_region(None, C.byref(_mlp(16, 64, 64, 3)), 4, 0, C.byref(off), C.byref(rb)) == -1

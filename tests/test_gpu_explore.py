@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, random_mlp
-from tests.test_gpu_parity import check_gradients, gfnx, say  # noqa: F401  (gfnx is the module fixture)
+from tests.test_gpu_parity import check_gradients, gfnx, relu_decisions, say  # noqa: F401  (gfnx is the module fixture)
 
 pytestmark = pytest.mark.gpu
 NTHREADS = min(16, os.cpu_count() or 1)
@@ -37,12 +37,14 @@ def test_exploring_rollout_against_reference(gfnx, oracle32, oracle64, case):
     say(f"[explore {name}] batch={batch} eps={eps}")
     sess = gfnx.Session(env, w, batch)
     sess.rollout(19, 3, epsilon=eps)
+    traj = sess.trajectories()
+    relu = relu_decisions(sess, traj)
     sess.tb_loss_grad(0.2)
-    traj, grads = sess.trajectories(), sess.gradients()
+    grads = sess.gradients()
     rep = oracle32.replay(env, w, 19, 3, traj["actions"], traj["length"], tie_tol=1e-5, nthreads=NTHREADS, epsilon=eps)
     assert (rep["violations"] == 0).all()
     clean = rep["near_ties"] == 0
-    assert clean.mean() > 0.99
+    assert int(rep["near_ties"].sum()) <= 10 * 2e-5 * int(traj["length"].sum()) + 3
     assert (rep["terminal_state"] == traj["terminal_state"]).all()
     free = oracle32.rollout(env, w, 19, 3, batch=batch, nthreads=NTHREADS, epsilon=eps)
     assert (free["length"][clean] == traj["length"][clean]).all()
@@ -51,7 +53,7 @@ def test_exploring_rollout_against_reference(gfnx, oracle32, oracle64, case):
     for k in ("log_pf", "log_pb", "log_reward"):
         err = np.abs(traj[k].astype(np.float64) - ref[k]) - (1e-4 * np.abs(ref[k]) + 1e-5)
         assert (err <= 0).all(), (k, float(err.max()))
-    check_gradients(oracle64, env, w, traj, grads, 0.2)
+    check_gradients(oracle64, env, w, traj, grads, 0.2, relu)
     # exploration really happened (or, at the paper's rate, at about that rate)
     plain = oracle32.rollout(env, w, 19, 3, batch=batch, nthreads=NTHREADS)
     differs = (plain["actions"] != traj["actions"]).any(0).mean()

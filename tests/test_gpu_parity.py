@@ -7,9 +7,11 @@ Bars (written out here):
   * log P_F, log P_B, log R: relative 1e-4 (absolute floor 1e-5) against the binary64 reference along the
     GPU's own action sequence;
   * loss and dloss/dlogZ: relative 1e-4 (floor 1e-6); each gradient tensor: max |diff| <= 1e-4 * max |ref| + 1e-7,
-    plus, when the reference finds hidden units whose pre-activation is within 2e-6 of its terms' magnitude of the ReLU kink on some
-    transition, its bound on what deciding ReLU' the other way there would change (the sign of such a value is
-    a float-decided bit, like the near-tie argmax; the bound is 0 when there are no such units).
+    with no further allowance.  The derivative of the ReLU of a hidden unit whose pre-activation is zero to within
+    binary32 rounding (|z| < 2e-6 * (|bias| + sum |terms|)) is a float-decided bit, like the near-tie argmax: there,
+    and only there, the reference takes the bit the GPU recorded (read from the workspace between the rollout and
+    the gradient call); every other recorded bit must equal the reference's own z > 0 -- checked for every hidden
+    unit of every transition of the batch.
 """
 import math
 import os
@@ -54,6 +56,38 @@ def say(msg):
     print(msg, flush=True)
 
 
+REGION_H1_SIGNS, REGION_H2_SIGNS, REGION_H2_ROWS = 0, 1, 2
+
+
+def unpack_signs(packed, width):
+    """[n, row_bytes] bytes of a sign-mask region -> [n, width] of 0 / 1: unit u is bit (u % 256) / 4 of the 64-bit
+    little-endian word 4 * (u / 256) + u % 4 of its row (include/gfnx.h, gfnx_workspace_region)."""
+    n = packed.shape[0]
+    bits = np.unpackbits(np.ascontiguousarray(packed), axis=1, bitorder="little")  # [n, words * 64], word-major
+    blocks = bits.reshape(n, -1, 4, 64).transpose(0, 1, 3, 2)                      # [n, block, bit l, word k]
+    return np.ascontiguousarray(blocks.reshape(n, -1)[:, :width])
+
+
+def relu_decisions(sess, traj):
+    """The ReLU' bits the rollout recorded for every live transition, ordered column by column, step by step.  Call
+    between the rollout and the gradient pass (the gradient pass consumes the workspace)."""
+    import torch
+    length = traj["length"].astype(np.int64)
+    batch = length.shape[0]
+    cols = np.repeat(np.arange(batch, dtype=np.int64), length)
+    first = np.cumsum(length) - length
+    steps = np.arange(int(length.sum()), dtype=np.int64) - np.repeat(first, length)
+    rows = torch.as_tensor(steps * batch + cols, device=sess.device)
+    h1, h2 = sess.w["W1"].shape[1], sess.w["W2"].shape[1]
+    relu1 = unpack_signs(sess.workspace_rows(REGION_H1_SIGNS, rows).cpu().numpy(), h1)
+    packed2 = sess.workspace_rows(REGION_H2_SIGNS, rows)
+    if packed2 is None:  # narrow networks keep no h2 bits: the sign of the stored activation
+        relu2 = (sess.workspace_rows(REGION_H2_ROWS, rows).view(torch.float32) > 0).to(torch.uint8).cpu().numpy()
+    else:
+        relu2 = unpack_signs(packed2.cpu().numpy(), h2)
+    return relu1, relu2
+
+
 def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, free_run=True):
     """Compares columns [b0, b1) of the GPU trajectories with the reference; returns number of near-tie steps."""
     b1 = traj["length"].shape[0] if b1 is None else b1
@@ -64,7 +98,9 @@ def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, f
     rep = o32.replay(env, w, seed, iteration, acts, length, b_offset=b0, tie_tol=1e-5, nthreads=NTHREADS)
     assert (rep["violations"] == 0).all(), "GPU action differs from the reference argmax beyond the 1e-5 margin"
     clean = rep["near_ties"] == 0
-    assert clean.mean() > 0.99
+    # a step is a near tie when the reference's top-2 gap is under 1e-5 AND the GPU's rounding flips it: at most
+    # a few times the ~1e-5 per step that the gap alone allows
+    assert int(rep["near_ties"].sum()) <= 10 * 2e-5 * int(length.sum()) + 3, int(rep["near_ties"].sum())
     assert (rep["terminal_state"] == traj["terminal_state"][:, b0:b1]).all()
     for t in range(acts.shape[0]):  # padding after the end of each trajectory
         pad = t >= length
@@ -84,19 +120,26 @@ def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, f
     return int(rep["near_ties"].sum())
 
 
-def check_gradients(o64, env, w, traj, grads, log_z):
-    g = o64.tb_loss_grad(env, w, traj["actions"], traj["length"], log_z, nthreads=NTHREADS, kink_tol=KINK_REL)
+def check_gradients(o64, env, w, traj, grads, log_z, relu=None):
+    """Loss, dloss/dlogZ and the six gradient tensors against the binary64 reference along the GPU's actions, at the
+    bars of the module docstring.  relu = (relu1, relu2) from relu_decisions()."""
+    assert relu is not None, "the ReLU decisions of the rollout are part of every gradient check"
+    g = o64.tb_loss_grad_follow(env, w, traj["actions"], traj["length"], relu[0], relu[1], log_z,
+                                kink_tol=KINK_REL, nthreads=NTHREADS)
+    assert g["mismatched"] == 0, "a recorded ReLU' bit differs from the reference outside the rounding margin"
+    n_units = int(traj["length"].sum()) * (w["W1"].shape[1] + w["W2"].shape[1])
+    assert g["followed"] <= 2e-5 * n_units + 2, g["followed"]  # the margin may only ever cover a sliver of the units
     assert abs(grads["loss"] - g["loss"]) <= 1e-4 * abs(g["loss"]) + 1e-6, (grads["loss"], g["loss"])
     assert abs(grads["dlogz"] - g["dlogz"]) <= 1e-4 * abs(g["dlogz"]) + 1e-6, (grads["dlogz"], g["dlogz"])
-    n_units = int(traj["length"].sum()) * (w["W1"].shape[1] + w["W2"].shape[1])
-    assert g["n_kink"] <= 2e-5 * n_units + 2, g["n_kink"]  # the margin may only ever cover a sliver of the units
+    worst = {}
     for k in KEYS:
         scale = np.abs(g[k]).max()
         err = np.abs(grads[k].astype(np.float64) - g[k]).max()
-        assert err <= 1e-4 * scale + 1e-7 + g["slack"][k], (k, float(err), float(scale), g["n_kink"], g["slack"][k])
-    if g["n_kink"]:
-        say(f"    {g['n_kink']} hidden units on the ReLU kink; slack/bar " +
-            " ".join(f"{k}:{g['slack'][k] / (1e-4 * np.abs(g[k]).max() + 1e-7):.2g}" for k in KEYS))
+        worst[k] = err / (1e-4 * scale + 1e-7)
+        assert err <= 1e-4 * scale + 1e-7, (k, float(err), float(scale), g["followed"], g["flipped"])
+    say(f"    gradients: err/bar " + " ".join(f"{k}:{worst[k]:.2g}" for k in KEYS) +
+        f"; {n_units} ReLU' bits equal to the reference's, {g['followed']} inside the rounding margin taken from "
+        f"the GPU ({g['flipped']} of them the other way)")
     return g
 
 
@@ -104,10 +147,12 @@ def run_case(gfnx, o32, o64, env, w, batch, seed, iteration, log_z, name, free_r
     say(f"[case {name}] batch={batch} seed={seed} iteration={iteration}")
     sess = gfnx.Session(env, w, batch)
     sess.rollout(seed, iteration)
+    traj = sess.trajectories()
+    relu = relu_decisions(sess, traj)
     sess.tb_loss_grad(log_z)
-    traj, grads = sess.trajectories(), sess.gradients()
+    grads = sess.gradients()
     ties = check_trajectories(o32, o64, env, w, seed, iteration, traj, free_run=free_run)
-    check_gradients(o64, env, w, traj, grads, log_z)
+    check_gradients(o64, env, w, traj, grads, log_z, relu)
     say(f"[case {name}] ok: {int(traj['length'].sum())} transitions, {ties} near-tie steps, loss {grads['loss']:.6g}")
     return sess, traj, grads
 
@@ -172,6 +217,12 @@ def _wide_cases():
         ("bitseq24k4_256", bitseq_env(24, 4, 7, mode_seed=2), (6 * 17, 256, 256, 16), 45),
         ("grid4x6_128_256", grid_env(4, 6), (24, 128, 256, 5), 70),
         ("grid4x6_256_64", grid_env(4, 6), (24, 256, 64, 5), 70),
+        # 512-wide: four layer-2 tiles per wave in the rollout, the split-contraction input-gradient kernel
+        ("bitseq24k4_512", bitseq_env(24, 4, 7, mode_seed=2), (6 * 17, 512, 512, 16), 150),
+        ("grid4x6_512_384", grid_env(4, 6), (24, 512, 384, 5), 70),
+        # Ising one-hot layer-1 gradient at 256 wide, 50 one-hot columns in use
+        ("ising5_256", ising_env(5), (75, 256, 256, 50), 40),
+        ("grid11x2_320_192", grid_env(2, 11), (22, 320, 192, 3), 300),
     ]
 
 
@@ -246,8 +297,10 @@ def test_trajectory_buffer_longer_than_the_environment_needs(gfnx, oracle32, ora
                           int(sess.terminal_state.data_ptr()), int(sess.log_pf.data_ptr()),
                           int(sess.log_pb.data_ptr()), int(sess.log_reward.data_ptr()))
     sess.rollout(15, 2)
+    traj = sess.trajectories()
+    relu = relu_decisions(sess, traj)
     sess.tb_loss_grad(0.3)
-    traj, grads = sess.trajectories(), sess.gradients()
+    grads = sess.gradients()
     assert (traj["actions"][sess.max_steps:] == 0xFF).all()
     ref = gfnx.Session(env, w, 90)
     ref.rollout(15, 2)
@@ -259,7 +312,7 @@ def test_trajectory_buffer_longer_than_the_environment_needs(gfnx, oracle32, ora
     for k in KEYS:
         assert np.array_equal(grads[k], g2[k])
     check_trajectories(oracle32, oracle64, env, w, 15, 2, traj)
-    check_gradients(oracle64, env, w, traj, grads, 0.3)
+    check_gradients(oracle64, env, w, traj, grads, 0.3, relu)
 
 
 def test_longest_supported_walks(gfnx, oracle32, oracle64):
@@ -349,12 +402,14 @@ def test_replay_of_all_trajectories_and_optimal_policy(gfnx, oracle64):
     wr = random_mlp(8, 64, 64, 3, seed=36, scale=3.0)
     sess.set_weights(wr)
     sess.replay(actions, length)
+    traj = sess.trajectories()
+    relu = relu_decisions(sess, traj)
     sess.tb_loss_grad(0.4)
-    traj, grads = sess.trajectories(), sess.gradients()
+    grads = sess.gradients()
     ref = oracle64.replay(env, wr, 0, 0, actions, length, tie_tol=1e30)
     for k in ("log_pf", "log_pb", "log_reward"):
         assert np.allclose(traj[k], ref[k], rtol=1e-4, atol=1e-5)
-    check_gradients(oracle64, env, wr, dict(actions=actions, length=length), grads, 0.4)
+    check_gradients(oracle64, env, wr, dict(actions=actions, length=length), grads, 0.4, relu)
 
 
 def test_sampler_reaches_reward_distribution_on_gpu(gfnx):
@@ -381,13 +436,18 @@ def _full_size(gfnx, o32, o64, name, sample, full_grad, iteration=0):
     say(f"[full {name}] batch={wl.batch} seed={wl.seed} iteration={iteration}")
     sess = gfnx.Session(wl.env, w, wl.batch)
     sess.rollout(wl.seed, iteration)
+    traj = sess.trajectories()
+    relu = relu_decisions(sess, traj) if full_grad else None
     sess.tb_loss_grad(wl.log_z)
-    traj, grads = sess.trajectories(), sess.gradients()
+    grads = sess.gradients()
     sd, _, na, ms = wl.env.dims()
     assert (traj["length"] >= 1).all() and (traj["length"] <= ms).all()
     ties = 0
-    for b0 in sample:  # contiguous column blocks, checked one by one against the reference
-        ties += check_trajectories(o32, o64, wl.env, w, wl.seed, iteration, traj, b0, min(b0 + 128, wl.batch))
+    if sample is None:  # every trajectory of the batch against the reference
+        ties = check_trajectories(o32, o64, wl.env, w, wl.seed, iteration, traj)
+    else:
+        for b0, b1 in sample:  # contiguous column blocks
+            ties += check_trajectories(o32, o64, wl.env, w, wl.seed, iteration, traj, b0, min(b1, wl.batch))
     # properties that hold at any size
     delta = wl.log_z + traj["log_pf"].astype(np.float64) - traj["log_reward"] - traj["log_pb"]
     assert abs(grads["loss"] - np.mean(delta ** 2)) <= 1e-4 * np.mean(delta ** 2) + 1e-6
@@ -400,33 +460,49 @@ def _full_size(gfnx, o32, o64, name, sample, full_grad, iteration=0):
     if wl.env.kind == 0:
         assert (traj["length"] == traj["terminal_state"].astype(int).sum(0) + 1).all()
     if full_grad:
-        check_gradients(o64, wl.env, w, traj, grads, wl.log_z)
-    say(f"[full {name}] ok: {int(traj['length'].sum())} transitions, {ties} near-tie steps in the sample")
+        check_gradients(o64, wl.env, w, traj, grads, wl.log_z, relu)
+    say(f"[full {name}] ok: {int(traj['length'].sum())} transitions, {ties} near-tie steps")
 
 
 def test_full_c2(gfnx, oracle32, oracle64):
-    _full_size(gfnx, oracle32, oracle64, "c2", sample=[0, 1931, 3968], full_grad=True)
+    _full_size(gfnx, oracle32, oracle64, "c2", sample=None, full_grad=True)
 
 
 def test_full_c2_long_walk(gfnx, oracle32, oracle64):
-    _full_size(gfnx, oracle32, oracle64, "c2_long", sample=[512], full_grad=True)
+    _full_size(gfnx, oracle32, oracle64, "c2_long", sample=None, full_grad=True)
 
 
 def test_full_c3(gfnx, oracle32, oracle64):
-    _full_size(gfnx, oracle32, oracle64, "c3", sample=[0, 3968], full_grad=True)
+    _full_size(gfnx, oracle32, oracle64, "c3", sample=None, full_grad=True)
 
 
 def test_full_c4(gfnx, oracle32, oracle64):
-    _full_size(gfnx, oracle32, oracle64, "c4", sample=[0, 2048], full_grad=True)
+    _full_size(gfnx, oracle32, oracle64, "c4", sample=None, full_grad=True)
 
 
 def test_full_c5(gfnx, oracle32, oracle64):
-    _full_size(gfnx, oracle32, oracle64, "c5", sample=[0, 7777, 16256], full_grad=True)
+    _full_size(gfnx, oracle32, oracle64, "c5", sample=None, full_grad=True)
 
 
 def test_full_c5_long_walk(gfnx, oracle32, oracle64):
     """3.1 M transitions: trajectories are checked on a sample; the gradient through the identities above
     (the full reference gradient at this size takes minutes on the host) and through the reduced batch below."""
-    _full_size(gfnx, oracle32, oracle64, "c5_long", sample=[4096], full_grad=False)
+    _full_size(gfnx, oracle32, oracle64, "c5_long", sample=[(0, 256), (4096, 4608), (16128, 16384)], full_grad=False)
     wl = workloads()["c5_long"]
     run_case(gfnx, oracle32, oracle64, wl.env, wl.mlp(), 256, wl.seed, 1, wl.log_z, "c5_long_b256", free_run=False)
+
+
+def test_grid_reward_on_the_thresholds_side11(gfnx, oracle32, oracle64):
+    """Side 11: x = 2, 8 sit exactly on |x/10 - 0.5| = 0.3 and x = 1, 9 on 0.4 (strict inequalities of the reward
+    equation: on the threshold means outside the band).  The batch must reach such cells, and every log-reward must
+    be the equation's value in exact rationals."""
+    env = grid_env(2, 11)
+    w = random_mlp(22, 64, 64, 3, seed=43, scale=1.0)
+    w["b3"][2] -= 2.0
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, 3000, seed=21, iteration=0, log_z=0.0, name="grid2x11")
+    ts = traj["terminal_state"].astype(int)
+    on_edge = np.isin(ts, (1, 2, 8, 9)).all(axis=0)
+    assert on_edge.sum() >= 20, int(on_edge.sum())
+    want = np.array([math.log(grid_reward((int(x), int(y)), 11)) for x, y in ts.T])
+    assert np.abs(traj["log_reward"] - want).max() < 1e-6
+    assert {round(float(v), 4) for v in traj["log_reward"][on_edge]} <= {round(math.log(1e-3), 4), round(math.log(0.501), 4)}

@@ -240,121 +240,3 @@ def test_training_converges_to_the_reward_distribution(gfnx, oracle64):
     from tests.helpers import grid_reward
     target = np.array([grid_reward((i, j), side) for i in range(side) for j in range(side)]) / 16.064
     assert 0.5 * np.abs(probs - target).sum() < 0.05
-
-
-def test_paper_hypergrid_experiment(gfnx):
-    """The paper's own hypergrid experiment (Appendix "Hypergrid"): 4-D grid of side 20, TB, MLP 2 x 256, batch 16,
-    Adam 1e-3 (1e-1 for log Z), 10^6 training trajectories; metric: total variation between R/Z and the empirical
-    distribution of the last 2 * 10^5 terminal states sampled during training, next to the same metric of a perfect
-    sampler (which is not zero at that sample size).  The run must reach the perfect sampler's level, and log Z the
-    closed-form log 5672."""
-    import torch
-    d, side, batch = 4, 20, 16
-    env = grid_env(d, side)
-    sess = gfnx.Session(env, xavier_mlp(d * side, 256, 256, d + 1, seed=7), batch)
-    sess.init_optimizer(log_z=0.0, lr=1e-3, lr_log_z=1e-1)
-    v = np.abs(np.arange(side) / (side - 1) - 0.5)
-    in1, in2 = (0.25 < v).astype(float), ((0.3 < v) & (v < 0.4)).astype(float)
-    reward = (1e-3 + 0.5 * np.einsum("a,b,c,d->abcd", in1, in1, in1, in1)
-              + 2.0 * np.einsum("a,b,c,d->abcd", in2, in2, in2, in2))
-    assert abs(reward.sum() - 5672.0) < 1e-6
-    target = (reward / reward.sum()).reshape(-1)
-
-    def tv_of(states):
-        idx = ((states[:, 0] * side + states[:, 1]) * side + states[:, 2]) * side + states[:, 3]
-        return 0.5 * np.abs(np.bincount(idx, minlength=side ** d) / len(idx) - target).sum()
-
-    keep = 200000 // batch
-    rng = np.random.default_rng(0)
-    perfect = np.stack(np.unravel_index(rng.choice(side ** d, size=keep * batch, p=target), (side,) * d), 1)
-    tv_perfect = tv_of(perfect)
-    ring = torch.zeros((keep, d, batch), dtype=torch.int8, device=sess.device)
-    iters = 1000000 // batch
-    tv_early = None
-    for it in range(iters):
-        sess.train_step(11, it)
-        ring[it % keep].copy_(sess.terminal_state)
-        if it + 1 == keep:
-            tv_early = tv_of(ring.permute(0, 2, 1).reshape(-1, d).cpu().numpy().astype(int))
-            say(f"[paper grid] after {it + 1} iterations: TV {tv_early:.3f}")
-    tv_final = tv_of(ring.permute(0, 2, 1).reshape(-1, d).cpu().numpy().astype(int))
-    log_z = float(sess.log_z.item())
-    say(f"[paper grid] TV of the last 2e5 terminal states {tv_final:.4f} (perfect sampler {tv_perfect:.4f}); "
-        f"log Z {log_z:.3f} (exact {math.log(5672):.3f})")
-    assert tv_early > 0.5
-    assert tv_final < tv_perfect + 0.02
-    assert abs(log_z - math.log(5672)) < 0.05
-
-
-def test_training_on_bit_sequences_reaches_the_reward_distribution(gfnx, oracle64):
-    """Left-to-right bit sequences small enough to enumerate (n = 12, k = 4: 4096 strings, one trajectory each): after
-    TB training, the exact P_theta(x) (teacher-forced log P_F of every string) is close to R/Z in total variation, the
-    log-probabilities correlate with the log-rewards (the paper's metric for this environment is that Pearson
-    correlation, Appendix "Bit sequences"), and log Z is the log of the true normalising constant."""
-    import itertools
-    from paper_2511_16592_amd.workloads import bitseq_env
-    env = bitseq_env(12, 4, 3, mode_seed=5, uniform_bits=True)
-    sd, od, na, ms = env.dims()
-    sess = gfnx.Session(env, xavier_mlp(od, 64, 64, na, seed=8), 64)
-    sess.init_optimizer(log_z=0.0)
-    allx = np.array(list(itertools.product(range(16), repeat=3)), dtype=np.uint8)
-    logr = np.array([oracle64.log_reward(env, list(map(int, x))) for x in allx])
-    log_z_true = float(np.logaddexp.reduce(logr))
-    target = np.exp(logr - log_z_true)
-    ev = gfnx.Session(env, sess.weights(), 4096)
-
-    def exact_log_p():
-        ev.set_weights(sess.weights())
-        ev.replay(np.ascontiguousarray(allx.T), np.full(4096, 3, np.int32))
-        return ev.trajectories()["log_pf"].astype(np.float64)
-
-    lp0 = exact_log_p()
-    assert abs(np.exp(lp0).sum() - 1.0) < 1e-5           # the policy's terminal distribution is normalised
-    tv0 = 0.5 * np.abs(np.exp(lp0) - target).sum()
-    for it in range(6000):
-        sess.train_step(3, it)
-    lp = exact_log_p()
-    tv = 0.5 * np.abs(np.exp(lp) - target).sum()
-    pearson = float(np.corrcoef(lp, logr)[0, 1])
-    log_z = float(sess.log_z.item())
-    say(f"[bitseq training] TV {tv0:.3f} -> {tv:.4f}; Pearson {pearson:.4f}; log Z {log_z:.3f} (true {log_z_true:.3f})")
-    assert tv0 > 0.1 and tv < 0.03
-    assert pearson > 0.99
-    assert abs(log_z - log_z_true) < 0.02
-
-
-def test_training_on_ising_with_estimated_terminal_probabilities(gfnx, oracle64):
-    """3 x 3 Ising assignments (512 terminal states, 9! orders each): after TB training, P_theta(x) of EVERY state,
-    estimated from 32 backward rollouts each (gfnx_backward_rollout + gfnx_replay + gfnx_log_prob_estimate), sums to
-    one, is close to R/Z and correlates with the log-reward."""
-    import itertools
-    env = ising_env(3)
-    sd, od, na, ms = env.dims()
-    sess = gfnx.Session(env, xavier_mlp(od, 64, 64, na, seed=9), 64)
-    sess.init_optimizer(log_z=0.0)
-    allx = np.array(list(itertools.product((-1, 1), repeat=9)), dtype=np.int8)
-    logr = np.array([oracle64.log_reward(env, list(map(int, x))) for x in allx])
-    log_z_true = float(np.logaddexp.reduce(logr))
-    target = np.exp(logr - log_z_true)
-    n_samples = 32
-    ev = gfnx.Session(env, sess.weights(), 512 * n_samples)
-
-    def estimated_log_p():
-        ev.set_weights(sess.weights())
-        return ev.estimate_log_prob(allx, n_samples, seed=4, iteration=0).cpu().numpy().astype(np.float64)
-
-    lp0 = estimated_log_p()
-    assert abs(np.exp(lp0).sum() - 1.0) < 0.03            # unbiased estimates of a normalised distribution
-    tv0 = 0.5 * np.abs(np.exp(lp0) - target).sum()
-    for it in range(6000):
-        sess.train_step(3, it)
-    lp = estimated_log_p()
-    tv = 0.5 * np.abs(np.exp(lp) - target).sum()
-    pearson = float(np.corrcoef(lp, logr)[0, 1])
-    log_z = float(sess.log_z.item())
-    say(f"[ising training] sum of estimates {np.exp(lp).sum():.4f}; TV {tv0:.3f} -> {tv:.4f}; Pearson {pearson:.4f}; "
-        f"log Z {log_z:.3f} (true {log_z_true:.3f})")
-    assert abs(np.exp(lp).sum() - 1.0) < 0.03
-    assert tv0 > 0.5 and tv < 0.06
-    assert pearson > 0.98
-    assert abs(log_z - log_z_true) < 0.06
