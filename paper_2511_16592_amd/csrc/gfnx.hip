@@ -138,6 +138,13 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   return GFNX_OK;
 }
 
+// Split parts of a weight-gradient contraction that can receive rows: a part holds at least three chunks of 32 rows
+// (split_chunks_per_part), so small batches need far fewer partial tiles than the S workgroups launched.
+inline size_t parts_in_use(const Shapes& s, int S) {
+  const size_t chunks = (s.rows + 31) / 32, most = (chunks + 2) / 3;
+  return most < (size_t)S ? (most ? most : 1) : (size_t)S;
+}
+
 Layout make_layout(const Shapes& s) {
   Layout L;
   size_t o = 0;
@@ -154,12 +161,13 @@ Layout make_layout(const Shapes& s) {
   L.m1 = o; o += align256(8 * s.rows * (size_t)s.mw1);
   L.m2 = o; o += align256(8 * s.rows * (size_t)s.mw2);
   L.sb = o; o += align256(s.rows * (size_t)s.sbytes);
-  L.part1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)s.s1 * s.p1 * s.qtot1 : 0);
-  L.dbp1 = o; o += align256(s.onehot ? sizeof(float) * (size_t)s.s1 * s.qtot1 : 0);
-  L.part2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.H1 * s.qtot2);
-  L.dbp2 = o; o += align256(sizeof(float) * (size_t)s.s2 * s.qtot2);
-  L.part3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.H2 * s.qtot3);
-  L.dbp3 = o; o += align256(sizeof(float) * (size_t)s.s3 * s.qtot3);
+  const size_t n1 = parts_in_use(s, s.s1), n2 = parts_in_use(s, s.s2), n3 = parts_in_use(s, s.s3);
+  L.part1 = o; o += align256(s.onehot ? sizeof(float) * n1 * s.p1 * s.qtot1 : 0);
+  L.dbp1 = o; o += align256(s.onehot ? sizeof(float) * n1 * s.qtot1 : 0);
+  L.part2 = o; o += align256(sizeof(float) * n2 * s.H1 * s.qtot2);
+  L.dbp2 = o; o += align256(sizeof(float) * n2 * s.qtot2);
+  L.part3 = o; o += align256(sizeof(float) * n3 * s.H2 * s.qtot3);
+  L.dbp3 = o; o += align256(sizeof(float) * n3 * s.qtot3);
   L.cs = o; o += align256(s.onehot ? 0 : sizeof(float) * (size_t)s.max_steps * s.H1);  // per-step column sums of G1
   L.phi = o; o += align256(s.flow ? sizeof(float) * s.rows : 0);
   L.dl = o; o += align256(s.flow ? sizeof(float) * s.rows : 0);
