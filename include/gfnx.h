@@ -271,6 +271,23 @@ int gfnx_train_step_opts(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* l
                          const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, const gfnx_train_opts* opts,
                          int64_t step, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* gfnx_train_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same training iteration with the workspace taken from a fixed array of
+ * GFNX_STATIC_SCRATCH_BYTES that is part of the library's device code (each GPU the library runs on holds its own copy
+ * until the process ends) instead of a caller-provided buffer.  The call itself allocates and frees nothing (keep
+ * gfnx_timing_enable off: the timing aid creates events).  Inputs, outputs, optimiser state and results are exactly
+ * those of gfnx_train_step; the calling thread's current device must be the one that holds the buffers.
+ * Limits: gfnx_workspace_bytes(env, mlp, traj->batch) must not exceed GFNX_STATIC_SCRATCH_BYTES, else
+ * GFNX_E_WORKSPACE is returned before anything is launched (64 MiB hold batches of 16 to 64 trajectories of every
+ * configuration of the paper's three environments).  Every call on a GPU uses that GPU's one array, whose contents
+ * are whatever the previous call left (nothing in it has to start at zero: each call writes what it reads): calls
+ * that overlap on one GPU, on any streams, race; calls in stream order do not.
+ * Errors: as gfnx_train_step; GFNX_E_WORKSPACE as above; GFNX_E_HIP if the array's address cannot be obtained. */
+#define GFNX_STATIC_SCRATCH_BYTES (64u << 20)
+int gfnx_train_step_static(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                           uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                           const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* hip_stream);
+
 /* Measurement aid (not part of the method; not thread-safe).  While enabled, every kernel (or small group
  * of kernels) the library launches is bracketed by HIP events recorded on the launch stream, labelled
  * "rollout", "gemm_tn_w2", ...  gfnx_timing_enable(on) also discards the records taken so far;

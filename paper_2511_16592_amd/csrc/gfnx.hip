@@ -12,6 +12,7 @@
 #include "rollout_kernel.h"
 
 #include <cmath>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -208,6 +209,27 @@ EnvParams env_params(const gfnx_env_desc* env, const Shapes& s) {
 
 template <typename T>
 inline T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
+
+// Workspace of the entry point that allocates nothing (gfnx_train_step_static): device memory that is part of the
+// loaded code object, one copy per GPU at that GPU's own address.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the device address is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[GFNX_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GFNX_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return GFNX_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return GFNX_OK;
+}
 
 // Raises a kernel's dynamic-LDS limit; the runtime call is made once per kernel instantiation and size (the
 // largest size asked for so far is remembered per call site through `granted`).
@@ -761,6 +783,25 @@ int gfnx_train_step(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_
   const gfnx_train_opts opts = {0.f, -1.f};
   return gfnx_train_step_opts(env, mlp, log_z_dev, seed, iteration, traj, loss_dev, dlogz_dev, grads, state, cfg, &opts,
                               step, ws, ws_bytes, hip_stream);
+}
+
+int gfnx_train_step_static(const gfnx_env_desc* env, const gfnx_mlp* mlp, float* log_z_dev, uint64_t seed,
+                           uint64_t iteration, gfnx_traj* traj, float* loss_dev, float* dlogz_dev, gfnx_mlp_grad* grads,
+                           const gfnx_adam_state* state, const gfnx_adam_cfg* cfg, int64_t step, void* hip_stream) {
+  // the size is checked on the host before the runtime is touched
+  if (!env || !mlp || !traj) return GFNX_E_NULL;
+  const size_t need = gfnx_workspace_bytes(env, mlp, traj->batch);
+  if (need == 0) {  // let the shape checks name the error
+    Shapes s;
+    const int rc = check_shapes(env, mlp, traj->batch, &s);
+    return rc ? rc : GFNX_E_BAD_SHAPE;
+  }
+  if (need > (size_t)GFNX_STATIC_SCRATCH_BYTES) return GFNX_E_WORKSPACE;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc) return rc;
+  return gfnx_train_step(env, mlp, log_z_dev, seed, iteration, traj, loss_dev, dlogz_dev, grads, state, cfg, step, ws,
+                         (size_t)GFNX_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int gfnx_timing_enable(int on) {

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgfnx_hip.so")
 GFNX_OK = 0
 EXPORTS = ("gfnx_env_dims", "gfnx_workspace_bytes", "gfnx_workspace_region", "gfnx_rollout", "gfnx_rollout_explore", "gfnx_replay",
            "gfnx_tb_loss_grad", "gfnx_subtb_loss_grad",
-           "gfnx_adam_step", "gfnx_train_step", "gfnx_train_step_opts", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
+           "gfnx_adam_step", "gfnx_train_step", "gfnx_train_step_opts", "gfnx_train_step_static", "gfnx_backward_rollout", "gfnx_log_prob_estimate",
            "gfnx_status_string", "gfnx_timing_enable", "gfnx_timing_only", "gfnx_timing_labels", "gfnx_timing_get")
 
 
@@ -108,6 +108,10 @@ def load_library() -> C.CDLL:
                                         C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
                                         C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p, C.c_size_t,
                                         C.c_void_p]
+        lib.gfnx_train_step_static.restype = C.c_int
+        lib.gfnx_train_step_static.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_void_p, C.c_uint64, C.c_uint64,
+                                               C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
+                                               C.POINTER(AdamState), C.POINTER(AdamCfg), C.c_int64, C.c_void_p]
         lib.gfnx_train_step_opts.restype = C.c_int
         lib.gfnx_train_step_opts.argtypes = [C.POINTER(EnvDesc), C.POINTER(Mlp), C.c_void_p, C.c_uint64, C.c_uint64,
                                              C.POINTER(Traj), C.c_void_p, C.c_void_p, C.POINTER(MlpGrad),
@@ -322,6 +326,14 @@ class Session:
                                              C.byref(self.cgrads), C.byref(self.adam_state), C.byref(self.adam_cfg),
                                              C.byref(opts), self.updates, _ptr(self.workspace), self.workspace_bytes,
                                              self._stream()))
+
+    def train_step_static(self, seed: int, iteration: int) -> None:
+        """train_step on the library's own fixed scratch array (gfnx_train_step_static): no workspace is passed."""
+        self.updates += 1
+        _check(self.lib.gfnx_train_step_static(C.byref(self.desc), C.byref(self.mlp), _ptr(self.log_z), seed,
+                                               iteration, C.byref(self.traj), _ptr(self.loss), _ptr(self.dlogz),
+                                               C.byref(self.cgrads), C.byref(self.adam_state), C.byref(self.adam_cfg),
+                                               self.updates, self._stream()))
 
     def weights(self) -> Dict:
         """Host copies (numpy) of the six weight tensors."""

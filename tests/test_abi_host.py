@@ -230,3 +230,24 @@ def test_workspace_regions(lib):
         assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), batch, 0, None, C.byref(rb)) == -1
         assert lib.gfnx_workspace_region(C.byref(d), C.byref(m), 0, 0, C.byref(off), C.byref(rb)) == -3
     assert lib.gfnx_workspace_region(None, C.byref(_mlp(16, 64, 64, 3)), 4, 0, C.byref(off), C.byref(rb)) == -1
+
+
+def test_static_scratch_entry_point_rejects_oversize_on_the_host(lib):
+    """gfnx_train_step_static: a configuration whose workspace exceeds the fixed 64 MiB array is refused with
+    GFNX_E_WORKSPACE before the runtime is touched (so this runs without a GPU); NULL and shape errors come first."""
+    env = ising_env(10)
+    d = gfnx.env_desc(env)
+    m = _mlp(300, 256, 256, 200)
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 4096) > (64 << 20)
+    t = _traj(4096, 100)
+    g = gfnx.MlpGrad(*[0x1000] * 6)
+    st = gfnx.AdamState(g, g, 0x1000)
+    cfg = gfnx.AdamCfg(1e-3, 1e-1, 0.9, 0.999, 1e-8)
+    call = lambda dd, mm, tt: lib.gfnx_train_step_static(dd, mm, 0x1000, 0, 0, tt, 0x1000, 0x1000, C.byref(g),
+                                                          C.byref(st), C.byref(cfg), 1, None)
+    assert call(C.byref(d), C.byref(m), C.byref(t)) == -4
+    assert call(None, C.byref(m), C.byref(t)) == -1
+    assert call(C.byref(d), C.byref(m), None) == -1
+    assert call(C.byref(d), C.byref(_mlp(299, 256, 256, 200)), C.byref(t)) == -3
+    small = _traj(16, 100)
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 16) <= (64 << 20)
