@@ -71,7 +71,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t hdr, w2p, w3p, w2t, w3t, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
   size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
   size_t total;
 };
@@ -154,6 +154,7 @@ Layout make_layout(const Shapes& s) {
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
   L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T, W3^T for the gradient pass
   L.w3t = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
+  L.d1 = o; o += align256(sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1 (rollout)
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
@@ -250,7 +251,8 @@ int rollout_state_pitch(const Shapes& s) {
 }
 
 size_t rollout_lds_bytes(const Shapes& s, bool grid) {
-  return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), s.H1 == 256 && s.H2 == 256, grid).total;
+  const bool stat = s.H1 == 256 && s.H2 == 256;
+  return (size_t)rollout_lds_layout(s.H1, s.H2, s.A16, rollout_state_pitch(s), stat, grid && stat).total;
 }
 
 template <int ENV, bool REPLAY, int NCH, bool EXPLORE>
@@ -309,6 +311,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   p.In = s.obs_dim; p.H1 = s.H1; p.H2 = s.H2; p.A = s.A; p.A16 = s.A16;
   p.W1 = mlp->W1; p.b1 = mlp->b1; p.b2 = mlp->b2; p.b3 = mlp->b3;
   p.W2p = at<float>(ws, L.w2p); p.W3p = at<float>(ws, L.w3p);
+  p.D1 = at<double>(ws, L.d1);
   p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
   p.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFull);
   p.B = s.B; p.T = traj->max_steps;
@@ -339,7 +342,11 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
     // packed and transposed weights, and (free-running rollout) every action byte preset to the 0xFF padding
     GFNX_TIMED("prepare", st);
     PrepareParams pp = {};
-    pp.W2 = mlp->W2; pp.W3 = mlp->W3; pp.H1 = s.H1; pp.H2 = s.H2; pp.A = s.A; pp.A16 = s.A16;
+    pp.W1 = mlp->W1; pp.W2 = mlp->W2; pp.W3 = mlp->W3;
+    pp.In = s.obs_dim; pp.H1 = s.H1; pp.H2 = s.H2; pp.A = s.A; pp.A16 = s.A16;
+    pp.D1 = at<double>(ws, L.d1);
+    pp.kind = env->kind;
+    pp.group = env->kind == GFNX_ENV_GRID ? env->grid_side : (env->kind == GFNX_ENV_BITSEQ ? (1 << env->k_bits) + 1 : 3);
     pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
     pp.W2t = at<float>(ws, L.w2t); pp.W3t = at<float>(ws, L.w3t);
     pp.actions = replay ? nullptr : traj->actions;

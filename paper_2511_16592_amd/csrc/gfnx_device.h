@@ -8,6 +8,7 @@ namespace gfnx {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kSlots = 16;         // trajectories per workgroup of the rollout kernel (one MFMA N-tile)
 constexpr int kPitch = 68;         // floats per feature-quad row of an activation tile in LDS (16 slots * 4 + 4 pad)
@@ -30,6 +31,7 @@ struct RolloutParams {
   int In, H1, H2, A, A16;
   const float *W1, *b1, *b2, *b3;
   const float *W2p, *W3p;  // weights re-laid-out as MFMA A-operands
+  const double* D1;        // [In][H1] difference rows of layer 1: W1[r] - W1[row that r replaces], binary64
   uint32_t seed_lo, seed_hi, iter_lo;
   int B, T;  // batch, traj.max_steps
   int tpw;   // trajectories owned by one workgroup (multiple of kSlots)

@@ -16,7 +16,8 @@
 //       rotations plus one swizzle, log P_F / log P_B, the row of the logit gradient, environment
 //       transition, terminal log-reward, action byte; then the same lanes update the layer-1
 //       pre-activation: layer 1 is a one-hot gather and a transition swaps exactly one active row, so z1 is
-//       kept in LDS (as a high + low pair) and updated as z1 += W1[new] - W1[old].
+//       kept in LDS in binary64 and updated as z1 += (W1[new] - W1[old]), the difference rows prepared once per
+//       rollout in binary64; what the matrix phase reads is h1 = relu((float)z1), written next to it.
 // The post-ReLU activations h1, h2, their sign masks (1 bit per unit; those of h2 only where the gradient pass
 // reads them), the state bytes and the logit-gradient direction (onehot(a) - p) of every transition are written to
 // HBM rows t*B + b for the gradient pass.  Nothing the kernel writes to global memory is read back by it, so the
@@ -102,19 +103,20 @@ constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile 
 
 // Byte offsets of the kernel's LDS regions (shared by the launch code, which sizes the allocation).
 struct RolloutLds {
-  int z1s, z1s2, z1l, h2s, lgs, z1i, flags, st, w2l, total;
+  int h1s, h1s2, z1d, h2s, lgs, z1i, flags, st, w2l, total;
 };
-// grid: the high part of z1 is double-buffered (read by the step in progress, written for the next one)
-__host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16, int SBL, bool stat, bool grid) {
+constexpr int kPitchD = 66;  // doubles per feature-quad row of the binary64 z1 tile (16 slots * 4 + 2 pad: conflict-free)
+// rows2: h1 is double-buffered (read by the step in progress, written for the next one)
+__host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16, int SBL, bool stat, bool rows2) {
   const int ks = logits_ksplit(A16 >> 4, H2 >> 4);
   RolloutLds L;
   int o = 0;
-  L.z1s = o; o += (H1 >> 2) * kPitch * 4;            // pre-activation of layer 1, high part
-  L.z1s2 = grid ? o : L.z1s; if (grid) o += (H1 >> 2) * kPitch * 4;
-  L.z1l = o; o += (H1 >> 2) * kPitch * 4;            // ... low part (z1 = hi + lo carries the sum to ~48 bits)
+  L.h1s = o; o += (H1 >> 2) * kPitch * 4;            // h1 = relu(z1) in binary32, B-operand order
+  L.h1s2 = rows2 ? o : L.h1s; if (rows2) o += (H1 >> 2) * kPitch * 4;
+  L.z1d = o; o += (H1 >> 2) * kPitchD * 8;           // pre-activation of layer 1 in binary64
   L.h2s = o; o += (H2 >> 2) * kPitch * 4;
   L.lgs = o; o += ks * (A16 >> 2) * kPitch * 4;      // [KS][A16 / 4] partial logits
-  L.z1i = o; o += 2 * H1 * 4;                        // z1(s_0): high and low parts, for slots that restart
+  L.z1i = o; o += H1 * 8;                            // z1(s_0) in binary64, for slots that restart
   L.flags = o; o += (kSlots + 4) * 4;                // srow[kSlots], qnext, live
   L.st = o; o += kSlots * SBL;                       // state bytes, SBL per slot (a multiple of 16)
   L.w2l = o; if (stat) o += (16 - kW2RegQ) * 16 * 64 * 16;  // 16 tiles x (16 - kW2RegQ) steps x 64 lanes x 16 bytes
@@ -140,13 +142,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   const int NT2 = H2 >> 4, NT3 = A16 >> 4, nchunk = A16 >> 2;
   const int KS = logits_ksplit(NT3, Q2);
 
-  const RolloutLds L = rollout_lds_layout(H1, H2, A16, SBL, STAT, ENV == 0);
-  float* z1a = (float*)(smem_raw + L.z1s);
-  float* z1b = (float*)(smem_raw + L.z1s2);
-  float* z1l = (float*)(smem_raw + L.z1l);
+  const RolloutLds L = rollout_lds_layout(H1, H2, A16, SBL, STAT, ENV == 0 && STAT);
+  float* z1a = (float*)(smem_raw + L.h1s);
+  float* z1b = (float*)(smem_raw + L.h1s2);
+  double* z1d = (double*)(smem_raw + L.z1d);
   float* h2s = (float*)(smem_raw + L.h2s);
   float* lgs = (float*)(smem_raw + L.lgs);
-  float* z1i = (float*)(smem_raw + L.z1i);
+  double* z1i = (double*)(smem_raw + L.z1i);
   int* srow = (int*)(smem_raw + L.flags);     // [kSlots] row t*B + b of the slot's current transition
   int* qnext = srow + kSlots;                 // next trajectory of this workgroup's range to start
   uint32_t* live = (uint32_t*)(qnext + 1);    // bit j: slot j is running a trajectory
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   // Grids: SU occupies four of the eight waves, so the other four write the h1 rows and sign masks of the step during
   // SU instead of all eight doing it at the head of the L2 phase.  They read the z1 the step was computed from while
   // SU writes the next one, hence the two buffers (z1a / z1b, swapped every step; one buffer otherwise).
-  constexpr bool kRowsInSU = ENV == 0;
+  constexpr bool kRowsInSU = ENV == 0 && STAT;
   constexpr bool kTail = STAT && ENV == 0;
   constexpr int kTailSlots = 4;
   constexpr int LPS = ENV == 0 ? 16 : 32;
@@ -176,18 +178,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   for (int f = tid; f < H1; f += kRolloutThreads) {
     double z = (double)p.b1[f];
     for (int s = 0; s < e.state_dim; ++s) z += (double)p.W1[(size_t)initial_row<ENV>(e, s) * H1 + f];
-    const float hi = (float)z, lo = (float)(z - (double)hi);
+    const float h = relu1((float)z);
     float* dh = z1a + (f >> 2) * kPitch + (f & 3);
     float* dh2 = z1b + (f >> 2) * kPitch + (f & 3);
-    float* dl = z1l + (f >> 2) * kPitch + (f & 3);
+    double* dz = z1d + (f >> 2) * kPitchD + (f & 3);
 #pragma unroll
-    for (int j = 0; j < kSlots; ++j) { dh[j * 4] = hi; dh2[j * 4] = hi; dl[j * 4] = lo; }
-    z1i[f] = hi;
-    z1i[H1 + f] = lo;
+    for (int j = 0; j < kSlots; ++j) { dh[j * 4] = h; dh2[j * 4] = h; dz[j * 4] = z; }
+    z1i[f] = z;
   }
   for (int i = tid; 4 * i < SBL * kSlots; i += kRolloutThreads) ((uint32_t*)st)[i] = 0u;
-  if constexpr (kTail)  // the four-slot path reads back whole h2 tiles of which it has written four columns
-    for (int i = tid; i < (H2 >> 2) * kPitch; i += kRolloutThreads) h2s[i] = 0.f;
   if (tid < kSlots) srow[tid] = b0 + tid;
   if (tid == 0) {
     *qnext = b0 + kSlots;
@@ -255,7 +254,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     sr[0] = srow[w]; sr[1] = srow[w + 8];
     my_alive = (live_mask >> j16) & 1u; my_row = srow[j16];
     su_alive = (live_mask >> sj) & 1u;
-    const float* z1s = (iter & 1) ? z1b : z1a;  // z1 of this step
+    const float* z1s = (iter & 1) ? z1b : z1a;  // h1 of this step
     float* z1n = (iter & 1) ? z1a : z1b;        // ... of the next one (the same buffer unless double-buffered)
     int srk[4];                                 // rows of the four slots a non-SU wave writes out on grids
 #pragma unroll
@@ -271,7 +270,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         const int fg = lane + 64 * it;
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (fg < (H1 >> 2)) {
-          v = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
+          v = *(const f32x4*)&z1s[fg * kPitch + jj * 4];
           *(f32x4*)&dst[fg * 4] = v;
         }
         store_sign_mask(p.m1buf + (row * p.MW1 + 4 * it), v, lane);
@@ -289,7 +288,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         // activations this lane feeds it.
 #define GFNX_L2_STEP(NEXT_READS, MFMA4, SLOT, ACC0, ACC1)                                                      \
         {                                                                                            \
-          const f32x4 bv = relu4(bvn);                                                               \
+          const f32x4 bv = bvn;                                                                      \
           if (q + 1 < 16) bvn = *(const f32x4*)&z1s[(4 * (q + 1) + g) * kPitch + (SLOT) * 4];        \
           f32x4 a0, a1;                                                                              \
           if (q < kW2RegQ) {                                                                         \
@@ -303,7 +302,6 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           MFMA4(ACC1, a1, bv);                                                                       \
           __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                                \
           __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                         \
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0); /* relu of the next step's activations */ \
         }
         bool tail = false;
         if constexpr (kTail) tail = __popc(live_mask) <= kTailSlots;  // the same in every wave
@@ -313,49 +311,82 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           // Fed with the same resident W2 operands, lane l = 16 g + 4 m + j therefore accumulates, for the slot it
           // picks for j, units 16 tile + 4 m + r over the contraction indices of lane group g; the four groups
           // are summed across lanes, the four columns go to LDS and come back in the layout of the 16-slot path.
-          int jj = lane & 3;
-          if (jj >= __popc(live_mask)) jj = 0;
+          // the (at most four) running slots, found on the scalar unit; lanes beyond their number repeat the first
           uint32_t wd = live_mask;
-          int sl = 0;  // jj-th running slot
-          int c = __popc(wd & 0xFFu); if (jj >= c) { jj -= c; sl += 8; wd >>= 8; }
-          c = __popc(wd & 0xFu); if (jj >= c) { jj -= c; sl += 4; wd >>= 4; }
-          c = __popc(wd & 0x3u); if (jj >= c) { jj -= c; sl += 2; wd >>= 2; }
-          if (jj >= (int)(wd & 1u)) sl += 1;
-          f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + sl * 4];
+          const int s0 = __builtin_ctz(wd);
+          wd &= wd - 1u;
+          const int s1 = wd ? __builtin_ctz(wd) : s0;
+          wd = wd ? (wd & (wd - 1u)) : 0u;
+          const int s2 = wd ? __builtin_ctz(wd) : s0;
+          wd = wd ? (wd & (wd - 1u)) : 0u;
+          const int s3 = wd ? __builtin_ctz(wd) : s0;
+          const int jj = lane & 3;
+          const int sl = jj == 0 ? s0 : (jj == 1 ? s1 : (jj == 2 ? s2 : s3));  // jj-th running slot
+          // The 4x4x1 instruction occupies the pipe for 8 cycles, so the activations are requested two contraction
+          // steps (128 cycles of matrix work) ahead of their use, and dependent instructions are four apart: the
+          // two accumulators of a tile alternate, and the two tiles alternate inside each pair.
           f32x4 ta0 = {0.f, 0.f, 0.f, 0.f}, ta0b = ta0, ta1 = ta0, ta1b = ta0;
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          f32x4 raw1 = *(const f32x4*)&z1s[(4 + g) * kPitch + sl * 4];
+          f32x4 bv = *(const f32x4*)&z1s[g * kPitch + sl * 4];
+#define GFNX_TAIL_STEP(NEXT_READS)                                                                    \
+          {                                                                                           \
+            f32x4 raw2 = raw1;                                                                        \
+            if (q + 2 < 16) raw2 = *(const f32x4*)&z1s[(4 * (q + 2) + g) * kPitch + sl * 4];          \
+            f32x4 a0, a1;                                                                             \
+            if (q < kW2RegQ) {                                                                        \
+              a0 = w2r[0][q];                                                                         \
+              a1 = w2r[1][q];                                                                         \
+            } else {                                                                                  \
+              a0 = wl[(q - kW2RegQ) * 64];                                                            \
+              a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];                                         \
+            }                                                                                         \
+            ta0 = __builtin_amdgcn_mfma_f32_4x4x1f32(a0.x, bv.x, ta0, 0, 0, 0);                       \
+            ta1 = __builtin_amdgcn_mfma_f32_4x4x1f32(a1.x, bv.x, ta1, 0, 0, 0);                       \
+            ta0b = __builtin_amdgcn_mfma_f32_4x4x1f32(a0.y, bv.y, ta0b, 0, 0, 0);                     \
+            ta1b = __builtin_amdgcn_mfma_f32_4x4x1f32(a1.y, bv.y, ta1b, 0, 0, 0);                     \
+            ta0 = __builtin_amdgcn_mfma_f32_4x4x1f32(a0.z, bv.z, ta0, 0, 0, 0);                       \
+            ta1 = __builtin_amdgcn_mfma_f32_4x4x1f32(a1.z, bv.z, ta1, 0, 0, 0);                       \
+            ta0b = __builtin_amdgcn_mfma_f32_4x4x1f32(a0.w, bv.w, ta0b, 0, 0, 0);                     \
+            ta1b = __builtin_amdgcn_mfma_f32_4x4x1f32(a1.w, bv.w, ta1b, 0, 0, 0);                     \
+            bv = raw1;                                                                                \
+            raw1 = raw2;                                                                              \
+            /* issue order: the LDS reads placed ahead (activations of step q + 2, LDS-resident weights of */ \
+            /* step q + 1), then this step's eight matrix instructions */                               \
+            __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                               \
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                        \
+          }
 #pragma unroll
-          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4S, sl, ta0, ta1)
+          for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_TAIL_STEP(1)
 #pragma unroll
-          for (int q = kW2RegQ - 1; q < 15; ++q) GFNX_L2_STEP(3, GFNX_MFMA4S, sl, ta0, ta1)
+          for (int q = kW2RegQ - 1; q < 14; ++q) GFNX_TAIL_STEP(3)
+          {
+            constexpr int q = 14;
+            GFNX_TAIL_STEP(2)
+          }
           {
             constexpr int q = 15;
-            GFNX_L2_STEP(0, GFNX_MFMA4S, sl, ta0, ta1)
+            GFNX_TAIL_STEP(0)
           }
+#undef GFNX_TAIL_STEP
           acc[0] = ta0 + ta0b;
           acc[1] = ta1 + ta1b;
+          // The four partial sums (one per lane group g) meet in this wave's own 2 KiB of the h2 tile: every lane
+          // writes its partial columns, [tile][g][unit quad m][slot jj] (linear in the lane index), and reads, in
+          // the layout of the 16-slot path, the four parts of (unit quad g, slot j16): rank of slot j16 among the
+          // running ones (a slot that is not running reads some running slot's column; its results are unused).
+          f32x4* part = (f32x4*)(h2s + 8 * w * kPitch);  // (the rows of the h2 tile that this wave owns)
 #pragma unroll
-          for (int n = 0; n < 2; ++n)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              float v = acc[n][r];
-              v += __shfl_xor(v, 16);
-              v += __shfl_xor(v, 32);
-              acc[n][r] = v;
-            }
-          const int m4 = (lane >> 2) & 3;
-          if (g == 0) {
-#pragma unroll
-            for (int n = 0; n < 2; ++n) *(f32x4*)&h2s[(4 * (2 * w + n) + m4) * kPitch + sl * 4] = acc[n];
-          }
+          for (int n = 0; n < 2; ++n) part[n * 64 + lane] = acc[n];
+          const int rk = min(__popc(live_mask & ((1u << j16) - 1u)), 3);
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's own columns, written above
 #pragma unroll
-          for (int n = 0; n < 2; ++n) acc[n] = *(const f32x4*)&h2s[(4 * (2 * w + n) + g) * kPitch + j16 * 4];
+          for (int n = 0; n < 2; ++n) {
+            const f32x4* src = part + n * 64 + 4 * g + rk;
+            acc[n] = (src[0] + src[16]) + (src[32] + src[48]);
+          }
         } else {
           f32x4 bvn = *(const f32x4*)&z1s[g * kPitch + j16 * 4];
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the read of step 0 above
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // and its relu
 #pragma unroll
           for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_L2_STEP(1, GFNX_MFMA4, j16, acc[0], acc[1])
 #pragma unroll
@@ -390,7 +421,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             const int qn = min(q + 2, Q1 - 1);
 #pragma unroll
             for (int n = 0; n < NTW; ++n) r[d][n] = wt[n][qn * 64];
-            const f32x4 bv = relu4(bvn);
+            const f32x4 bv = bvn;
             bvn = *(const f32x4*)&z1s[(4 * min(q + 1, Q1 - 1) + g) * kPitch + j16 * 4];
 #pragma unroll
             for (int n = 0; n < NTW; ++n) acc[n] = mfma16(cur[n].x, bv.x, acc[n]);
@@ -403,7 +434,6 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             __builtin_amdgcn_sched_group_barrier(0x020, NTW, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * NTW, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
           }
         }
       }
@@ -552,7 +582,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           const int fg = lane + 64 * it;
           f32x4 v = {0.f, 0.f, 0.f, 0.f};
           if (fg < (H1 >> 2)) {
-            v = relu4(*(const f32x4*)&z1s[fg * kPitch + jj * 4]);
+            v = *(const f32x4*)&z1s[fg * kPitch + jj * 4];
             *(f32x4*)&dst[fg * 4] = v;
           }
           store_sign_mask(p.m1buf + (row * p.MW1 + 4 * it), v, lane);
@@ -745,13 +775,17 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           rnew = 3 * (act >> 1) + 2 * (act & 1);
         }
       }
-      constexpr int kPre = 64 / LPS;  // W1 row pieces requested early: all of a 256-wide layer
-      f32x4 wo[kPre], wn[kPre];
+      // pieces of the difference row W1[rnew] - W1[rold] (binary64, indexed by rnew) requested early: all of a
+      // 256-wide layer
+      constexpr int kPre = 64 / LPS;
+      f64x2 da[kPre], db[kPre];
+      (void)rold;
 #pragma unroll
       for (int it = 0; it < kPre; ++it) {
         const int fg = min(si + LPS * it, (H1 >> 2) - 1);
-        wo[it] = *(const f32x4*)&p.W1[(size_t)rold * H1 + 4 * fg];
-        wn[it] = *(const f32x4*)&p.W1[(size_t)rnew * H1 + 4 * fg];
+        const f64x2* dp = (const f64x2*)&p.D1[(size_t)rnew * H1 + 4 * fg];
+        da[it] = dp[0];
+        db[it] = dp[1];
       }
 
       {  // direction of the logit gradient: onehot(a) - p on valid actions, 0 elsewhere (weight 0 there)
@@ -792,7 +826,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           const int bad1 = grp_sum<LPS>((si < e.d && !(hm < q4)) ? 1 : 0);
           const int bad2 = grp_sum<LPS>((si < e.d && !((3 * hm < q10) && (q10 < 4 * hm))) ? 1 : 0);
           const float r = e.r0 + e.r1 * (bad1 == 0 ? 1.f : 0.f) + e.r2 * (bad2 == 0 ? 1.f : 0.f);
-          logr = logf(r);
+          logr = __builtin_amdgcn_logf(r) * 0.693147180559945f;  // hardware log2: |error| ~1e-6 on |log R| <= 7
           term = true;
         }
       } else if (ENV == 1) {
@@ -866,8 +900,12 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           if (REPLAY) len_given = p.length[sb];
           for (int s4 = si; 4 * s4 < SBL; s4 += LPS) ((uint32_t*)stj)[s4] = 0u;
           for (int fg = si; fg < (H1 >> 2); fg += LPS) {
-            *(f32x4*)&z1n[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[4 * fg];
-            *(f32x4*)&z1l[fg * kPitch + sj * 4] = *(const f32x4*)&z1i[H1 + 4 * fg];
+            const f64x2 a = ((const f64x2*)&z1i[4 * fg])[0], b = ((const f64x2*)&z1i[4 * fg])[1];
+            f64x2* zp = (f64x2*)&z1d[fg * kPitchD + sj * 4];
+            zp[0] = a;
+            zp[1] = b;
+            *(f32x4*)&z1n[fg * kPitch + sj * 4] =
+                (f32x4){relu1((float)a.x), relu1((float)a.y), relu1((float)b.x), relu1((float)b.y)};
           }
           if (si == 0) srow[sj] = sb;
         } else if (si == 0) {
@@ -876,51 +914,68 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
       } else {
         ts = t + 1;
         if (si == 0) srow[sj] = ts * B + sb;
-        // z1 += W1[new row] - W1[old row] for this slot; the running sum is carried as hi + lo so that,
-        // however long the walk, relu and its derivative see the correctly rounded sum of the active rows
-        const float* wo_row = p.W1 + (size_t)rold * H1;
-        const float* wn_row = p.W1 + (size_t)rnew * H1;
-        auto update = [&](int fg, f32x4 o, f32x4 n) {
-          f32x4* lp = (f32x4*)&z1l[fg * kPitch + sj * 4];
-          f32x4 hi = *(const f32x4*)&z1s[fg * kPitch + sj * 4], lo = *lp;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const double z = ((double)hi[k] + (double)lo[k]) - (double)o[k] + (double)n[k];
-            hi[k] = (float)z;
-            lo[k] = (float)(z - (double)hi[k]);
-          }
-          *(f32x4*)&z1n[fg * kPitch + sj * 4] = hi;
-          *lp = lo;
+        // z1 += W1[new row] - W1[old row] for this slot, in binary64 (the difference row comes prepared): however
+        // long the walk, relu and its derivative see the correctly rounded sum of the active rows
+        auto update = [&](int fg, f64x2 a, f64x2 b) {
+          f64x2* zp = (f64x2*)&z1d[fg * kPitchD + sj * 4];
+          const f64x2 z0 = zp[0] + a, z1 = zp[1] + b;
+          zp[0] = z0;
+          zp[1] = z1;
+          *(f32x4*)&z1n[fg * kPitch + sj * 4] =
+              (f32x4){relu1((float)z0.x), relu1((float)z0.y), relu1((float)z1.x), relu1((float)z1.y)};
         };
 #pragma unroll
         for (int it = 0; it < kPre; ++it)
-          if (si + LPS * it < (H1 >> 2)) update(si + LPS * it, wo[it], wn[it]);
-        for (int fg = si + LPS * kPre; fg < (H1 >> 2); fg += LPS)
-          update(fg, *(const f32x4*)&wo_row[4 * fg], *(const f32x4*)&wn_row[4 * fg]);
+          if (si + LPS * it < (H1 >> 2)) update(si + LPS * it, da[it], db[it]);
+        for (int fg = si + LPS * kPre; fg < (H1 >> 2); fg += LPS) {
+          const f64x2* dp = (const f64x2*)&p.D1[(size_t)rnew * H1 + 4 * fg];
+          update(fg, dp[0], dp[1]);
+        }
       }
-      // the W1 rows were requested on every path but are consumed only when the trajectory goes on: read them
+      // the difference rows were requested on every path but are consumed only when the trajectory goes on: read them
       // here, so that the wait for these loads (not for the stores issued after them) closes the phase and the
       // next phase does not start by waiting for everything outstanding
 #pragma unroll
-      for (int it = 0; it < kPre; ++it) asm volatile("" ::"v"(wo[it]), "v"(wn[it]));
+      for (int it = 0; it < kPre; ++it) asm volatile("" ::"v"(da[it]), "v"(db[it]));
     }
     lds_barrier();
   }
 }
 
-// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 32 / 64
-// blocks of 256 threads):
+// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 32 / 64 / 512
+// blocks of 256 threads; the last range writes the difference rows of layer 1, see difference_rows_part):
 //   W2p, W3p  W[K][N] row-major -> MFMA A-operand order, out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
 //             zero beyond column N (the rollout's layer-2 and logit weights);
 //   W2t, W3t  transposes Wt[n][k] = W[k][n] (register slices of the input-gradient kernels load coalesced);
 //   actions   every action byte <- 0xFF padding, as 32-bit words (the buffer is 4-byte aligned); skipped when null.
 struct PrepareParams {
-  const float *W2, *W3;
-  int H1, H2, A, A16;
+  const float *W1, *W2, *W3;
+  int In, H1, H2, A, A16;
   float *W2p, *W3p, *W2t, *W3t;
+  double* D1;       // [In][H1] difference rows of layer 1
+  int kind, group;  // environment kind; one-hot columns per state component (grid side, 2^k + 1, 3)
   uint8_t* actions;
   size_t action_bytes;
 };
+// D1[r] = W1[r] - W1[old(r)] in binary64: the change of the layer-1 pre-activation when the transition makes one-hot
+// row r active in place of row old(r) -- grid: r - 1 (the coordinate one lower; rows of coordinate 0 are never entered),
+// bit sequences: the "empty" row of the position, Ising: the "unassigned" row of the site.
+__device__ __forceinline__ void difference_rows_part(const PrepareParams& p, int block, int blocks) {
+  const int qv = p.H1 >> 2;  // four columns per thread
+  const size_t total = (size_t)p.In * qv;
+  for (size_t i = (size_t)block * 256 + threadIdx.x; i < total; i += (size_t)blocks * 256) {
+    const int r = (int)(i / qv), f = 4 * (int)(i - (size_t)r * qv);
+    const int c = r / p.group, v = r - c * p.group;
+    int ro;
+    if (p.kind == 0) ro = v > 0 ? r - 1 : r;
+    else if (p.kind == 1) ro = c * p.group + (p.group - 1);
+    else ro = c * p.group + 1;
+    const f32x4 a = *(const f32x4*)&p.W1[(size_t)r * p.H1 + f], b = *(const f32x4*)&p.W1[(size_t)ro * p.H1 + f];
+    f64x2* d = (f64x2*)&p.D1[(size_t)r * p.H1 + f];
+    d[0] = (f64x2){(double)a.x - (double)b.x, (double)a.y - (double)b.y};
+    d[1] = (f64x2){(double)a.z - (double)b.z, (double)a.w - (double)b.w};
+  }
+}
 __device__ __forceinline__ void pack_weights_part(const float* __restrict__ W, int K, int N, int NT,
                                                   float* __restrict__ out, int block, int blocks) {
   const int Q = K >> 4;
@@ -941,7 +996,8 @@ __device__ __forceinline__ void transpose_part(const float* __restrict__ W, int 
     Wt[i] = W[(size_t)pp * Q + q];
   }
 }
-constexpr int kPrepareBlocks = 128 + 64 + 128 + 32 + 64;
+constexpr int kDiffBlocks = 512;
+constexpr int kPrepareBlocks = 128 + 64 + 128 + 32 + 64 + kDiffBlocks;
 __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   int b = blockIdx.x;
   if (b < 128) { pack_weights_part(p.W2, p.H1, p.H2, p.H2 >> 4, p.W2p, b, 128); return; }
@@ -952,6 +1008,7 @@ __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   b -= 128;
   if (b < 32) { transpose_part(p.W3, p.H2, p.A, p.W3t, b, 32); return; }
   b -= 32;
+  if (b >= 64) { difference_rows_part(p, b - 64, kDiffBlocks); return; }
   if (p.actions) {
     const size_t words = p.action_bytes >> 2;
     for (size_t i = (size_t)b * 256 + threadIdx.x; i < words; i += (size_t)64 * 256) ((uint32_t*)p.actions)[i] = 0xFFFFFFFFu;
