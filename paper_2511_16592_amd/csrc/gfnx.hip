@@ -257,21 +257,22 @@ size_t rollout_lds_bytes(const Shapes& s, bool grid) {
 
 template <int ENV, bool REPLAY, int NCH, bool EXPLORE>
 int launch_rollout_ntw(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st) {
-#define GFNX_LAUNCH(N, STATIONARY)                                                                          \
+#define GFNX_LAUNCH(N, STATIONARY, CA16)                                                                    \
   {                                                                                                         \
-    auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH, EXPLORE>;                                      \
+    auto k = rollout_kernel<ENV, REPLAY, N, STATIONARY, NCH, EXPLORE, CA16>;                                \
     GFNX_ALLOW_LDS(k, lds)                                                                                  \
     hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, p);                                         \
   }
   if (p.H1 == 256 && p.H2 == 256) {  // layer 2 resident in registers
-    GFNX_LAUNCH(2, true)
+    if (ENV == 0 && p.A16 == 16) GFNX_LAUNCH(2, true, (ENV == 0 ? 16 : 0))
+    else GFNX_LAUNCH(2, true, 0)
     return GFNX_OK;
   }
   switch ((p.H2 / 16 + 7) / 8) {  // 16-feature tiles of layer 2 per wave
-    case 1: GFNX_LAUNCH(1, false) break;
-    case 2: GFNX_LAUNCH(2, false) break;
-    case 3: GFNX_LAUNCH(3, false) break;
-    case 4: GFNX_LAUNCH(4, false) break;
+    case 1: GFNX_LAUNCH(1, false, 0) break;
+    case 2: GFNX_LAUNCH(2, false, 0) break;
+    case 3: GFNX_LAUNCH(3, false, 0) break;
+    case 4: GFNX_LAUNCH(4, false, 0) break;
     default: return GFNX_E_UNSUPPORTED;
   }
 #undef GFNX_LAUNCH

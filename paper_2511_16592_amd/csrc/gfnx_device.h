@@ -111,9 +111,11 @@ __device__ __forceinline__ float uniform_from_bits(uint32_t w) {
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // Value of the lane `n` positions further round the aligned row of 16 lanes (DPP row rotation).
+// (every lane of a rotation has a source, so the "old" operand is left undefined: the move can then be folded into
+// the instruction that consumes it)
 template <int N>
 __device__ __forceinline__ int row16_rot(int v) {
-  return __builtin_amdgcn_update_dpp(v, v, 0x120 + N, 0xF, 0xF, false);
+  return __builtin_amdgcn_mov_dpp(v, 0x120 + N, 0xF, 0xF, true);
 }
 template <int N>
 __device__ __forceinline__ float row16_rot(float v) {

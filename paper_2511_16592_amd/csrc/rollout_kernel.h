@@ -130,14 +130,16 @@ __host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16
 //        W3 as well.
 // NCH  = chunks of four logits a lane may own in SU: 1 up to 128 actions, else 2.
 // EXPLORE = epsilon-uniform exploration compiled in (free-running rollouts with epsilon > 0 only).
-template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH, bool EXPLORE>
+// CA16 = the padded number of logits when it is known at compile time (16: narrow grids, the shape whose per-step
+//        latency matters most), 0 = taken from the parameters.
+template <int ENV, bool REPLAY, int NTW, bool STAT, int NCH, bool EXPLORE, int CA16>
 __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const EnvParams& e = p.env;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int g = lane >> 4, j16 = lane & 15;
   const int H1 = STAT ? 256 : p.H1, H2 = STAT ? 256 : p.H2;
-  const int A = p.A, A16 = p.A16, B = p.B, SBL = p.SBL;
+  const int A = p.A, A16 = CA16 ? CA16 : p.A16, B = p.B, SBL = p.SBL;
   const int Q1 = H1 >> 4, Q2 = H2 >> 4;
   const int NT2 = H2 >> 4, NT3 = A16 >> 4, nchunk = A16 >> 2;
   const int KS = logits_ksplit(NT3, Q2);
