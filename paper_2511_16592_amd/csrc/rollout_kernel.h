@@ -103,7 +103,7 @@ constexpr int kW2RegQ = 12;  // contraction steps (of 16) of a resident W2 tile 
 
 // Byte offsets of the kernel's LDS regions (shared by the launch code, which sizes the allocation).
 struct RolloutLds {
-  int h1s, h1s2, z1d, h2s, lgs, z1i, flags, st, w2l, total;
+  int h1s, h1s2, z1d, h2s, lgs, z1i, flags, st, ulog, w2l, total;
 };
 constexpr int kPitchD = 66;  // doubles per feature-quad row of the binary64 z1 tile (16 slots * 4 + 2 pad: conflict-free)
 // rows2: h1 is double-buffered (read by the step in progress, written for the next one)
@@ -117,8 +117,9 @@ __host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16
   L.h2s = o; o += (H2 >> 2) * kPitch * 4;
   L.lgs = o; o += ks * (A16 >> 2) * kPitch * 4;      // [KS][A16 / 4] partial logits
   L.z1i = o; o += H1 * 8;                            // z1(s_0) in binary64, for slots that restart
-  L.flags = o; o += (kSlots + 4) * 4;                // srow[kSlots], qnext, live
+  L.flags = o; o += (2 * kSlots + 4) * 4;            // srow[kSlots], qnext, live, (pad), utag[kSlots]
   L.st = o; o += kSlots * SBL;                       // state bytes, SBL per slot (a multiple of 16)
+  L.ulog = o; if (rows2 && A16 == 16) o += kSlots * 4 * 16;  // draws made ahead: -log2(u) of 16 actions per slot
   L.w2l = o; if (stat) o += (16 - kW2RegQ) * 16 * 64 * 16;  // 16 tiles x (16 - kW2RegQ) steps x 64 lanes x 16 bytes
   L.total = o;
   return L;
@@ -154,6 +155,8 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   int* srow = (int*)(smem_raw + L.flags);     // [kSlots] row t*B + b of the slot's current transition
   int* qnext = srow + kSlots;                 // next trajectory of this workgroup's range to start
   uint32_t* live = (uint32_t*)(qnext + 1);    // bit j: slot j is running a trajectory
+  int* utag = srow + kSlots + 4;              // [kSlots] row index (t*B + b) the draws in `ulog` were made for
+  f32x4* ulog = (f32x4*)(smem_raw + L.ulog);  // [kSlots][4 chunks] -log2(u) of the slot's next step
   int8_t* st = (int8_t*)(smem_raw + L.st);
   const f32x4* w2l = (const f32x4*)(smem_raw + L.w2l);
 
@@ -167,6 +170,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   // SU writes the next one, hence the two buffers (z1a / z1b, swapped every step; one buffer otherwise).
   constexpr bool kRowsInSU = ENV == 0 && STAT;
   constexpr bool kTail = STAT && ENV == 0;
+  // Narrow grids, free-running: the random draws of a step do not depend on the logits, so the four waves that are
+  // not in SU make them one step ahead -- Philox and -log2(u) for the slot's next step, assuming its trajectory
+  // goes on -- and SU takes them from LDS when they are for its (trajectory, step), else draws them itself.
+  constexpr bool kDrawAhead = kRowsInSU && !REPLAY && CA16 == 16;
   constexpr int kTailSlots = 4;
   constexpr int LPS = ENV == 0 ? 16 : 32;
   constexpr int kSuWaves = kSlots / (64 / LPS);
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     z1i[f] = z;
   }
   for (int i = tid; 4 * i < SBL * kSlots; i += kRolloutThreads) ((uint32_t*)st)[i] = 0u;
-  if (tid < kSlots) srow[tid] = b0 + tid;
+  if (tid < kSlots) { srow[tid] = b0 + tid; utag[tid] = -1; }
   if (tid == 0) {
     *qnext = b0 + kSlots;
     const int n0 = bend - b0;  // at least one: the grid has no empty workgroup
@@ -261,6 +268,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
     int srk[4];                                 // rows of the four slots a non-SU wave writes out on grids
 #pragma unroll
     for (int k = 0; k < 4; ++k) srk[k] = kRowsInSU ? srow[4 * (w & 3) + k] : 0;
+    const int ahead_row = kDrawAhead ? srow[4 * (w & 3) + g] : 0;  // slot whose next draws this lane makes
     // ================= L2: h2 = relu(W2^T relu(z1) + b2)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {  // h1 rows and sign masks of slots w and w + 8
@@ -489,6 +497,13 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         }
       }
     }
+    // draws made ahead for this step: read before the barrier, since the other waves overwrite them during SU
+    f32x4 ul_ahead = {0.f, 0.f, 0.f, 0.f};
+    int ul_tag = -1;
+    if (kDrawAhead && su_wave) {
+      ul_ahead = ulog[sj * 4 + (si & 3)];
+      ul_tag = utag[sj];
+    }
     lds_barrier();
 
     // ================= L3: logits = W3^T h2 (+ b3 added in SU)
@@ -590,6 +605,19 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           store_sign_mask(p.m1buf + (row * p.MW1 + 4 * it), v, lane);
         }
       }
+      if constexpr (kDrawAhead) {
+        const int dj = 4 * (w & 3) + g;  // 16 lanes per slot, as in SU; lane j16 < 4 owns chunk j16
+        if (((live_mask >> dj) & 1u) && j16 < 4) {
+          const int t1 = ahead_row / B + 1, b = ahead_row - (t1 - 1) * B;
+          uint32_t wd[4];
+          philox4x32_10_ukey((uint32_t)b, (uint32_t)t1, (uint32_t)j16, p.iter_lo, p.seed_lo, p.seed_hi, wd);
+          f32x4 ul;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) ul[k] = -__builtin_amdgcn_logf(uniform_from_bits(wd[k]));
+          ulog[dj * 4 + j16] = ul;
+          if (j16 == 0) utag[dj] = t1 * B + b;
+        }
+      }
     }
     if (su_wave && su_alive) {
       const int t = ts;
@@ -677,11 +705,18 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
 #pragma unroll
         for (int n = 0; n < NCH; ++n) {
           const int c = si + LPS * n;
-          uint32_t wd[4];
-          philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
+          f32x4 ul;  // -log2(u) of the four actions
+          if (kDrawAhead && ul_tag == t * B + sb) {
+            ul = ul_ahead;  // (lanes beyond the four chunks hold a copy of one of them; their weights are 0)
+          } else {
+            uint32_t wd[4];
+            philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, (uint32_t)c, p.iter_lo, p.seed_lo, p.seed_hi, wd);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) ul[k] = -__builtin_amdgcn_logf(uniform_from_bits(wd[k]));
+          }
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
-            const float r = -__builtin_amdgcn_logf(uniform_from_bits(wd[k])) * __builtin_amdgcn_rcpf(wv[n][k]);
+            const float r = ul[k] * __builtin_amdgcn_rcpf(wv[n][k]);
             const unsigned long long key =
                 ((unsigned long long)__builtin_bit_cast(uint32_t, r) << 32) | (uint32_t)(4 * c + k);
             best = key < best ? key : best;
