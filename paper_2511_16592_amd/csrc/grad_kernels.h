@@ -17,7 +17,6 @@
 namespace gfnx {
 
 constexpr int kHdrNLive = 0;    // header words (int32)
-constexpr int kHdrMaxLen = 1;
 constexpr int kHdrCnt = 16;     // cnt[t] = number of trajectories longer than t, t < 256
 constexpr int kHdrOff = 16 + 256;  // off[t] = first list position of step t
 constexpr int kHdrWords = 16 + 512;
@@ -25,8 +24,11 @@ constexpr int kHdrWords = 16 + 512;
 // Workgroup t lists the live transitions of step t in increasing b: rows[off[t] + rank] = t*B + b, and next to each
 // the coefficient of its trajectory, crow[off[t] + rank] = 2 delta_b / B with the TB residual
 // delta_b = log Z + log P_F - log R - log P_B.  Every workgroup derives the list offsets itself from the histogram
-// of the lengths (B integers: cheaper than a launch of its own); workgroup 0 also writes them to the header for
-// the kernels that follow, together with the loss (mean delta^2) and dloss/dlogZ (2 mean delta).
+// of the lengths (B integers: cheaper than a launch of its own): cnt[u] = #{b : len_b > u} is a suffix sum of the
+// histogram and off[u] a prefix sum of cnt, both taken by one wavefront with four entries per lane; workgroup 0 also
+// writes them to the header for the kernels that follow, together with the loss (mean delta^2) and dloss/dlogZ
+// (2 mean delta).  The list itself takes two sweeps over the lengths (count per wavefront, then write), one barrier
+// between them.  T <= 256.
 __global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ length, const float* __restrict__ lpf,
                                                     const float* __restrict__ lpb, const float* __restrict__ logr,
                                                     float log_z, const float* __restrict__ log_z_dev, int B, int T,
@@ -34,12 +36,12 @@ __global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ leng
                                                     int* __restrict__ hdr, int* __restrict__ rows,
                                                     float* __restrict__ crow) {
   if (log_z_dev) log_z = *log_z_dev;  // log Z kept on the device (training loop) instead of passed by value
-  __shared__ int hist[258];
-  __shared__ float red2[1024], red1[1024];
+  __shared__ int hist[260];             // hist[l] = #{b : len_b = l}, l = 0 .. 256 (clamped to [0, T])
+  __shared__ int cnts[256], offs[256];
+  __shared__ float red2[16], red1[16];
   __shared__ int wsum[16];
-  __shared__ int base, mycnt;
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  for (int i = tid; i < 258; i += 1024) hist[i] = 0;
+  for (int i = tid; i < 260; i += 1024) hist[i] = 0;
   __syncthreads();
   float s2 = 0.f, s1 = 0.f;
   for (int b = tid; b < B; b += 1024) {
@@ -52,57 +54,78 @@ __global__ __launch_bounds__(1024) void rows_kernel(const int* __restrict__ leng
     len = len < 0 ? 0 : (len > T ? T : len);
     atomicAdd(&hist[len], 1);
   }
-  if (t == 0) {
-    red2[tid] = s2;
-    red1[tid] = s1;
-    __syncthreads();
-    for (int o = 512; o > 0; o >>= 1) {
-      if (tid < o) { red2[tid] += red2[tid + o]; red1[tid] += red1[tid + o]; }
-      __syncthreads();
-    }
+  if (t == 0) {  // fixed-order sums: lanes of a wavefront by halving, then the sixteen wavefronts in order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { s2 += __shfl_down(s2, o); s1 += __shfl_down(s1, o); }
+    if (lane == 0) { red2[wv] = s2; red1[wv] = s1; }
   }
   __syncthreads();
-  if (tid == 0) {
-    // cnt[u] = #{b : len_b > u} = sum_{l > u} hist[l]; off[u] = sum_{v < u} cnt[v]
-    int off = 0, run = 0, maxlen = 0, off_t = 0, cnt_t = 0;
-    for (int l = T; l >= 1; --l) {
-      run += hist[l];
-      hist[l] = run;  // now cnt[l - 1]
-      if (run && maxlen == 0) maxlen = l;
+  if (wv == 0) {
+    // lane i owns steps u = 4i .. 4i+3: cnt[u] = sum_{l > u} hist[l], off[u] = sum_{v < u} cnt[v]
+    int h[4], c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) h[k] = hist[4 * lane + k + 1];
+    c[3] = h[3]; c[2] = h[2] + c[3]; c[1] = h[1] + c[2]; c[0] = h[0] + c[1];
+    int above = c[0];  // inclusive suffix sum of the lane totals, then made exclusive
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_down(above, o);
+      if (lane + o < 64) above += v;
     }
-    for (int u = 0; u < T; ++u) {
-      const int c = hist[u + 1];
-      if (u == t) { off_t = off; cnt_t = c; }
-      if (t == 0) { hdr[kHdrCnt + u] = c; hdr[kHdrOff + u] = off; }
-      off += c;
+    above -= c[0];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] += above;
+    const int mine = c[0] + c[1] + c[2] + c[3];
+    int before = mine;  // inclusive prefix sum of the lane totals, then made exclusive
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(before, o);
+      if (lane >= o) before += v;
+    }
+    before -= mine;
+    int run = before;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int u = 4 * lane + k;
+      cnts[u] = c[k];
+      offs[u] = run;
+      if (t == 0 && u < T) { hdr[kHdrCnt + u] = c[k]; hdr[kHdrOff + u] = run; }
+      run += c[k];
     }
     if (t == 0) {
-      hdr[kHdrNLive] = off;
-      hdr[kHdrMaxLen] = maxlen;
-      *loss = red2[0] / (float)B;
-      *dlogz = 2.f * red1[0] / (float)B;
+      if (lane == 63) hdr[kHdrNLive] = run;  // all live transitions: the last lane's running total
+      if (lane == 0) {
+        float a2 = 0.f, a1 = 0.f;
+        for (int k = 0; k < 16; ++k) { a2 += red2[k]; a1 += red1[k]; }
+        *loss = a2 / (float)B;
+        *dlogz = 2.f * a1 / (float)B;
+      }
     }
-    base = off_t;
-    mycnt = cnt_t;
   }
   __syncthreads();
+  const int mycnt = cnts[t];
   if (mycnt == 0) return;
-  for (int b0 = 0; b0 < B; b0 += 1024) {
-    const int b = b0 + tid;
-    const bool on = b < B && length[b] > t;
+  // this workgroup's rows: wavefront w takes the b-range [w * per, (w + 1) * per), per a multiple of 64
+  const int per = ((B + 15) / 16 + 63) & ~63;
+  const int lo = wv * per, hi = min(B, lo + per);
+  int mine = 0;
+  for (int b = lo + lane; b < hi; b += 64) mine += length[b] > t ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+  if (lane == 0) wsum[wv] = mine;
+  __syncthreads();
+  int pos = offs[t];
+  for (int k = 0; k < wv; ++k) pos += wsum[k];
+  for (int b0 = lo; b0 < hi; b0 += 64) {
+    const int b = b0 + lane;
+    const bool on = b < hi && length[b] > t;
     const unsigned long long bal = __ballot(on);
-    const int before = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wsum[wv] = __popcll(bal);
-    __syncthreads();
-    int woff = 0, tot = 0;
-    for (int k = 0; k < 16; ++k) { if (k < wv) woff += wsum[k]; tot += wsum[k]; }
     if (on) {
-      rows[base + woff + before] = t * B + b;
-      crow[base + woff + before] = 2.f * (log_z + lpf[b] - logr[b] - lpb[b]) / (float)B;
+      const int at = pos + __popcll(bal & ((1ull << lane) - 1ull));
+      rows[at] = t * B + b;
+      crow[at] = 2.f * (log_z + lpf[b] - logr[b] - lpb[b]) / (float)B;
     }
-    __syncthreads();
-    if (tid == 0) base += tot;
-    __syncthreads();
+    pos += __popcll(bal);
   }
 }
 
