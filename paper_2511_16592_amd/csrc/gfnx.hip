@@ -8,6 +8,7 @@
 #include "grad_kernels.h"
 #include "grad_kernels2.h"
 #include "grad_kernels3.h"
+#include "grad_kernels4.h"
 #include "subtb_kernels.h"
 #include "rollout_kernel.h"
 
@@ -520,22 +521,22 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     // dW3 = H2^T G3, db3; G3 = coef * e is formed on load
     GFNX_TIMED("gemm_tn_w3", st);
     if (s.qt3 == 32) {
-      auto k = gemm_tn2_kernel<8, 1, 1, 1, true>;
-      const int lds = 2 * 32 * (256 + 32) * 4;
+      auto k = gemm_tn3_kernel<8, 1, 1, 1, true>;
+      const int lds = (int)gemm_tn3_lds_bytes<8, 1, 1, 1>();
       GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     } else if (s.qt3 == 224) {
       // 193..224 logits (Ising 10 x 10: 200): a 256 x 224 tile, each wave 32 rows by seven column blocks, instead
       // of a 256 x 256 one an eighth of which would be padding
-      auto k = gemm_tn2_kernel<8, 1, 1, 7, true>;
-      const int lds = 2 * 32 * (256 + 224) * 4;
+      auto k = gemm_tn3_kernel<8, 1, 1, 7, true>;
+      const int lds = (int)gemm_tn3_lds_bytes<8, 1, 1, 7>();
       GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     } else {
-      auto k = gemm_tn2_kernel<2, 4, 4, 2, true>;
-      const int lds = 2 * 32 * (256 + 256) * 4;
+      auto k = gemm_tn3_kernel<2, 4, 4, 2, true>;
+      const int lds = (int)gemm_tn3_lds_bytes<2, 4, 4, 2>();
       GFNX_ALLOW_LDS(k, lds)
       hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
@@ -558,8 +559,8 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // layer 2: dW2 = H1^T G2, db2
     GFNX_TIMED("gemm_tn_w2", st);
-    auto k = gemm_tn2_kernel<2, 4, 4, 2, false>;
-    const int lds = 2 * 32 * (256 + 256) * 4;
+    auto k = gemm_tn3_kernel<2, 4, 4, 2, false>;
+    const int lds = (int)gemm_tn3_lds_bytes<2, 4, 4, 2>();
     GFNX_ALLOW_LDS(k, lds)
     hipLaunchKernelGGL(k, dim3(pt2, s.qtot2 / 256, s.s2), dim3(512), lds, st, h1buf, s.H1, s.H1, h2buf, s.H2, (const float*)crow, rows, hdr,
                        s.qtot2, part2, dbp2);

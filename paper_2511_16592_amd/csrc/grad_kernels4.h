@@ -1,0 +1,303 @@
+// Weight-gradient contraction dW = X^T G on the bf16 matrix cores with binary32-equivalent arithmetic.
+//
+// Every binary32 operand is cut into three bf16 pieces of 8 significant bits each, x = x_h + x_m + x_l exactly (by
+// truncation, as in dw1_onehot_kernel), and a product x * g is formed from the six piece products of weight down to
+// 2^-16: x_h g_h, x_h g_m, x_m g_h, x_h g_l, x_l g_h, x_m g_m.  Each piece product is exact (8 x 8 significant bits) and
+// is accumulated in binary32 by the matrix core; what is dropped (x_m g_l, x_l g_m, x_l g_l) is below 2^-23 |x g|, the
+// size of the rounding error of one binary32 multiply-add.  Per 32 x 32 x 16 block of work, six bf16 instructions
+// (6 x 32 = 192 cycles of the matrix pipe) replace eight binary32 ones of 32 x 32 x 2 (8 x 64 = 512 cycles).
+//
+// One workgroup = 8 waves holds a PT x QT accumulator tile (256 x 256, 256 x 224 or 256 x 32) like gemm_tn2_kernel,
+// and the transitions are split over blockIdx.z in the same way (same partial-tile layout, same reductions).  The
+// matrix instruction contracts 16 transition rows and wants, per lane, 8 consecutive ROWS of one column: each thread
+// therefore loads its column of 8 rows straight from global memory (lanes = consecutive columns: coalesced), splits
+// the 8 values once, and writes three 16-byte pieces to LDS in operand order [piece][row octet][column]; every wave
+// then reads its operands with 16-byte LDS loads.  Steps of 16 rows are double-buffered in LDS: while the matrix cores
+// work on step s, the values of step s+1 (in registers since the previous step) are split and written, and the loads
+// of step s+2 are in flight; the row ids run one step further ahead.  One barrier per step.
+#pragma once
+#include "gfnx_device.h"
+#include "grad_kernels.h"
+#include "grad_kernels2.h"
+#include "grad_kernels3.h"
+
+namespace gfnx {
+
+// x = h + m + l exactly, each with at most 8 significant bits; returned as bf16 bit patterns in the HIGH half of a word
+__device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32_t& l) {
+  h = __builtin_bit_cast(uint32_t, x) & 0xFFFF0000u;
+  const float r1 = x - __builtin_bit_cast(float, h);
+  m = __builtin_bit_cast(uint32_t, r1) & 0xFFFF0000u;
+  const float r2 = r1 - __builtin_bit_cast(float, m);
+  l = __builtin_bit_cast(uint32_t, r2);  // at most 8 significant bits are left: the low half is zero
+}
+
+// eight binary32 values (consecutive contraction rows of one column) -> three packed operands of eight bf16
+__device__ __forceinline__ void split3x8(const float v[8], u32x4& ph, u32x4& pm, u32x4& pl) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    uint32_t h0, m0, l0, h1, m1, l1;
+    split3(v[2 * k], h0, m0, l0);
+    split3(v[2 * k + 1], h1, m1, l1);
+    ph[k] = (h0 >> 16) | h1;
+    pm[k] = (m0 >> 16) | m1;
+    pl[k] = (l0 >> 16) | (l1 & 0xFFFF0000u);
+  }
+}
+
+constexpr int kTn3Step = 16;  // transition rows per matrix instruction / pipeline step
+
+template <int WP, int WQ, int PBW, int QBW>
+constexpr size_t gemm_tn3_lds_bytes() {
+  return (size_t)2 * 3 * 2 * (WP * PBW * 32 + WQ * QBW * 32) * 16;  // 2 buffers x 3 pieces x 2 row octets x columns
+}
+
+template <int WP, int WQ, int PBW, int QBW, bool SCALE>
+__global__ __launch_bounds__(512) void gemm_tn3_kernel(const float* __restrict__ X, int ldx, int P,
+                                                       const float* __restrict__ G, int ldg,
+                                                       const float* __restrict__ crow,
+                                                       const int* __restrict__ rows, const int* __restrict__ hdr,
+                                                       int QTOT, float* __restrict__ part,
+                                                       float* __restrict__ dbpart) {
+  constexpr int PT = WP * PBW * 32, QT = WQ * QBW * 32;
+  constexpr int XU = (2 * PT + 511) / 512, GU = (2 * QT + 511) / 512;  // (column, row octet) units per thread
+  static_assert(WP * WQ == 8, "eight waves");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  constexpr int kBufVecs = 3 * 2 * (PT + QT);  // 16-byte vectors per buffer
+  u32x4* lds = (u32x4*)smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int ptile = blockIdx.x, qtile = blockIdx.y, s = blockIdx.z, S = gridDim.z;
+  const int n = hdr[kHdrNLive];
+  const int chunks = (n + 31) / 32;
+  const int per = split_chunks_per_part(chunks, S);
+  const int c0 = s * per, c1 = min(chunks, c0 + per);
+  if (c0 >= c1) return;  // parts beyond the live transitions write nothing; the reduction skips them too
+  const int row0 = 32 * c0, row1 = min(n, 32 * c1);  // this part's slice of the row list
+  const int steps = (row1 - row0 + kTn3Step - 1) / kTn3Step;
+  const int pbase = (w / WQ) * PBW * 32, qbase = (w % WQ) * QBW * 32;
+  const int kg = lane >> 5, l32 = lane & 31;
+
+  f32x16 acc[PBW][QBW];
+#pragma unroll
+  for (int a = 0; a < PBW; ++a)
+#pragma unroll
+    for (int b = 0; b < QBW; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  float dbacc[GU];
+#pragma unroll
+  for (int u = 0; u < GU; ++u) dbacc[u] = 0.f;
+
+  // ---- loader roles: unit u of this thread = (column, row octet) of X and of G
+  int xcol[XU], xoct[XU], gcol[GU], goct[GU];
+  bool xon[XU], gon[GU];
+#pragma unroll
+  for (int u = 0; u < XU; ++u) {
+    const int i = tid + 512 * u;
+    xcol[u] = i % PT; xoct[u] = i / PT;
+    xon[u] = i < 2 * PT && ptile * PT + xcol[u] < P;
+  }
+#pragma unroll
+  for (int u = 0; u < GU; ++u) {
+    const int i = tid + 512 * u;
+    gcol[u] = i % QT; goct[u] = i / QT;
+    gon[u] = i < 2 * QT && qtile * QT + gcol[u] < ldg;
+  }
+  // row ids (and coefficients) of the eight rows of every unit, one step ahead of the values
+  int4 xid[XU][2], gid[GU][2];
+  f32x4 gcf[GU][2];
+  // (loads are unconditional -- a list position past this part's range, or a step past its end, is read at a clamped
+  // index and the id replaced by -1; a row id of -1 or a column past the operand is read at row / column 0 and the
+  // value replaced by zero -- so that the loop body is branch-free)
+  auto load_ids = [&](int step) {
+    const int stc = min(step, steps - 1);
+    const int lim = step < steps ? row1 : 0;  // list positions >= lim hold no row of this step
+#pragma unroll
+    for (int u = 0; u < XU; ++u) {
+      const int li = row0 + stc * kTn3Step + 8 * min(xoct[u], 1);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int lj = li + 4 * hh;
+        int4 v = *(const int4*)&rows[lj];
+        v.x = lj < lim ? v.x : -1;
+        v.y = lj + 1 < lim ? v.y : -1;
+        v.z = lj + 2 < lim ? v.z : -1;
+        v.w = lj + 3 < lim ? v.w : -1;
+        xid[u][hh] = v;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      const int li = row0 + stc * kTn3Step + 8 * min(goct[u], 1);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int lj = li + 4 * hh;
+        int4 v = *(const int4*)&rows[lj];
+        v.x = lj < lim ? v.x : -1;
+        v.y = lj + 1 < lim ? v.y : -1;
+        v.z = lj + 2 < lim ? v.z : -1;
+        v.w = lj + 3 < lim ? v.w : -1;
+        gid[u][hh] = v;
+        if (SCALE) gcf[u][hh] = *(const f32x4*)&crow[lj];
+      }
+    }
+  };
+  // the values are used (masked, scaled, split) one step after their loads are issued; what that needs of the ids
+  // and coefficients, which are overwritten in between, is kept beside them
+  float xv[XU][8], gv[GU][8], gcv[GU][8];
+  uint32_t xok[XU], gok[GU];
+  auto load_values = [&]() {
+#pragma unroll
+    for (int u = 0; u < XU; ++u) {
+      const int id[8] = {xid[u][0].x, xid[u][0].y, xid[u][0].z, xid[u][0].w,
+                         xid[u][1].x, xid[u][1].y, xid[u][1].z, xid[u][1].w};
+      const float* src = X + (xon[u] ? ptile * PT + xcol[u] : 0);
+      xok[u] = 0u;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        xv[u][k] = src[(size_t)max(id[k], 0) * ldx];
+        xok[u] |= (uint32_t)(xon[u] && id[k] >= 0) << k;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      const int id[8] = {gid[u][0].x, gid[u][0].y, gid[u][0].z, gid[u][0].w,
+                         gid[u][1].x, gid[u][1].y, gid[u][1].z, gid[u][1].w};
+      const float cf[8] = {gcf[u][0].x, gcf[u][0].y, gcf[u][0].z, gcf[u][0].w,
+                           gcf[u][1].x, gcf[u][1].y, gcf[u][1].z, gcf[u][1].w};
+      const float* src = G + (gon[u] ? qtile * QT + gcol[u] : 0);
+      gok[u] = 0u;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        gv[u][k] = src[(size_t)max(id[k], 0) * ldg];
+        gok[u] |= (uint32_t)(gon[u] && id[k] >= 0) << k;
+        if (SCALE) gcv[u][k] = cf[k];
+      }
+    }
+  };
+  // split the values in hand and write them to LDS buffer `buf` in operand order [piece][row octet][column]
+  auto store_step = [&](int buf) {
+    u32x4* XS = lds + buf * kBufVecs;
+    u32x4* GS = XS + 3 * 2 * PT;
+#pragma unroll
+    for (int u = 0; u < XU; ++u) {
+      if (tid + 512 * u < 2 * PT) {
+        u32x4 ph, pm, pl;
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = ((xok[u] >> k) & 1u) ? xv[u][k] : 0.f;
+        split3x8(v, ph, pm, pl);
+        XS[(0 * 2 + xoct[u]) * PT + xcol[u]] = ph;
+        XS[(1 * 2 + xoct[u]) * PT + xcol[u]] = pm;
+        XS[(2 * 2 + xoct[u]) * PT + xcol[u]] = pl;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      if (tid + 512 * u < 2 * QT) {
+        u32x4 ph, pm, pl;
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = ((gok[u] >> k) & 1u) ? (SCALE ? gv[u][k] * gcv[u][k] : gv[u][k]) : 0.f;
+        split3x8(v, ph, pm, pl);
+        GS[(0 * 2 + goct[u]) * QT + gcol[u]] = ph;
+        GS[(1 * 2 + goct[u]) * QT + gcol[u]] = pm;
+        GS[(2 * 2 + goct[u]) * QT + gcol[u]] = pl;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dbacc[u] += v[k];
+      }
+    }
+  };
+
+  // ---- prologue: step 0 in LDS, values of step 1 in flight, ids of step 2 in hand
+  load_ids(0);
+  load_values();
+  load_ids(1);
+  store_step(0);
+  load_values();
+  load_ids(2);
+  lds_barrier();
+  for (int st = 0; st < steps; ++st) {
+    const u32x4* XS = lds + (st & 1) * kBufVecs;
+    const u32x4* GS = XS + 3 * 2 * PT;
+    store_step((st + 1) & 1);  // step st+1 (zeros past the end); that buffer was last read for step st-1
+    load_values();             // step st+2, ids already here
+    load_ids(st + 3);
+    // the operand pieces of the narrower side of the wave's sub-tile stay in registers, the other side streams
+    if constexpr (QBW <= PBW) {
+      u32x4 bh[QBW], bm[QBW], bl[QBW];
+#pragma unroll
+      for (int b = 0; b < QBW; ++b) {
+        const int col = qbase + 32 * b + l32;
+        bh[b] = GS[(0 * 2 + kg) * QT + col];
+        bm[b] = GS[(1 * 2 + kg) * QT + col];
+        bl[b] = GS[(2 * 2 + kg) * QT + col];
+      }
+#pragma unroll
+      for (int a = 0; a < PBW; ++a) {
+        const int col = pbase + 32 * a + l32;
+        const u32x4 ah = XS[(0 * 2 + kg) * PT + col];
+        const u32x4 am = XS[(1 * 2 + kg) * PT + col];
+        const u32x4 al = XS[(2 * 2 + kg) * PT + col];
+#pragma unroll
+        for (int b = 0; b < QBW; ++b) {  // smallest products first
+          acc[a][b] = mfma32_bf16(am, bm[b], acc[a][b]);
+          acc[a][b] = mfma32_bf16(al, bh[b], acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah, bl[b], acc[a][b]);
+          acc[a][b] = mfma32_bf16(am, bh[b], acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah, bm[b], acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah, bh[b], acc[a][b]);
+        }
+      }
+    } else {
+      u32x4 ah[PBW], am[PBW], al[PBW];
+#pragma unroll
+      for (int a = 0; a < PBW; ++a) {
+        const int col = pbase + 32 * a + l32;
+        ah[a] = XS[(0 * 2 + kg) * PT + col];
+        am[a] = XS[(1 * 2 + kg) * PT + col];
+        al[a] = XS[(2 * 2 + kg) * PT + col];
+      }
+#pragma unroll
+      for (int b = 0; b < QBW; ++b) {
+        const int col = qbase + 32 * b + l32;
+        const u32x4 bh = GS[(0 * 2 + kg) * QT + col];
+        const u32x4 bm = GS[(1 * 2 + kg) * QT + col];
+        const u32x4 bl = GS[(2 * 2 + kg) * QT + col];
+#pragma unroll
+        for (int a = 0; a < PBW; ++a) {
+          acc[a][b] = mfma32_bf16(am[a], bm, acc[a][b]);
+          acc[a][b] = mfma32_bf16(al[a], bh, acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah[a], bl, acc[a][b]);
+          acc[a][b] = mfma32_bf16(am[a], bh, acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah[a], bm, acc[a][b]);
+          acc[a][b] = mfma32_bf16(ah[a], bh, acc[a][b]);
+        }
+      }
+    }
+    lds_barrier();
+  }
+
+  float* out = part + (size_t)s * P * QTOT;
+#pragma unroll
+  for (int a = 0; a < PBW; ++a)
+#pragma unroll
+    for (int b = 0; b < QBW; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int pi = ptile * PT + pbase + 32 * a + 8 * (r >> 2) + 4 * kg + (r & 3);
+        const int qi = qtile * QT + qbase + 32 * b + l32;
+        if (pi < P) out[(size_t)pi * QTOT + qi] = acc[a][b][r];
+      }
+  if (ptile == 0) {
+    // bias gradient: column sums of G; the two row octets of a column meet in LDS (fixed order)
+    float* cs = (float*)smem_raw;  // [2][QT]; the last step's barrier has been passed by every wave
+#pragma unroll
+    for (int u = 0; u < GU; ++u)
+      if (tid + 512 * u < 2 * QT) cs[goct[u] * QT + gcol[u]] = dbacc[u];
+    __syncthreads();
+    if (tid < QT) dbpart[(size_t)s * QTOT + qtile * QT + tid] = cs[tid] + cs[QT + tid];
+  }
+}
+
+}  // namespace gfnx
