@@ -544,17 +544,40 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   }
   add_job(part3, s.s3, s.H2, s.qtot3, s.A, grads->dW3);
   add_job(dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
-  const int nt_lds = (2 * 64 * 258 + 256 + 1024 + 256) * 4;
-  float* w2t = at<float>(ws, L.w2t);
-  float* w3t = at<float>(ws, L.w3t);
+  const int rt32 = (int)((s.rows + kNt3Rows - 1) / kNt3Rows);
+  // Out = (Gin W^T) . [act > 0] on the live rows, persistent over the row tiles: about one workgroup per CU
+  auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int kvalid, float* out, int ldo,
+                        int P, const unsigned long long* mask, int mw) -> int {
+    if (K <= 256) {
+      const int ctiles = (P + 127) / 128, lds = (int)gemm_nt3_lds_bytes<2>();
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
+      if (scale) {
+        auto k = gemm_nt3_kernel<2, true>;
+        GFNX_ALLOW_LDS(k, lds)
+        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+                           (const float*)crow, (const int*)rows, (const int*)hdr);
+      } else {
+        auto k = gemm_nt3_kernel<2, false>;
+        GFNX_ALLOW_LDS(k, lds)
+        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+                           (const float*)crow, (const int*)rows, (const int*)hdr);
+      }
+    } else {
+      const int ctiles = (P + 63) / 64, lds = (int)gemm_nt3_lds_bytes<4>();
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
+      if (scale) return GFNX_E_UNSUPPORTED;  // (the logit layer has at most 256 outputs)
+      auto k = gemm_nt3_kernel<4, false>;
+      GFNX_ALLOW_LDS(k, lds)
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+                         (const float*)crow, (const int*)rows, (const int*)hdr);
+    }
+    return GFNX_OK;
+  };
   if (!narrow) {
-    // G2 = ((coef * e) W3^T) . [h2 > 0] over h2; persistent: about one workgroup per CU
+    // G2 = ((coef * e) W3^T) . [h2 > 0] over h2
     GFNX_TIMED("gemm_nt_g2", st);
-    const int gx = row_tiles < 256 / pt3 ? row_tiles : 256 / pt3;
-    auto k = gemm_nt2_kernel<true>;
-    GFNX_ALLOW_LDS(k, nt_lds)
-    hipLaunchKernelGGL(k, dim3(gx, pt3), dim3(512), nt_lds, st, ebuf, s.A16, s.A16, (const float*)w3t, s.A, h2buf, s.H2, s.H2,
-                       at<unsigned long long>(ws, L.m2), s.mw2, (const float*)crow, rows, hdr);
+    rc = launch_nt3(true, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2, at<unsigned long long>(ws, L.m2), s.mw2);
+    if (rc) return rc;
   }
   {
     // layer 2: dW2 = H1^T G2, db2
@@ -570,22 +593,8 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
-    if (s.H2 <= 256) {
-      const int gx = row_tiles < 256 / pt2 ? row_tiles : 256 / pt2;
-      auto k = gemm_nt2_kernel<false>;
-      GFNX_ALLOW_LDS(k, nt_lds)
-      hipLaunchKernelGGL(k, dim3(gx, pt2), dim3(512), nt_lds, st, h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf, s.H1, s.H1,
-                         at<unsigned long long>(ws, L.m1), s.mw1, (const float*)crow, rows, hdr);
-    } else {
-      const int ctiles = (s.H1 + 127) / 128, rt32 = (int)((s.rows + 31) / 32);
-      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
-      const int lds = (int)gemm_nt2k_lds_bytes();
-      auto k = gemm_nt2k_kernel;
-      GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)h2buf, s.H2, s.H2, (const float*)w2t, s.H2, h1buf,
-                         s.H1, s.H1, (const unsigned long long*)at<unsigned long long>(ws, L.m1), s.mw1, (const int*)rows,
-                         (const int*)hdr);
-    }
+    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
+    if (rc) return rc;
   }
   // layer 1
   if (s.onehot) {

@@ -301,3 +301,194 @@ __global__ __launch_bounds__(512) void gemm_tn3_kernel(const float* __restrict__
 }
 
 }  // namespace gfnx
+
+namespace gfnx {
+
+// Input-gradient product Out = (Gin W^T) . [act > 0] with the same three-piece arithmetic:
+//   Out[i][p] = (sum_k Gin[i][k] * W[p][k]) * [act[i][p] > 0]  for the live rows i, written over the stored activation.
+// W is the layer's own weight matrix, row-major [P][Kvalid] (its rows are contiguous in k, which is what the B operand
+// of the 32 x 32 x 16 instruction wants: no transposed copy); the ReLU derivative comes from the recorded sign masks.
+//
+// The eight waves are CB = 8 / KH column blocks of 32 outputs x KH parts of the contraction, 128 indices each
+// (KH = 2: contraction lengths up to 256, 128 outputs per workgroup; KH = 4: up to 512, 64 outputs per workgroup);
+// a wave keeps the three pieces of its 32 x 128 slice of W in 96 registers for the whole kernel.  Tiles of 32
+// transition rows go through LDS already split: every thread loads 8 consecutive values of a row (two 16-byte
+// loads), splits them once, and writes three 16-byte pieces in operand order [piece][k octet][row]; the waves read
+// their operands with 16-byte LDS loads.  NBUF = 2 (KH = 2): the tile after next is being loaded, the next one split
+// and written, while the matrix cores work on the current one -- one barrier per tile.  The partial sums of the KH
+// parts meet in a double-buffered LDS exchange after that barrier, in fixed order, and the part-0 waves store.
+// grid = (row-tile workers (grid-stride), ceil(P / (32 CB))).  SCALE: Gin rows are multiplied by crow on load.
+constexpr int kNt3Rows = 32;
+
+template <int KH>
+constexpr size_t gemm_nt3_lds_bytes() {
+  constexpr int CB = 8 / KH, NBUF = KH == 2 ? 2 : 1, OCTS = 16 * KH;
+  return (size_t)NBUF * 3 * OCTS * kNt3Rows * 16        // operand pieces
+         + (size_t)2 * (KH - 1) * CB * 64 * 64            // partial-sum exchange
+         + 8 * kNt3Rows * 4 + 8 * kNt3Rows * 4            // row ids and coefficients, a ring of eight tiles
+         + 4 * kNt3Rows * 16 * 4;                         // sign-mask words, a ring of four tiles
+}
+
+template <int KH, bool SCALE>
+__global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__ Gin, int ldgi, int K,
+                                                       const float* __restrict__ W, int Kvalid,
+                                                       float* __restrict__ ActOut, int ldo, int P,
+                                                       const unsigned long long* __restrict__ mask, int MW,
+                                                       const float* __restrict__ crow,
+                                                       const int* __restrict__ rows, const int* __restrict__ hdr) {
+  constexpr int CB = 8 / KH, PT = 32 * CB, NBUF = KH == 2 ? 2 : 1, OCTS = 16 * KH, R = kNt3Rows;
+  constexpr int U = OCTS * R / 512;  // (row, k octet) units per thread and tile: 2 (KH = 2) or 4
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  u32x4* AS = (u32x4*)smem_raw;                                   // [NBUF][3][OCTS][R]
+  f32x16* XCH = (f32x16*)(AS + NBUF * 3 * OCTS * R);              // [2][KH - 1][CB][64]
+  int* ridb = (int*)(XCH + 2 * (KH - 1) * CB * 64);               // [8][R]
+  float* cfb = (float*)(ridb + 8 * R);                            // [8][R]
+  uint32_t* MSb = (uint32_t*)(cfb + 8 * R);                       // [4][R][16]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int cb = w % CB, kh = w / CB, kg = lane >> 5, l32 = lane & 31;
+  const int n = hdr[kHdrNLive];
+  const int tiles = (n + R - 1) / R;
+  const int pl = 32 * cb + l32, pcol = blockIdx.y * PT + pl;
+  const int mwords = 2 * MW;  // 32-bit mask words per row (at most 16)
+
+  // ---- this wave's slice of W: pieces of W[pcol][128 kh + 16 step + 8 kg .. + 7], step = 0 .. 7
+  u32x4 wh[8], wm[8], wl[8];
+#pragma unroll
+  for (int st = 0; st < 8; ++st) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int kk = 128 * kh + 16 * st + 8 * kg + k;
+      v[k] = (kk < Kvalid && pcol < P) ? W[(size_t)pcol * Kvalid + kk] : 0.f;
+    }
+    split3x8(v, wh[st], wm[st], wl[st]);
+  }
+
+  // ---- loader roles: unit = (row, k octet), rows fastest so that the LDS writes of a wave are contiguous
+  const int octs = K >> 3;  // octets that exist (K is a multiple of 16)
+  f32x4 pre[U][2];
+  uint32_t mpre = 0;
+  int idreg = -1;
+  float cfreg = 0.f;
+  auto fetch_ids = [&](int tile) {  // threads 0 .. R-1
+    if (tid < R) {
+      const bool on = tile < tiles && tile * R + tid < n;
+      idreg = on ? rows[tile * R + tid] : -1;
+      if (SCALE) cfreg = on ? crow[tile * R + tid] : 0.f;
+    }
+  };
+  auto load_rows = [&](const int* ids) {
+    if (tid < R * 16) {  // sign-mask words of the tile: R rows x (up to) 16 words
+      const int rr = ids[tid >> 4], wd = tid & 15;
+      mpre = (rr >= 0 && wd < mwords) ? ((const uint32_t*)mask)[(size_t)rr * mwords + wd] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = tid + 512 * u, row = i & (R - 1), oct = i / R;
+      const int rr = ids[row];
+      const size_t off = (size_t)max(rr, 0) * ldgi + 8 * min(oct, octs - 1);
+      pre[u][0] = *(const f32x4*)&Gin[off];
+      pre[u][1] = *(const f32x4*)&Gin[off + 4];
+    }
+  };
+  auto store_tile = [&](int buf, const int* ids, const float* cfs) {
+    u32x4* dst = AS + buf * 3 * OCTS * R;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = tid + 512 * u, row = i & (R - 1), oct = i / R;
+      const bool on = ids[row] >= 0 && oct < octs;
+      const float c = SCALE ? cfs[row] : 1.f;
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        v[k] = on ? (SCALE ? pre[u][0][k] * c : pre[u][0][k]) : 0.f;
+        v[4 + k] = on ? (SCALE ? pre[u][1][k] * c : pre[u][1][k]) : 0.f;
+      }
+      u32x4 ph, pm, pq;
+      split3x8(v, ph, pm, pq);
+      dst[(0 * OCTS + oct) * R + row] = ph;
+      dst[(1 * OCTS + oct) * R + row] = pm;
+      dst[(2 * OCTS + oct) * R + row] = pq;
+    }
+  };
+
+  // Tile k of this workgroup is row tile blockIdx.x + k * gridDim.x.  Row ids, coefficients and mask words live in
+  // LDS rings from the request of a tile's rows to its epilogue; the epilogue of a tile runs after that tile's
+  // barrier, beside the next tile's writes, so the rings are one tile deeper than the look-ahead.
+  const int t0 = blockIdx.x, dt = gridDim.x;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    fetch_ids(t0 + k * dt);
+    if (tid < R) { ridb[R * k + tid] = idreg; cfb[R * k + tid] = cfreg; }
+  }
+  lds_barrier();
+  load_rows(ridb);
+  if (NBUF == 2) {
+    store_tile(0, ridb, cfb);
+    if (tid < R * 16) MSb[tid] = mpre;
+    load_rows(ridb + R);
+  }
+  fetch_ids(t0 + 3 * dt);
+  lds_barrier();
+  int it = 0;
+  for (int tile = t0; tile < tiles; tile += dt, ++it) {
+    const int* rid = ridb + R * (it & 7);
+    if (NBUF == 2) {
+      // rows of tile it+1 (in registers) are split into the other buffer, rows of tile it+2 requested
+      store_tile((it + 1) & 1, ridb + R * ((it + 1) & 7), cfb + R * ((it + 1) & 7));
+      if (tid < R * 16) MSb[((it + 1) & 3) * R * 16 + tid] = mpre;
+      if (tid < R) { ridb[R * ((it + 3) & 7) + tid] = idreg; cfb[R * ((it + 3) & 7) + tid] = cfreg; }
+      load_rows(ridb + R * ((it + 2) & 7));
+      fetch_ids(tile + 4 * dt);
+    } else {
+      // one buffer: split this tile's rows (in registers), then request the next tile's
+      store_tile(0, rid, cfb + R * (it & 7));
+      if (tid < R * 16) MSb[(it & 3) * R * 16 + tid] = mpre;
+      if (tid < R) { ridb[R * ((it + 3) & 7) + tid] = idreg; cfb[R * ((it + 3) & 7) + tid] = cfreg; }
+      lds_barrier();
+      load_rows(ridb + R * ((it + 1) & 7));
+      fetch_ids(tile + 4 * dt);
+    }
+    const u32x4* src = AS + (NBUF == 2 ? (it & 1) : 0) * 3 * OCTS * R;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      if (128 * kh + 16 * st < K) {  // (uniform) steps past the contraction length hold nothing
+        const int oct = 16 * kh + 2 * st + kg;
+        const u32x4 ah = src[(0 * OCTS + oct) * R + l32];
+        const u32x4 am = src[(1 * OCTS + oct) * R + l32];
+        const u32x4 al = src[(2 * OCTS + oct) * R + l32];
+        acc = mfma32_bf16(am, wm[st], acc);  // smallest products first
+        acc = mfma32_bf16(al, wh[st], acc);
+        acc = mfma32_bf16(ah, wl[st], acc);
+        acc = mfma32_bf16(am, wh[st], acc);
+        acc = mfma32_bf16(ah, wm[st], acc);
+        acc = mfma32_bf16(ah, wh[st], acc);
+      }
+    }
+    f32x16* xch = XCH + (size_t)(it & 1) * (KH - 1) * CB * 64;
+    if (kh > 0) xch[((kh - 1) * CB + cb) * 64 + lane] = acc;
+    lds_barrier();
+    if (kh == 0) {
+#pragma unroll
+      for (int q = 0; q < KH - 1; ++q) acc += xch[(q * CB + cb) * 64 + lane];
+      if (pcol < P) {
+        const uint32_t* MS = MSb + (it & 3) * R * 16;
+        // unit u = pcol: bit (u % 256) / 4 of the 64-bit word 4 (u / 256) + u % 4 of the row
+        const int bitpos = (pcol & 255) >> 2;
+        const int word32 = 2 * (4 * (pcol >> 8) + (pcol & 3)) + (bitpos >> 5);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = 8 * (r >> 2) + 4 * kg + (r & 3);
+          const int r0 = rid[i];
+          const uint32_t b0 = (MS[i * 16 + word32] >> (bitpos & 31)) & 1u;
+          if (r0 >= 0) ActOut[(size_t)r0 * ldo + pcol] = b0 ? acc[r] : 0.f;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace gfnx
