@@ -72,7 +72,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, w3t, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t hdr, w2p, w3p, w2t, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
   size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
   size_t total;
 };
@@ -153,8 +153,7 @@ Layout make_layout(const Shapes& s) {
   L.hdr = o; o += align256(sizeof(int) * kHdrWords);
   L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
-  L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T, W3^T for the gradient pass
-  L.w3t = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
+  L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T for the 512-wide input-gradient kernel
   L.d1 = o; o += align256(sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1 (rollout)
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
@@ -356,7 +355,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
     pp.kind = env->kind;
     pp.group = env->kind == GFNX_ENV_GRID ? env->grid_side : (env->kind == GFNX_ENV_BITSEQ ? (1 << env->k_bits) + 1 : 3);
     pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
-    pp.W2t = at<float>(ws, L.w2t); pp.W3t = at<float>(ws, L.w3t);
+    pp.W2t = at<float>(ws, L.w2t);
     pp.actions = replay ? nullptr : traj->actions;
     pp.action_bytes = (size_t)traj->max_steps * s.B;
     hipLaunchKernelGGL(prepare_kernel, dim3(kPrepareBlocks), dim3(256), 0, st, pp);
@@ -494,7 +493,6 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   dp.H1 = s.H1; dp.B = B;
   dp.actions = traj->actions; dp.length = traj->length; dp.term = traj->terminal_state;
   dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
-  const int row_tiles = (int)((s.rows + 63) / 64);
 
   // the split partial tiles of every weight / bias gradient are summed by one launch at the end of the pass
   ReduceJobs jobs = {};
@@ -563,13 +561,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                            (const float*)crow, (const int*)rows, (const int*)hdr);
       }
     } else {
-      const int ctiles = (P + 63) / 64, lds = (int)gemm_nt3_lds_bytes<4>();
-      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
-      if (scale) return GFNX_E_UNSUPPORTED;  // (the logit layer has at most 256 outputs)
-      auto k = gemm_nt3_kernel<4, false>;
-      GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
-                         (const float*)crow, (const int*)rows, (const int*)hdr);
+      return GFNX_E_UNSUPPORTED;  // (longer contractions take the binary32 kernel below)
     }
     return GFNX_OK;
   };
@@ -593,8 +585,21 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
-    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
-    if (rc) return rc;
+    if (s.H2 <= 256) {
+      rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
+      if (rc) return rc;
+    } else {
+      // contraction lengths above 256: the binary32 kernel with the slice of W^T in registers
+      const int ctiles = (s.H1 + 127) / 128;
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
+      const int lds = (int)gemm_nt2k_lds_bytes();
+      auto k = gemm_nt2k_kernel;
+      GFNX_ALLOW_LDS(k, lds)
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)h2buf, s.H2, s.H2,
+                         (const float*)at<float>(ws, L.w2t), s.H2, h1buf, s.H1, s.H1,
+                         (const unsigned long long*)at<unsigned long long>(ws, L.m1), s.mw1, (const int*)rows,
+                         (const int*)hdr);
+    }
   }
   // layer 1
   if (s.onehot) {

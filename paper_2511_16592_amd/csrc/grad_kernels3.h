@@ -11,7 +11,7 @@
 //   - the one-hot operand of a round is built in LDS in MFMA A-operand order, [step][row-octet][column][8 x bf16];
 //   - each lane fetches its G1 values (its column, 8 rows per step) straight from global memory, one step ahead;
 //     a row of G1 is read by exactly one wave per 32 columns, so there is nothing to share through LDS.
-// The transitions are split over the workgroups exactly as gemm_tn2_kernel splits them, partial tiles and column
+// The transitions are split over the workgroups exactly as gemm_tn3_kernel splits them, partial tiles and column
 // sums (the bias gradient) have the same layout, and the same fixed-order reductions finish the job.
 #pragma once
 #include "gfnx_device.h"
@@ -189,7 +189,7 @@ inline size_t dw1_onehot_lds_bytes() { return 3 * kDw1Round * 4 + kDw1Round * 11
 // A wave takes one transition at a time (eight in flight): lane l owns hidden units 4l .. 4l+3, i.e. 16 bytes of
 // the 1 KiB row it reads and writes, its 4 x 16 slice of W3 and a 4 x 16 accumulator of dW3 in registers.  The
 // work is HBM-bound (read h2, write G2: 2 KiB per transition); the 128 multiply-adds per lane hide under it.
-// Transitions are split over the workgroups as in gemm_tn2_kernel and the partial tiles / column sums have its
+// Transitions are split over the workgroups as in gemm_tn3_kernel and the partial tiles / column sums have its
 // layout (part[s][unit][QTOT], dbpart[s][QTOT]), so the same reduction finishes dW3 and db3.
 // crow[i] is the coefficient 2 delta_b / B of live transition i.
 constexpr int kNarrowInFlight = 8;

@@ -7,8 +7,10 @@
 // size of the rounding error of one binary32 multiply-add.  Per 32 x 32 x 16 block of work, six bf16 instructions
 // (6 x 32 = 192 cycles of the matrix pipe) replace eight binary32 ones of 32 x 32 x 2 (8 x 64 = 512 cycles).
 //
-// One workgroup = 8 waves holds a PT x QT accumulator tile (256 x 256, 256 x 224 or 256 x 32) like gemm_tn2_kernel,
-// and the transitions are split over blockIdx.z in the same way (same partial-tile layout, same reductions).  The
+// One workgroup = 8 waves holds a PT x QT accumulator tile (256 x 256, 256 x 224 or 256 x 32) of
+// v_mfma_f32_32x32x16_bf16 blocks in registers (blockIdx.x / .y pick the tile of wider operands); the transitions are
+// split over blockIdx.z (split_chunks_per_part), every part writes a partial tile part[s][p][QTOT] and, for
+// blockIdx.x = 0, the column sums of G (the bias gradient) dbpart[s][QTOT]; reduce_jobs_kernel sums the parts.  The
 // matrix instruction contracts 16 transition rows and wants, per lane, 8 consecutive ROWS of one column: each thread
 // therefore loads its column of 8 rows straight from global memory (lanes = consecutive columns: coalesced), splits
 // the 8 values once, and writes three 16-byte pieces to LDS in operand order [piece][row octet][column]; every wave
@@ -310,7 +312,8 @@ namespace gfnx {
 // of the 32 x 32 x 16 instruction wants: no transposed copy); the ReLU derivative comes from the recorded sign masks.
 //
 // The eight waves are CB = 8 / KH column blocks of 32 outputs x KH parts of the contraction, 128 indices each
-// (KH = 2: contraction lengths up to 256, 128 outputs per workgroup; KH = 4: up to 512, 64 outputs per workgroup);
+// (KH = 2, the one in use: contraction lengths up to 256, 128 outputs per workgroup; longer contractions keep the
+// binary32 kernel gemm_nt2k_kernel, which measured faster than the KH = 4 form of this one);
 // a wave keeps the three pieces of its 32 x 128 slice of W in 96 registers for the whole kernel.  Tiles of 32
 // transition rows go through LDS already split: every thread loads 8 consecutive values of a row (two 16-byte
 // loads), splits them once, and writes three 16-byte pieces in operand order [piece][k octet][row]; the waves read

@@ -979,16 +979,16 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   }
 }
 
-// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 32 / 64 / 512
+// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 64 / 512
 // blocks of 256 threads; the last range writes the difference rows of layer 1, see difference_rows_part):
 //   W2p, W3p  W[K][N] row-major -> MFMA A-operand order, out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
 //             zero beyond column N (the rollout's layer-2 and logit weights);
-//   W2t, W3t  transposes Wt[n][k] = W[k][n] (register slices of the input-gradient kernels load coalesced);
+//   W2t       transpose Wt[n][k] = W[k][n] (register slices of the 512-wide input-gradient kernel load coalesced);
 //   actions   every action byte <- 0xFF padding, as 32-bit words (the buffer is 4-byte aligned); skipped when null.
 struct PrepareParams {
   const float *W1, *W2, *W3;
   int In, H1, H2, A, A16;
-  float *W2p, *W3p, *W2t, *W3t;
+  float *W2p, *W3p, *W2t;
   double* D1;       // [In][H1] difference rows of layer 1
   int kind, group;  // environment kind; one-hot columns per state component (grid side, 2^k + 1, 3)
   uint8_t* actions;
@@ -1034,7 +1034,7 @@ __device__ __forceinline__ void transpose_part(const float* __restrict__ W, int 
   }
 }
 constexpr int kDiffBlocks = 512;
-constexpr int kPrepareBlocks = 128 + 64 + 128 + 32 + 64 + kDiffBlocks;
+constexpr int kPrepareBlocks = 128 + 64 + 128 + 64 + kDiffBlocks;
 __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   int b = blockIdx.x;
   if (b < 128) { pack_weights_part(p.W2, p.H1, p.H2, p.H2 >> 4, p.W2p, b, 128); return; }
@@ -1043,8 +1043,6 @@ __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   b -= 64;
   if (b < 128) { transpose_part(p.W2, p.H1, p.H2, p.W2t, b, 128); return; }
   b -= 128;
-  if (b < 32) { transpose_part(p.W3, p.H2, p.A, p.W3t, b, 32); return; }
-  b -= 32;
   if (b >= 64) { difference_rows_part(p, b - 64, kDiffBlocks); return; }
   if (p.actions) {
     const size_t words = p.action_bytes >> 2;
