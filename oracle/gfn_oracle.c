@@ -20,7 +20,10 @@
  *   - hypergrid environment and reward: Appendix "Hypergrid", reward equation,
  *     and the usage listing in "Library Details" (stop action is the LAST index);
  *   - bit sequences, autoregressive fixed-length scheme: Appendix "Sequential
- *     environments" (generation schemes) and "Bit sequences" (reward equation);
+ *     environments" (generation schemes) and "Bit sequences" (reward equation); and in the
+ *     non-autoregressive scheme of the same appendix, the one the paper's bit-sequence
+ *     experiments use (an action = an empty position and the k-bit word written there;
+ *     backward actions remove the word of any filled position);
  *   - Ising partial assignments: Appendix "Ising model" (energy equation,
  *     state / action description);
  *   - environments emit log-reward only on the terminal transition: "Library
@@ -46,13 +49,15 @@
  *   one-hot  grid: index H*i + x_i;  bitseq: 257*pos + tok (tok 256 = empty);
  *            Ising: 3*site + (x+1) with x in {-1, 0(unassigned), +1}.
  *   actions  grid: a<d increments coordinate a, a==d stops;  bitseq: step t writes
- *            token a at position t;  Ising: site = a/2, spin = 2*(a%2)-1.
+ *            token a at position t;  Ising: site = a/2, spin = 2*(a%2)-1;  non-autoregressive
+ *            bitseq: position = a / 2^k, word = a % 2^k, valid iff the position is empty.
  *   sampler  Gumbel-max over the valid actions, lowest index wins exact ties.
  *   RNG      Philox4x32-10 (Salmon et al., SC'11): key = (seed lo, seed hi),
  *            counter = (trajectory b, step t, a/4, iteration lo); output word a%4
  *            serves action a.  u = ((w>>9)+0.5)*2^-23,  g = -log(-log(u)).
  *   log P_B  grid increment: -log #{i : child_i > 0}; grid stop: 0; bitseq: 0;
- *            Ising: -log(#assigned sites of the child) = -log(t+1).
+ *            Ising: -log(#assigned sites of the child) = -log(t+1); non-autoregressive bitseq:
+ *            -log(#filled positions of the child) = -log(t+1).
  *   explore  epsilon-uniform exploration: one more Philox call per step, counter (b, t,
  *            0xFFFFFFFE, iteration lo); word 0 -> u, explore iff u < epsilon (binary32);
  *            word 1 -> the j-th valid action in increasing order, j = floor(w * n / 2^32).
@@ -91,6 +96,7 @@ typedef ORACLE_REAL real;
 #define ENV_GRID 0
 #define ENV_BITSEQ 1
 #define ENV_ISING 2
+#define ENV_BITSEQ_NA 3 /* bit sequences, non-autoregressive scheme: an action picks an empty position and a word */
 
 #define MAX_STATE 1024
 #define MAX_ACT 256
@@ -175,6 +181,12 @@ int oracle_env_dims(const oracle_env* e, int32_t* state_dim, int32_t* obs_dim, i
     *obs_dim = 3 * d;
     *n_actions = 2 * d;
     *max_steps = d;
+  } else if (e->kind == ENV_BITSEQ_NA) {
+    int len = e->n_bits / e->k_bits;
+    *state_dim = len;
+    *obs_dim = len * ((1 << e->k_bits) + 1);
+    *n_actions = len << e->k_bits;
+    *max_steps = len;
   } else {
     return -1;
   }
@@ -183,14 +195,14 @@ int oracle_env_dims(const oracle_env* e, int32_t* state_dim, int32_t* obs_dim, i
 
 /* state vector s[state_dim]: grid coordinate; bitseq token (empty = 2^k); Ising spin (0 = unassigned) */
 static void env_reset(const oracle_env* e, int* s, int sd) {
-  for (int i = 0; i < sd; ++i) s[i] = (e->kind == ENV_BITSEQ) ? (1 << e->k_bits) : 0;
+  for (int i = 0; i < sd; ++i) s[i] = (e->kind == ENV_BITSEQ || e->kind == ENV_BITSEQ_NA) ? (1 << e->k_bits) : 0;
 }
 
 /* indices of the non-zero entries of the one-hot observation, in increasing order */
 static int env_obs_rows(const oracle_env* e, const int* s, int sd, int* rows) {
   for (int i = 0; i < sd; ++i) {
     if (e->kind == ENV_GRID) rows[i] = e->grid_side * i + s[i];
-    else if (e->kind == ENV_BITSEQ) rows[i] = ((1 << e->k_bits) + 1) * i + s[i];
+    else if (e->kind == ENV_BITSEQ || e->kind == ENV_BITSEQ_NA) rows[i] = ((1 << e->k_bits) + 1) * i + s[i];
     else rows[i] = 3 * i + (s[i] + 1);
   }
   return sd;
@@ -201,6 +213,7 @@ static void env_valid(const oracle_env* e, const int* s, int t, int n_actions, i
   for (int a = 0; a < n_actions; ++a) {
     if (e->kind == ENV_GRID) valid[a] = (a == e->grid_dim) ? 1 : (s[a] < e->grid_side - 1);
     else if (e->kind == ENV_BITSEQ) valid[a] = 1;
+    else if (e->kind == ENV_BITSEQ_NA) valid[a] = (s[a >> e->k_bits] == (1 << e->k_bits));
     else valid[a] = (s[a / 2] == 0);
   }
 }
@@ -216,6 +229,10 @@ static int env_step(const oracle_env* e, int* s, int sd, int t, int a) {
     s[t] = a;
     return t + 1 == sd;
   }
+  if (e->kind == ENV_BITSEQ_NA) {
+    s[a >> e->k_bits] = a & ((1 << e->k_bits) - 1);
+    return t + 1 == sd; /* every step fills one position: terminal when none is empty */
+  }
   s[a / 2] = 2 * (a % 2) - 1;
   return t + 1 == sd;
 }
@@ -229,7 +246,7 @@ static real env_log_pb(const oracle_env* e, const int* s, int sd, int t, int a) 
     return -rlog((real)count);
   }
   if (e->kind == ENV_BITSEQ) return 0;
-  return -rlog((real)(t + 1));
+  return -rlog((real)(t + 1)); /* Ising, non-autoregressive bitseq: the child has t+1 assigned sites / filled positions */
 }
 
 static real env_log_reward(const oracle_env* e, const int* s, int sd) {
@@ -248,7 +265,7 @@ static real env_log_reward(const oracle_env* e, const int* s, int sd) {
     real r = (real)e->r0 + (real)e->r1 * (real)in1 + (real)e->r2 * (real)in2;
     return rlog(r);
   }
-  if (e->kind == ENV_BITSEQ) {
+  if (e->kind == ENV_BITSEQ || e->kind == ENV_BITSEQ_NA) {
     int k = e->k_bits, n = e->n_bits, words = (n + 31) / 32;
     int dmin = n + 1;
     for (int m = 0; m < e->n_modes; ++m) {
@@ -346,7 +363,7 @@ int oracle_policy_logits(const oracle_env* e, const oracle_mlp* m, const int32_t
   int t = 0;
   for (int i = 0; i < sd; ++i) {
     s[i] = state[i];
-    if (e->kind == ENV_BITSEQ) t += (s[i] != (1 << e->k_bits));
+    if (e->kind == ENV_BITSEQ || e->kind == ENV_BITSEQ_NA) t += (s[i] != (1 << e->k_bits));
     if (e->kind == ENV_ISING) t += (s[i] != 0);
   }
   act_buf a = act_alloc(m);
@@ -928,6 +945,8 @@ static int env_backward_choices(const oracle_env* e, const int* s, int sd, int* 
     int last = -1; /* left-to-right scheme: only the last written position can be emptied */
     for (int i = 0; i < sd; ++i) if (s[i] != (1 << e->k_bits)) last = i;
     if (last >= 0) choice[n++] = last;
+  } else if (e->kind == ENV_BITSEQ_NA) {
+    for (int i = 0; i < sd; ++i) if (s[i] != (1 << e->k_bits)) choice[n++] = i; /* any filled position */
   } else {
     for (int i = 0; i < sd; ++i) if (s[i] != 0) choice[n++] = i;
   }
@@ -938,6 +957,7 @@ static int env_backward_choices(const oracle_env* e, const int* s, int sd, int* 
 static int env_backward_step(const oracle_env* e, int* s, int c) {
   if (e->kind == ENV_GRID) { s[c] -= 1; return c; }
   if (e->kind == ENV_BITSEQ) { int a = s[c]; s[c] = 1 << e->k_bits; return a; }
+  if (e->kind == ENV_BITSEQ_NA) { int a = (c << e->k_bits) + s[c]; s[c] = 1 << e->k_bits; return a; }
   { int a = 2 * c + (s[c] > 0 ? 1 : 0); s[c] = 0; return a; }
 }
 
@@ -954,7 +974,10 @@ int oracle_backward_rollout(const oracle_env* env, uint64_t seed, uint64_t itera
   const uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
   for (int b = 0; b < batch; ++b) {
     int s[MAX_STATE], choice[MAX_STATE], rev[MAX_STATE + 1];
-    for (int i = 0; i < sd; ++i) s[i] = terminal_state[(size_t)i * batch + b];
+    for (int i = 0; i < sd; ++i) {
+      s[i] = terminal_state[(size_t)i * batch + b];
+      if (env->kind == ENV_BITSEQ || env->kind == ENV_BITSEQ_NA) s[i] &= 0xFF; /* tokens are unsigned bytes */
+    }
     int k = 0, draws = 0;
     real lpb = 0;
     if (env->kind == ENV_GRID) rev[k++] = env->grid_dim; /* un-stop: the terminal copy has one parent */

@@ -16,7 +16,7 @@ from typing import Dict, Optional
 
 import numpy as np
 
-ENV_GRID, ENV_BITSEQ, ENV_ISING = 0, 1, 2
+ENV_GRID, ENV_BITSEQ, ENV_ISING, ENV_BITSEQ_NA = 0, 1, 2, 3
 
 
 @dataclass(frozen=True)
@@ -51,6 +51,9 @@ class EnvSpec:
         if self.kind == ENV_ISING:
             d = self.lattice_n ** 2
             return d, 3 * d, 2 * d, d
+        if self.kind == ENV_BITSEQ_NA:
+            length = self.n_bits // self.k_bits
+            return length, length * ((1 << self.k_bits) + 1), length << self.k_bits, length
         raise ValueError("unknown environment kind")
 
 
@@ -95,6 +98,14 @@ def bitseq_env(n_bits: int, k_bits: int, n_modes: int, mode_seed: int, beta: flo
                uniform_bits: bool = False) -> EnvSpec:
     bits = bitseq_modes(n_bits, n_modes, mode_seed, uniform_bits)
     return EnvSpec(kind=ENV_BITSEQ, n_bits=n_bits, k_bits=k_bits, modes=pack_bits(bits), beta=beta)
+
+
+def bitseq_na_env(n_bits: int, k_bits: int, n_modes: int, mode_seed: int, beta: float = 3.0,
+                  uniform_bits: bool = False) -> EnvSpec:
+    """Bit sequences in the non-autoregressive scheme (Appendix "Sequential environments"): same strings, modes
+    and reward as bitseq_env; an action picks an empty position and the k-bit word written there."""
+    bits = bitseq_modes(n_bits, n_modes, mode_seed, uniform_bits)
+    return EnvSpec(kind=ENV_BITSEQ_NA, n_bits=n_bits, k_bits=k_bits, modes=pack_bits(bits), beta=beta)
 
 
 def xavier_mlp(in_dim: int, h1: int, h2: int, n_actions: int, seed: int,
