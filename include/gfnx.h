@@ -7,8 +7,8 @@
  * is stateless: reset gives s_0, a step maps (state, action) to the child state and emits the
  * log-reward on the terminal transition only ("Library Details", implementation notes and usage
  * listing).  The three environments are the hypergrid (Appendix "Hypergrid"), bit sequences in the
- * autoregressive fixed-length scheme (Appendix "Sequential environments" / "Bit sequences") and the
- * Ising partial-assignment environment (Appendix "Ising model").
+ * autoregressive fixed-length scheme and in the non-autoregressive scheme (Appendix "Sequential environments" /
+ * "Bit sequences") and the Ising partial-assignment environment (Appendix "Ising model").
  *
  * General rules for every call
  *   - returns GFNX_OK (0) or a negative gfnx_status; never throws, aborts or synchronises;
@@ -26,7 +26,8 @@
  *             Ising: 3*site + (x+1), x = 0 for an unassigned site, site = row*N + col.
  *   actions   grid: a < d increments coordinate a (masked when x_a = H-1), a = d stops (last
  *             index, as in the paper's usage listing);  bitseq: step t writes token a at position t;
- *             Ising: site = a/2, spin = 2*(a%2)-1, masked once the site is assigned.
+ *             Ising: site = a/2, spin = 2*(a%2)-1, masked once the site is assigned;  bitseq_na: position = a / 2^k,
+ *             word = a % 2^k, masked once the position is filled.
  *   sampling  Gumbel-max over the valid actions: argmax_a (logit_a + g_a), lowest index on ties,
  *             g = -log(-log(u)), u = ((w >> 9) + 0.5) * 2^-23, w = word (a % 4) of
  *             Philox4x32-10(counter = (b, t, a / 4, iteration lo32), key = (seed lo32, seed hi32)),
@@ -34,7 +35,7 @@
  *             on the batch it is in; its floating-point sums may be rounded in a different order
  *             (relative differences of 1e-7) when the trajectories running beside it differ.
  *   log P_B   uniform over parents: grid increment -log #{i : child_i > 0}, grid stop 0,
- *             bitseq 0, Ising -log(t+1).
+ *             bitseq 0, Ising and bitseq_na -log(t+1).
  */
 #ifndef GFNX_H
 #define GFNX_H
@@ -56,7 +57,7 @@ typedef enum {
   GFNX_E_HIP = -6          /* a HIP runtime call or kernel launch failed */
 } gfnx_status;
 
-typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2 } gfnx_env_kind;
+typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2, GFNX_ENV_BITSEQ_NA = 3 } gfnx_env_kind;
 
 /* Environment + reward descriptor (host struct, copied by value during the call).
  *   grid   : grid_dim d in 1..16, grid_side H in 2..127; reward of the Appendix "Hypergrid" equation,
@@ -68,6 +69,12 @@ typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2 } gfnx
  *   ising  : lattice_n N in 3..10 (N*N <= 100 sites, periodic), R = exp(coupling * sum over the 2*N*N
  *            nearest-neighbour bonds of x_i x_j), each bond counted once (Appendix "Ising model",
  *            energy equation with J = (coupling/2) * adjacency).
+ *   bitseq_na : the same strings, modes and reward as bitseq in the non-autoregressive scheme of Appendix
+ *            "Sequential environments" (the one the paper's bit-sequence experiments use): an action picks an empty
+ *            position and the k-bit word written there, a = position * 2^k + word, L * 2^k actions, masked once
+ *            the position is filled; L steps; log P_B = -log(t+1) (uniform over the filled positions of the
+ *            child).  The kernels take at most 256 actions (e.g. n_bits = 64, k_bits = 4); the paper's instance
+ *            (n = 120, k = 8: 3840 actions, which do not fit the one-byte action plane) is GFNX_E_UNSUPPORTED.
  * Fields of the other kinds are ignored. */
 typedef struct {
   int32_t kind;

@@ -3,7 +3,8 @@
 // A backward rollout ("Library Details": a rollout started at terminal states with the backward step in place of
 // the step; backward actions are the structural choices only) under the fixed uniform backward policy draws, for
 // every trajectory, parents of the current state until s_0 is reached.  No network is involved: one lane per
-// trajectory, the set of undoable indices (grid: coordinates > 0, Ising: assigned sites) as a 128-bit mask in
+// trajectory, the set of undoable indices (grid: coordinates > 0, Ising: assigned sites, non-autoregressive bit
+// sequences: filled positions) as a 128-bit mask in
 // registers, the grid's coordinates in LDS.  The j-th undoable index in increasing order is taken, with
 // j = floor(w * n / 2^32), w = word 0 of Philox4x32-10(counter = (b, k, 0xFFFFFFFF, iteration lo)), k = index of
 // the backward move; the grid's un-stop move and every move of the left-to-right bit sequences have one parent and
@@ -60,7 +61,8 @@ __global__ __launch_bounds__(kBackwardThreads) void backward_rollout_kernel(Back
       on = v > 0;
       moves += v;
     } else {
-      on = true;  // a terminal Ising state has every site assigned: anything not positive counts as -1
+      on = true;  // a terminal Ising state has every site assigned (anything not positive counts as -1), a
+                  // terminal string of the non-autoregressive bit sequences every position filled
       up = v > 0;
       moves += 1;
     }
@@ -97,6 +99,10 @@ __global__ __launch_bounds__(kBackwardThreads) void backward_rollout_kernel(Back
       const int v = coord[idx][lane] - 1;
       coord[idx][lane] = (int8_t)v;
       clear = v == 0;
+    } else if (e.kind == 3) {
+      // non-autoregressive bit sequences: the word of the position that is emptied
+      a = (idx << e.k_bits) + ((int)p.term[(size_t)idx * B + b] & ((1 << e.k_bits) - 1));
+      clear = true;
     } else {
       const uint32_t sw = q == 0 ? s0 : q == 1 ? s1 : q == 2 ? s2 : s3;
       a = 2 * idx + ((sw & bit) ? 1 : 0);

@@ -100,6 +100,14 @@ int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
     *od = 3 * d;
     *na = 2 * d;
     *ms = d;
+  } else if (env->kind == GFNX_ENV_BITSEQ_NA) {
+    if (env->k_bits < 1 || env->k_bits > 8 || env->n_bits < env->k_bits || env->n_bits % env->k_bits) return GFNX_E_BAD_ENV;
+    const int len = env->n_bits / env->k_bits;
+    if (len > 32 || env->n_modes < 1) return GFNX_E_BAD_ENV;
+    *sd = len;
+    *od = len * ((1 << env->k_bits) + 1);
+    *na = len << env->k_bits;  // (the kernels take at most 256 actions: larger instances are GFNX_E_UNSUPPORTED)
+    *ms = len;
   } else {
     return GFNX_E_BAD_ENV;
   }
@@ -110,7 +118,7 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   if (!env || !mlp) return GFNX_E_NULL;
   int rc = env_dims(env, &s->state_dim, &s->obs_dim, &s->n_actions, &s->max_steps);
   if (rc) return rc;
-  if (env->kind == GFNX_ENV_BITSEQ && !env->modes_dev) return GFNX_E_NULL;
+  if ((env->kind == GFNX_ENV_BITSEQ || env->kind == GFNX_ENV_BITSEQ_NA) && !env->modes_dev) return GFNX_E_NULL;
   if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2 || !mlp->W3 || !mlp->b3) return GFNX_E_NULL;
   if (batch <= 0) return GFNX_E_BAD_SHAPE;
   if (mlp->in_dim != s->obs_dim) return GFNX_E_BAD_SHAPE;
@@ -198,7 +206,7 @@ EnvParams env_params(const gfnx_env_desc* env, const Shapes& s) {
   e.d = env->grid_dim; e.H = env->grid_side;
   e.r0 = env->r0; e.r1 = env->r1; e.r2 = env->r2;
   e.n_bits = env->n_bits; e.k_bits = env->k_bits; e.n_modes = env->n_modes;
-  e.L = env->kind == GFNX_ENV_BITSEQ ? env->n_bits / env->k_bits : 0;
+  e.L = (env->kind == GFNX_ENV_BITSEQ || env->kind == GFNX_ENV_BITSEQ_NA) ? env->n_bits / env->k_bits : 0;
   e.words = (env->n_bits + 31) / 32;
   e.modes = env->modes_dev;
   e.beta = env->beta;
@@ -293,6 +301,9 @@ int launch_rollout(const RolloutParams& p, dim3 grid, size_t lds, hipStream_t st
     case GFNX_ENV_BITSEQ:
       return wide ? launch_rollout_ntw<1, REPLAY, 2, EXPLORE>(p, grid, lds, st)
                   : launch_rollout_ntw<1, REPLAY, 1, EXPLORE>(p, grid, lds, st);
+    case GFNX_ENV_BITSEQ_NA:
+      return wide ? launch_rollout_ntw<3, REPLAY, 2, EXPLORE>(p, grid, lds, st)
+                  : launch_rollout_ntw<3, REPLAY, 1, EXPLORE>(p, grid, lds, st);
     default:
       return wide ? launch_rollout_ntw<2, REPLAY, 2, EXPLORE>(p, grid, lds, st)
                   : launch_rollout_ntw<2, REPLAY, 1, EXPLORE>(p, grid, lds, st);
@@ -352,8 +363,8 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
     pp.W1 = mlp->W1; pp.W2 = mlp->W2; pp.W3 = mlp->W3;
     pp.In = s.obs_dim; pp.H1 = s.H1; pp.H2 = s.H2; pp.A = s.A; pp.A16 = s.A16;
     pp.D1 = at<double>(ws, L.d1);
-    pp.kind = env->kind;
-    pp.group = env->kind == GFNX_ENV_GRID ? env->grid_side : (env->kind == GFNX_ENV_BITSEQ ? (1 << env->k_bits) + 1 : 3);
+    pp.kind = env->kind == GFNX_ENV_BITSEQ_NA ? (int)GFNX_ENV_BITSEQ : env->kind;  // same "empty" row per position
+    pp.group = env->kind == GFNX_ENV_GRID ? env->grid_side : (env->kind == GFNX_ENV_ISING ? 3 : (1 << env->k_bits) + 1);
     pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
     pp.W2t = at<float>(ws, L.w2t);
     pp.actions = replay ? nullptr : traj->actions;
@@ -394,7 +405,7 @@ size_t gfnx_workspace_bytes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32
   static const float dummy = 0.f;
   m.W1 = m.b1 = m.W2 = m.b2 = m.W3 = m.b3 = &dummy;
   gfnx_env_desc e = *env;
-  if (e.kind == GFNX_ENV_BITSEQ && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
+  if ((e.kind == GFNX_ENV_BITSEQ || e.kind == GFNX_ENV_BITSEQ_NA) && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
   if (check_shapes(&e, &m, batch, &s)) return 0;
   return make_layout(s).total;
 }
@@ -407,7 +418,7 @@ int gfnx_workspace_region(const gfnx_env_desc* env, const gfnx_mlp* mlp, int32_t
   static const float dummy = 0.f;
   m.W1 = m.b1 = m.W2 = m.b2 = m.W3 = m.b3 = &dummy;
   gfnx_env_desc e = *env;
-  if (e.kind == GFNX_ENV_BITSEQ && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
+  if ((e.kind == GFNX_ENV_BITSEQ || e.kind == GFNX_ENV_BITSEQ_NA) && !e.modes_dev) e.modes_dev = (const uint32_t*)&dummy;
   const int rc = check_shapes(&e, &m, batch, &s);
   if (rc) return rc;
   const Layout L = make_layout(s);
@@ -647,6 +658,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                            s.state_dim, T, 1 << env->k_bits, grads->dW1, grads->db1);
         break;
       }
+      case GFNX_ENV_BITSEQ_NA: hipLaunchKernelGGL(dw1_kernel<3>, dim3(B), dim3(256), 0, st, dp); break;
       default: hipLaunchKernelGGL(dw1_kernel<2>, dim3(B), dim3(256), 0, st, dp); break;
     }
   }

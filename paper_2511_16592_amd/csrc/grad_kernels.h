@@ -196,7 +196,7 @@ struct Dw1Params {
 // One workgroup per trajectory; dW1[r] += sum of g1_t over the steps t at which one-hot row r is active.
 // A row is active on a contiguous run of steps, so no per-step scatter over all active rows is needed:
 //   grid    one running sum per coordinate, flushed to row (i, x_i) when coordinate i is incremented;
-//   bitseq, Ising   a position has two phases: its "empty/unassigned" row is active up to the step that
+//   bitseq (either scheme), Ising   a position has two phases: its "empty/unassigned" row is active up to the step that
 //           fills it (a prefix sum of g1), the row of the value written is active afterwards (a suffix
 //           sum, taken in a second sweep from the end).
 // Only sums of like terms are formed (no differences of long prefix sums), the total is the bias gradient.
@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
     for (int s = 0; s < e.state_dim; ++s) st[s] = 0;
     for (int t = 0; t + 1 < len; ++t) {
       int a = p.actions[(size_t)t * B + b];
-      if (ENV == 0 ? (a >= e.d || st[a] >= e.H - 1) : (a >= e.n_actions)) { bad = 1; break; }
+      if (ENV == 0 ? (a >= e.d || st[a] >= e.H - 1)
+                   : (ENV == 3 ? (a >= e.n_actions || st[a >> e.k_bits]) : (a >= e.n_actions))) { bad = 1; break; }
       if (ENV == 0) {
         rold[t] = e.H * a + st[a];  // row left by this increment
         rnew[t] = a;                // coordinate whose running sum is flushed
@@ -225,6 +226,11 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
         rold[t] = ((1 << e.k_bits) + 1) * t + (1 << e.k_bits);
         rnew[t] = ((1 << e.k_bits) + 1) * t + a;
         st[t] = 1;
+      } else if (ENV == 3) {
+        const int pos = a >> e.k_bits;
+        rold[t] = ((1 << e.k_bits) + 1) * pos + (1 << e.k_bits);
+        rnew[t] = ((1 << e.k_bits) + 1) * pos + (a & ((1 << e.k_bits) - 1));
+        st[pos] = 1;
       } else {
         rold[t] = 3 * (a >> 1) + 1;
         rnew[t] = 3 * (a >> 1) + 1 + 2 * (a & 1) - 1;
@@ -235,7 +241,7 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
     int n = 0;
     for (int s = 0; s < e.state_dim; ++s) {
       if (ENV == 0) rend[n++] = e.H * s + st[s];
-      else if (ENV == 1) { if (!st[s]) rend[n++] = ((1 << e.k_bits) + 1) * s + (1 << e.k_bits); }
+      else if (ENV == 1 || ENV == 3) { if (!st[s]) rend[n++] = ((1 << e.k_bits) + 1) * s + (1 << e.k_bits); }
       else { if (!st[s]) rend[n++] = 3 * s + 1; }
     }
     nend = n;

@@ -33,7 +33,7 @@ constexpr int kRolloutThreads = 64 * kRolloutWaves;
 template <int ENV>
 __device__ __forceinline__ int initial_row(const EnvParams& e, int s) {
   if (ENV == 0) return e.H * s;
-  if (ENV == 1) return ((1 << e.k_bits) + 1) * s + (1 << e.k_bits);
+  if (ENV == 1 || ENV == 3) return ((1 << e.k_bits) + 1) * s + (1 << e.k_bits);
   return 3 * s + 1;
 }
 
@@ -125,6 +125,7 @@ __host__ __device__ inline RolloutLds rollout_lds_layout(int H1, int H2, int A16
   return L;
 }
 
+// ENV  = 0 hypergrid, 1 bit sequences left to right, 2 Ising, 3 bit sequences in the non-autoregressive scheme.
 // NTW  = 16-feature tiles of layer 2 per wave, ceil(H2 / 128).
 // STAT = layer 2 is 256 x 256: each wave keeps its two tiles of W2 (32 KiB) on chip for the whole rollout,
 //        kW2RegQ/16 of them in registers and the rest in LDS; with a single logit tile (grids) its eighth of
@@ -664,6 +665,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
             ok = (uint32_t)(a == e.d) | ((uint32_t)(a < e.d) & (uint32_t)(sv < e.H - 1));
           } else if (ENV == 1) {
             ok = (uint32_t)(a < A);
+          } else if (ENV == 3) {
+            // non-autoregressive bit sequences: action a writes to position a >> k; state byte 0 = empty
+            const uint32_t sv = (uint8_t)stj[min(a >> e.k_bits, e.L - 1)];
+            ok = (uint32_t)(a < A) & (uint32_t)(sv == 0u);
           } else {
             const uint32_t sv = (sw >> (8 * (k >> 1))) & 0xFFu;
             ok = (uint32_t)(a < A) & (uint32_t)(sv == 0u);
@@ -807,6 +812,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
         } else if (ENV == 1) {
           rold = ((1 << e.k_bits) + 1) * ts + (1 << e.k_bits);
           rnew = ((1 << e.k_bits) + 1) * ts + act;
+        } else if (ENV == 3) {
+          rold = ((1 << e.k_bits) + 1) * (act >> e.k_bits) + (1 << e.k_bits);
+          rnew = ((1 << e.k_bits) + 1) * (act >> e.k_bits) + (act & ((1 << e.k_bits) - 1));
         } else {
           rold = 3 * (act >> 1) + 1;
           rnew = 3 * (act >> 1) + 2 * (act & 1);
@@ -884,6 +892,29 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           logr = -(e.beta / (float)e.n_bits) * (float)dmin;
           term = true;
         }
+      } else if (ENV == 3) {
+        // non-autoregressive bit sequences: `site` = position, `spin` = the k-bit word written there (state byte
+        // word + 1, 0 = empty); the backward policy is uniform over the t+1 filled positions of the child
+        const int k = e.k_bits;
+        site = act >> k;
+        spin = act & ((1 << k) - 1);
+        if (si == 0) stj[site] = (int8_t)(spin + 1);
+        lpb -= __builtin_amdgcn_logf((float)(t + 1)) * 0.693147180559945f;
+        if (t == e.L - 1) {
+          int dmin = 0x7fffffff;
+          for (int mm = si; mm < e.n_modes; mm += LPS) {
+            int dist = 0;
+            for (int pos = 0; pos < e.L; ++pos) {
+              const uint32_t tok = (pos == site) ? (uint32_t)spin : (uint32_t)(uint8_t)stj[pos] - 1u;
+              const uint32_t rev = __brev(tok) >> (32 - k);
+              dist += __popc(rev ^ mode_chunk(e.modes, e.words, mm, pos, k));
+            }
+            dmin = min(dmin, dist);
+          }
+          dmin = grp_min<LPS>(dmin);
+          logr = -(e.beta / (float)e.n_bits) * (float)dmin;
+          term = true;
+        }
       } else {
         site = act >> 1;
         spin = 2 * (act & 1) - 1;
@@ -922,6 +953,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           int v;
           if (ENV == 0) v = xi;  // state_dim <= 16: lane s holds coordinate s
           else if (ENV == 1) v = (s == t && given_ok) ? act : (int)(uint8_t)stj[s];
+          else if (ENV == 3) v = (s == site) ? spin : (int)(uint8_t)stj[s] - 1;
           else v = (s == site) ? spin : stj[s];
           p.term[(size_t)s * B + sb] = (int8_t)v;
         }

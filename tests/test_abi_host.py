@@ -7,7 +7,7 @@ import re
 import pytest
 
 from paper_2511_16592_amd import gfnx
-from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, workloads
+from paper_2511_16592_amd.workloads import bitseq_env, bitseq_na_env, grid_env, ising_env, workloads
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -251,3 +251,22 @@ def test_static_scratch_entry_point_rejects_oversize_on_the_host(lib):
     assert call(C.byref(d), C.byref(_mlp(299, 256, 256, 200)), C.byref(t)) == -3
     small = _traj(16, 100)
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(m), 16) <= (64 << 20)
+
+
+def test_non_autoregressive_bit_sequence_dims_and_limits(lib):
+    """gfnx_env_dims of the (position, word) environment; 256 actions are the most the kernels take: the paper's
+    n = 120, k = 8 instance (3840 actions) is reported as unsupported by the size query."""
+    assert gfnx.env_dims(bitseq_na_env(24, 4, 3, 1)) == (6, 6 * 17, 6 * 16, 6)
+    assert gfnx.env_dims(bitseq_na_env(64, 4, 3, 1)) == (16, 16 * 17, 256, 16)
+    assert gfnx.env_dims(bitseq_na_env(120, 8, 3, 1)) == (15, 3855, 3840, 15)
+    d = gfnx.env_desc(bitseq_na_env(64, 4, 3, 1), 0x1000)
+    assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16 * 17, 256, 256, 256)), 64) > 0
+    big = gfnx.env_desc(bitseq_na_env(120, 8, 3, 1), 0x1000)
+    assert lib.gfnx_workspace_bytes(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 64) == 0
+    t = _traj(64, 15)
+    assert lib.gfnx_rollout(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.byref(t), 0x10000, 1 << 30,
+                            None) == -5
+    bad = gfnx.env_desc(bitseq_na_env(64, 4, 3, 1), 0x1000)
+    bad.k_bits = 5
+    out = C.c_int32()
+    assert lib.gfnx_env_dims(C.byref(bad), C.byref(out), None, None, None) == -2

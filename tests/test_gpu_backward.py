@@ -10,7 +10,7 @@ import os
 import numpy as np
 import pytest
 
-from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, random_mlp, workloads
+from paper_2511_16592_amd.workloads import bitseq_env, bitseq_na_env, grid_env, ising_env, random_mlp, workloads
 from tests.helpers import grid_reward, grid_terminal_distribution
 from tests.test_oracle_backward import _random_terminal_states
 
@@ -46,6 +46,8 @@ CASES = [
     ("bitseq120", bitseq_env(120, 8, 60, mode_seed=3), (64, 128), 130),
     ("ising3", ising_env(3), (64, 64), 33),
     ("ising10", ising_env(10), (256, 256), 260),
+    ("bitseq_na24", bitseq_na_env(24, 4, 7, mode_seed=2), (64, 64), 45),
+    ("bitseq_na64_256", bitseq_na_env(64, 4, 20, mode_seed=3), (256, 256), 130),
 ]
 
 

@@ -9,7 +9,7 @@ import os
 import numpy as np
 import pytest
 
-from paper_2511_16592_amd.workloads import bitseq_env, grid_env, ising_env, random_mlp
+from paper_2511_16592_amd.workloads import bitseq_env, bitseq_na_env, grid_env, ising_env, random_mlp
 from tests.test_gpu_parity import check_gradients, gfnx, relu_decisions, say  # noqa: F401  (gfnx is the module fixture)
 
 pytestmark = pytest.mark.gpu
@@ -26,6 +26,8 @@ CASES = [
     ("bitseq24", bitseq_env(24, 4, 7, mode_seed=2), (64, 64), 45, 0.5),
     ("bitseq120", bitseq_env(120, 8, 60, mode_seed=3), (64, 128), 40, 0.2),
     ("bitseq120_256", bitseq_env(120, 8, 60, mode_seed=3), (256, 256), 40, 0.2),
+    ("bitseq_na24", bitseq_na_env(24, 4, 7, mode_seed=2), (64, 64), 45, 0.4),
+    ("bitseq_na64_256", bitseq_na_env(64, 4, 20, mode_seed=3), (256, 256), 40, 0.2),
 ]
 
 

@@ -19,7 +19,8 @@ import os
 import numpy as np
 import pytest
 
-from paper_2511_16592_amd.workloads import (bitseq_env, grid_env, ising_env, random_mlp, workloads, xavier_mlp)
+from paper_2511_16592_amd.workloads import (bitseq_env, bitseq_na_env, grid_env, ising_env, random_mlp, workloads,
+                                            xavier_mlp)
 from tests.helpers import (chi2_sf, enumerate_grid_trajectories, grid_reward, optimal_policy_mlp_2d,
                            pack_trajectories)
 
@@ -231,6 +232,44 @@ def test_wide_networks_small_envs(gfnx, oracle32, oracle64, case):
     name, env, (n_in, h1, h2, n_act), batch = case
     w = random_mlp(n_in, h1, h2, n_act, seed=36, scale=1.5)
     run_case(gfnx, oracle32, oracle64, env, w, batch, seed=11, iteration=5, log_z=0.4, name=name)
+
+
+def _na_cases():
+    """Bit sequences in the non-autoregressive scheme (position, word): one and two logit chunks per lane, resident
+    and streamed layer 2, one-bit words (two positions per chunk of four actions), words that straddle the 32-bit
+    words of the packed modes, the largest action space the kernels take (256), a batch with slot refill."""
+    return [
+        ("na12k2", bitseq_na_env(12, 2, 5, mode_seed=2, uniform_bits=True), (64, 64), 60),
+        ("na24k4", bitseq_na_env(24, 4, 7, mode_seed=2), (64, 128), 45),
+        ("na8k1", bitseq_na_env(8, 1, 4, mode_seed=4, uniform_bits=True), (64, 64), 70),
+        ("na21k3", bitseq_na_env(21, 3, 5, mode_seed=4, uniform_bits=True), (128, 64), 33),
+        ("na24k4_256", bitseq_na_env(24, 4, 7, mode_seed=2), (256, 256), 90),
+        ("na64k4_256", bitseq_na_env(64, 4, 20, mode_seed=3), (256, 256), 300),
+        ("na64k4_512_refill", bitseq_na_env(64, 4, 20, mode_seed=3), (512, 512), 4200),
+        ("na40k5", bitseq_na_env(40, 5, 9, mode_seed=6, uniform_bits=True), (192, 64), 50),
+    ]
+
+
+@pytest.mark.parametrize("case", _na_cases(), ids=lambda c: c[0])
+def test_non_autoregressive_bit_sequences(gfnx, oracle32, oracle64, case):
+    name, env, (h1, h2), batch = case
+    sd, od, na, ms = env.dims()
+    w = random_mlp(od, h1, h2, na, seed=39, scale=1.5)
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, batch, seed=17, iteration=3, log_z=0.3, name=name)
+    assert (traj["length"] == ms).all()
+    pos = traj["actions"].astype(int) >> env.k_bits
+    assert (np.sort(pos, axis=0) == np.arange(ms)[:, None]).all()       # every position filled exactly once
+    assert np.allclose(traj["log_pb"], -math.lgamma(ms + 1), rtol=1e-5)  # uniform over the filled positions
+    if batch >= 60:
+        assert len({tuple(pos[:, b]) for b in range(batch)}) > batch // 3  # in many different orders
+
+
+def test_paper_size_non_autoregressive_instance_is_refused(gfnx):
+    """n = 120, k = 8: 3840 actions, more than the one-byte action plane and the logit tile take."""
+    env = bitseq_na_env(120, 8, 60, mode_seed=3)
+    with pytest.raises(gfnx.GfnxError) as err:
+        gfnx.Session(env, random_mlp(3855, 64, 64, 3840, seed=1), 16)
+    assert err.value.status in (-3, -5)
 
 
 def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):

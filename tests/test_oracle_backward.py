@@ -14,7 +14,7 @@ def _random_terminal_states(env, batch, rng):
     sd = env.dims()[0]
     if env.kind == 0:
         return rng.integers(0, env.grid_side, size=(sd, batch)).astype(np.int8)
-    if env.kind == 1:
+    if env.kind in (1, 3):
         return rng.integers(0, 1 << env.k_bits, size=(sd, batch)).astype(np.uint8).view(np.int8)
     return (2 * rng.integers(0, 2, size=(sd, batch)) - 1).astype(np.int8)
 
