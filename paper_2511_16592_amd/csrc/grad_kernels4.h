@@ -18,6 +18,7 @@
 // work on step s, the values of step s+1 (in registers since the previous step) are split and written, and the loads
 // of step s+2 are in flight; the row ids run one step further ahead.  One barrier per step.
 #pragma once
+#include <type_traits>
 #include "gfnx_device.h"
 #include "grad_kernels.h"
 #include "grad_kernels2.h"
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(512) void gemm_tn3_kernel(const float* __restrict__
       xok[u] = 0u;
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        xv[u][k] = src[(size_t)max(id[k], 0) * ldx];
+        xv[u][k] = src[(uint64_t)(uint32_t)max(id[k], 0) * (uint32_t)ldx];
         xok[u] |= (uint32_t)(xon[u] && id[k] >= 0) << k;
       }
     }
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(512) void gemm_tn3_kernel(const float* __restrict__
       gok[u] = 0u;
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        gv[u][k] = src[(size_t)max(id[k], 0) * ldg];
+        gv[u][k] = src[(uint64_t)(uint32_t)max(id[k], 0) * (uint32_t)ldg];
         gok[u] |= (uint32_t)(gon[u] && id[k] >= 0) << k;
         if (SCALE) gcv[u][k] = cf[k];
       }
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
   f32x16* XCH = (f32x16*)(AS + NBUF * 3 * OCTS * R);              // [2][KH - 1][CB][64]
   int* ridb = (int*)(XCH + 2 * (KH - 1) * CB * 64);               // [8][R]
   float* cfb = (float*)(ridb + 8 * R);                            // [8][R]
-  uint32_t* MSb = (uint32_t*)(cfb + 8 * R);                       // [4][R][16]
+  uint32_t* MSb = (uint32_t*)(cfb + 8 * R);                       // [4][16 words][R]: the mask words, transposed
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int cb = w % CB, kh = w / CB, kg = lane >> 5, l32 = lane & 31;
   const int n = hdr[kHdrNLive];
@@ -383,13 +384,13 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
   auto load_rows = [&](const int* ids) {
     if (tid < R * 16) {  // sign-mask words of the tile: R rows x (up to) 16 words
       const int rr = ids[tid >> 4], wd = tid & 15;
-      mpre = (rr >= 0 && wd < mwords) ? ((const uint32_t*)mask)[(size_t)rr * mwords + wd] : 0u;
+      mpre = (rr >= 0 && wd < mwords) ? ((const uint32_t*)mask)[(uint64_t)(uint32_t)max(rr, 0) * (uint32_t)mwords + (uint32_t)wd] : 0u;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int i = tid + 512 * u, row = i & (R - 1), oct = i / R;
       const int rr = ids[row];
-      const size_t off = (size_t)max(rr, 0) * ldgi + 8 * min(oct, octs - 1);
+      const uint64_t off = (uint64_t)(uint32_t)max(rr, 0) * (uint32_t)ldgi + (uint32_t)(8 * min(oct, octs - 1));
       pre[u][0] = *(const f32x4*)&Gin[off];
       pre[u][1] = *(const f32x4*)&Gin[off + 4];
     }
@@ -428,7 +429,7 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
   load_rows(ridb);
   if (NBUF == 2) {
     store_tile(0, ridb, cfb);
-    if (tid < R * 16) MSb[tid] = mpre;
+    if (tid < R * 16) MSb[(tid & 15) * R + (tid >> 4)] = mpre;
     load_rows(ridb + R);
   }
   fetch_ids(t0 + 3 * dt);
@@ -439,14 +440,14 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
     if (NBUF == 2) {
       // rows of tile it+1 (in registers) are split into the other buffer, rows of tile it+2 requested
       store_tile((it + 1) & 1, ridb + R * ((it + 1) & 7), cfb + R * ((it + 1) & 7));
-      if (tid < R * 16) MSb[((it + 1) & 3) * R * 16 + tid] = mpre;
+      if (tid < R * 16) MSb[((it + 1) & 3) * R * 16 + (tid & 15) * R + (tid >> 4)] = mpre;
       if (tid < R) { ridb[R * ((it + 3) & 7) + tid] = idreg; cfb[R * ((it + 3) & 7) + tid] = cfreg; }
       load_rows(ridb + R * ((it + 2) & 7));
       fetch_ids(tile + 4 * dt);
     } else {
       // one buffer: split this tile's rows (in registers), then request the next tile's
       store_tile(0, rid, cfb + R * (it & 7));
-      if (tid < R * 16) MSb[(it & 3) * R * 16 + tid] = mpre;
+      if (tid < R * 16) MSb[(it & 3) * R * 16 + (tid & 15) * R + (tid >> 4)] = mpre;
       if (tid < R) { ridb[R * ((it + 3) & 7) + tid] = idreg; cfb[R * ((it + 3) & 7) + tid] = cfreg; }
       lds_barrier();
       load_rows(ridb + R * ((it + 1) & 7));
@@ -456,19 +457,29 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    {
+      // steps past the contraction length hold nothing (uniform); the operands of step st+1 are read before the six
+      // matrix instructions of step st
+      const int nst = min(8, max(0, (K - 128 * kh + 15) >> 4));
+      const u32x4* ap = src + (16 * kh + kg) * R + l32;
+      u32x4 ah = ap[0], am = ap[OCTS * R], al = ap[2 * OCTS * R];
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      if (128 * kh + 16 * st < K) {  // (uniform) steps past the contraction length hold nothing
-        const int oct = 16 * kh + 2 * st + kg;
-        const u32x4 ah = src[(0 * OCTS + oct) * R + l32];
-        const u32x4 am = src[(1 * OCTS + oct) * R + l32];
-        const u32x4 al = src[(2 * OCTS + oct) * R + l32];
-        acc = mfma32_bf16(am, wm[st], acc);  // smallest products first
-        acc = mfma32_bf16(al, wh[st], acc);
-        acc = mfma32_bf16(ah, wl[st], acc);
-        acc = mfma32_bf16(am, wh[st], acc);
-        acc = mfma32_bf16(ah, wm[st], acc);
-        acc = mfma32_bf16(ah, wh[st], acc);
+      for (int st = 0; st < 8; ++st) {
+        if (st < nst) {
+          u32x4 nh = ah, nm = am, nl = al;
+          if (st + 1 < nst) {
+            nh = ap[2 * (st + 1) * R];
+            nm = ap[(OCTS + 2 * (st + 1)) * R];
+            nl = ap[(2 * OCTS + 2 * (st + 1)) * R];
+          }
+          acc = mfma32_bf16(am, wm[st], acc);  // smallest products first
+          acc = mfma32_bf16(al, wh[st], acc);
+          acc = mfma32_bf16(ah, wl[st], acc);
+          acc = mfma32_bf16(am, wh[st], acc);
+          acc = mfma32_bf16(ah, wm[st], acc);
+          acc = mfma32_bf16(ah, wh[st], acc);
+          ah = nh; am = nm; al = nl;
+        }
       }
     }
     f32x16* xch = XCH + (size_t)(it & 1) * (KH - 1) * CB * 64;
@@ -478,17 +489,36 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
 #pragma unroll
       for (int q = 0; q < KH - 1; ++q) acc += xch[(q * CB + cb) * 64 + lane];
       if (pcol < P) {
-        const uint32_t* MS = MSb + (it & 3) * R * 16;
-        // unit u = pcol: bit (u % 256) / 4 of the 64-bit word 4 (u / 256) + u % 4 of the row
+        // unit u = pcol: bit (u % 256) / 4 of the 64-bit word 4 (u / 256) + u % 4 of the row; the words of this
+        // lane's column and the row ids come as four 16-byte reads each (rows 8 q + 4 kg .. + 3, q = 0 .. 3).
+        // Only the last row tile holds padding rows (id -1): every other tile stores without a test.
         const int bitpos = (pcol & 255) >> 2;
         const int word32 = 2 * (4 * (pcol >> 8) + (pcol & 3)) + (bitpos >> 5);
+        const uint32_t* MS = MSb + (it & 3) * R * 16 + word32 * R;
+        const uint32_t rowbytes = (uint32_t)ldo * 4u;
+        char* const colbase = (char*)(ActOut + pcol);
+        auto store_rows = [&](auto all_rows) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int i = 8 * (r >> 2) + 4 * kg + (r & 3);
-          const int r0 = rid[i];
-          const uint32_t b0 = (MS[i * 16 + word32] >> (bitpos & 31)) & 1u;
-          if (r0 >= 0) ActOut[(size_t)r0 * ldo + pcol] = b0 ? acc[r] : 0.f;
-        }
+          for (int q = 0; q < 4; ++q) {
+            const int4 ids = *(const int4*)&rid[8 * q + 4 * kg];
+            const int4 mw = *(const int4*)&MS[8 * q + 4 * kg];
+            const int id4[4] = {ids.x, ids.y, ids.z, ids.w};
+            const int mw4[4] = {mw.x, mw.y, mw.z, mw.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              // all ones where the unit was active
+              const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(mw4[k], bitpos & 31, 1);
+              const float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
+              const float v = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
+              float* dst = (float*)(colbase + (uint64_t)(uint32_t)id4[k] * rowbytes);
+              if (decltype(all_rows)::value || id4[k] >= 0) *dst = v;
+            }
+          }
+        };
+        if ((tile + 1) * R <= n)
+          store_rows(std::true_type{});
+        else
+          store_rows(std::false_type{});
       }
     }
   }
