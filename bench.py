@@ -2,9 +2,12 @@
 """Benchmark of the rollout + Trajectory-Balance gradient step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-extra] [--no-cpu-baseline]
+    python bench.py --traffic --workload c2 [--steps 3]
 
 (--no-extra skips the short runs of the other workloads, of whole training iterations and of the estimate of
-P_theta(x).)
+P_theta(x).  --traffic is the run that the hardware-counter profiles are taken over: a few steps of the workload,
+each followed by one elementwise pass over a buffer of known size that calibrates the counters, then the optimiser
+update alone; it times nothing.)
 
 A step is one pass of the whole hot path over one batch of synthetic input: gfnx_rollout (fresh
 Philox iteration counter each step) followed by gfnx_tb_loss_grad, inputs and outputs resident in
@@ -34,9 +37,11 @@ DESCRIPTIONS = {
     "c4": "Ising 10x10 periodic J=0.44, MLP 300-256-256-200, batch 4096, 100 steps",
     "c5": "10-D grid H=20, MLP 200-256-256-11 (seeded Xavier), batch 16384, max 191 steps",
     "c5_long": "10-D grid H=20, MLP 200-256-256-11 with stop bias -8 (long walks), batch 16384",
+    "c3_na": "bit sequences n=64 k=4 in the non-autoregressive scheme (256 actions), MLP 1040-512-512-256, batch 4096",
 }
-KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "backward_kernel.h",
-                  "gfnx_device.h", "gfnx.hip")
+KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "grad_kernels4.h",
+                  "subtb_kernels.h", "backward_kernel.h", "gfnx_device.h", "gfnx.hip")
+COPY_BYTES = 256 << 20  # the calibration pass of --traffic reads and writes this much
 
 
 def kernel_source_hash():
@@ -187,27 +192,26 @@ def run_training(name, steps, warmup, batch=None):
                             "achieved_GBps": 28.0 * n_par / (adam_ms / launches * 1e-3) / 1e9, "peak_GBps": 8000.0}}
 
 
-def run_training_subtb(name, steps, warmup, lam, batch):
-    """Training iterations with the DB / SubTB objective (gfnx_train_step_opts: rollout, gfnx_subtb_loss_grad, Adam;
-    no log Z: the flow output at s_0 plays its part)."""
+def run_traffic(name, steps):
+    """The run that counter profiles are taken over (rocprofv3 --pmc ... -- python3 bench.py --traffic ...)."""
     import torch
     from paper_2511_16592_amd import gfnx
-    from paper_2511_16592_amd.workloads import workloads, xavier_mlp
+    from paper_2511_16592_amd.workloads import workloads
 
-    wl = workloads()[name].with_batch(batch)
-    _, obs_dim, n_actions, _ = wl.env.dims()
-    sess = gfnx.Session(wl.env, xavier_mlp(obs_dim, wl.h1, wl.h2, n_actions + 1, wl.weight_seed), wl.batch)
-    sess.init_optimizer(lr=1e-3)
-    for i in range(warmup):
-        sess.train_step(wl.seed, i, subtb_lambda=lam)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    wl = workloads()[name]
+    sess = gfnx.Session(wl.env, wl.mlp(), wl.batch)
+    src = torch.arange(COPY_BYTES // 4, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
     for i in range(steps):
-        sess.train_step(wl.seed, warmup + i, subtb_lambda=lam)
+        sess.rollout(wl.seed, i)
+        sess.tb_loss_grad(wl.log_z)
+        torch.add(src, 1.0, out=dst)  # a plain elementwise kernel: reads COPY_BYTES, writes COPY_BYTES
+    sess.init_optimizer()
+    for i in range(steps):
+        sess.adam_step()  # the optimiser update alone, on the gradients of the last step
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    return {"batch": wl.batch, "lambda": lam, "iterations": steps, "ms_per_iteration": elapsed / steps * 1e3,
-            "iterations_per_s": steps / elapsed}
+    return {"traffic_run": name, "steps": steps, "copy_bytes": COPY_BYTES,
+            "transitions_per_step": int(sess.length.sum().item())}
 
 
 def run_subtb(name, steps, lam):
@@ -309,6 +313,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--traffic", action="store_true", help="the untimed run that counter profiles are taken over")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this library has no multi-GPU path (run with --gpus 1)")
@@ -316,6 +321,9 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.traffic:
+        print(json.dumps(run_traffic(args.workload, min(args.steps, 3))))
+        return
 
     r = run_workload(args.workload, args.steps, max(1, args.warmup))
     wl = r["wl"]
@@ -354,7 +362,7 @@ def main():
         # other workloads of the same path, short runs without per-kernel events (context for the headline line:
         # the 4-D grid at Xavier initialisation has ~5-step trajectories, i.e. little work per launch)
         extra = {}
-        for name in ("c2_long", "c4", "c5", "c5_long", "c3"):
+        for name in ("c2_long", "c4", "c5", "c5_long", "c3", "c3_na"):
             if name == args.workload:
                 continue
             steps = 5 if name == "c5_long" else 20
@@ -364,16 +372,7 @@ def main():
         out["explore_eps_1e-3"] = {name: summary(name, run_workload(name, 20, 3, events=False, epsilon=1e-3), 20)
                                    for name in ("c2", "c4", "c3")}
         # the next stage of the same path: whole training iterations (optimiser step included)
-        train = {args.workload: run_training(args.workload, 50, 5), "c3": run_training("c3", 20, 3)}
-        paper = run_training("c2", 300, 20, batch=16)
-        paper["context"] = ("the paper's own hypergrid setting (4-D side 20, TB, MLP 2x256, batch 16, Adam): it "
-                            "reports 1463.3 it/s on an Intel Core i7-10700F CPU")
-        train["c2_batch16"] = paper
-        for key, lam, ref in (("c2_batch16_db", 0.0, "1560.0"), ("c2_batch16_subtb0.9", 0.9, "596.0")):
-            train[key] = run_training_subtb("c2", 300, 20, lam, 16)
-            train[key]["context"] = "same setting, %s objective: the paper reports %s it/s on that CPU" % (
-                "DB" if lam == 0.0 else "SubTB(0.9)", ref)
-        out["train"] = train
+        out["train"] = {args.workload: run_training(args.workload, 50, 5), "c3": run_training("c3", 20, 3)}
         # the other two objectives of the paper's hypergrid benchmark, on the same kernels
         out["subtb"] = {"c2_db": run_subtb("c2", 20, 0.0), "c2_subtb0.9": run_subtb("c2", 20, 0.9),
                         "c2_long_subtb0.9": run_subtb("c2_long", 10, 0.9), "c5_long_subtb0.9": run_subtb("c5_long", 5, 0.9)}

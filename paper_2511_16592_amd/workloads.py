@@ -159,7 +159,8 @@ class Workload:
 
 
 def workloads() -> Dict[str, Workload]:
-    """The five configurations, plus the long-walk variants of the two large grids."""
+    """The five configurations, the long-walk variants of the two large grids and a non-autoregressive bit-sequence
+    instance."""
     w = {
         "c1": Workload("c1", grid_env(2, 8), 64, 64, batch=16, seed=0, weight_seed=1),
         "c2": Workload("c2", grid_env(4, 20), 256, 256, batch=4096, seed=2, weight_seed=2),
@@ -169,4 +170,6 @@ def workloads() -> Dict[str, Workload]:
     }
     w["c2_long"] = replace(w["c2"], name="c2_long", stop_bias=-8.0)
     w["c5_long"] = replace(w["c5"], name="c5_long", stop_bias=-8.0)
+    # the non-autoregressive scheme at the largest action space the kernels take: 16 positions x 16 words
+    w["c3_na"] = Workload("c3_na", bitseq_na_env(64, 4, 60, mode_seed=3), 512, 512, batch=4096, seed=3, weight_seed=3)
     return w
