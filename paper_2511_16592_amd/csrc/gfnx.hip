@@ -72,7 +72,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, w2t, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t hdr, w2p, w3p, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
   size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
   size_t total;
 };
@@ -161,7 +161,6 @@ Layout make_layout(const Shapes& s) {
   L.hdr = o; o += align256(sizeof(int) * kHdrWords);
   L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
-  L.w2t = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);   // W2^T for the 512-wide input-gradient kernel
   L.d1 = o; o += align256(sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1 (rollout)
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
@@ -357,7 +356,7 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   const size_t lds = rollout_lds_bytes(s, env->kind == GFNX_ENV_GRID);
   if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
   {
-    // packed and transposed weights, and (free-running rollout) every action byte preset to the 0xFF padding
+    // packed weights, difference rows, and (free-running rollout) every action byte preset to the 0xFF padding
     GFNX_TIMED("prepare", st);
     PrepareParams pp = {};
     pp.W1 = mlp->W1; pp.W2 = mlp->W2; pp.W3 = mlp->W3;
@@ -366,7 +365,6 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
     pp.kind = env->kind == GFNX_ENV_BITSEQ_NA ? (int)GFNX_ENV_BITSEQ : env->kind;  // same "empty" row per position
     pp.group = env->kind == GFNX_ENV_GRID ? env->grid_side : (env->kind == GFNX_ENV_ISING ? 3 : (1 << env->k_bits) + 1);
     pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
-    pp.W2t = at<float>(ws, L.w2t);
     pp.actions = replay ? nullptr : traj->actions;
     pp.action_bytes = (size_t)traj->max_steps * s.B;
     hipLaunchKernelGGL(prepare_kernel, dim3(kPrepareBlocks), dim3(256), 0, st, pp);
@@ -572,7 +570,15 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                            (const float*)crow, (const int*)rows, (const int*)hdr);
       }
     } else {
-      return GFNX_E_UNSUPPORTED;  // (longer contractions take the binary32 kernel below)
+      // contraction lengths 257 .. 512: four contraction parts x two column blocks per workgroup (never scaled: only
+      // layer 2 of a wide network is that long, the logit layer has at most 256 outputs)
+      if (scale || K > 512) return GFNX_E_UNSUPPORTED;
+      const int ctiles = (P + 63) / 64, lds = (int)gemm_nt3_lds_bytes<4>();
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
+      auto k = gemm_nt3_kernel<4, false>;
+      GFNX_ALLOW_LDS(k, lds)
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+                         (const float*)crow, (const int*)rows, (const int*)hdr);
     }
     return GFNX_OK;
   };
@@ -596,21 +602,8 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
-    if (s.H2 <= 256) {
-      rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
-      if (rc) return rc;
-    } else {
-      // contraction lengths above 256: the binary32 kernel with the slice of W^T in registers
-      const int ctiles = (s.H1 + 127) / 128;
-      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
-      const int lds = (int)gemm_nt2k_lds_bytes();
-      auto k = gemm_nt2k_kernel;
-      GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)h2buf, s.H2, s.H2,
-                         (const float*)at<float>(ws, L.w2t), s.H2, h1buf, s.H1, s.H1,
-                         (const unsigned long long*)at<unsigned long long>(ws, L.m1), s.mw1, (const int*)rows,
-                         (const int*)hdr);
-    }
+    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
+    if (rc) return rc;
   }
   // layer 1
   if (s.onehot) {

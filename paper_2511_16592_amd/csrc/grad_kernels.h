@@ -7,7 +7,7 @@
 //   dW3 = H2^T G3, db3 = colsum G3                   (gemm_tn3_kernel, split over the transitions)
 //   G2 = (G3 W3^T) . [h2 > 0]   written over h2      (gemm_nt3_kernel; both in logit_bwd_narrow_kernel for <= 16 logits)
 //   dW2 = H1^T G2, db2 = colsum G2                   (gemm_tn3_kernel)
-//   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt3_kernel / gemm_nt2k_kernel)
+//   G1 = (G2 W2^T) . [h1 > 0]   written over h1      (gemm_nt3_kernel)
 //   dW1, db1 from G1                                 (dw1_onehot_kernel; dw1_kernel below for wide one-hot inputs)
 // This file: rows_kernel (residuals, loss, the list), adam_kernel (optimiser step), fill_kernel, dw1_kernel
 // (per-trajectory segment sums with atomics).

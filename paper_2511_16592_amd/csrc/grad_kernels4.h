@@ -313,13 +313,13 @@ namespace gfnx {
 // of the 32 x 32 x 16 instruction wants: no transposed copy); the ReLU derivative comes from the recorded sign masks.
 //
 // The eight waves are CB = 8 / KH column blocks of 32 outputs x KH parts of the contraction, 128 indices each
-// (KH = 2, the one in use: contraction lengths up to 256, 128 outputs per workgroup; longer contractions keep the
-// binary32 kernel gemm_nt2k_kernel, which measured faster than the KH = 4 form of this one);
+// (KH = 2: contraction lengths up to 256, 128 outputs per workgroup; KH = 4: up to 512, 64 outputs per workgroup);
 // a wave keeps the three pieces of its 32 x 128 slice of W in 96 registers for the whole kernel.  Tiles of 32
 // transition rows go through LDS already split: every thread loads 8 consecutive values of a row (two 16-byte
 // loads), splits them once, and writes three 16-byte pieces in operand order [piece][k octet][row]; the waves read
 // their operands with 16-byte LDS loads.  NBUF = 2 (KH = 2): the tile after next is being loaded, the next one split
-// and written, while the matrix cores work on the current one -- one barrier per tile.  The partial sums of the KH
+// and written, while the matrix cores work on the current one -- one barrier per tile (KH = 4 has LDS for one
+// operand buffer: two barriers per tile).  The partial sums of the KH
 // parts meet in a double-buffered LDS exchange after that barrier, in fixed order, and the part-0 waves store.
 // grid = (row-tile workers (grid-stride), ceil(P / (32 CB))).  SCALE: Gin rows are multiplied by crow on load.
 constexpr int kNt3Rows = 32;

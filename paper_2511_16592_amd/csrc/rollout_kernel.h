@@ -1011,16 +1011,15 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   }
 }
 
-// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 128 / 64 / 512
+// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 64 / 512
 // blocks of 256 threads; the last range writes the difference rows of layer 1, see difference_rows_part):
 //   W2p, W3p  W[K][N] row-major -> MFMA A-operand order, out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
 //             zero beyond column N (the rollout's layer-2 and logit weights);
-//   W2t       transpose Wt[n][k] = W[k][n] (register slices of the 512-wide input-gradient kernel load coalesced);
 //   actions   every action byte <- 0xFF padding, as 32-bit words (the buffer is 4-byte aligned); skipped when null.
 struct PrepareParams {
   const float *W1, *W2, *W3;
   int In, H1, H2, A, A16;
-  float *W2p, *W3p, *W2t;
+  float *W2p, *W3p;
   double* D1;       // [In][H1] difference rows of layer 1
   int kind, group;  // environment kind; one-hot columns per state component (grid side, 2^k + 1, 3)
   uint8_t* actions;
@@ -1057,24 +1056,14 @@ __device__ __forceinline__ void pack_weights_part(const float* __restrict__ W, i
     out[i] = n < N ? W[(size_t)k * N + n] : 0.f;
   }
 }
-__device__ __forceinline__ void transpose_part(const float* __restrict__ W, int P, int Q, float* __restrict__ Wt,
-                                               int block, int blocks) {
-  const int total = P * Q;
-  for (int i = block * 256 + threadIdx.x; i < total; i += blocks * 256) {
-    const int q = i / P, pp = i - q * P;
-    Wt[i] = W[(size_t)pp * Q + q];
-  }
-}
 constexpr int kDiffBlocks = 512;
-constexpr int kPrepareBlocks = 128 + 64 + 128 + 64 + kDiffBlocks;
+constexpr int kPrepareBlocks = 128 + 64 + 64 + kDiffBlocks;
 __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   int b = blockIdx.x;
   if (b < 128) { pack_weights_part(p.W2, p.H1, p.H2, p.H2 >> 4, p.W2p, b, 128); return; }
   b -= 128;
   if (b < 64) { pack_weights_part(p.W3, p.H2, p.A, p.A16 >> 4, p.W3p, b, 64); return; }
   b -= 64;
-  if (b < 128) { transpose_part(p.W2, p.H1, p.H2, p.W2t, b, 128); return; }
-  b -= 128;
   if (b >= 64) { difference_rows_part(p, b - 64, kDiffBlocks); return; }
   if (p.actions) {
     const size_t words = p.action_bytes >> 2;
