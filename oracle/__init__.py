@@ -56,6 +56,12 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
+def _action_plane(actions16: np.ndarray, env) -> np.ndarray:
+    """The C side keeps actions in 16 bits (padding 0xFFFF).  Environments with at most 256 actions hand them out as
+    bytes (padding 0xFF), the form the rest of the tests use; wider ones keep the 16-bit plane."""
+    return actions16.astype(np.uint8) if env.dims()[2] <= 256 else actions16
+
+
 class Oracle:
     def __init__(self, precision: str = "f64"):
         assert precision in ("f32", "f64")
@@ -134,7 +140,7 @@ class Oracle:
         m, _k2 = self._mlp(w)
         sd, _, _, ms = env.dims()
         T = ms if max_steps is None else max_steps
-        out = dict(actions=np.zeros((T, batch), dtype=np.uint8), length=np.zeros(batch, dtype=np.int32),
+        out = dict(actions=np.zeros((T, batch), dtype=np.uint16), length=np.zeros(batch, dtype=np.int32),
                    terminal_state=np.zeros((sd, batch), dtype=np.int8),
                    log_pf=np.zeros(batch, dtype=self.real), log_pb=np.zeros(batch, dtype=self.real),
                    log_reward=np.zeros(batch, dtype=self.real), min_margin=np.zeros(batch, dtype=self.real))
@@ -144,6 +150,7 @@ class Oracle:
                                      _ptr(out["log_pf"]), _ptr(out["log_pb"]), _ptr(out["log_reward"]),
                                      _ptr(out["min_margin"]), self.creal(epsilon), C.c_int(nthreads))
         assert rc == 0, rc
+        out["actions"] = _action_plane(out["actions"], env)
         return out
 
     def replay(self, env, w, seed: int, iteration: int, actions: np.ndarray, length: np.ndarray,
@@ -151,7 +158,7 @@ class Oracle:
         e, _k1 = self._env(env)
         m, _k2 = self._mlp(w)
         sd = env.dims()[0]
-        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        actions = np.ascontiguousarray(actions, dtype=np.uint16)
         length = np.ascontiguousarray(length, dtype=np.int32)
         T, batch = actions.shape
         out = dict(terminal_state=np.zeros((sd, batch), dtype=np.int8),
@@ -172,7 +179,7 @@ class Oracle:
                      nthreads: int = 1, kink_tol: float = 0.0) -> Dict[str, np.ndarray]:
         e, _k1 = self._env(env)
         m, arrs = self._mlp(w)
-        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        actions = np.ascontiguousarray(actions, dtype=np.uint16)
         length = np.ascontiguousarray(length, dtype=np.int32)
         T, batch = actions.shape
         g = {("d" + k): np.zeros_like(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
@@ -199,7 +206,7 @@ class Oracle:
         step.  Returns the gradients plus `followed`, `flipped`, `mismatched` (see oracle_tb_loss_grad_follow)."""
         e, _k1 = self._env(env)
         m, arrs = self._mlp(w)
-        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        actions = np.ascontiguousarray(actions, dtype=np.uint16)
         length = np.ascontiguousarray(length, dtype=np.int32)
         T, batch = actions.shape
         relu1 = np.ascontiguousarray(relu1, dtype=np.uint8)
@@ -225,7 +232,7 @@ class Oracle:
         """SubTB(lambda) loss (lambda = 0: DB) and gradient for a network whose last output is log F(s)."""
         e, _k1 = self._env(env)
         m, arrs = self._mlp(w)
-        actions = np.ascontiguousarray(actions, dtype=np.uint8)
+        actions = np.ascontiguousarray(actions, dtype=np.uint16)
         length = np.ascontiguousarray(length, dtype=np.int32)
         T, batch = actions.shape
         g = {("d" + k): np.zeros_like(arrs[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")}
@@ -247,12 +254,13 @@ class Oracle:
         sd, batch = ts.shape
         assert sd == env.dims()[0]
         T = env.dims()[3] if max_steps is None else max_steps
-        out = dict(actions=np.zeros((T, batch), dtype=np.uint8), length=np.zeros(batch, dtype=np.int32),
+        out = dict(actions=np.zeros((T, batch), dtype=np.uint16), length=np.zeros(batch, dtype=np.int32),
                    log_pb=np.zeros(batch, dtype=self.real))
         rc = self.lib.oracle_backward_rollout(C.byref(e), C.c_uint64(seed), C.c_uint64(iteration), C.c_int32(b_offset),
                                               C.c_int32(batch), C.c_int32(T), _ptr(ts), _ptr(out["actions"]),
                                               _ptr(out["length"]), _ptr(out["log_pb"]))
         assert rc == 0, rc
+        out["actions"] = _action_plane(out["actions"], env)
         return out
 
     def log_prob_estimate(self, log_pf: np.ndarray, log_pb: np.ndarray, n_states: int, n_samples: int) -> np.ndarray:

@@ -99,7 +99,11 @@ typedef ORACLE_REAL real;
 #define ENV_BITSEQ_NA 3 /* bit sequences, non-autoregressive scheme: an action picks an empty position and a word */
 
 #define MAX_STATE 1024
-#define MAX_ACT 256
+#define MAX_ACT 4096
+/* One action per (step, trajectory) in 16 bits (the non-autoregressive bit sequences of the paper's experiments have
+ * 15 x 256 = 3840 actions); ACT_PAD fills the steps past the end of a trajectory. */
+typedef uint16_t act_t;
+#define ACT_PAD 0xFFFFu
 
 typedef struct {
   int32_t kind;
@@ -384,7 +388,7 @@ typedef struct {
   uint64_t seed, iteration;
   int32_t b_offset;         /* global index of column 0 of the buffers */
   int32_t batch, max_steps; /* buffer shapes */
-  uint8_t* actions;         /* [max_steps][batch] */
+  act_t* actions;         /* [max_steps][batch] */
   int32_t* length;          /* [batch] */
   int8_t* terminal_state;   /* [state_dim][batch] */
   real *log_pf, *log_pb, *log_reward;
@@ -415,7 +419,7 @@ static void* rollout_worker(void* arg) {
     int steps_given = J->replay ? J->length[col] : ms;
     if (steps_given > J->max_steps) steps_given = J->max_steps;
     if (!J->replay)
-      for (int t = 0; t < J->max_steps; ++t) J->actions[(size_t)t * J->batch + col] = 0xFF;
+      for (int t = 0; t < J->max_steps; ++t) J->actions[(size_t)t * J->batch + col] = ACT_PAD;
     for (int t = 0; t < steps_given; ++t) {
       int nr = env_obs_rows(e, s, sd, rows);
       mlp_forward(m, rows, nr, &A);
@@ -458,7 +462,7 @@ static void* rollout_worker(void* arg) {
           if (pert[best] - pert[act] < J->tie_tol) ties++; else viol++;
         }
       } else {
-        J->actions[(size_t)t * J->batch + col] = (uint8_t)act;
+        J->actions[(size_t)t * J->batch + col] = (act_t)act;
       }
       lpf += A.logp[act];
       int term = env_step(e, s, sd, t, act);
@@ -509,7 +513,7 @@ static int run_rollout(rollout_job* base, int nthreads) {
 
 /* Samples `batch` trajectories with global indices b_offset .. b_offset+batch-1. */
 int oracle_rollout(const oracle_env* env, const oracle_mlp* mlp, uint64_t seed, uint64_t iteration, int32_t b_offset,
-                   int32_t batch, int32_t max_steps, uint8_t* actions, int32_t* length, int8_t* terminal_state,
+                   int32_t batch, int32_t max_steps, act_t* actions, int32_t* length, int8_t* terminal_state,
                    real* log_pf, real* log_pb, real* log_reward, real* min_margin, real epsilon, int nthreads) {
   rollout_job J;
   memset(&J, 0, sizeof(J));
@@ -526,13 +530,13 @@ int oracle_rollout(const oracle_env* env, const oracle_mlp* mlp, uint64_t seed, 
  * of steps where it is invalid or further away (violations).  With epsilon > 0 the steps
  * where the exploration draw decides must carry exactly the action it picks. */
 int oracle_replay(const oracle_env* env, const oracle_mlp* mlp, uint64_t seed, uint64_t iteration, int32_t b_offset,
-                  int32_t batch, int32_t max_steps, const uint8_t* actions, const int32_t* length,
+                  int32_t batch, int32_t max_steps, const act_t* actions, const int32_t* length,
                   int8_t* terminal_state, real* log_pf, real* log_pb, real* log_reward, real tie_tol,
                   int32_t* near_ties, int32_t* violations, real* min_margin, real epsilon, int nthreads) {
   rollout_job J;
   memset(&J, 0, sizeof(J));
   J.env = env; J.mlp = mlp; J.seed = seed; J.iteration = iteration; J.b_offset = b_offset;
-  J.batch = batch; J.max_steps = max_steps; J.actions = (uint8_t*)actions; J.length = (int32_t*)length;
+  J.batch = batch; J.max_steps = max_steps; J.actions = (act_t*)actions; J.length = (int32_t*)length;
   J.terminal_state = terminal_state; J.log_pf = log_pf; J.log_pb = log_pb; J.log_reward = log_reward;
   J.replay = 1; J.tie_tol = tie_tol; J.near_ties = near_ties; J.violations = violations; J.min_margin = min_margin;
   J.epsilon = epsilon;
@@ -545,7 +549,7 @@ typedef struct {
   const oracle_env* env;
   const oracle_mlp* mlp;
   int32_t batch, max_steps;
-  const uint8_t* actions;
+  const act_t* actions;
   const int32_t* length;
   real log_z;
   real* delta; /* [batch] */
@@ -724,7 +728,7 @@ done:
  * dW1 db1 dW2 db2 dW3 db3) on what the gradient would change by if ReLU' were decided the other way on
  * those units -- the analogue, for the derivative of the ReLU, of the near-tie margin of the sampler. */
 static int tb_loss_grad_impl(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
-                             const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                             const act_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
                              oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out,
                              int64_t* n_kink_out, const uint8_t* relu1, const uint8_t* relu2, const int64_t* first,
                              int64_t* counts_out, int nthreads) {
@@ -791,7 +795,7 @@ static int tb_loss_grad_impl(const oracle_env* env, const oracle_mlp* mlp, int32
 }
 
 int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
-                        const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                        const act_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
                         oracle_grad* grads, real* delta_out, real kink_tol, real* slack_out, int64_t* n_kink_out,
                         int nthreads) {
   return tb_loss_grad_impl(env, mlp, batch, max_steps, actions, length, log_z, loss, dlogz, grads, delta_out,
@@ -806,7 +810,7 @@ int oracle_tb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t ba
  * counts_out[3] = {units whose given decision was followed (counted among units with |z| < 1e-3), of which the given
  * decision differs from z > 0, disagreements outside the margin (must be 0 for a correct implementation)}. */
 int oracle_tb_loss_grad_follow(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
-                               const uint8_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
+                               const act_t* actions, const int32_t* length, real log_z, real* loss, real* dlogz,
                                oracle_grad* grads, real kink_tol, const uint8_t* relu1, const uint8_t* relu2,
                                const int64_t* first, int64_t* counts_out, int nthreads) {
   if (!relu1 || !relu2 || !first || !counts_out) return -7;
@@ -853,7 +857,7 @@ static void backprop_outputs(const oracle_mlp* m, const act_buf* A, const int* r
  * loss = mean over the batch; grads (overwritten) hold its gradient; P_B is fixed.
  * u_out, optional: [max_steps + 1][batch], u_t of every trajectory (0 beyond its length). */
 int oracle_subtb_loss_grad(const oracle_env* env, const oracle_mlp* mlp, int32_t batch, int32_t max_steps,
-                           const uint8_t* actions, const int32_t* length, real lambda, real* loss,
+                           const act_t* actions, const int32_t* length, real lambda, real* loss,
                            oracle_grad* grads, real* u_out) {
   int32_t sd, od, na, ms;
   if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
@@ -966,7 +970,7 @@ static int env_backward_step(const oracle_env* e, int* s, int c) {
  * until s_0 is reached.  Outputs the trajectory in FORWARD order (actions[t][b], 0xFF padding, length[b]) and
  * log P_B(tau | x) summed in the order the moves are drawn. */
 int oracle_backward_rollout(const oracle_env* env, uint64_t seed, uint64_t iteration, int32_t b_offset,
-                            int32_t batch, int32_t max_steps, const int8_t* terminal_state, uint8_t* actions,
+                            int32_t batch, int32_t max_steps, const int8_t* terminal_state, act_t* actions,
                             int32_t* length, real* log_pb) {
   int32_t sd, od, na, ms;
   if (oracle_env_dims(env, &sd, &od, &na, &ms)) return -1;
@@ -994,7 +998,7 @@ int oracle_backward_rollout(const oracle_env* env, uint64_t seed, uint64_t itera
       ++draws;
     }
     length[b] = k;
-    for (int t = 0; t < max_steps; ++t) actions[(size_t)t * batch + b] = t < k ? (uint8_t)rev[k - 1 - t] : 0xFF;
+    for (int t = 0; t < max_steps; ++t) actions[(size_t)t * batch + b] = t < k ? (act_t)rev[k - 1 - t] : ACT_PAD;
     log_pb[b] = lpb;
   }
   return 0;

@@ -127,3 +127,87 @@ def test_backward_rollout_reverses_forward(oracle64):
     first_removed = back["actions"][-1].astype(int) >> 2  # the last forward action is the first backward move
     counts = np.bincount(first_removed, minlength=5)
     assert chi2_sf(float(((counts - 60.0) ** 2 / 60.0).sum()), 4) > 1e-4
+
+
+def test_more_than_256_actions(oracle32, oracle64):
+    """n = 16, k = 8: two positions x 256 words = 512 actions, which no longer fit one byte: the action plane is
+    16 bits wide there.  Structure of sampled trajectories, both steps of the policy against a dense numpy forward
+    pass with the mask written out, first and second actions by chi-square (marginals over position and over the top
+    bits of the word), the reward against the left-to-right environment, replay of the rollout's own actions, and
+    backward rollouts."""
+    env = bitseq_na_env(16, 8, 3, mode_seed=9)
+    ar = bitseq_env(16, 8, 3, mode_seed=9)
+    assert oracle32.env_dims(env) == (2, 2 * 257, 512, 2) == env.dims()
+    w = random_mlp(514, 16, 16, 512, seed=21, scale=3.0)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    n = 30000
+    out = oracle32.rollout(env, w, seed=5, iteration=1, batch=n, nthreads=8)
+    acts = out["actions"]
+    assert acts.dtype == np.uint16 and acts.max() > 255 and acts.max() < 512
+    pos, word = acts.astype(int) >> 8, acts.astype(int) & 255
+    assert (pos[0] != pos[1]).all() and (out["length"] == 2).all()
+    ts = out["terminal_state"].view(np.uint8).astype(int)
+    assert (ts[pos[0], np.arange(n)] == word[0]).all() and (ts[pos[1], np.arange(n)] == word[1]).all()
+    assert np.allclose(out["log_pb"], -math.log(2.0), rtol=1e-6)
+    for b in range(0, n, 1500):
+        x = [int(v) for v in ts[:, b]]
+        assert abs(out["log_reward"][b] - oracle64.log_reward(ar, x)) < 1e-5
+    # the policy at s_0 and after the first action, from a dense forward pass
+    def dense_logp(state):  # state: word per position or None
+        x = np.zeros(514)
+        for p, v in enumerate(state):
+            x[257 * p + (256 if v is None else v)] = 1.0
+        h1 = np.maximum(x @ w64["W1"] + w64["b1"], 0)
+        h2 = np.maximum(h1 @ w64["W2"] + w64["b2"], 0)
+        lg = h2 @ w64["W3"] + w64["b3"]
+        valid = np.array([state[a >> 8] is None for a in range(512)])
+        lg = np.where(valid, lg, -np.inf)
+        return lg - (np.log(np.exp(lg - lg.max()).sum()) + lg.max()), valid
+    lp0, v0 = dense_logp([None, None])
+    assert v0.all()
+    _, logp, valid = oracle64.policy(env, w64, [256, 256])
+    assert valid.all() and np.allclose(logp, lp0, atol=1e-12)
+    lp1, v1 = dense_logp([None, 77])
+    _, logp, valid = oracle64.policy(env, w64, [256, 77])
+    assert (valid == v1).all() and valid[:256].all() and not valid[256:].any()
+    assert np.allclose(logp[:256], lp1[:256], atol=1e-12)
+    # first actions: chi-square over 32 bins (position x top 4 bits of the word)
+    bins0 = np.bincount((acts[0].astype(int) >> 4), minlength=32)
+    want0 = np.exp(lp0).reshape(32, 16).sum(1) * n
+    assert chi2_sf(float(((bins0 - want0) ** 2 / want0).sum()), 31) > 1e-4
+    # log P_F of the sampled trajectories against the dense pass (a sample of them)
+    for b in range(0, n, 3000):
+        st = [None, None]
+        lp = dense_logp(st)[0][acts[0, b]]
+        st[pos[0, b]] = word[0, b]
+        lp += dense_logp(st)[0][acts[1, b]]
+        assert abs(lp - out["log_pf"][b]) < 2e-4 * max(1.0, abs(lp))
+    # replay of the rollout's own actions: no violation, same scalars; a second write to the same position is one
+    sub = np.ascontiguousarray(acts[:, :200])
+    rep = oracle32.replay(env, w, 5, 1, sub, out["length"][:200], tie_tol=1e-5, nthreads=4)
+    assert (rep["violations"] == 0).all() and (rep["near_ties"] == 0).all()
+    assert np.array_equal(rep["log_pf"], out["log_pf"][:200])
+    bad = sub.copy()
+    bad[1, 0] = bad[0, 0] ^ 1
+    assert oracle32.replay(env, w, 5, 1, bad, out["length"][:200], tie_tol=1e-5)["violations"][0] >= 1
+    # gradient along these actions: finite differences on a few entries of every tensor
+    g = oracle64.tb_loss_grad(env, w64, sub[:, :6], out["length"][:6], log_z=0.1)
+    rng = np.random.default_rng(8)
+    for k in ("W1", "b1", "W2", "b2", "W3", "b3"):
+        grad = g["d" + k]
+        flat = np.flatnonzero(np.abs(grad.ravel()) > 0)
+        for i in rng.choice(flat, size=min(3, flat.size), replace=False):
+            wp = {q: v.copy() for q, v in w64.items()}
+            wm = {q: v.copy() for q, v in w64.items()}
+            wp[k].ravel()[i] += 1e-6
+            wm[k].ravel()[i] -= 1e-6
+            fd = (oracle64.tb_loss_grad(env, wp, sub[:, :6], out["length"][:6], log_z=0.1)["loss"] -
+                  oracle64.tb_loss_grad(env, wm, sub[:, :6], out["length"][:6], log_z=0.1)["loss"]) / 2e-6
+            assert abs(fd - grad.ravel()[i]) <= 2e-5 * max(1.0, abs(fd)), (k, i)
+    # backward rollouts: 16-bit actions, reversible
+    states = np.random.default_rng(2).integers(0, 256, size=(2, 400)).astype(np.uint8).view(np.int8)
+    back = oracle64.backward_rollout(env, seed=3, iteration=0, terminal_state=states)
+    assert back["actions"].dtype == np.uint16 and np.allclose(back["log_pb"], -math.log(2.0))
+    fwd = oracle64.replay(env, w64, 0, 0, back["actions"], back["length"], tie_tol=1e30)
+    assert (fwd["violations"] == 0).all() and (fwd["terminal_state"] == states).all()
+    assert 140 < int((back["actions"][1].astype(int) >> 8).sum()) < 260   # either position is removed first
