@@ -38,6 +38,8 @@ DESCRIPTIONS = {
     "c5": "10-D grid H=20, MLP 200-256-256-11 (seeded Xavier), batch 16384, max 191 steps",
     "c5_long": "10-D grid H=20, MLP 200-256-256-11 with stop bias -8 (long walks), batch 16384",
     "c3_na": "bit sequences n=64 k=4 in the non-autoregressive scheme (256 actions), MLP 1040-512-512-256, batch 4096",
+    "c3_na120": "bit sequences n=120 k=8 in the non-autoregressive scheme (3840 actions), MLP 3855-512-512-3840, "
+                "batch 4096",
 }
 KERNEL_SOURCES = ("rollout_kernel.h", "grad_kernels.h", "grad_kernels2.h", "grad_kernels3.h", "grad_kernels4.h",
                   "subtb_kernels.h", "backward_kernel.h", "gfnx_device.h", "gfnx.hip")
@@ -362,10 +364,10 @@ def main():
         # other workloads of the same path, short runs without per-kernel events (context for the headline line:
         # the 4-D grid at Xavier initialisation has ~5-step trajectories, i.e. little work per launch)
         extra = {}
-        for name in ("c2_long", "c4", "c5", "c5_long", "c3", "c3_na"):
+        for name in ("c2_long", "c4", "c5", "c5_long", "c3", "c3_na", "c3_na120"):
             if name == args.workload:
                 continue
-            steps = 5 if name == "c5_long" else 20
+            steps = 5 if name in ("c5_long", "c3_na120") else 20
             extra[name] = summary(name, run_workload(name, steps, 3, events=False), steps)
         out["extra"] = extra
         # the same step with epsilon-uniform exploration at the paper's rate

@@ -73,8 +73,11 @@ typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2, GFNX_
  *            "Sequential environments" (the one the paper's bit-sequence experiments use): an action picks an empty
  *            position and the k-bit word written there, a = position * 2^k + word, L * 2^k actions, masked once
  *            the position is filled; L steps; log P_B = -log(t+1) (uniform over the filled positions of the
- *            child).  The kernels take at most 256 actions (e.g. n_bits = 64, k_bits = 4); the paper's instance
- *            (n = 120, k = 8: 3840 actions, which do not fit the one-byte action plane) is GFNX_E_UNSUPPORTED.
+ *            child).  Up to 256 actions (e.g. n_bits = 64, k_bits = 4) everything works as for the other kinds.
+ *            Larger instances (the paper's own: n = 120, k = 8, 3840 actions) must have a multiple of 256 actions,
+ *            at most 8192, and use the 16-bit action plane gfnx_traj.actions16; gfnx_rollout, gfnx_replay,
+ *            gfnx_tb_loss_grad, the training iterations without exploration and gfnx_backward_rollout take them,
+ *            gfnx_rollout_explore with epsilon > 0 is GFNX_E_UNSUPPORTED.
  * Fields of the other kinds are ignored. */
 typedef struct {
   int32_t kind;
@@ -114,13 +117,17 @@ typedef struct {
  *   terminal_state [state_dim][batch] grid coordinate / token byte / spin of the terminal state;
  *   log_pf, log_pb [batch] sums over the trajectory of log P_F(s_t | s_t-1) and log P_B(s_t-1 | s_t)
  *                  (Background, eq. forward_backward_traj);
- *   log_reward     [batch] log R of the terminal state. */
+ *   log_reward     [batch] log R of the terminal state;
+ *   actions16      [max_steps][batch] the same plane in 16 bits per transition (padding 0xFFFF, 4-byte aligned), used
+ *                  INSTEAD of `actions` (which may then be NULL) by environments with more than 256 actions
+ *                  (gfnx_env_dims); ignored, and may be NULL, otherwise. */
 typedef struct {
   int32_t batch, max_steps;
   uint8_t* actions;
   int32_t* length;
   int8_t* terminal_state;
   float *log_pf, *log_pb, *log_reward;
+  uint16_t* actions16;
 } gfnx_traj;
 
 /* Host-only: sizes implied by an environment descriptor.  max_steps is the longest possible

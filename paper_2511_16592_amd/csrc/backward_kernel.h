@@ -22,6 +22,7 @@ struct BackwardParams {
   int B, T;
   const int8_t* term;  // [state_dim][B] terminal states (input)
   uint8_t* actions;    // [T][B]
+  uint16_t* actions16; // [T][B], used instead when not null (environments with more than 256 actions)
   int* length;
   float* lpb;
 };
@@ -109,9 +110,14 @@ __global__ __launch_bounds__(kBackwardThreads) void backward_rollout_kernel(Back
       clear = true;
     }
     if (clear) { m0 &= q == 0 ? ~bit : ~0u; m1 &= q == 1 ? ~bit : ~0u; m2 &= q == 2 ? ~bit : ~0u; m3 &= q == 3 ? ~bit : ~0u; }
-    p.actions[(size_t)(moves - 1 - k) * B + b] = (uint8_t)a;  // the k-th undone move is forward step moves-1-k
+    // the k-th undone move is forward step moves-1-k
+    if (p.actions16) p.actions16[(size_t)(moves - 1 - k) * B + b] = (uint16_t)a;
+    else p.actions[(size_t)(moves - 1 - k) * B + b] = (uint8_t)a;
   }
-  for (int t = len; t < p.T; ++t) p.actions[t * B + b] = 0xFF;
+  for (int t = len; t < p.T; ++t) {
+    if (p.actions16) p.actions16[t * B + b] = 0xFFFF;
+    else p.actions[t * B + b] = 0xFF;
+  }
   p.length[b] = len;
   p.lpb[b] = lpb;
 }

@@ -11,6 +11,7 @@
 #include "grad_kernels4.h"
 #include "subtb_kernels.h"
 #include "rollout_kernel.h"
+#include "rollout_wide_kernel.h"
 
 #include <cmath>
 #include <mutex>
@@ -69,10 +70,11 @@ struct Shapes {
   int onehot;   // layer-1 weight gradient as a one-hot contraction: 0 no, 1 grid, 2 Ising
   int sbytes;   // state bytes recorded per transition row for it
   int p1;       // rows of that contraction's output tile
+  int wide;     // non-autoregressive bit sequences with more than 256 actions: 16-bit action plane, paged logits
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, d1, crow, rows, h1, h2, e, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t hdr, w2p, w3p, d1, crow, rows, h1, h2, e, lse, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
   size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
   size_t total;
 };
@@ -106,7 +108,7 @@ int env_dims(const gfnx_env_desc* env, int* sd, int* od, int* na, int* ms) {
     if (len > 32 || env->n_modes < 1) return GFNX_E_BAD_ENV;
     *sd = len;
     *od = len * ((1 << env->k_bits) + 1);
-    *na = len << env->k_bits;  // (the kernels take at most 256 actions: larger instances are GFNX_E_UNSUPPORTED)
+    *na = len << env->k_bits;
     *ms = len;
   } else {
     return GFNX_E_BAD_ENV;
@@ -126,7 +128,10 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   if (!s->flow && mlp->n_actions != s->n_actions) return GFNX_E_BAD_SHAPE;
   if (mlp->h1 <= 0 || mlp->h2 <= 0) return GFNX_E_BAD_SHAPE;
   if (mlp->h1 % 64 || mlp->h2 % 64 || mlp->h1 > 512 || mlp->h2 > 512) return GFNX_E_UNSUPPORTED;
-  if (s->n_actions > 256 || s->max_steps > 256 || s->state_dim > kMaxStateDim) return GFNX_E_UNSUPPORTED;
+  // more than 256 actions: the non-autoregressive bit sequences only, in whole pages of 256 actions
+  s->wide = s->n_actions > 256 ? 1 : 0;
+  if (s->wide && (env->kind != GFNX_ENV_BITSEQ_NA || s->n_actions % 256 || s->n_actions > 8192)) return GFNX_E_UNSUPPORTED;
+  if (s->max_steps > 256 || s->state_dim > kMaxStateDim) return GFNX_E_UNSUPPORTED;
   s->H1 = mlp->h1; s->H2 = mlp->h2; s->A = mlp->n_actions; s->A16 = (s->A + 15) & ~15; s->B = batch;
   s->rows = (size_t)s->max_steps * (size_t)batch;
   if (s->rows > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
@@ -141,8 +146,9 @@ int check_shapes(const gfnx_env_desc* env, const gfnx_mlp* mlp, int batch, Shape
   s->qtot2 = 256 * qn2;
   s->s2 = 256 / (pt2 * qn2);
   s->qt3 = s->A16 <= 32 ? 32 : ((s->A16 > 192 && s->A16 <= 224) ? 224 : 256);  // 224: seven 32-column blocks per wave
-  s->qtot3 = s->qt3;
-  s->s3 = 256 / pt3;
+  const int qn3 = s->A16 <= 256 ? 1 : (s->A16 + 255) / 256;
+  s->qtot3 = s->qt3 * qn3;
+  s->s3 = 256 / (pt3 * qn3) > 0 ? 256 / (pt3 * qn3) : 1;
   s->qtot1 = 256 * pt2;
   s->s1 = 256 / pt2;
   return GFNX_OK;
@@ -161,12 +167,13 @@ Layout make_layout(const Shapes& s) {
   L.hdr = o; o += align256(sizeof(int) * kHdrWords);
   L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
-  L.d1 = o; o += align256(sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1 (rollout)
+  L.d1 = o; o += align256(s.wide ? 0 : sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
   L.h1 = o; o += align256(sizeof(float) * s.rows * s.H1);
   L.h2 = o; o += align256(sizeof(float) * s.rows * s.H2);
   L.e = o; o += align256(sizeof(float) * s.rows * s.A16);
+  L.lse = o; o += align256(s.wide ? sizeof(float) * s.rows : 0);  // log-sum-exp of every row's valid logits
   L.m1 = o; o += align256(8 * s.rows * (size_t)s.mw1);
   L.m2 = o; o += align256(8 * s.rows * (size_t)s.mw2);
   L.sb = o; o += align256(s.rows * (size_t)s.sbytes);
@@ -187,7 +194,8 @@ Layout make_layout(const Shapes& s) {
 
 int check_traj(const gfnx_traj* t, const Shapes& s) {
   if (!t) return GFNX_E_NULL;
-  if (!t->actions || !t->length || !t->terminal_state || !t->log_pf || !t->log_pb || !t->log_reward) return GFNX_E_NULL;
+  if (!(s.wide ? (const void*)t->actions16 : (const void*)t->actions)) return GFNX_E_NULL;
+  if (!t->length || !t->terminal_state || !t->log_pf || !t->log_pb || !t->log_reward) return GFNX_E_NULL;
   if (t->batch <= 0 || t->max_steps < s.max_steps) return GFNX_E_BAD_SHAPE;
   return GFNX_OK;
 }
@@ -322,6 +330,55 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
   rc = check_workspace(ws, ws_bytes, L);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+
+  if (s.wide) {
+    // more than 256 actions: the paged rollout of the non-autoregressive bit sequences
+    if (epsilon > 0.f) return GFNX_E_UNSUPPORTED;
+    WideParams q = {};
+    q.env = env_params(env, s);
+    q.In = s.obs_dim; q.H1 = s.H1; q.H2 = s.H2; q.A = s.A;
+    q.W1 = mlp->W1; q.b1 = mlp->b1; q.b2 = mlp->b2; q.b3 = mlp->b3;
+    q.W2p = at<float>(ws, L.w2p); q.W3p = at<float>(ws, L.w3p);
+    q.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); q.seed_hi = (uint32_t)(seed >> 32);
+    q.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFull);
+    q.B = s.B; q.T = traj->max_steps;
+    q.actions = traj->actions16; q.length = traj->length; q.term = traj->terminal_state;
+    q.lpf = traj->log_pf; q.lpb = traj->log_pb; q.logr = traj->log_reward;
+    q.h1buf = at<float>(ws, L.h1); q.h2buf = at<float>(ws, L.h2); q.lgbuf = at<float>(ws, L.e);
+    q.lsebuf = at<float>(ws, L.lse);
+    q.m1buf = at<unsigned long long>(ws, L.m1); q.m2buf = at<unsigned long long>(ws, L.m2);
+    q.MW1 = s.mw1; q.MW2 = s.mw2;
+    int tpw = kSlots * ((s.B + 256 * kSlots - 1) / (256 * kSlots));
+    q.tpw = tpw;
+    const dim3 grid((s.B + tpw - 1) / tpw);
+    const size_t lds = (size_t)wide_lds_layout(s.H1, s.H2).total;
+    if (lds > 160 * 1024) return GFNX_E_UNSUPPORTED;
+    {
+      GFNX_TIMED("prepare", st);
+      PrepareParams pp = {};
+      pp.W1 = mlp->W1; pp.W2 = mlp->W2; pp.W3 = mlp->W3;
+      pp.In = s.obs_dim; pp.H1 = s.H1; pp.H2 = s.H2; pp.A = s.A; pp.A16 = s.A16;
+      pp.D1 = nullptr;  // layer 1 is summed from scratch every step
+      pp.kind = (int)GFNX_ENV_BITSEQ; pp.group = (1 << env->k_bits) + 1;
+      pp.W2p = at<float>(ws, L.w2p); pp.W3p = at<float>(ws, L.w3p);
+      pp.actions = replay ? nullptr : (uint8_t*)traj->actions16;  // every 16-bit entry <- 0xFFFF
+      pp.action_bytes = 2 * (size_t)traj->max_steps * s.B;
+      hipLaunchKernelGGL(prepare_kernel, dim3(kPrepareBlocks), dim3(256), 0, st, pp);
+    }
+    {
+      GFNX_TIMED("rollout", st);
+      if (replay) {
+        auto k = rollout_wide_kernel<true>;
+        GFNX_ALLOW_LDS(k, (int)lds)
+        hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, q);
+      } else {
+        auto k = rollout_wide_kernel<false>;
+        GFNX_ALLOW_LDS(k, (int)lds)
+        hipLaunchKernelGGL(k, grid, dim3(kRolloutThreads), lds, st, q);
+      }
+    }
+    return hipGetLastError() == hipSuccess ? GFNX_OK : GFNX_E_HIP;
+  }
 
   RolloutParams p = {};
   p.env = env_params(env, s);
@@ -497,10 +554,16 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
                        (const float*)dl, (const float*)phi, s.n_actions, s.A16, ebuf, crow, (const float*)lossb, B,
                        loss_dev);
   }
+  if (s.wide) {
+    // paged rollout: the stored logits of every live row become onehot(a) - p in place
+    GFNX_TIMED("logit_grad", st);
+    hipLaunchKernelGGL(wide_logit_grad_kernel, dim3(2048), dim3(256), 0, st, ebuf, (const float*)at<float>(ws, L.lse),
+                       (const uint16_t*)traj->actions16, s.A, (const int*)rows, (const int*)hdr);
+  }
   Dw1Params dp = {};
   dp.env = env_params(env, s);
   dp.H1 = s.H1; dp.B = B;
-  dp.actions = traj->actions; dp.length = traj->length; dp.term = traj->terminal_state;
+  dp.actions = traj->actions; dp.actions16 = s.wide ? traj->actions16 : nullptr; dp.length = traj->length; dp.term = traj->terminal_state;
   dp.g1 = h1buf; dp.dW1 = grads->dW1; dp.db1 = grads->db1;
 
   // the split partial tiles of every weight / bias gradient are summed by one launch at the end of the pass
@@ -545,7 +608,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       auto k = gemm_tn3_kernel<2, 4, 4, 2, true>;
       const int lds = (int)gemm_tn3_lds_bytes<2, 4, 4, 2>();
       GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(pt3, 1, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
+      hipLaunchKernelGGL(k, dim3(pt3, s.qtot3 / 256, s.s3), dim3(512), lds, st, h2buf, s.H2, s.H2, ebuf, s.A16, (const float*)crow, rows, hdr,
                          s.qtot3, part3, dbp3);
     }
   }
@@ -553,20 +616,20 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   add_job(dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
   const int rt32 = (int)((s.rows + kNt3Rows - 1) / kNt3Rows);
   // Out = (Gin W^T) . [act > 0] on the live rows, persistent over the row tiles: about one workgroup per CU
-  auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int kvalid, float* out, int ldo,
-                        int P, const unsigned long long* mask, int mw) -> int {
+  auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int ldw, int kvalid, int mode,
+                        float* out, int ldo, int P, const unsigned long long* mask, int mw) -> int {
     if (K <= 256) {
       const int ctiles = (P + 127) / 128, lds = (int)gemm_nt3_lds_bytes<2>();
       const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
       if (scale) {
         auto k = gemm_nt3_kernel<2, true>;
         GFNX_ALLOW_LDS(k, lds)
-        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
                            (const float*)crow, (const int*)rows, (const int*)hdr);
       } else {
         auto k = gemm_nt3_kernel<2, false>;
         GFNX_ALLOW_LDS(k, lds)
-        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
                            (const float*)crow, (const int*)rows, (const int*)hdr);
       }
     } else {
@@ -577,7 +640,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
       auto k = gemm_nt3_kernel<4, false>;
       GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, kvalid, out, ldo, P, mask, mw,
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
                          (const float*)crow, (const int*)rows, (const int*)hdr);
     }
     return GFNX_OK;
@@ -585,8 +648,21 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   if (!narrow) {
     // G2 = ((coef * e) W3^T) . [h2 > 0] over h2
     GFNX_TIMED("gemm_nt_g2", st);
-    rc = launch_nt3(true, ebuf, s.A16, s.A16, mlp->W3, s.A, h2buf, s.H2, s.H2, at<unsigned long long>(ws, L.m2), s.mw2);
-    if (rc) return rc;
+    if (!s.wide) {
+      rc = launch_nt3(true, ebuf, s.A16, s.A16, mlp->W3, s.A, s.A, 0, h2buf, s.H2, s.H2,
+                      at<unsigned long long>(ws, L.m2), s.mw2);
+      if (rc) return rc;
+    } else {
+      // the contraction over thousands of actions runs page by page (256 actions each, in order), the partial sums
+      // kept in the output rows; the last page applies the mask
+      const int pages = s.A / 256;
+      for (int pg = 0; pg < pages; ++pg) {
+        const int mode = (pg > 0 ? kNt3AddToOut : 0) | (pg + 1 < pages ? kNt3NoMask : 0);
+        rc = launch_nt3(true, ebuf + 256 * pg, s.A16, 256, mlp->W3 + 256 * pg, s.A, 256, mode, h2buf, s.H2, s.H2,
+                        at<unsigned long long>(ws, L.m2), s.mw2);
+        if (rc) return rc;
+      }
+    }
   }
   {
     // layer 2: dW2 = H1^T G2, db2
@@ -602,7 +678,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
-    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
+    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, s.H2, 0, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
     if (rc) return rc;
   }
   // layer 1
@@ -735,9 +811,12 @@ int gfnx_backward_rollout(const gfnx_env_desc* env, uint64_t seed, uint64_t iter
   int sd, od, na, ms;
   const int rc = env_dims(env, &sd, &od, &na, &ms);
   if (rc) return rc;
-  if (!traj->actions || !traj->length || !traj->terminal_state || !traj->log_pb) return GFNX_E_NULL;
+  const bool wide = na > 256;  // 16-bit action plane (non-autoregressive bit sequences only)
+  if (!(wide ? (const void*)traj->actions16 : (const void*)traj->actions)) return GFNX_E_NULL;
+  if (!traj->length || !traj->terminal_state || !traj->log_pb) return GFNX_E_NULL;
   if (traj->batch <= 0 || traj->max_steps < ms) return GFNX_E_BAD_SHAPE;
-  if (na > 256 || ms > 256 || sd > kMaxStateDim) return GFNX_E_UNSUPPORTED;  // the limits of the forward kernels
+  if ((wide && (env->kind != GFNX_ENV_BITSEQ_NA || na % 256 || na > 8192)) || ms > 256 || sd > kMaxStateDim)
+    return GFNX_E_UNSUPPORTED;  // the limits of the forward kernels
   if (env->kind == GFNX_ENV_GRID && sd > 16) return GFNX_E_UNSUPPORTED;
   if ((size_t)traj->max_steps * (size_t)traj->batch > 0x7fffffffull) return GFNX_E_UNSUPPORTED;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -748,7 +827,8 @@ int gfnx_backward_rollout(const gfnx_env_desc* env, uint64_t seed, uint64_t iter
   p.seed_lo = (uint32_t)(seed & 0xFFFFFFFFull); p.seed_hi = (uint32_t)(seed >> 32);
   p.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFull);
   p.B = traj->batch; p.T = traj->max_steps;
-  p.term = traj->terminal_state; p.actions = traj->actions; p.length = traj->length; p.lpb = traj->log_pb;
+  p.term = traj->terminal_state; p.actions = traj->actions; p.actions16 = wide ? traj->actions16 : nullptr;
+  p.length = traj->length; p.lpb = traj->log_pb;
   {
     GFNX_TIMED("backward", st);
     hipLaunchKernelGGL(backward_rollout_kernel, dim3((p.B + kBackwardThreads - 1) / kBackwardThreads),

@@ -186,6 +186,7 @@ struct Dw1Params {
   EnvParams env;
   int H1, B;
   const uint8_t* actions;
+  const uint16_t* actions16;  // used instead of `actions` when not null (more than 256 actions)
   const int* length;
   const int8_t* term;
   const float* g1;  // rows t*B + b, H1 floats
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(256) void dw1_kernel(const Dw1Params p) {
     bad = 0;
     for (int s = 0; s < e.state_dim; ++s) st[s] = 0;
     for (int t = 0; t + 1 < len; ++t) {
-      int a = p.actions[(size_t)t * B + b];
+      int a = p.actions16 ? (int)p.actions16[(size_t)t * B + b] : (int)p.actions[(size_t)t * B + b];
       if (ENV == 0 ? (a >= e.d || st[a] >= e.H - 1)
                    : (ENV == 3 ? (a >= e.n_actions || st[a >> e.k_bits]) : (a >= e.n_actions))) { bad = 1; break; }
       if (ENV == 0) {

@@ -309,8 +309,9 @@ namespace gfnx {
 
 // Input-gradient product Out = (Gin W^T) . [act > 0] with the same three-piece arithmetic:
 //   Out[i][p] = (sum_k Gin[i][k] * W[p][k]) * [act[i][p] > 0]  for the live rows i, written over the stored activation.
-// W is the layer's own weight matrix, row-major [P][Kvalid] (its rows are contiguous in k, which is what the B operand
-// of the 32 x 32 x 16 instruction wants: no transposed copy); the ReLU derivative comes from the recorded sign masks.
+// W is the layer's own weight matrix, row-major with ldw floats per row of which Kvalid are used (its rows are
+// contiguous in k, which is what the B operand of the 32 x 32 x 16 instruction wants: no transposed copy); the ReLU
+// derivative comes from the recorded sign masks.
 //
 // The eight waves are CB = 8 / KH column blocks of 32 outputs x KH parts of the contraction, 128 indices each
 // (KH = 2: contraction lengths up to 256, 128 outputs per workgroup; KH = 4: up to 512, 64 outputs per workgroup);
@@ -323,6 +324,9 @@ namespace gfnx {
 // parts meet in a double-buffered LDS exchange after that barrier, in fixed order, and the part-0 waves store.
 // grid = (row-tile workers (grid-stride), ceil(P / (32 CB))).  SCALE: Gin rows are multiplied by crow on load.
 constexpr int kNt3Rows = 32;
+// `mode` bits: a contraction longer than the kernel takes runs as several launches over slices of it, in a fixed order:
+// every launch but the first adds to what Out already holds, every launch but the last leaves the mask for later
+constexpr int kNt3AddToOut = 1, kNt3NoMask = 2;
 
 template <int KH>
 constexpr size_t gemm_nt3_lds_bytes() {
@@ -335,7 +339,7 @@ constexpr size_t gemm_nt3_lds_bytes() {
 
 template <int KH, bool SCALE>
 __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__ Gin, int ldgi, int K,
-                                                       const float* __restrict__ W, int Kvalid,
+                                                       const float* __restrict__ W, int ldw, int Kvalid, int mode,
                                                        float* __restrict__ ActOut, int ldo, int P,
                                                        const unsigned long long* __restrict__ mask, int MW,
                                                        const float* __restrict__ crow,
@@ -363,7 +367,7 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int kk = 128 * kh + 16 * st + 8 * kg + k;
-      v[k] = (kk < Kvalid && pcol < P) ? W[(size_t)pcol * Kvalid + kk] : 0.f;
+      v[k] = (kk < Kvalid && pcol < P) ? W[(size_t)pcol * ldw + kk] : 0.f;
     }
     split3x8(v, wh[st], wm[st], wl[st]);
   }
@@ -508,10 +512,12 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
             for (int k = 0; k < 4; ++k) {
               // all ones where the unit was active
               const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(mw4[k], bitpos & 31, 1);
-              const float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
-              const float v = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
+              float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
               float* dst = (float*)(colbase + (uint64_t)(uint32_t)id4[k] * rowbytes);
-              if (decltype(all_rows)::value || id4[k] >= 0) *dst = v;
+              const bool row_ok = decltype(all_rows)::value || id4[k] >= 0;
+              if ((mode & kNt3AddToOut) && row_ok) av += *dst;
+              const float v = (mode & kNt3NoMask) ? av : __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
+              if (row_ok) *dst = v;
             }
           }
         };

@@ -1064,7 +1064,10 @@ __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   b -= 128;
   if (b < 64) { pack_weights_part(p.W3, p.H2, p.A, p.A16 >> 4, p.W3p, b, 64); return; }
   b -= 64;
-  if (b >= 64) { difference_rows_part(p, b - 64, kDiffBlocks); return; }
+  if (b >= 64) {
+    if (p.D1) difference_rows_part(p, b - 64, kDiffBlocks);
+    return;
+  }
   if (p.actions) {
     const size_t words = p.action_bytes >> 2;
     for (size_t i = (size_t)b * 256 + threadIdx.x; i < words; i += (size_t)64 * 256) ((uint32_t*)p.actions)[i] = 0xFFFFFFFFu;

@@ -54,7 +54,7 @@ class AdamState(C.Structure):
 class Traj(C.Structure):
     _fields_ = [("batch", C.c_int32), ("max_steps", C.c_int32), ("actions", C.c_void_p), ("length", C.c_void_p),
                 ("terminal_state", C.c_void_p), ("log_pf", C.c_void_p), ("log_pb", C.c_void_p),
-                ("log_reward", C.c_void_p)]
+                ("log_reward", C.c_void_p), ("actions16", C.c_void_p)]
 
 
 class GfnxError(RuntimeError):
@@ -195,14 +195,17 @@ class Session:
         self.mlp = Mlp(self.w["W1"].shape[0], self.w["W1"].shape[1], self.w["W2"].shape[1], self.w["W3"].shape[1],
                        *[_ptr(self.w[k]) for k in ("W1", "b1", "W2", "b2", "W3", "b3")])
         T, B = self.max_steps, self.batch
-        self.actions = torch.empty((T, B), dtype=torch.uint8, device=dev)
+        # one byte per transition, or 16 bits for environments with more than 256 actions (gfnx_traj.actions16)
+        self.wide_actions = self.n_actions > 256
+        self.actions = torch.empty((T, B), dtype=torch.int16 if self.wide_actions else torch.uint8, device=dev)
         self.length = torch.empty(B, dtype=torch.int32, device=dev)
         self.terminal_state = torch.empty((self.state_dim, B), dtype=torch.int8, device=dev)
         self.log_pf = torch.empty(B, dtype=torch.float32, device=dev)
         self.log_pb = torch.empty(B, dtype=torch.float32, device=dev)
         self.log_reward = torch.empty(B, dtype=torch.float32, device=dev)
-        self.traj = Traj(B, T, _ptr(self.actions), _ptr(self.length), _ptr(self.terminal_state), _ptr(self.log_pf),
-                         _ptr(self.log_pb), _ptr(self.log_reward))
+        self.traj = Traj(B, T, None if self.wide_actions else _ptr(self.actions), _ptr(self.length),
+                         _ptr(self.terminal_state), _ptr(self.log_pf), _ptr(self.log_pb), _ptr(self.log_reward),
+                         _ptr(self.actions) if self.wide_actions else None)
         self.grads = {"d" + k: torch.empty_like(v) for k, v in self.w.items()}
         self.cgrads = MlpGrad(*[_ptr(self.grads[k]) for k in ("dW1", "db1", "dW2", "db2", "dW3", "db3")])
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -230,10 +233,19 @@ class Session:
                                                  float(epsilon), C.byref(self.traj), _ptr(self.workspace),
                                                  self.workspace_bytes, self._stream()))
 
+    def _actions_tensor(self, actions):
+        """Host action array [T, B] as a tensor of the plane's element type (torch has no uint16: the 16-bit plane is
+        held as int16 with the same bits)."""
+        import numpy as np
+        if self.wide_actions:
+            return self.torch.from_numpy(np.ascontiguousarray(actions, dtype=np.uint16).view(np.int16))
+        return self.torch.as_tensor(actions, dtype=self.torch.uint8)
+
     def replay(self, actions, length) -> None:
-        """Teacher-forced pass along the given host arrays actions [T, B] (uint8) and length [B]."""
+        """Teacher-forced pass along the given host arrays actions [T, B] (uint8, or uint16 for environments with
+        more than 256 actions) and length [B]."""
         torch = self.torch
-        self.actions.copy_(torch.as_tensor(actions, dtype=torch.uint8))
+        self.actions.copy_(self._actions_tensor(actions))
         self.length.copy_(torch.as_tensor(length, dtype=torch.int32))
         _check(self.lib.gfnx_replay(C.byref(self.desc), C.byref(self.mlp), C.byref(self.traj), _ptr(self.workspace),
                                     self.workspace_bytes, self._stream()))
@@ -349,7 +361,9 @@ class Session:
     def trajectories(self) -> Dict:
         """Host copies (numpy) of the trajectory arrays."""
         self.torch.cuda.synchronize(self.device)
-        return dict(actions=self.actions.cpu().numpy(), length=self.length.cpu().numpy(),
+        import numpy as np
+        acts = self.actions.cpu().numpy()
+        return dict(actions=acts.view(np.uint16) if self.wide_actions else acts, length=self.length.cpu().numpy(),
                     terminal_state=self.terminal_state.cpu().numpy(), log_pf=self.log_pf.cpu().numpy(),
                     log_pb=self.log_pb.cpu().numpy(), log_reward=self.log_reward.cpu().numpy())
 

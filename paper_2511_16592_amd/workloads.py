@@ -172,4 +172,7 @@ def workloads() -> Dict[str, Workload]:
     w["c5_long"] = replace(w["c5"], name="c5_long", stop_bias=-8.0)
     # the non-autoregressive scheme at the largest action space the kernels take: 16 positions x 16 words
     w["c3_na"] = Workload("c3_na", bitseq_na_env(64, 4, 60, mode_seed=3), 512, 512, batch=4096, seed=3, weight_seed=3)
+    # ... and at the size of the paper's bit-sequence experiments: 15 positions x 256 words = 3840 actions
+    w["c3_na120"] = Workload("c3_na120", bitseq_na_env(120, 8, 60, mode_seed=3), 512, 512, batch=4096, seed=3,
+                             weight_seed=3)
     return w

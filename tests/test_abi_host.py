@@ -254,18 +254,26 @@ def test_static_scratch_entry_point_rejects_oversize_on_the_host(lib):
 
 
 def test_non_autoregressive_bit_sequence_dims_and_limits(lib):
-    """gfnx_env_dims of the (position, word) environment; 256 actions are the most the kernels take: the paper's
-    n = 120, k = 8 instance (3840 actions) is reported as unsupported by the size query."""
+    """gfnx_env_dims of the (position, word) environment; up to 256 actions use the byte plane; more (the paper's
+    n = 120, k = 8 instance: 3840 actions) must be a multiple of 256 and need the 16-bit plane of gfnx_traj."""
     assert gfnx.env_dims(bitseq_na_env(24, 4, 3, 1)) == (6, 6 * 17, 6 * 16, 6)
     assert gfnx.env_dims(bitseq_na_env(64, 4, 3, 1)) == (16, 16 * 17, 256, 16)
     assert gfnx.env_dims(bitseq_na_env(120, 8, 3, 1)) == (15, 3855, 3840, 15)
     d = gfnx.env_desc(bitseq_na_env(64, 4, 3, 1), 0x1000)
     assert lib.gfnx_workspace_bytes(C.byref(d), C.byref(_mlp(16 * 17, 256, 256, 256)), 64) > 0
     big = gfnx.env_desc(bitseq_na_env(120, 8, 3, 1), 0x1000)
-    assert lib.gfnx_workspace_bytes(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 64) == 0
-    t = _traj(64, 15)
-    assert lib.gfnx_rollout(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.byref(t), 0x10000, 1 << 30,
-                            None) == -5
+    need = lib.gfnx_workspace_bytes(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 64)
+    assert need > 64 * 15 * 3840 * 4          # the logit rows of every transition are part of it
+    t = _traj(64, 15)                          # byte plane only: the 16-bit plane is missing
+    assert lib.gfnx_rollout(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.byref(t), 0x10000, need,
+                            None) == -1
+    t16 = gfnx.Traj(64, 15, None, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert lib.gfnx_rollout(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.byref(t16), 0x10000, need - 1,
+                            None) == -4        # everything else accepted: only the workspace is too small
+    assert lib.gfnx_rollout_explore(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.c_float(0.1),
+                                    C.byref(t16), 0x10000, need, None) == -5
+    odd = gfnx.env_desc(bitseq_na_env(60, 5, 3, 1, uniform_bits=True), 0x1000)   # 12 x 32 = 384 actions
+    assert lib.gfnx_workspace_bytes(C.byref(odd), C.byref(_mlp(12 * 33, 64, 64, 384)), 64) == 0
     bad = gfnx.env_desc(bitseq_na_env(64, 4, 3, 1), 0x1000)
     bad.k_bits = 5
     out = C.c_int32()

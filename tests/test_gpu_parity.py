@@ -107,6 +107,8 @@ def check_trajectories(o32, o64, env, w, seed, iteration, traj, b0=0, b1=None, f
         pad = t >= length
         if na <= 255:
             assert (acts[t][pad] == 0xFF).all()
+        elif na > 256:
+            assert (acts[t][pad] == 0xFFFF).all()
     if free_run:
         free = o32.rollout(env, w, seed, iteration, batch=b1 - b0, b_offset=b0, max_steps=acts.shape[0],
                            nthreads=NTHREADS)
@@ -264,12 +266,87 @@ def test_non_autoregressive_bit_sequences(gfnx, oracle32, oracle64, case):
         assert len({tuple(pos[:, b]) for b in range(batch)}) > batch // 3  # in many different orders
 
 
-def test_paper_size_non_autoregressive_instance_is_refused(gfnx):
-    """n = 120, k = 8: 3840 actions, more than the one-byte action plane and the logit tile take."""
+def _na_wide_cases():
+    """More than 256 actions (16-bit action plane, logits in pages of 256): two to five pages, words of 5, 6 and 8
+    bits, hidden widths from 64 to 512, a batch with several groups of 16 trajectories per workgroup."""
+    return [
+        ("na16k8", bitseq_na_env(16, 8, 5, mode_seed=2), (64, 64), 50),
+        ("na24k8_128_192", bitseq_na_env(24, 8, 7, mode_seed=3), (128, 192), 37),
+        ("na80k5", bitseq_na_env(80, 5, 6, mode_seed=4, uniform_bits=True), (64, 128), 33),
+        ("na96k6_256", bitseq_na_env(96, 6, 9, mode_seed=5, uniform_bits=True), (256, 256), 70),
+        ("na40k8_512", bitseq_na_env(40, 8, 20, mode_seed=3), (512, 512), 300),
+        ("na16k8_groups", bitseq_na_env(16, 8, 5, mode_seed=2), (64, 64), 4200),
+    ]
+
+
+@pytest.mark.parametrize("case", _na_wide_cases(), ids=lambda c: c[0])
+def test_non_autoregressive_bit_sequences_beyond_256_actions(gfnx, oracle32, oracle64, case):
+    name, env, (h1, h2), batch = case
+    sd, od, na, ms = env.dims()
+    assert na > 256 and na % 256 == 0
+    w = random_mlp(od, h1, h2, na, seed=41, scale=1.5)
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, batch, seed=19, iteration=2, log_z=0.2, name=name)
+    assert traj["actions"].dtype == np.uint16 and (traj["length"] == ms).all()
+    pos = traj["actions"].astype(int) >> env.k_bits
+    assert (np.sort(pos, axis=0) == np.arange(ms)[:, None]).all()       # every position filled exactly once
+    assert np.allclose(traj["log_pb"], -math.lgamma(ms + 1), rtol=1e-5)  # uniform over the filled positions
+    if batch >= 60:
+        assert traj["actions"].max() > 255
+
+
+def test_teacher_forced_pass_beyond_256_actions(gfnx, oracle64):
+    """gfnx_replay along given 16-bit actions: the rollout's own actions give its scalars and gradient back; an
+    action on a filled position cuts that trajectory without touching the others."""
+    env = bitseq_na_env(24, 8, 7, mode_seed=3)
+    sd, od, na, ms = env.dims()
+    w = random_mlp(od, 64, 128, na, seed=43, scale=1.5)
+    sess = gfnx.Session(env, w, 90)
+    sess.rollout(23, 1)
+    sess.tb_loss_grad(0.1)
+    traj, g1 = sess.trajectories(), sess.gradients()
+    sess.replay(traj["actions"], traj["length"])
+    sess.tb_loss_grad(0.1)
+    again, g2 = sess.trajectories(), sess.gradients()
+    for k in ("log_pf", "log_pb", "log_reward"):
+        np.testing.assert_allclose(again[k], traj[k], rtol=1e-6, atol=1e-6)
+    assert (again["terminal_state"] == traj["terminal_state"]).all()
+    for k in KEYS:
+        np.testing.assert_allclose(g2[k], g1[k], rtol=1e-5, atol=1e-7 * np.abs(g1[k]).max())
+    bad = traj["actions"].copy()
+    bad[1, 5] = bad[0, 5] ^ 1   # the position filled at step 0 again
+    sess.replay(bad, traj["length"])
+    cut = sess.trajectories()
+    ref = oracle64.replay(env, {k: v.astype(np.float64) for k, v in w.items()}, 0, 0, np.ascontiguousarray(bad[:1, 5:6]),
+                          np.array([1], np.int32), tie_tol=1e30)
+    assert abs(cut["log_pf"][5] - ref["log_pf"][0]) < 1e-4 * abs(ref["log_pf"][0]) + 1e-5   # the first step only
+    keep = np.arange(90) != 5
+    np.testing.assert_allclose(cut["log_pf"][keep], traj["log_pf"][keep], rtol=1e-6, atol=1e-6)
+
+
+def test_full_paper_size_non_autoregressive_bit_sequences(gfnx, oracle32, oracle64):
+    """The paper's own bit-sequence setting: n = 120, k = 8 (15 positions x 256 words = 3840 actions), 60 modes,
+    batch 4096, MLP 3855 - 512 - 512 - 3840: every action, scalar and gradient tensor against the reference."""
     env = bitseq_na_env(120, 8, 60, mode_seed=3)
+    sd, od, na, ms = env.dims()
+    assert (od, na, ms) == (3855, 3840, 15)
+    w = xavier_mlp(od, 512, 512, na, seed=3)
+    _, traj, _ = run_case(gfnx, oracle32, oracle64, env, w, 4096, seed=3, iteration=0, log_z=0.0, name="na120k8_4096")
+    pos = traj["actions"].astype(int) >> 8
+    assert (np.sort(pos, axis=0) == np.arange(15)[:, None]).all()
+
+
+def test_action_space_limits_of_the_non_autoregressive_kind(gfnx):
+    """More than 256 actions must come in whole pages of 256 (n = 60, k = 5: 384 actions is refused), and exploration
+    is not built for them."""
+    env = bitseq_na_env(60, 5, 4, mode_seed=3, uniform_bits=True)
     with pytest.raises(gfnx.GfnxError) as err:
-        gfnx.Session(env, random_mlp(3855, 64, 64, 3840, seed=1), 16)
+        gfnx.Session(env, random_mlp(12 * 33, 64, 64, 384, seed=1), 16)
     assert err.value.status in (-3, -5)
+    env = bitseq_na_env(16, 8, 5, mode_seed=2)
+    sess = gfnx.Session(env, random_mlp(514, 64, 64, 512, seed=1), 16)
+    with pytest.raises(gfnx.GfnxError) as err:
+        sess.rollout(1, 0, epsilon=0.1)
+    assert err.value.status == -5
 
 
 def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
