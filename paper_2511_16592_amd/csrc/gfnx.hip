@@ -618,31 +618,34 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   // Out = (Gin W^T) . [act > 0] on the live rows, persistent over the row tiles: about one workgroup per CU
   auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int ldw, int kvalid, int mode,
                         float* out, int ldo, int P, const unsigned long long* mask, int mw) -> int {
+#define GFNX_NT3(KH, SCALE, MODE, CTILES)                                                                        \
+    {                                                                                                            \
+      const int ctiles = (CTILES), lds = (int)gemm_nt3_lds_bytes<KH>();                                          \
+      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);                         \
+      auto k = gemm_nt3_kernel<KH, SCALE, MODE>;                                                                 \
+      GFNX_ALLOW_LDS(k, lds)                                                                                     \
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, out, ldo, P, mask, mw, \
+                         (const float*)crow, (const int*)rows, (const int*)hdr);                                 \
+    }
     if (K <= 256) {
-      const int ctiles = (P + 127) / 128, lds = (int)gemm_nt3_lds_bytes<2>();
-      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
-      if (scale) {
-        auto k = gemm_nt3_kernel<2, true>;
-        GFNX_ALLOW_LDS(k, lds)
-        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
-                           (const float*)crow, (const int*)rows, (const int*)hdr);
+      if (!scale) {
+        if (mode) return GFNX_E_UNSUPPORTED;
+        GFNX_NT3(2, false, 0, (P + 127) / 128)
       } else {
-        auto k = gemm_nt3_kernel<2, false>;
-        GFNX_ALLOW_LDS(k, lds)
-        hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
-                           (const float*)crow, (const int*)rows, (const int*)hdr);
+        switch (mode) {
+          case 0: GFNX_NT3(2, true, 0, (P + 127) / 128) break;
+          case kNt3NoMask: GFNX_NT3(2, true, kNt3NoMask, (P + 127) / 128) break;
+          case kNt3AddToOut | kNt3NoMask: GFNX_NT3(2, true, (kNt3AddToOut | kNt3NoMask), (P + 127) / 128) break;
+          default: GFNX_NT3(2, true, kNt3AddToOut, (P + 127) / 128) break;
+        }
       }
     } else {
       // contraction lengths 257 .. 512: four contraction parts x two column blocks per workgroup (never scaled: only
-      // layer 2 of a wide network is that long, the logit layer has at most 256 outputs)
-      if (scale || K > 512) return GFNX_E_UNSUPPORTED;
-      const int ctiles = (P + 63) / 64, lds = (int)gemm_nt3_lds_bytes<4>();
-      const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);
-      auto k = gemm_nt3_kernel<4, false>;
-      GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, mode, out, ldo, P, mask, mw,
-                         (const float*)crow, (const int*)rows, (const int*)hdr);
+      // layer 2 of a wide network is that long; longer contractions run in slices of 256)
+      if (scale || mode || K > 512) return GFNX_E_UNSUPPORTED;
+      GFNX_NT3(4, false, 0, (P + 63) / 64)
     }
+#undef GFNX_NT3
     return GFNX_OK;
   };
   if (!narrow) {

@@ -324,7 +324,7 @@ namespace gfnx {
 // parts meet in a double-buffered LDS exchange after that barrier, in fixed order, and the part-0 waves store.
 // grid = (row-tile workers (grid-stride), ceil(P / (32 CB))).  SCALE: Gin rows are multiplied by crow on load.
 constexpr int kNt3Rows = 32;
-// `mode` bits: a contraction longer than the kernel takes runs as several launches over slices of it, in a fixed order:
+// MODE bits: a contraction longer than the kernel takes runs as several launches over slices of it, in a fixed order:
 // every launch but the first adds to what Out already holds, every launch but the last leaves the mask for later
 constexpr int kNt3AddToOut = 1, kNt3NoMask = 2;
 
@@ -337,9 +337,9 @@ constexpr size_t gemm_nt3_lds_bytes() {
          + 4 * kNt3Rows * 16 * 4;                         // sign-mask words, a ring of four tiles
 }
 
-template <int KH, bool SCALE>
+template <int KH, bool SCALE, int MODE>
 __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__ Gin, int ldgi, int K,
-                                                       const float* __restrict__ W, int ldw, int Kvalid, int mode,
+                                                       const float* __restrict__ W, int ldw, int Kvalid,
                                                        float* __restrict__ ActOut, int ldo, int P,
                                                        const unsigned long long* __restrict__ mask, int MW,
                                                        const float* __restrict__ crow,
@@ -461,6 +461,17 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    // accumulating launch: what the output tile holds so far is requested now and added in the epilogue
+    f32x16 prev;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) prev[r] = 0.f;
+    if ((MODE & kNt3AddToOut) && kh == 0 && pcol < P) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int id = rid[8 * (r >> 2) + 4 * kg + (r & 3)];
+        prev[r] = ActOut[(uint64_t)(uint32_t)max(id, 0) * (uint32_t)ldo + (uint32_t)pcol];
+      }
+    }
     {
       // steps past the contraction length hold nothing (uniform); the operands of step st+1 are read before the six
       // matrix instructions of step st
@@ -515,8 +526,8 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
               float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
               float* dst = (float*)(colbase + (uint64_t)(uint32_t)id4[k] * rowbytes);
               const bool row_ok = decltype(all_rows)::value || id4[k] >= 0;
-              if ((mode & kNt3AddToOut) && row_ok) av += *dst;
-              const float v = (mode & kNt3NoMask) ? av : __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
+              if (MODE & kNt3AddToOut) av += prev[4 * q + k];
+              const float v = (MODE & kNt3NoMask) ? av : __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
               if (row_ok) *dst = v;
             }
           }

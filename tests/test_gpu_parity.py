@@ -311,7 +311,8 @@ def test_teacher_forced_pass_beyond_256_actions(gfnx, oracle64):
         np.testing.assert_allclose(again[k], traj[k], rtol=1e-6, atol=1e-6)
     assert (again["terminal_state"] == traj["terminal_state"]).all()
     for k in KEYS:
-        np.testing.assert_allclose(g2[k], g1[k], rtol=1e-5, atol=1e-7 * np.abs(g1[k]).max())
+        # (dW1 is summed with atomics: the order of the additions differs from launch to launch)
+        np.testing.assert_allclose(g2[k], g1[k], rtol=1e-4, atol=1e-6 * np.abs(g1[k]).max())
     bad = traj["actions"].copy()
     bad[1, 5] = bad[0, 5] ^ 1   # the position filled at step 0 again
     sess.replay(bad, traj["length"])
