@@ -75,9 +75,7 @@ typedef enum { GFNX_ENV_GRID = 0, GFNX_ENV_BITSEQ = 1, GFNX_ENV_ISING = 2, GFNX_
  *            the position is filled; L steps; log P_B = -log(t+1) (uniform over the filled positions of the
  *            child).  Up to 256 actions (e.g. n_bits = 64, k_bits = 4) everything works as for the other kinds.
  *            Larger instances (the paper's own: n = 120, k = 8, 3840 actions) must have a multiple of 256 actions,
- *            at most 8192, and use the 16-bit action plane gfnx_traj.actions16; gfnx_rollout, gfnx_replay,
- *            gfnx_tb_loss_grad, the training iterations without exploration and gfnx_backward_rollout take them,
- *            gfnx_rollout_explore with epsilon > 0 is GFNX_E_UNSUPPORTED.
+ *            at most 8192, and use the 16-bit action plane gfnx_traj.actions16.
  * Fields of the other kinds are ignored. */
 typedef struct {
   int32_t kind;

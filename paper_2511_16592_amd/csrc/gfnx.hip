@@ -333,8 +333,8 @@ int rollout_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, uint64_t seed, u
 
   if (s.wide) {
     // more than 256 actions: the paged rollout of the non-autoregressive bit sequences
-    if (epsilon > 0.f) return GFNX_E_UNSUPPORTED;
     WideParams q = {};
+    q.eps = epsilon;
     q.env = env_params(env, s);
     q.In = s.obs_dim; q.H1 = s.H1; q.H2 = s.H2; q.A = s.A;
     q.W1 = mlp->W1; q.b1 = mlp->b1; q.b2 = mlp->b2; q.b3 = mlp->b3;

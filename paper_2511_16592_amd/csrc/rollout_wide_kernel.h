@@ -15,6 +15,9 @@
 //   SU   the lanes' maxima, sums and best keys meet (DPP / swizzle reductions), log P_F, the row's log-sum-exp to
 //        HBM, transition, log P_B -= log(t+1), reward after the last step.
 // REPLAY follows given actions instead of sampling (an impossible action cuts the trajectory, as in the general kernel).
+// Epsilon-uniform exploration (free-running only): one more Philox call per step, counter (b, t, 0xFFFFFFFE, iteration);
+// word 0 decides, word 1 picks the j-th valid action in increasing order -- here simply word j mod 2^k of the
+// (j div 2^k)-th empty position, known before the logits are.
 #pragma once
 #include "gfnx_device.h"
 #include "grad_kernels.h"
@@ -39,6 +42,7 @@ struct WideParams {
   float* lsebuf;         // [row] log-sum-exp of the valid logits (NaN: the row carries no gradient)
   unsigned long long *m1buf, *m2buf;
   int MW1, MW2;
+  float eps;  // epsilon-uniform exploration: probability of a uniform draw over the valid actions (0 = off)
 };
 
 struct WideLds {
@@ -197,8 +201,22 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_wide_kernel(const Wid
       // ================= L3 + per-page part of SU
       const size_t myrow = (size_t)t * B + (size_t)sb;
       const uint32_t myfill = filled[sj];
-      int given = 0;
+      int given = -1;  // REPLAY: the action to follow; free-running: the explored action of this step, if any
       if (REPLAY && running) given = p.actions[myrow];
+      if (!REPLAY && p.eps > 0.f && running) {
+        uint32_t we[4];
+        philox4x32_10_ukey((uint32_t)sb, (uint32_t)t, 0xFFFFFFFEu, p.iter_lo, p.seed_lo, p.seed_hi, we);
+        if (uniform_from_bits(we[0]) < p.eps) {
+          const int j = (int)__umulhi(we[1], (uint32_t)((Lp - t) << kb));  // Lp - t positions are empty
+          int left = j >> kb, pos_e = 0;
+          for (int q = 0; q < Lp; ++q) {
+            const bool empty = ((myfill >> q) & 1u) == 0u;
+            if (empty && left == 0) { pos_e = q; break; }
+            left -= empty ? 1 : 0;
+          }
+          given = (pos_e << kb) | (j & (nw - 1));
+        }
+      }
       float m_run = -INFINITY, s_run = 0.f;  // online softmax of this lane's logits
       unsigned long long best = ~0ull;       // (inverted order of the Gumbel key, action): smallest wins
       float l_best = 0.f;                    // logit of this lane's best (REPLAY: of the given action, if this lane owns it)
@@ -277,9 +295,10 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_wide_kernel(const Wid
                 const float y = lg[k] + gn;
                 const unsigned long long key =
                     ((unsigned long long)(~float_order(y)) << 32) | (uint32_t)(a0 + k);
-                if (((ok >> k) & 1u) && key < best) { best = key; l_best = lg[k]; }
+                if (((ok >> k) & 1u) && key < best && given < 0) { best = key; l_best = lg[k]; }
               }
-            } else {
+            }
+            if (REPLAY || given >= 0) {
 #pragma unroll
               for (int k = 0; k < 4; ++k)
                 if (a0 + k == given) l_best = lg[k];
@@ -297,7 +316,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_wide_kernel(const Wid
         bool given_ok = true;
         if (!REPLAY) {
           best = grp32_min_u64(best);
-          act = (int)(uint32_t)best;
+          act = given >= 0 ? given : (int)(uint32_t)best;
         } else {
           act = given;
           given_ok = act < A && (((myfill >> (act >> kb)) & 1u) == 0u);

@@ -270,8 +270,6 @@ def test_non_autoregressive_bit_sequence_dims_and_limits(lib):
     t16 = gfnx.Traj(64, 15, None, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
     assert lib.gfnx_rollout(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.byref(t16), 0x10000, need - 1,
                             None) == -4        # everything else accepted: only the workspace is too small
-    assert lib.gfnx_rollout_explore(C.byref(big), C.byref(_mlp(3855, 256, 256, 3840)), 0, 0, C.c_float(0.1),
-                                    C.byref(t16), 0x10000, need, None) == -5
     odd = gfnx.env_desc(bitseq_na_env(60, 5, 3, 1, uniform_bits=True), 0x1000)   # 12 x 32 = 384 actions
     assert lib.gfnx_workspace_bytes(C.byref(odd), C.byref(_mlp(12 * 33, 64, 64, 384)), 64) == 0
     bad = gfnx.env_desc(bitseq_na_env(64, 4, 3, 1), 0x1000)

@@ -48,6 +48,7 @@ CASES = [
     ("ising10", ising_env(10), (256, 256), 260),
     ("bitseq_na24", bitseq_na_env(24, 4, 7, mode_seed=2), (64, 64), 45),
     ("bitseq_na64_256", bitseq_na_env(64, 4, 20, mode_seed=3), (256, 256), 130),
+    ("bitseq_na40k8_paged", bitseq_na_env(40, 8, 20, mode_seed=3), (128, 64), 150),   # 1280 actions: 16-bit plane
 ]
 
 

@@ -28,6 +28,9 @@ CASES = [
     ("bitseq120_256", bitseq_env(120, 8, 60, mode_seed=3), (256, 256), 40, 0.2),
     ("bitseq_na24", bitseq_na_env(24, 4, 7, mode_seed=2), (64, 64), 45, 0.4),
     ("bitseq_na64_256", bitseq_na_env(64, 4, 20, mode_seed=3), (256, 256), 40, 0.2),
+    ("bitseq_na16k8_paged", bitseq_na_env(16, 8, 5, mode_seed=2), (64, 64), 60, 0.4),          # 512 actions
+    ("bitseq_na40k8_paged_512", bitseq_na_env(40, 8, 20, mode_seed=3), (512, 512), 40, 0.2),   # 1280 actions
+    ("bitseq_na96k6_paged_paper_eps", bitseq_na_env(96, 6, 9, mode_seed=5, uniform_bits=True), (128, 128), 900, 1e-3),
 ]
 
 

@@ -337,17 +337,11 @@ def test_full_paper_size_non_autoregressive_bit_sequences(gfnx, oracle32, oracle
 
 
 def test_action_space_limits_of_the_non_autoregressive_kind(gfnx):
-    """More than 256 actions must come in whole pages of 256 (n = 60, k = 5: 384 actions is refused), and exploration
-    is not built for them."""
+    """More than 256 actions must come in whole pages of 256 (n = 60, k = 5: 384 actions is refused)."""
     env = bitseq_na_env(60, 5, 4, mode_seed=3, uniform_bits=True)
     with pytest.raises(gfnx.GfnxError) as err:
         gfnx.Session(env, random_mlp(12 * 33, 64, 64, 384, seed=1), 16)
     assert err.value.status in (-3, -5)
-    env = bitseq_na_env(16, 8, 5, mode_seed=2)
-    sess = gfnx.Session(env, random_mlp(514, 64, 64, 512, seed=1), 16)
-    with pytest.raises(gfnx.GfnxError) as err:
-        sess.rollout(1, 0, epsilon=0.1)
-    assert err.value.status == -5
 
 
 def test_rollout_is_deterministic_and_batch_split_invariant(gfnx):
