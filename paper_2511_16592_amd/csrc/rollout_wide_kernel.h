@@ -117,10 +117,20 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_wide_kernel(const Wid
             if (on) {
               const f32x4 bb = *(const f32x4*)&p.b1[4 * fg];
               double z0 = bb.x, z1 = bb.y, z2 = bb.z, z3 = bb.w;
-              for (int pos = 0; pos < Lp; ++pos) {
-                const int r = (nw + 1) * pos + (((fl >> pos) & 1u) ? (int)words[jj * 32 + pos] : nw);
-                const f32x4 x = *(const f32x4*)&p.W1[(size_t)r * H1 + 4 * fg];
-                z0 += (double)x.x; z1 += (double)x.y; z2 += (double)x.z; z3 += (double)x.w;
+              for (int p0 = 0; p0 < Lp; p0 += 8) {  // eight rows requested together, added in position order
+                f32x4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                  const int pos = min(p0 + u, Lp - 1);
+                  const int r = (nw + 1) * pos + (((fl >> pos) & 1u) ? (int)words[jj * 32 + pos] : nw);
+                  x[u] = *(const f32x4*)&p.W1[(size_t)r * H1 + 4 * fg];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                  if (p0 + u < Lp) {
+                    z0 += (double)x[u].x; z1 += (double)x[u].y; z2 += (double)x[u].z; z3 += (double)x[u].w;
+                  }
+                }
               }
               v = (f32x4){relu1((float)z0), relu1((float)z1), relu1((float)z2), relu1((float)z3)};
               *(f32x4*)&p.h1buf[row * H1 + 4 * fg] = v;
