@@ -117,8 +117,10 @@ __global__ __launch_bounds__(512) void dw1_onehot_kernel(const float* __restrict
   lds_barrier();
   uint4 streg = fetch_state(ids);
   idreg = fetch_id(1);
-  float gn[8];
+  // the G values are requested two steps before their use
+  float gn[8], gn2[8];
   load_g(ids, 0, gn);
+  load_g(ids, 1, gn2);
 
   for (int it = 0; it < rounds; ++it) {
     const int* idb = ids + R * (it % 3);
@@ -135,9 +137,9 @@ __global__ __launch_bounds__(512) void dw1_onehot_kernel(const float* __restrict
     for (int step = 0; step < 4; ++step) {
       float g[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) g[k] = gn[k];
-      if (step < 3) load_g(idb, step + 1, gn);
-      else load_g(idb_next, 0, gn);  // first step of the next round (ids of an absent round are all -1)
+      for (int k = 0; k < 8; ++k) { g[k] = gn[k]; gn[k] = gn2[k]; }
+      if (step < 2) load_g(idb, step + 2, gn2);
+      else load_g(idb_next, step - 2, gn2);  // first steps of the next round (ids of an absent round are all -1)
       // three bf16 pieces per value, packed in contraction order
       u32x4 bh, bm, bl;
 #pragma unroll
