@@ -234,7 +234,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_wide_kernel(const Wid
         float* lgp = lgs + (page & 1) * 64 * kPitch;
         {
           // tiles 16 page + w and 16 page + w + 8: two independent accumulator chains, weights two steps ahead
-          constexpr int kL3Ahead = 2;
+          constexpr int kL3Ahead = 4;
           f32x4 acc[2];
 #pragma unroll
           for (int n = 0; n < 2; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
