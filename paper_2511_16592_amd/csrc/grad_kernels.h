@@ -344,23 +344,25 @@ __global__ __launch_bounds__(256) void bitseq_empty_rows_kernel(const float* __r
 // the word written there afterwards, so over the steps of one trajectory the two together are active exactly once per
 // step: dW1[empty(s)] = (sum of G1 over all live rows) - sum over the words w of dW1[token(s, w)].  The token rows come
 // from the per-trajectory suffix sums (dw1_kernel<3>, suffix_only), the total from the per-step column sums; on average
-// the empty row holds half of the total, so the difference loses no accuracy that matters.  grid (positions); block 0
-// also writes db1.
+// the empty row holds half of the total, so the difference loses no accuracy that matters.  The blocks of position 0
+// also write db1.
 __global__ __launch_bounds__(256) void na_empty_rows_kernel(const float* __restrict__ cs, int H1, int T, int tokens,
                                                             float* __restrict__ dW1, float* __restrict__ db1) {
-  const int s = blockIdx.x;  // position
-  for (int f = threadIdx.x; f < H1; f += 256) {
+  // grid (positions, ceil(H1 / 64)): 64 features x four quarters of the word range per block
+  __shared__ float red[4][64];
+  const int s = blockIdx.x, f = 64 * blockIdx.y + (threadIdx.x & 63), part = threadIdx.x >> 6;
+  float a = 0.f;
+  if (f < H1) {
+    const float* tok = dW1 + (size_t)(tokens + 1) * s * H1 + f;
+    for (int w = part; w < tokens; w += 4) a += tok[(size_t)w * H1];
+  }
+  red[part][threadIdx.x & 63] = a;
+  __syncthreads();
+  if (part == 0 && f < H1) {
     float tot = 0.f;
     for (int t = 0; t < T; ++t) tot += cs[(size_t)t * H1 + f];
-    const float* tok = dW1 + (size_t)(tokens + 1) * s * H1 + f;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int w = 0;
-    for (; w + 4 <= tokens; w += 4) {
-      a0 += tok[(size_t)w * H1]; a1 += tok[(size_t)(w + 1) * H1];
-      a2 += tok[(size_t)(w + 2) * H1]; a3 += tok[(size_t)(w + 3) * H1];
-    }
-    for (; w < tokens; ++w) a0 += tok[(size_t)w * H1];
-    dW1[((size_t)(tokens + 1) * s + tokens) * H1 + f] = tot - ((a0 + a1) + (a2 + a3));
+    const int l = threadIdx.x;
+    dW1[((size_t)(tokens + 1) * s + tokens) * H1 + f] = tot - ((red[0][l] + red[1][l]) + (red[2][l] + red[3][l]));
     if (s == 0) db1[f] = tot;
   }
 }

@@ -1011,7 +1011,7 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
   }
 }
 
-// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 64 / 64 / 512
+// Everything a rollout needs prepared from the weights, in one launch (block ranges of 128 / 256 / 64 / 512
 // blocks of 256 threads; the last range writes the difference rows of layer 1, see difference_rows_part):
 //   W2p, W3p  W[K][N] row-major -> MFMA A-operand order, out[nt][q][lane][s] = W[16q + 4*(lane/16) + s][16nt + lane%16],
 //             zero beyond column N (the rollout's layer-2 and logit weights);
@@ -1057,13 +1057,13 @@ __device__ __forceinline__ void pack_weights_part(const float* __restrict__ W, i
   }
 }
 constexpr int kDiffBlocks = 512;
-constexpr int kPrepareBlocks = 128 + 64 + 64 + kDiffBlocks;
+constexpr int kPrepareBlocks = 128 + 256 + 64 + kDiffBlocks;
 __global__ __launch_bounds__(256) void prepare_kernel(const PrepareParams p) {
   int b = blockIdx.x;
   if (b < 128) { pack_weights_part(p.W2, p.H1, p.H2, p.H2 >> 4, p.W2p, b, 128); return; }
   b -= 128;
-  if (b < 64) { pack_weights_part(p.W3, p.H2, p.A, p.A16 >> 4, p.W3p, b, 64); return; }
-  b -= 64;
+  if (b < 256) { pack_weights_part(p.W3, p.H2, p.A, p.A16 >> 4, p.W3p, b, 256); return; }
+  b -= 256;
   if (b >= 64) {
     if (p.D1) difference_rows_part(p, b - 64, kDiffBlocks);
     return;
