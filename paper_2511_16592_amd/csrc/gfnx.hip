@@ -724,7 +724,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         dp.suffix_only = 1;
         hipLaunchKernelGGL(fill_kernel, dim3(64), dim3(256), 0, st, cs, (size_t)T * s.H1, 0.f);
         hipLaunchKernelGGL(dw1_kernel<1>, dim3(B), dim3(256), 0, st, dp);
-        hipLaunchKernelGGL(colsum_steps_kernel, dim3(T, 16), dim3(256), 0, st, (const float*)h1buf, s.H1, (const int*)rows,
+        hipLaunchKernelGGL(colsum_steps_kernel, dim3(T, 64), dim3(256), 0, st, (const float*)h1buf, s.H1, (const int*)rows,
                            (const int*)hdr, cs);
         hipLaunchKernelGGL(bitseq_empty_rows_kernel, dim3(s.state_dim), dim3(256), 0, st, (const float*)cs, s.H1,
                            s.state_dim, T, 1 << env->k_bits, grads->dW1, grads->db1);
@@ -736,7 +736,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
         dp.suffix_only = 1;
         hipLaunchKernelGGL(fill_kernel, dim3(64), dim3(256), 0, st, cs, (size_t)T * s.H1, 0.f);
         hipLaunchKernelGGL(dw1_kernel<3>, dim3(B), dim3(256), 0, st, dp);
-        hipLaunchKernelGGL(colsum_steps_kernel, dim3(T, 16), dim3(256), 0, st, (const float*)h1buf, s.H1, (const int*)rows,
+        hipLaunchKernelGGL(colsum_steps_kernel, dim3(T, 64), dim3(256), 0, st, (const float*)h1buf, s.H1, (const int*)rows,
                            (const int*)hdr, cs);
         hipLaunchKernelGGL(na_empty_rows_kernel, dim3(s.state_dim, (s.H1 + 63) / 64), dim3(256), 0, st, (const float*)cs, s.H1, T,
                            1 << env->k_bits, grads->dW1, grads->db1);
