@@ -90,7 +90,7 @@ typedef struct {
 
 /* Policy network In -> h1 -> h2 -> n_actions with ReLU (the paper's "MLP with 2 hidden layers").
  * Device pointers, row-major [in][out], biases [out].  h1 and h2 must be multiples of 64 and at most
- * 512; n_actions at most 256. */
+ * 512; n_actions at most 256, except for the non-autoregressive bit sequences (see gfnx_env_desc). */
 typedef struct {
   int32_t in_dim, h1, h2, n_actions;
   const float *W1, *b1, *W2, *b2, *W3, *b3;
@@ -211,10 +211,11 @@ int gfnx_subtb_loss_grad(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gf
 /* Backward rollout ("Library Details": a rollout started at terminal states with the backward step in place of
  * the step) under the fixed uniform backward policy.  INPUT: traj->terminal_state [state_dim][batch] (grid
  * coordinates, clamped into 0..H-1; token bytes; spins, anything not positive counting as -1).  OUTPUT, for a
- * trajectory tau_b ~ P_B(. | x_b) drawn parent by parent until s_0: traj->actions in FORWARD order with 0xFF
- * padding, traj->length, traj->log_pb = log P_B(tau_b | x_b).  traj->log_pf and traj->log_reward are not touched
+ * trajectory tau_b ~ P_B(. | x_b) drawn parent by parent until s_0: traj->actions (traj->actions16 beyond 256
+ * actions) in FORWARD order with 0xFF (0xFFFF) padding, traj->length, traj->log_pb = log P_B(tau_b | x_b).  traj->log_pf and traj->log_reward are not touched
  * (they may be NULL); gfnx_replay on the same `traj` then evaluates log P_F along these trajectories.  Parents are
- * taken in increasing index order (grid: coordinates > 0; Ising: assigned sites), the j-th with
+ * taken in increasing index order (grid: coordinates > 0; Ising: assigned sites; non-autoregressive bit sequences:
+ * filled positions), the j-th with
  * j = floor(w * n / 2^32), w = word 0 of Philox4x32-10(counter = (b, k, 0xFFFFFFFF, iteration lo32), key = seed),
  * k = index of the backward move; moves with a single parent (the grid's un-stop, every move of the left-to-right
  * bit sequences) draw nothing.  No workspace and no network are needed; env->modes_dev is not read.
