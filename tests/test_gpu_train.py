@@ -240,3 +240,25 @@ def test_training_converges_to_the_reward_distribution(gfnx, oracle64):
     from tests.helpers import grid_reward
     target = np.array([grid_reward((i, j), side) for i in range(side) for j in range(side)]) / 16.064
     assert 0.5 * np.abs(probs - target).sum() < 0.05
+
+
+def test_training_iterations_beyond_256_actions(gfnx):
+    """Whole training iterations (rollout with exploration, TB gradient, Adam) on a non-autoregressive bit-sequence
+    instance with 512 actions -- the paged rollout and the 16-bit action plane inside gfnx_train_step_opts: the TB loss
+    falls by an order of magnitude and log Z moves towards log of the sum of the rewards."""
+    from paper_2511_16592_amd.workloads import bitseq_na_env
+    env = bitseq_na_env(16, 8, 4, mode_seed=6)
+    w0 = xavier_mlp(2 * 257, 128, 128, 512, seed=31)
+    sess = gfnx.Session(env, w0, 64)
+    sess.init_optimizer(log_z=0.0, lr=1e-3, lr_log_z=1e-1)
+    losses = []
+    for it in range(1500):
+        sess.train_step(9, it, epsilon=1e-3)
+        if it < 20 or it >= 1480:
+            losses.append(sess.loss.clone())
+    losses = [float(x.item()) for x in losses]
+    traj = sess.trajectories()
+    assert traj["actions"].dtype == np.uint16 and (traj["length"] == 2).all()
+    say(f"[train 512 actions] loss {np.mean(losses[:20]):.3g} -> {np.mean(losses[20:]):.3g}, log Z {float(sess.log_z.item()):.3f}")
+    assert np.mean(losses[20:]) < 0.1 * np.mean(losses[:20])
+    assert np.isfinite(list(sess.weights()["W3"].ravel())).all()
