@@ -74,7 +74,7 @@ struct Shapes {
 };
 
 struct Layout {
-  size_t hdr, w2p, w3p, d1, crow, rows, h1, h2, e, lse, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
+  size_t hdr, w2p, w3p, w3s, d1, crow, rows, h1, h2, e, lse, m1, m2, sb, part2, dbp2, part3, dbp3, part1, dbp1, cs;
   size_t phi, dl, lossb;  // flow networks: log F(s_t) and log P_F - log P_B per transition, loss per trajectory
   size_t total;
 };
@@ -167,6 +167,8 @@ Layout make_layout(const Shapes& s) {
   L.hdr = o; o += align256(sizeof(int) * kHdrWords);
   L.w2p = o; o += align256(sizeof(float) * (size_t)s.H1 * s.H2);
   L.w3p = o; o += align256(sizeof(float) * (size_t)s.H2 * s.A16);
+  // paged logit layer: W3 cut into bf16 pieces in the register order of the input-gradient kernel (6 bytes per weight)
+  L.w3s = o; o += align256(s.wide ? (size_t)((s.H2 + 127) / 128) * 128 * s.A16 * 6 : 0);
   L.d1 = o; o += align256(s.wide ? 0 : sizeof(double) * (size_t)s.obs_dim * s.H1);  // difference rows of layer 1
   L.rows = o; o += align256(sizeof(int) * s.rows);
   L.crow = o; o += align256(sizeof(float) * s.rows);  // coefficient of each live transition
@@ -616,34 +618,25 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   add_job(dbp3, s.s3, 1, s.qtot3, s.A, grads->db3);
   const int rt32 = (int)((s.rows + kNt3Rows - 1) / kNt3Rows);
   // Out = (Gin W^T) . [act > 0] on the live rows, persistent over the row tiles: about one workgroup per CU
-  auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int ldw, int kvalid, int mode,
-                        float* out, int ldo, int P, const unsigned long long* mask, int mw) -> int {
-#define GFNX_NT3(KH, SCALE, MODE, CTILES)                                                                        \
+  auto launch_nt3 = [&](bool scale, const float* gin, int ldgi, int K, const float* W, int ldw, int kvalid, float* out,
+                        int ldo, int P, const unsigned long long* mask, int mw) -> int {
+#define GFNX_NT3(KH, SCALE, CTILES)                                                                               \
     {                                                                                                            \
       const int ctiles = (CTILES), lds = (int)gemm_nt3_lds_bytes<KH>();                                          \
       const int gx = rt32 < 256 / ctiles ? rt32 : (256 / ctiles > 0 ? 256 / ctiles : 1);                         \
-      auto k = gemm_nt3_kernel<KH, SCALE, MODE>;                                                                 \
+      auto k = gemm_nt3_kernel<KH, SCALE>;                                                                       \
       GFNX_ALLOW_LDS(k, lds)                                                                                     \
       hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, gin, ldgi, K, W, ldw, kvalid, out, ldo, P, mask, mw, \
                          (const float*)crow, (const int*)rows, (const int*)hdr);                                 \
     }
     if (K <= 256) {
-      if (!scale) {
-        if (mode) return GFNX_E_UNSUPPORTED;
-        GFNX_NT3(2, false, 0, (P + 127) / 128)
-      } else {
-        switch (mode) {
-          case 0: GFNX_NT3(2, true, 0, (P + 127) / 128) break;
-          case kNt3NoMask: GFNX_NT3(2, true, kNt3NoMask, (P + 127) / 128) break;
-          case kNt3AddToOut | kNt3NoMask: GFNX_NT3(2, true, (kNt3AddToOut | kNt3NoMask), (P + 127) / 128) break;
-          default: GFNX_NT3(2, true, kNt3AddToOut, (P + 127) / 128) break;
-        }
-      }
+      if (scale) GFNX_NT3(2, true, (P + 127) / 128)
+      else GFNX_NT3(2, false, (P + 127) / 128)
     } else {
       // contraction lengths 257 .. 512: four contraction parts x two column blocks per workgroup (never scaled: only
-      // layer 2 of a wide network is that long; longer contractions run in slices of 256)
-      if (scale || mode || K > 512) return GFNX_E_UNSUPPORTED;
-      GFNX_NT3(4, false, 0, (P + 63) / 64)
+      // layer 2 of a wide network is that long; the logit layer of the paged rollout has a kernel of its own)
+      if (scale || K > 512) return GFNX_E_UNSUPPORTED;
+      GFNX_NT3(4, false, (P + 63) / 64)
     }
 #undef GFNX_NT3
     return GFNX_OK;
@@ -652,19 +645,23 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
     // G2 = ((coef * e) W3^T) . [h2 > 0] over h2
     GFNX_TIMED("gemm_nt_g2", st);
     if (!s.wide) {
-      rc = launch_nt3(true, ebuf, s.A16, s.A16, mlp->W3, s.A, s.A, 0, h2buf, s.H2, s.H2,
+      rc = launch_nt3(true, ebuf, s.A16, s.A16, mlp->W3, s.A, s.A, h2buf, s.H2, s.H2,
                       at<unsigned long long>(ws, L.m2), s.mw2);
       if (rc) return rc;
     } else {
-      // the contraction over thousands of actions runs page by page (256 actions each, in order), the partial sums
-      // kept in the output rows; the last page applies the mask
-      const int pages = s.A / 256;
-      for (int pg = 0; pg < pages; ++pg) {
-        const int mode = (pg > 0 ? kNt3AddToOut : 0) | (pg + 1 < pages ? kNt3NoMask : 0);
-        rc = launch_nt3(true, ebuf + 256 * pg, s.A16, 256, mlp->W3 + 256 * pg, s.A, 256, mode, h2buf, s.H2, s.H2,
-                        at<unsigned long long>(ws, L.m2), s.mw2);
-        if (rc) return rc;
-      }
+      // the contraction over thousands of actions runs page by page (256 actions each, in order) inside one kernel,
+      // against W3 cut into pieces beforehand
+      const int pages = s.A / 256, ctiles = (s.H2 + 127) / 128;
+      u32x4* w3s = at<u32x4>(ws, L.w3s);
+      hipLaunchKernelGGL(split_w_pages_kernel, dim3(pages, ctiles), dim3(512), 0, st, mlp->W3, s.A, s.H2, pages, w3s);
+      const int groups = (int)((s.rows + kNt3pTiles * kNt3Rows - 1) / (kNt3pTiles * kNt3Rows));
+      (void)groups;
+      const int lds = (int)gemm_nt3p_lds_bytes();
+      auto k = gemm_nt3p_kernel;
+      GFNX_ALLOW_LDS(k, lds)
+      hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)ebuf, s.A16, pages, (const u32x4*)w3s, h2buf,
+                         s.H2, s.H2, (const unsigned long long*)at<unsigned long long>(ws, L.m2), s.mw2,
+                         (const float*)crow, (const int*)rows, (const int*)hdr);
     }
   }
   {
@@ -681,7 +678,7 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
   {
     // G1 = (G2 W2^T) . [h1 > 0] over h1
     GFNX_TIMED("gemm_nt_g1", st);
-    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, s.H2, 0, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
+    rc = launch_nt3(false, h2buf, s.H2, s.H2, mlp->W2, s.H2, s.H2, h1buf, s.H1, s.H1, at<unsigned long long>(ws, L.m1), s.mw1);
     if (rc) return rc;
   }
   // layer 1

@@ -324,9 +324,6 @@ namespace gfnx {
 // parts meet in a double-buffered LDS exchange after that barrier, in fixed order, and the part-0 waves store.
 // grid = (row-tile workers (grid-stride), ceil(P / (32 CB))).  SCALE: Gin rows are multiplied by crow on load.
 constexpr int kNt3Rows = 32;
-// MODE bits: a contraction longer than the kernel takes runs as several launches over slices of it, in a fixed order:
-// every launch but the first adds to what Out already holds, every launch but the last leaves the mask for later
-constexpr int kNt3AddToOut = 1, kNt3NoMask = 2;
 
 template <int KH>
 constexpr size_t gemm_nt3_lds_bytes() {
@@ -337,7 +334,7 @@ constexpr size_t gemm_nt3_lds_bytes() {
          + 4 * kNt3Rows * 16 * 4;                         // sign-mask words, a ring of four tiles
 }
 
-template <int KH, bool SCALE, int MODE>
+template <int KH, bool SCALE>
 __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__ Gin, int ldgi, int K,
                                                        const float* __restrict__ W, int ldw, int Kvalid,
                                                        float* __restrict__ ActOut, int ldo, int P,
@@ -461,17 +458,6 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    // accumulating launch: what the output tile holds so far is requested now and added in the epilogue
-    f32x16 prev;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) prev[r] = 0.f;
-    if ((MODE & kNt3AddToOut) && kh == 0 && pcol < P) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int id = rid[8 * (r >> 2) + 4 * kg + (r & 3)];
-        prev[r] = ActOut[(uint64_t)(uint32_t)max(id, 0) * (uint32_t)ldo + (uint32_t)pcol];
-      }
-    }
     {
       // steps past the contraction length hold nothing (uniform); the operands of step st+1 are read before the six
       // matrix instructions of step st
@@ -523,12 +509,10 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
             for (int k = 0; k < 4; ++k) {
               // all ones where the unit was active
               const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(mw4[k], bitpos & 31, 1);
-              float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
+              const float av = acc[4 * q + k];  // (a copy: the cast below must not see the vector element itself)
+              const float v = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
               float* dst = (float*)(colbase + (uint64_t)(uint32_t)id4[k] * rowbytes);
-              const bool row_ok = decltype(all_rows)::value || id4[k] >= 0;
-              if (MODE & kNt3AddToOut) av += prev[4 * q + k];
-              const float v = (MODE & kNt3NoMask) ? av : __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, av) & keep);
-              if (row_ok) *dst = v;
+              if (decltype(all_rows)::value || id4[k] >= 0) *dst = v;
             }
           }
         };
@@ -537,6 +521,206 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
         else
           store_rows(std::false_type{});
       }
+    }
+  }
+}
+
+// ---- Input-gradient product over a contraction of many pages of 256 (the logit layer of the paged rollout):
+//   Out[i][p] = (sum_k crow[i] * Gin[i][k] * W[p][k]) * [act[i][p] > 0],  k = 0 .. 256 * pages - 1.
+// Same three-piece arithmetic and the same wave roles as gemm_nt3_kernel<2> (4 column blocks of 32 outputs x 2 halves
+// of a page), but the partial sums stay in registers across the pages: a workgroup takes a group of two 32-row tiles
+// (two accumulators per wave: four would not leave registers for the slice), and for each page loads its slice of W once -- already cut into pieces and laid out in
+// register order by split_w_pages_kernel, 1 KiB per wave and load -- and runs the tiles of the group against it.  The slice
+// of the next page replaces the current one step by step during the last tile of the page, so its loads are in
+// flight under the matrix work.  Tiles of Gin go through LDS as in gemm_nt3_kernel (two buffers, one barrier per
+// tile); the two halves of the contraction meet once per group, in the epilogue.
+// grid = (workgroups), one-dimensional: a workgroup's 128-column tile follows from the XCD it runs on (workgroups are
+// dealt to the eight XCDs round-robin by their index), so that the workgroups sharing an L2 cache sweep the same
+// slices of W -- one column tile's pieces (a quarter of W at 512 outputs) stay in that cache, all of W would not.
+constexpr int kNt3pTiles = 2;
+
+// Wsplit[(((ctile * pages + page) * 8 + wave) * 8 + step) * 3 + piece][lane]: pieces of
+// W[128 ctile + 32 (wave % 4) + lane % 32][256 page + 128 (wave / 4) + 16 step + 8 (lane / 32) .. + 7].
+// One workgroup of 512 threads per (page, ctile).
+__global__ __launch_bounds__(512) void split_w_pages_kernel(const float* __restrict__ W, int ldw, int P, int pages,
+                                                            u32x4* __restrict__ Wsplit) {
+  const int page = blockIdx.x, ctile = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int cb = w & 3, kh = w >> 2, kg = lane >> 5, l32 = lane & 31;
+  const int pcol = 128 * ctile + 32 * cb + l32;
+  u32x4* dst = Wsplit + ((size_t)(ctile * pages + page) * 8 + w) * 8 * 3 * 64 + lane;
+#pragma unroll
+  for (int st = 0; st < 8; ++st) {
+    float v[8];
+    const int k0 = 256 * page + 128 * kh + 16 * st + 8 * kg;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = pcol < P ? W[(size_t)pcol * ldw + k0 + k] : 0.f;
+    u32x4 ph, pm, pl;
+    split3x8(v, ph, pm, pl);
+    dst[(st * 3 + 0) * 64] = ph;
+    dst[(st * 3 + 1) * 64] = pm;
+    dst[(st * 3 + 2) * 64] = pl;
+  }
+}
+
+constexpr size_t gemm_nt3p_lds_bytes() {
+  return (size_t)2 * 3 * 32 * kNt3Rows * 16          // operand pieces of two tiles
+         + (size_t)4 * 64 * 64                         // partial-sum exchange
+         + kNt3pTiles * kNt3Rows * 8;                  // row ids and coefficients of the group
+}
+
+__global__ __launch_bounds__(512) void gemm_nt3p_kernel(const float* __restrict__ Gin, int ldgi, int pages,
+                                                        const u32x4* __restrict__ Wsplit,
+                                                        float* __restrict__ ActOut, int ldo, int P,
+                                                        const unsigned long long* __restrict__ mask, int MW,
+                                                        const float* __restrict__ crow,
+                                                        const int* __restrict__ rows, const int* __restrict__ hdr) {
+  constexpr int CB = 4, OCTS = 32, R = kNt3Rows, TG = kNt3pTiles;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  u32x4* AS = (u32x4*)smem_raw;                                   // [2][3][OCTS][R]
+  f32x16* XCH = (f32x16*)(AS + 2 * 3 * OCTS * R);                 // [CB][64]
+  int* gid = (int*)(XCH + CB * 64);                               // [TG * R] row ids of the group (-1: no row)
+  float* gcf = (float*)(gid + TG * R);                            // [TG * R] their coefficients
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int cb = w % CB, kh = w / CB, kg = lane >> 5, l32 = lane & 31;
+  const int n = hdr[kHdrNLive];
+  const int groups = (n + TG * R - 1) / (TG * R);
+  // column tile and worker index of this workgroup
+  const int ctiles = (P + 127) / 128, id = blockIdx.x, nwg = gridDim.x;
+  int ctile, worker, workers;
+  if (8 % ctiles == 0 && nwg % 8 == 0) {
+    const int xpc = 8 / ctiles, xcd = id & 7;  // XCDs per column tile
+    ctile = xcd / xpc;
+    worker = (id >> 3) * xpc + (xcd % xpc);
+    workers = (nwg >> 3) * xpc;
+  } else {
+    ctile = id % ctiles;
+    worker = id / ctiles;
+    workers = (nwg - ctile + ctiles - 1) / ctiles;
+  }
+  const int pcol = ctile * 128 + 32 * cb + l32;
+  const int mwords = 2 * MW;
+  const u32x4* wsrc = Wsplit + ((size_t)ctile * pages * 8 + w) * 8 * 3 * 64 + lane;  // + page * 8 * 8 * 3 * 64
+  const size_t wpage = (size_t)8 * 8 * 3 * 64;
+  const int S = pages * TG;  // tiles in the sequence of a group: page-major, the group's four row tiles within a page
+
+  for (int grp = worker; grp < groups; grp += workers) {
+    // ---- the group's rows
+    if (tid < TG * R) {
+      const int li = grp * TG * R + tid;
+      gid[tid] = li < n ? rows[li] : -1;
+      gcf[tid] = li < n ? crow[li] : 0.f;
+    }
+    lds_barrier();
+    // loader: unit u of this thread = (row, k octet) of a tile, rows fastest
+    f32x4 pre[2][2];
+    auto load_rows = [&](int s) {  // tile s of the sequence: page s / TG, row tile s % TG
+      const int page = s / TG, g = s - page * TG;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int i = tid + 512 * u, row = i & (R - 1), oct = i >> 5;
+        const int rr = gid[g * R + row];
+        const uint64_t off = (uint64_t)(uint32_t)max(rr, 0) * (uint32_t)ldgi + (uint32_t)(256 * page + 8 * oct);
+        pre[u][0] = *(const f32x4*)&Gin[off];
+        pre[u][1] = *(const f32x4*)&Gin[off + 4];
+      }
+    };
+    auto store_tile = [&](int buf, int s) {
+      const int g = s % TG;
+      u32x4* dst = AS + buf * 3 * OCTS * R;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int i = tid + 512 * u, row = i & (R - 1), oct = i >> 5;
+        const bool on = gid[g * R + row] >= 0;
+        const float c = gcf[g * R + row];
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          v[k] = on ? pre[u][0][k] * c : 0.f;
+          v[4 + k] = on ? pre[u][1][k] * c : 0.f;
+        }
+        u32x4 ph, pm, pq;
+        split3x8(v, ph, pm, pq);
+        dst[(0 * OCTS + oct) * R + row] = ph;
+        dst[(1 * OCTS + oct) * R + row] = pm;
+        dst[(2 * OCTS + oct) * R + row] = pq;
+      }
+    };
+
+    u32x4 wh[8], wm[8], wl[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      wh[st] = wsrc[(st * 3 + 0) * 64];
+      wm[st] = wsrc[(st * 3 + 1) * 64];
+      wl[st] = wsrc[(st * 3 + 2) * 64];
+    }
+    f32x16 acc[TG];
+#pragma unroll
+    for (int g = 0; g < TG; ++g)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[g][r] = 0.f;
+
+    load_rows(0);
+    store_tile(0, 0);
+    if (S > 1) load_rows(1);
+    lds_barrier();
+
+    for (int page = 0; page < pages; ++page) {
+      const bool more_pages = page + 1 < pages;
+      const u32x4* wnext = wsrc + (size_t)(page + 1) * wpage;
+#pragma unroll
+      for (int g = 0; g < TG; ++g) {
+        const int s = page * TG + g;
+        // the tile after this one (in registers) is cut into the other buffer, the one after that requested
+        if (s + 1 < S) store_tile((s + 1) & 1, s + 1);
+        if (s + 2 < S) load_rows(s + 2);
+        const u32x4* ap = AS + (s & 1) * 3 * OCTS * R + (16 * kh + kg) * R + l32;
+        u32x4 ah = ap[0], am = ap[OCTS * R], al = ap[2 * OCTS * R];
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+          u32x4 nh = ah, nm = am, nl = al;
+          if (st + 1 < 8) {
+            nh = ap[2 * (st + 1) * R];
+            nm = ap[(OCTS + 2 * (st + 1)) * R];
+            nl = ap[(2 * OCTS + 2 * (st + 1)) * R];
+          }
+          acc[g] = mfma32_bf16(am, wm[st], acc[g]);  // smallest products first
+          acc[g] = mfma32_bf16(al, wh[st], acc[g]);
+          acc[g] = mfma32_bf16(ah, wl[st], acc[g]);
+          acc[g] = mfma32_bf16(am, wh[st], acc[g]);
+          acc[g] = mfma32_bf16(ah, wm[st], acc[g]);
+          acc[g] = mfma32_bf16(ah, wh[st], acc[g]);
+          if (g == TG - 1 && more_pages) {  // this step's slice of W is done with for this page: the next page's
+            asm volatile("" ::: "memory");  // (requested here, not earlier: the registers are in use until now)
+            wh[st] = wnext[(st * 3 + 0) * 64];
+            wm[st] = wnext[(st * 3 + 1) * 64];
+            wl[st] = wnext[(st * 3 + 2) * 64];
+          }
+          ah = nh; am = nm; al = nl;
+        }
+        lds_barrier();
+      }
+    }
+
+    // ---- epilogue: the two halves of the contraction meet, mask, store; one tile at a time
+    const int bitpos = (pcol & 255) >> 2;
+    const int word32 = 2 * (4 * (pcol >> 8) + (pcol & 3)) + (bitpos >> 5);
+#pragma unroll
+    for (int g = 0; g < TG; ++g) {
+      if (kh > 0) XCH[cb * 64 + lane] = acc[g];
+      lds_barrier();
+      if (kh == 0 && pcol < P) {
+        const f32x16 other = XCH[cb * 64 + lane];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int id = gid[g * R + 8 * (r >> 2) + 4 * kg + (r & 3)];
+          if (id >= 0) {
+            const uint32_t mw = ((const uint32_t*)mask)[(uint64_t)(uint32_t)id * (uint32_t)mwords + (uint32_t)word32];
+            const float a = acc[g][r] + other[r];
+            ActOut[(uint64_t)(uint32_t)id * (uint32_t)ldo + (uint32_t)pcol] = ((mw >> (bitpos & 31)) & 1u) ? a : 0.f;
+          }
+        }
+      }
+      lds_barrier();
     }
   }
 }
