@@ -655,11 +655,12 @@ int tb_loss_grad_impl(const gfnx_env_desc* env, const gfnx_mlp* mlp, const gfnx_
       u32x4* w3s = at<u32x4>(ws, L.w3s);
       hipLaunchKernelGGL(split_w_pages_kernel, dim3(pages, ctiles), dim3(512), 0, st, mlp->W3, s.A, s.H2, pages, w3s);
       const int groups = (int)((s.rows + kNt3pTiles * kNt3Rows - 1) / (kNt3pTiles * kNt3Rows));
-      (void)groups;
+      const int per = 256 / ctiles >= 8 ? (256 / ctiles) & ~7 : 256 / ctiles;  // workers per column tile
+      const int gx = groups < per ? groups : per;
       const int lds = (int)gemm_nt3p_lds_bytes();
       auto k = gemm_nt3p_kernel;
       GFNX_ALLOW_LDS(k, lds)
-      hipLaunchKernelGGL(k, dim3(256), dim3(512), lds, st, (const float*)ebuf, s.A16, pages, (const u32x4*)w3s, h2buf,
+      hipLaunchKernelGGL(k, dim3(gx, ctiles), dim3(512), lds, st, (const float*)ebuf, s.A16, pages, (const u32x4*)w3s, h2buf,
                          s.H2, s.H2, (const unsigned long long*)at<unsigned long long>(ws, L.m2), s.mw2,
                          (const float*)crow, (const int*)rows, (const int*)hdr);
     }

@@ -534,9 +534,9 @@ __global__ __launch_bounds__(512) void gemm_nt3_kernel(const float* __restrict__
 // of the next page replaces the current one step by step during the last tile of the page, so its loads are in
 // flight under the matrix work.  Tiles of Gin go through LDS as in gemm_nt3_kernel (two buffers, one barrier per
 // tile); the two halves of the contraction meet once per group, in the epilogue.
-// grid = (workgroups), one-dimensional: a workgroup's 128-column tile follows from the XCD it runs on (workgroups are
-// dealt to the eight XCDs round-robin by their index), so that the workgroups sharing an L2 cache sweep the same
-// slices of W -- one column tile's pieces (a quarter of W at 512 outputs) stay in that cache, all of W would not.
+// grid = (group workers (grid-stride), ceil(P / 128)): with a worker count that is a multiple of eight the column
+// tiles of one group run on the same XCD (workgroups are dealt to the XCDs round-robin by their linear index), so a
+// tile of Gin comes from HBM once and from that XCD's L2 cache for the other column tiles.
 constexpr int kNt3pTiles = 2;
 
 // Wsplit[(((ctile * pages + page) * 8 + wave) * 8 + step) * 3 + piece][lane]: pieces of
@@ -584,19 +584,7 @@ __global__ __launch_bounds__(512) void gemm_nt3p_kernel(const float* __restrict_
   const int cb = w % CB, kh = w / CB, kg = lane >> 5, l32 = lane & 31;
   const int n = hdr[kHdrNLive];
   const int groups = (n + TG * R - 1) / (TG * R);
-  // column tile and worker index of this workgroup
-  const int ctiles = (P + 127) / 128, id = blockIdx.x, nwg = gridDim.x;
-  int ctile, worker, workers;
-  if (8 % ctiles == 0 && nwg % 8 == 0) {
-    const int xpc = 8 / ctiles, xcd = id & 7;  // XCDs per column tile
-    ctile = xcd / xpc;
-    worker = (id >> 3) * xpc + (xcd % xpc);
-    workers = (nwg >> 3) * xpc;
-  } else {
-    ctile = id % ctiles;
-    worker = id / ctiles;
-    workers = (nwg - ctile + ctiles - 1) / ctiles;
-  }
+  const int ctile = blockIdx.y, worker = blockIdx.x, workers = gridDim.x;
   const int pcol = ctile * 128 + 32 * cb + l32;
   const int mwords = 2 * MW;
   const u32x4* wsrc = Wsplit + ((size_t)ctile * pages * 8 + w) * 8 * 3 * 64 + lane;  // + page * 8 * 8 * 3 * 64
