@@ -333,6 +333,55 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           const int s3 = wd ? __builtin_ctz(wd) : s0;
           const int jj = lane & 3;
           const int sl = jj == 0 ? s0 : (jj == 1 ? s1 : (jj == 2 ? s2 : s3));  // jj-th running slot
+          f32x4* part = (f32x4*)(h2s + 8 * w * kPitch);  // (the rows of the h2 tile that this wave owns)
+          if (__popc(live_mask) == 1) {
+            // One running slot (most steps of the longest walk of a batch): a matrix-vector product, which the vector
+            // unit does in half the time the matrix instruction needs for its four columns.  Lane 16 g + u multiplies
+            // the same resident operands (contraction indices of lane group g, unit 16 tile + u) with the slot's
+            // activations, 128 multiply-adds in four chains, and leaves its partial sum where the four-slot path
+            // leaves the column of its first slot.
+            float p0a = 0.f, p0b = 0.f, p1a = 0.f, p1b = 0.f;
+            // the activations are requested two steps ahead of their use, the LDS-resident weights one step ahead
+            f32x4 hraw = *(const f32x4*)&z1s[(4 + g) * kPitch + s0 * 4];
+            f32x4 hv = *(const f32x4*)&z1s[g * kPitch + s0 * 4];
+#define GFNX_ONE_STEP(NEXT_READS)                                                                     \
+            {                                                                                         \
+              f32x4 hraw2 = hraw;                                                                     \
+              if (q + 2 < 16) hraw2 = *(const f32x4*)&z1s[(4 * (q + 2) + g) * kPitch + s0 * 4];       \
+              f32x4 a0, a1;                                                                           \
+              if (q < kW2RegQ) {                                                                      \
+                a0 = w2r[0][q];                                                                       \
+                a1 = w2r[1][q];                                                                       \
+              } else {                                                                                \
+                a0 = wl[(q - kW2RegQ) * 64];                                                          \
+                a1 = wl[((16 - kW2RegQ) + (q - kW2RegQ)) * 64];                                       \
+              }                                                                                       \
+              p0a = __builtin_fmaf(a0.x, hv.x, p0a); p1a = __builtin_fmaf(a1.x, hv.x, p1a);           \
+              p0b = __builtin_fmaf(a0.y, hv.y, p0b); p1b = __builtin_fmaf(a1.y, hv.y, p1b);           \
+              p0a = __builtin_fmaf(a0.z, hv.z, p0a); p1a = __builtin_fmaf(a1.z, hv.z, p1a);           \
+              p0b = __builtin_fmaf(a0.w, hv.w, p0b); p1b = __builtin_fmaf(a1.w, hv.w, p1b);           \
+              hv = hraw;                                                                              \
+              hraw = hraw2;                                                                           \
+              __builtin_amdgcn_sched_group_barrier(0x100, NEXT_READS, 0);                             \
+              __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);                                      \
+            }
+#pragma unroll
+            for (int q = 0; q < kW2RegQ - 1; ++q) GFNX_ONE_STEP(1)
+#pragma unroll
+            for (int q = kW2RegQ - 1; q < 14; ++q) GFNX_ONE_STEP(3)
+            {
+              constexpr int q = 14;
+              GFNX_ONE_STEP(2)
+            }
+            {
+              constexpr int q = 15;
+              GFNX_ONE_STEP(0)
+            }
+#undef GFNX_ONE_STEP
+            float* pf = (float*)part;
+            pf[4 * (16 * g + (j16 & ~3)) + (j16 & 3)] = p0a + p0b;         // [tile 0][g][unit quad][slot 0], element unit % 4
+            pf[4 * (64 + 16 * g + (j16 & ~3)) + (j16 & 3)] = p1a + p1b;    // [tile 1] ...
+          } else {
           // The 4x4x1 instruction occupies the pipe for 8 cycles, so the activations are requested two contraction
           // steps (128 cycles of matrix work) ahead of their use, and dependent instructions are four apart: the
           // two accumulators of a tile alternate, and the two tiles alternate inside each pair.
@@ -385,9 +434,9 @@ __global__ __launch_bounds__(kRolloutThreads) void rollout_kernel(const RolloutP
           // writes its partial columns, [tile][g][unit quad m][slot jj] (linear in the lane index), and reads, in
           // the layout of the 16-slot path, the four parts of (unit quad g, slot j16): rank of slot j16 among the
           // running ones (a slot that is not running reads some running slot's column; its results are unused).
-          f32x4* part = (f32x4*)(h2s + 8 * w * kPitch);  // (the rows of the h2 tile that this wave owns)
 #pragma unroll
           for (int n = 0; n < 2; ++n) part[n * 64 + lane] = acc[n];
+          }
           const int rk = min(__popc(live_mask & ((1u << j16) - 1u)), 3);
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's own columns, written above
 #pragma unroll
