@@ -271,6 +271,7 @@ def _na_wide_cases():
     bits, hidden widths from 64 to 512, a batch with several groups of 16 trajectories per workgroup."""
     return [
         ("na16k8", bitseq_na_env(16, 8, 5, mode_seed=2), (64, 64), 50),
+        ("na16k8_b1", bitseq_na_env(16, 8, 5, mode_seed=2), (64, 64), 1),
         ("na24k8_128_192", bitseq_na_env(24, 8, 7, mode_seed=3), (128, 192), 37),
         ("na80k5", bitseq_na_env(80, 5, 6, mode_seed=4, uniform_bits=True), (64, 128), 33),
         ("na96k6_256", bitseq_na_env(96, 6, 9, mode_seed=5, uniform_bits=True), (256, 256), 70),
@@ -322,6 +323,19 @@ def test_teacher_forced_pass_beyond_256_actions(gfnx, oracle64):
     assert abs(cut["log_pf"][5] - ref["log_pf"][0]) < 1e-4 * abs(ref["log_pf"][0]) + 1e-5   # the first step only
     keep = np.arange(90) != 5
     np.testing.assert_allclose(cut["log_pf"][keep], traj["log_pf"][keep], rtol=1e-6, atol=1e-6)
+    # sequences that stop early (given lengths 1 and 2 of 3): the scalars of the steps taken, nothing more
+    short = traj["length"].copy()
+    short[7], short[20] = 1, 2
+    sess.replay(traj["actions"], short)
+    part = sess.trajectories()
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    for b, n in ((7, 1), (20, 2)):
+        ref = oracle64.replay(env, w64, 0, 0, np.ascontiguousarray(traj["actions"][:n, b:b + 1]), np.array([n], np.int32),
+                              tie_tol=1e30)
+        assert abs(part["log_pf"][b] - ref["log_pf"][0]) < 1e-4 * abs(ref["log_pf"][0]) + 1e-5
+        assert abs(part["log_pb"][b] - ref["log_pb"][0]) < 1e-5
+    keep = (np.arange(90) != 7) & (np.arange(90) != 20)
+    np.testing.assert_allclose(part["log_pf"][keep], traj["log_pf"][keep], rtol=1e-6, atol=1e-6)
 
 
 def test_full_paper_size_non_autoregressive_bit_sequences(gfnx, oracle32, oracle64):
