@@ -211,3 +211,23 @@ def test_more_than_256_actions(oracle32, oracle64):
     fwd = oracle64.replay(env, w64, 0, 0, back["actions"], back["length"], tie_tol=1e30)
     assert (fwd["violations"] == 0).all() and (fwd["terminal_state"] == states).all()
     assert 140 < int((back["actions"][1].astype(int) >> 8).sum()) < 260   # either position is removed first
+
+
+def test_uniform_exploration_beyond_256_actions(oracle32):
+    """epsilon = 1 on the 512-action instance: every step is uniform over the valid actions whatever the policy -- the
+    first action over all 512, the second over the 256 words of the other position -- and the explored action is the
+    j-th valid one in increasing order, j = floor(w n / 2^32) (the integer rule both sides implement)."""
+    env = bitseq_na_env(16, 8, 3, mode_seed=9)
+    w = random_mlp(514, 16, 16, 512, seed=22, scale=4.0)
+    n = 40000
+    out = oracle32.rollout(env, w, seed=6, iteration=0, batch=n, nthreads=8, epsilon=1.0)
+    a0, a1 = out["actions"][0].astype(int), out["actions"][1].astype(int)
+    c0 = np.bincount(a0 >> 4, minlength=32)                      # 32 bins of 16 actions
+    assert chi2_sf(float(((c0 - n / 32) ** 2 / (n / 32)).sum()), 31) > 1e-4
+    assert ((a1 >> 8) != (a0 >> 8)).all()                        # the filled position is masked
+    c1 = np.bincount(a1 & 255, minlength=256)
+    assert chi2_sf(float(((c1 - n / 256) ** 2 / (n / 256)).sum()), 255) > 1e-4
+    # the plain policy is far from uniform with these weights, so the above is the exploration's doing
+    plain = oracle32.rollout(env, w, seed=6, iteration=0, batch=n, nthreads=8)
+    cp = np.bincount(plain["actions"][0].astype(int) >> 4, minlength=32)
+    assert chi2_sf(float(((cp - n / 32) ** 2 / (n / 32)).sum()), 31) < 1e-6
